@@ -1,0 +1,157 @@
+/*
+ * pack.h - C ABI of the packed-training library for AMD MI355X (gfx950).
+ *
+ * The library implements the `pack` primitive of "Understanding and Optimizing Packed Neural
+ * Network Training for Hyper-Parameter Tuning" (Liu, Krishnan, Elmore, Franklin): K independent
+ * networks are joined into one network by concatenating their outputs (Section 2.2, Section 3.1);
+ * when they train on the same data the K inputs are rewritten to ONE shared input (Section 3.4);
+ * members with a smaller batch size train on a slice of the shared batch (Section 3.2); every
+ * member keeps its own hyper-parameters (Section 2.2, task trait (a)); and all members are
+ * differentiated and updated in one synchronised step (Section 2.2).  The guarantee the paper
+ * states in Section 2.2 is the contract of this ABI: every member's input, output and
+ * back-propagation are exactly those of the member trained alone on a dedicated device.
+ *
+ * One `pack_t` is one packed model resident on one GPU: the paper's `pack` + `load`.
+ * `pack_read_weights` + `pack_destroy` are the paper's `free` (retrieve the checkpoint, release
+ * the memory).  Plain SGD has no optimiser state, so the checkpoint is the weights.
+ *
+ * Conventions
+ *   - All functions return a pack_status; nothing is thrown across the ABI.  A failing call
+ *     leaves the pack unchanged.  pack_last_error() returns a thread-local description.
+ *   - "dev" pointers are device memory of the GPU that was current at pack_create; "host"
+ *     pointers are ordinary host memory.  The caller owns every buffer it passes in.  The library
+ *     owns weights (fp32 master, bf16 operand copy), activations, gradients, loss/prediction
+ *     buffers and the launch plan, and releases them in pack_destroy.
+ *   - pack_step only enqueues work on the stream given at pack_create and does not wait for it.
+ *     pack_read_* and pack_write_weights wait for that stream.
+ *   - Shared batch x: row-major [B, D] for flat inputs, NHWC [B, H, W, C] for images; element type
+ *     float for PACK_F32 packs, bfloat16 (upper 16 bits of a float) for PACK_BF16 packs.
+ *   - labels: int32 [B], one vector shared by all members (one dataset, Section 3.4), values in
+ *     [0, C_k) for every member k.
+ *   - Per-member flat weight blob (always float): layers in order; PACK_LINEAR stores
+ *     W[out][in] then b[out]; PACK_CONV3X3 stores W[Cout][Cin][3][3] then b[Cout].  A linear
+ *     layer applied to an image sees it flattened in NHWC order.
+ *   - PACK_BF16: matrix operands (x, activations, stored gradients, a per-step bf16 copy of the
+ *     weights) are bfloat16; products accumulate in fp32; bias add, ReLU, softmax
+ *     cross-entropy, weight gradients and the update are fp32; the master weights stay fp32.
+ */
+#ifndef PACK_H
+#define PACK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pack_ctx pack_t;
+
+typedef enum {
+    PACK_OK = 0,
+    PACK_EINVAL = 1,   /* null pointer, K < 1 or > PACK_MAX_MODELS, unknown op, bad stride, batch outside [1, B] */
+    PACK_ENOMEM = 2,   /* device or host allocation failed (the out-of-memory case of Section 4.2) */
+    PACK_EDEVICE = 3,  /* a HIP runtime call failed */
+    PACK_ESHAPE = 4,   /* layer list is not a classifier this library can run (see pack_create) */
+    PACK_ELABEL = 5    /* a label outside [0, C_k) was seen by the last step */
+} pack_status;
+
+typedef enum {
+    PACK_LINEAR = 0,    /* fully connected, with bias; `out` = output features */
+    PACK_CONV3X3 = 1,   /* 3x3 convolution, zero padding 1, with bias; `out` = channels, `stride` 1 or 2 */
+    PACK_RELU = 2,      /* max(z, 0); must directly follow PACK_LINEAR or PACK_CONV3X3 */
+    PACK_GAP = 3,       /* global average pool over H x W */
+    PACK_RES_BEGIN = 4, /* the current tensor becomes the shortcut source of a residual block */
+    PACK_RES_END = 5    /* y = relu(current + shortcut(source)); must directly follow PACK_CONV3X3.
+                           shortcut = identity when shapes agree; otherwise source[b,2i,2j,c] for
+                           c < Cin and 0 for the remaining channels (parameter-free) */
+} pack_op;
+
+typedef enum { PACK_F32 = 0, PACK_BF16 = 1 } pack_dtype;
+
+#define PACK_MAX_MODELS 256
+
+typedef struct {
+    int32_t op;      /* pack_op */
+    int32_t out;     /* output features / channels (PACK_LINEAR, PACK_CONV3X3), else ignored */
+    int32_t stride;  /* PACK_CONV3X3 only: 1 or 2 */
+} pack_layer;
+
+/* One member = the paper's "training task" (Section 2.2) minus device and step count. */
+typedef struct {
+    const pack_layer* layers;  /* host */
+    int32_t n_layers;
+    int32_t batch;             /* b_k in [1, B]: the member trains on rows [0, b_k) of the shared batch */
+} pack_model_spec;
+
+typedef struct {
+    int32_t B;                 /* rows of the shared batch */
+    int32_t in_h, in_w, in_c;  /* flat input of D features: in_h = in_w = 1, in_c = D */
+    int32_t dtype;             /* pack_dtype */
+} pack_input_spec;
+
+/* pack + load (Section 2.2): build the packed model for K members on the current device.
+ * `models` and the layer arrays are host memory and are copied.  Weights are initialised from
+ * `seed` (uniform in +-sqrt(6/fan_in), biases in +-1/sqrt(fan_in)); callers that need specific
+ * weights use pack_write_weights.  `hip_stream` is a hipStream_t (0 = the null stream) on
+ * which every later call enqueues its work.  The layer list of each member must end in a
+ * [b_k, C_k] tensor (a PACK_LINEAR, or PACK_GAP), the logits.
+ * Errors: PACK_EINVAL, PACK_ESHAPE (unsupported op order, RES_BEGIN/RES_END mismatch, shortcut
+ * shapes that neither agree nor halve, no parameterised layer), PACK_ENOMEM, PACK_EDEVICE. */
+pack_status pack_create(const pack_input_spec* input, const pack_model_spec* models, int32_t K,
+                        uint64_t seed, void* hip_stream, pack_t** out);
+
+/* load a member's weights (Section 2.2 `load`): host_src holds pack_num_params(p, k) floats in
+ * the blob layout above.  For PACK_BF16 the bf16 operand copy is refreshed too.
+ * Errors: PACK_EINVAL (k out of range, n_floats mismatch), PACK_EDEVICE. */
+pack_status pack_write_weights(pack_t* p, int32_t k, const float* host_src, size_t n_floats);
+
+/* One synchronised training step of all K members (Section 2.2; shared input Section 3.4; batch
+ * slices Section 3.2): forward, mean softmax cross-entropy over each member's own rows, backward,
+ * and W <- W - lr[k] * dW for every parameter of member k, with gradients taken at the
+ * pre-update weights.  x_dev: device, [B, H, W, C] of the pack's dtype; labels_dev: device int32
+ * [B]; lr_host: host float [K], copied during the call.  Enqueues only.
+ * Errors: PACK_EINVAL (null argument), PACK_EDEVICE (launch failure). */
+pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, const float* lr_host);
+
+/* Loss of each member at the last step, evaluated at that step's pre-update weights.
+ * host_dst: float [K].  Waits for the stream.  Returns PACK_ELABEL (and still fills host_dst)
+ * if the last step met a label outside [0, C_k); such rows contribute nothing. */
+pack_status pack_read_loss(pack_t* p, float* host_dst);
+
+/* free's checkpoint (Section 2.2): the member's current fp32 weights in the blob layout. */
+pack_status pack_read_weights(pack_t* p, int32_t k, float* host_dst, size_t n_floats);
+
+/* argmax over classes of the last step's logits of member k (lowest index on ties).
+ * host_dst: int32 [b_k]. */
+pack_status pack_read_pred(pack_t* p, int32_t k, int32_t* host_dst);
+
+/* Test hook: the gradients the last step applied to member k, in the blob layout. */
+pack_status pack_read_grads(pack_t* p, int32_t k, float* host_dst, size_t n_floats);
+
+/* Test hook: the last step's logits of member k, row-major float [b_k, C_k]. */
+pack_status pack_read_logits(pack_t* p, int32_t k, float* host_dst, size_t n_floats);
+
+/* Number of floats in member k's blob; 0 if p is null or k is out of range. */
+size_t pack_num_params(const pack_t* p, int32_t k);
+
+/* Number of classes C_k of member k; 0 if out of range. */
+int32_t pack_num_classes(const pack_t* p, int32_t k);
+
+/* Number of kernel launches one pack_step enqueues (a packing figure of merit: K members cost
+ * one launch sequence instead of K). */
+int32_t pack_num_launches(const pack_t* p);
+
+/* Bytes of device memory the pack holds (the paper's memory metric, Section 4.2: allocated). */
+size_t pack_device_bytes(const pack_t* p);
+
+/* Thread-local text describing the last failing call on this thread ("" if none). */
+const char* pack_last_error(void);
+
+/* free (Section 2.2): waits for the stream and releases everything the pack owns.  Null is a no-op. */
+void pack_destroy(pack_t* p);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PACK_H */

@@ -25,9 +25,16 @@ The paper fixes none of the layer numerics; the readings used here are:
   * argmax returns the smallest index attaining the maximum;
   * a linear layer applied to an image flattens it in NHWC order.
 
-bf16 packs ("bf16 operands, fp32 accumulate, fp32 master weights") have two modes here:
+bf16 packs ("bf16 inputs/weights, fp32 accumulate, fp32 master weights") have three modes here:
   mode "exact"   - float64 throughout; only the data (x, initial weights) is bf16-representable.
-  mode "rounded" - the same code with q() = round-to-nearest-even to bf16 applied where the
+                   Equals the other modes' definition at step 1 up to activation rounding.
+  mode "weights" - the precision the configuration itself fixes: every step multiplies by
+                   q(W_master), the bf16 copy of the master weights, and updates the unrounded
+                   master; everything else float64.  This is the reference for losses and
+                   weights of bf16 packs (an update smaller than half a bf16 ulp of a weight is
+                   invisible to the next forward pass until it accumulates in the master, so
+                   from step 2 on this differs from "exact" by far more than any tolerance).
+  mode "rounded" - "weights" plus q() = round-to-nearest-even to bf16 applied where the
                    device stores a matrix-core operand: the per-step operand copy of each weight
                    tensor (biases stay fp32), every stored activation (post-ReLU / post-residual,
                    GAP output; logits stay unrounded), every stored gradient with respect to a
@@ -149,10 +156,11 @@ class Model:
     flat weight vector (linear W[out][in], b[out]; conv W[Cout][Cin][3][3], b[Cout])."""
 
     def __init__(self, layers, in_shape, blob, mode="exact"):
-        assert mode in ("exact", "rounded")
+        assert mode in ("exact", "weights", "rounded")
         self.layers = [tuple(op) for op in layers]
         self.in_shape = tuple(in_shape)
-        self.q = q_bf16 if mode == "rounded" else _ident
+        self.q = q_bf16 if mode == "rounded" else _ident          # stored activations / gradients
+        self.qw = q_bf16 if mode in ("weights", "rounded") else _ident   # per-step operand copy of W
         self.params = []                                  # [W, b] per parameterised layer
         blob = np.asarray(blob, dtype=np.float64)
         h, w, c = self.in_shape
@@ -196,14 +204,14 @@ class Model:
                 W, b = self.params[pi]
                 cur = q(cur)                       # a stored operand is a rounded operand
                 flat = cur.reshape(cur.shape[0], -1)
-                z = flat @ q(W).T + b
+                z = flat @ self.qw(W).T + b
                 tape.append(("linear", pi, cur))
                 cur = z.reshape(z.shape[0], 1, 1, z.shape[1])
                 pi += 1
             elif kind == "conv3x3":
                 W, b = self.params[pi]
                 cur = q(cur)
-                z = conv3x3_forward(cur, q(W), b, op[2])
+                z = conv3x3_forward(cur, self.qw(W), b, op[2])
                 tape.append(("conv3x3", pi, cur, op[2]))
                 cur = z
                 pi += 1
@@ -252,11 +260,11 @@ class Model:
                 dz = q(g).reshape(g.shape[0], -1)
                 flat = inp.reshape(inp.shape[0], -1)
                 grads[pi] = [dz.T @ flat, dz.sum(axis=0)]
-                g = (dz @ q(W)).reshape(inp.shape) if pi != first_param else None
+                g = (dz @ self.qw(W)).reshape(inp.shape) if pi != first_param else None
             elif kind == "conv3x3":
                 _, pi, inp, s = rec
                 W, _b = self.params[pi]
-                dW, db, dx = conv3x3_backward(inp, q(W), s, q(g), need_dx=(pi != first_param))
+                dW, db, dx = conv3x3_backward(inp, self.qw(W), s, q(g), need_dx=(pi != first_param))
                 grads[pi] = [dW, db]
                 g = dx
             elif kind == "relu":

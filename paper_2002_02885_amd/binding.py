@@ -1,0 +1,179 @@
+"""ctypes binding of libpack.so: the same entry points as include/pack.h, with argument
+marshalling only.  Every step of the training path runs inside the library's kernels."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpack.so")
+
+PACK_OK, PACK_EINVAL, PACK_ENOMEM, PACK_EDEVICE, PACK_ESHAPE, PACK_ELABEL = range(6)
+PACK_F32, PACK_BF16 = 0, 1
+OPS = {"linear": 0, "conv3x3": 1, "relu": 2, "gap": 3, "res_begin": 4, "res_end": 5}
+STATUS_NAMES = ["PACK_OK", "PACK_EINVAL", "PACK_ENOMEM", "PACK_EDEVICE", "PACK_ESHAPE", "PACK_ELABEL"]
+
+EXPORTS = ["pack_create", "pack_write_weights", "pack_step", "pack_read_loss", "pack_read_weights",
+           "pack_read_pred", "pack_read_grads", "pack_read_logits", "pack_num_params",
+           "pack_num_classes", "pack_num_launches", "pack_device_bytes", "pack_last_error", "pack_destroy"]
+
+
+class pack_layer(C.Structure):
+    _fields_ = [("op", C.c_int32), ("out", C.c_int32), ("stride", C.c_int32)]
+
+
+class pack_model_spec(C.Structure):
+    _fields_ = [("layers", C.POINTER(pack_layer)), ("n_layers", C.c_int32), ("batch", C.c_int32)]
+
+
+class pack_input_spec(C.Structure):
+    _fields_ = [("B", C.c_int32), ("in_h", C.c_int32), ("in_w", C.c_int32), ("in_c", C.c_int32),
+                ("dtype", C.c_int32)]
+
+
+class PackError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"{STATUS_NAMES[status] if 0 <= status < 6 else status}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libpack.so (once).  There is no fallback: a missing library is an error."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2002_02885_amd.build`")
+        l = C.CDLL(LIB_PATH)
+        vp, i32, u64, sz = C.c_void_p, C.c_int32, C.c_uint64, C.c_size_t
+        fp = C.POINTER(C.c_float)
+        l.pack_create.argtypes = [C.POINTER(pack_input_spec), C.POINTER(pack_model_spec), i32, u64, vp, C.POINTER(vp)]
+        l.pack_write_weights.argtypes = [vp, i32, fp, sz]
+        l.pack_step.argtypes = [vp, vp, vp, fp]
+        l.pack_read_loss.argtypes = [vp, fp]
+        l.pack_read_weights.argtypes = [vp, i32, fp, sz]
+        l.pack_read_pred.argtypes = [vp, i32, C.POINTER(C.c_int32)]
+        l.pack_read_grads.argtypes = [vp, i32, fp, sz]
+        l.pack_read_logits.argtypes = [vp, i32, fp, sz]
+        l.pack_num_params.argtypes = [vp, i32]
+        l.pack_num_params.restype = sz
+        l.pack_num_classes.argtypes = [vp, i32]
+        l.pack_num_classes.restype = i32
+        l.pack_num_launches.argtypes = [vp]
+        l.pack_num_launches.restype = i32
+        l.pack_device_bytes.argtypes = [vp]
+        l.pack_device_bytes.restype = sz
+        l.pack_last_error.argtypes = []
+        l.pack_last_error.restype = C.c_char_p
+        l.pack_destroy.argtypes = [vp]
+        l.pack_destroy.restype = None
+        for name in ("pack_create", "pack_write_weights", "pack_step", "pack_read_loss",
+                     "pack_read_weights", "pack_read_pred", "pack_read_grads", "pack_read_logits"):
+            getattr(l, name).restype = C.c_int
+        _lib = l
+    return _lib
+
+
+def _check(status: int, allow: Sequence[int] = ()):
+    if status != PACK_OK and status not in allow:
+        raise PackError(status, lib().pack_last_error().decode())
+    return status
+
+
+def _fptr(a: np.ndarray):
+    return a.ctypes.data_as(C.POINTER(C.c_float))
+
+
+class Pack:
+    """One packed model on the current GPU.  `models` is a list of layer lists of tuples
+    ("linear", out) / ("conv3x3", out, stride) / ("relu",) / ("gap",) / ("res_begin",) /
+    ("res_end",); `batch[k]` is the number of leading rows of the shared batch member k uses."""
+
+    def __init__(self, B: int, in_shape: Tuple[int, int, int], dtype: str, models: List[list],
+                 batch: Sequence[int] = None, seed: int = 0, stream: int = 0):
+        self._h = C.c_void_p()
+        self.K = len(models)
+        self.B = B
+        self.dtype = dtype
+        batch = list(batch) if batch is not None else [B] * self.K
+        keep = []
+        specs = (pack_model_spec * max(self.K, 1))()
+        for k, layers in enumerate(models):
+            arr = (pack_layer * max(len(layers), 1))()
+            for i, op in enumerate(layers):
+                arr[i].op = OPS[op[0]] if op[0] in OPS else int(op[0])
+                arr[i].out = int(op[1]) if len(op) > 1 else 0
+                arr[i].stride = int(op[2]) if len(op) > 2 else 1
+            keep.append(arr)
+            specs[k].layers = arr
+            specs[k].n_layers = len(layers)
+            specs[k].batch = int(batch[k])
+        inp = pack_input_spec(B, in_shape[0], in_shape[1], in_shape[2], PACK_BF16 if dtype == "bf16" else PACK_F32)
+        _check(lib().pack_create(C.byref(inp), specs, self.K, seed, C.c_void_p(stream), C.byref(self._h)))
+        self.batch = batch
+
+    # -- the ABI, one method per entry point ---------------------------------------------------
+    def write_weights(self, k: int, blob: np.ndarray):
+        blob = np.ascontiguousarray(blob, dtype=np.float32)
+        _check(lib().pack_write_weights(self._h, k, _fptr(blob), blob.size))
+
+    def step(self, x_ptr: int, labels_ptr: int, lr: np.ndarray):
+        """x_ptr / labels_ptr are raw device addresses (e.g. torch tensor .data_ptr())."""
+        lr = np.ascontiguousarray(lr, dtype=np.float32)
+        assert lr.size == self.K
+        _check(lib().pack_step(self._h, C.c_void_p(x_ptr), C.c_void_p(labels_ptr), _fptr(lr)))
+
+    def read_loss(self, allow_label_error: bool = False) -> np.ndarray:
+        out = np.empty(self.K, dtype=np.float32)
+        st = _check(lib().pack_read_loss(self._h, _fptr(out)), allow=(PACK_ELABEL,) if allow_label_error else ())
+        self.last_status = st
+        return out
+
+    def read_weights(self, k: int) -> np.ndarray:
+        out = np.empty(self.num_params(k), dtype=np.float32)
+        _check(lib().pack_read_weights(self._h, k, _fptr(out), out.size))
+        return out
+
+    def read_grads(self, k: int) -> np.ndarray:
+        out = np.empty(self.num_params(k), dtype=np.float32)
+        _check(lib().pack_read_grads(self._h, k, _fptr(out), out.size))
+        return out
+
+    def read_pred(self, k: int) -> np.ndarray:
+        out = np.empty(self.batch[k], dtype=np.int32)
+        _check(lib().pack_read_pred(self._h, k, out.ctypes.data_as(C.POINTER(C.c_int32))))
+        return out
+
+    def read_logits(self, k: int) -> np.ndarray:
+        out = np.empty((self.batch[k], self.num_classes(k)), dtype=np.float32)
+        _check(lib().pack_read_logits(self._h, k, _fptr(out), out.size))
+        return out
+
+    def num_params(self, k: int) -> int:
+        return int(lib().pack_num_params(self._h, k))
+
+    def num_classes(self, k: int) -> int:
+        return int(lib().pack_num_classes(self._h, k))
+
+    def num_launches(self) -> int:
+        return int(lib().pack_num_launches(self._h))
+
+    def device_bytes(self) -> int:
+        return int(lib().pack_device_bytes(self._h))
+
+    def destroy(self):
+        if self._h:
+            lib().pack_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

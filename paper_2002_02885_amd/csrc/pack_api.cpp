@@ -1,0 +1,853 @@
+// Host side of the packed-training library: the C ABI of include/pack.h, the planner that turns
+// K layer lists into a static launch sequence over lists of problems, and weight I/O.
+//
+// The packed model of the paper (Section 2.2: outputs concatenated; Section 3.4: one shared input;
+// Section 3.2: smaller batches are slices of the shared batch) is represented as a plan, not as a
+// literal concatenated graph: slot s of the plan holds layer s of every member that has one, and
+// each slot is executed by one launch per kernel kind over a list of per-member problems.
+// Members therefore never exchange data, which is what makes packing lossless (Section 3.1).
+#include "../../include/pack.h"
+#include "pack_internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <string>
+#include <vector>
+
+using namespace packk;
+
+namespace {
+
+thread_local std::string g_err;
+
+pack_status fail(pack_status s, const std::string& msg) {
+    g_err = msg;
+    return s;
+}
+
+#define HIP_TRY(expr, status)                                                             \
+    do {                                                                                  \
+        hipError_t e_ = (expr);                                                           \
+        if (e_ != hipSuccess)                                                             \
+            return fail(status, std::string(#expr) + ": " + hipGetErrorString(e_));      \
+    } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+enum NodeKind { NODE_LINEAR = 0, NODE_CONV = 1, NODE_GAP = 2 };
+
+struct TensorInfo {
+    int n = 0, h = 0, w = 0, c = 0;
+    bool is_input = false;
+    bool f32 = false;        // logits are stored as float whatever the pack dtype
+    bool relu_out = false;   // produced through a ReLU: gradients written to it are masked
+    bool needs_grad = false;
+    bool grad_written = false;
+    void* act = nullptr;
+    void* dz = nullptr;
+    size_t elems() const { return (size_t)n * h * w * c; }
+};
+
+struct NodeInfo {
+    int kind = 0;
+    int in_t = -1, out_t = -1;
+    int out = 0, stride = 1;
+    bool relu = false;
+    int res_src = -1;        // tensor index of the shortcut source, -1 if none
+    bool res_down = false;
+    size_t w_off = 0, b_off = 0;   // element offsets into the parameter arena
+    size_t w_elems = 0;
+    int fan_in = 0;
+    size_t blob_off = 0;     // float offset of W in the member's public blob
+};
+
+struct ModelInfo {
+    std::vector<TensorInfo> tensors;
+    std::vector<NodeInfo> nodes;
+    int batch = 0, C = 0;
+    size_t n_params = 0;             // floats in the public blob
+    size_t arena_begin = 0, arena_end = 0;
+    int* pred = nullptr;
+    float* loss = nullptr;
+};
+
+enum LaunchKind { L_GEMM, L_COLSUM, L_REDUCE, L_CE, L_GAP_FWD, L_GAP_BWD, L_SHORTCUT, L_SGD };
+
+struct Launch {
+    int kind = 0, mode = 0;
+    size_t desc_off = 0;    // byte offset of the problem array in the descriptor buffer
+    size_t map_off = 0;     // byte offset of the tile / block map
+    int n = 0;              // grid size
+};
+
+}  // namespace
+
+struct pack_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    bool bf16 = false;
+    int K = 0;
+    pack_input_spec in{};
+    std::vector<ModelInfo> models;
+    float* master = nullptr;     // fp32 parameter arena
+    float* grad = nullptr;       // same layout
+    void* shadow = nullptr;      // bf16 copy of the arena (bf16 packs)
+    size_t arena_elems = 0;
+    long long* seg_end = nullptr;
+    char* slab = nullptr;        // activations, gradients wrt activations, loss, predictions
+    size_t slab_bytes = 0;
+    char* workspace = nullptr;   // partial sums of split reductions
+    size_t workspace_bytes = 0;
+    char* desc = nullptr;        // problem descriptors and block maps
+    size_t desc_bytes = 0;
+    int* err_flag = nullptr;
+    float* loss_all = nullptr;   // [K]
+    std::vector<Launch> plan;
+    size_t device_bytes = 0;
+};
+
+namespace {
+
+// ---- counter-based initialisation: value = hash(seed, member, tensor, index) -> uniform ---------
+inline uint64_t splitmix64(uint64_t x) {
+    x += 0x9E3779B97F4A7C15ull;
+    x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+    x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+    return x ^ (x >> 31);
+}
+inline float uniform_pm(uint64_t seed, uint64_t member, uint64_t tensor, uint64_t idx, float bound) {
+    const uint64_t h = splitmix64(splitmix64(splitmix64(seed ^ (member << 32)) ^ tensor) ^ idx);
+    const double u = (double)(h >> 11) * (1.0 / 9007199254740992.0);   // [0,1)
+    return (float)((2.0 * u - 1.0) * bound);
+}
+inline float round_to_bf16(float f) {
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return f;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    u &= 0xffff0000u;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+
+// ---- public blob <-> arena layout ----------------------------------------------------------------
+// linear: identical ([out][in]).  conv: blob [Cout][Cin][3][3]  <->  arena [Cout][3][3][Cin].
+void blob_to_arena(const ModelInfo& m, const float* blob, std::vector<float>& arena) {
+    arena.assign(m.arena_end - m.arena_begin, 0.f);
+    for (const NodeInfo& nd : m.nodes) {
+        if (nd.kind == NODE_GAP) continue;
+        float* W = arena.data() + (nd.w_off - m.arena_begin);
+        float* b = arena.data() + (nd.b_off - m.arena_begin);
+        const float* src = blob + nd.blob_off;
+        if (nd.kind == NODE_LINEAR) {
+            std::memcpy(W, src, nd.w_elems * sizeof(float));
+        } else {
+            const int cin = nd.fan_in / 9;
+            for (int o = 0; o < nd.out; ++o)
+                for (int c = 0; c < cin; ++c)
+                    for (int t = 0; t < 9; ++t)
+                        W[((size_t)o * 9 + t) * cin + c] = src[((size_t)o * cin + c) * 9 + t];
+        }
+        std::memcpy(b, src + nd.w_elems, (size_t)nd.out * sizeof(float));
+    }
+}
+
+void arena_to_blob(const ModelInfo& m, const std::vector<float>& arena, float* blob) {
+    for (const NodeInfo& nd : m.nodes) {
+        if (nd.kind == NODE_GAP) continue;
+        const float* W = arena.data() + (nd.w_off - m.arena_begin);
+        const float* b = arena.data() + (nd.b_off - m.arena_begin);
+        float* dst = blob + nd.blob_off;
+        if (nd.kind == NODE_LINEAR) {
+            std::memcpy(dst, W, nd.w_elems * sizeof(float));
+        } else {
+            const int cin = nd.fan_in / 9;
+            for (int o = 0; o < nd.out; ++o)
+                for (int c = 0; c < cin; ++c)
+                    for (int t = 0; t < 9; ++t)
+                        dst[((size_t)o * cin + c) * 9 + t] = W[((size_t)o * 9 + t) * cin + c];
+        }
+        std::memcpy(dst + nd.w_elems, b, (size_t)nd.out * sizeof(float));
+    }
+}
+
+// ---- parse one member's layer list -----------------------------------------------------------------
+pack_status parse_model(const pack_input_spec& in, const pack_model_spec& spec, int k, ModelInfo& m) {
+    const std::string who = "member " + std::to_string(k) + ": ";
+    if (!spec.layers || spec.n_layers < 1) return fail(PACK_EINVAL, who + "empty layer list");
+    if (spec.batch < 1 || spec.batch > in.B) return fail(PACK_EINVAL, who + "batch outside [1, B]");
+    m.batch = spec.batch;
+    TensorInfo t0;
+    t0.n = spec.batch; t0.h = in.in_h; t0.w = in.in_w; t0.c = in.in_c; t0.is_input = true;
+    m.tensors.push_back(t0);
+    int cur = 0;
+    std::vector<int> res_stack;
+    size_t blob_off = 0;
+    for (int i = 0; i < spec.n_layers; ++i) {
+        const pack_layer& L = spec.layers[i];
+        const int next_op = (i + 1 < spec.n_layers) ? spec.layers[i + 1].op : -1;
+        const TensorInfo src = m.tensors[cur];
+        switch (L.op) {
+            case PACK_LINEAR:
+            case PACK_CONV3X3: {
+                if (L.out < 1) return fail(PACK_EINVAL, who + "layer width < 1");
+                NodeInfo nd;
+                TensorInfo o;
+                o.n = src.n;
+                nd.in_t = cur;
+                nd.out = L.out;
+                if (L.op == PACK_LINEAR) {
+                    nd.kind = NODE_LINEAR;
+                    nd.fan_in = src.h * src.w * src.c;
+                    o.h = o.w = 1;
+                } else {
+                    if (L.stride != 1 && L.stride != 2) return fail(PACK_EINVAL, who + "conv stride must be 1 or 2");
+                    nd.kind = NODE_CONV;
+                    nd.stride = L.stride;
+                    nd.fan_in = 9 * src.c;
+                    o.h = (src.h - 1) / L.stride + 1;   // = floor((h + 2 - 3) / s) + 1
+                    o.w = (src.w - 1) / L.stride + 1;
+                }
+                o.c = L.out;
+                nd.w_elems = (size_t)L.out * nd.fan_in;
+                nd.blob_off = blob_off;
+                blob_off += nd.w_elems + L.out;
+                if (next_op == PACK_RELU) {
+                    nd.relu = true;
+                    ++i;
+                } else if (next_op == PACK_RES_END) {
+                    if (L.op != PACK_CONV3X3) return fail(PACK_ESHAPE, who + "RES_END must directly follow a CONV3X3");
+                    if (res_stack.empty()) return fail(PACK_ESHAPE, who + "RES_END without RES_BEGIN");
+                    nd.res_src = res_stack.back();
+                    res_stack.pop_back();
+                    const TensorInfo& s = m.tensors[nd.res_src];
+                    if (s.h == o.h && s.w == o.w && s.c == o.c) {
+                        nd.res_down = false;
+                    } else if ((s.h + 1) / 2 == o.h && (s.w + 1) / 2 == o.w && s.c <= o.c) {
+                        nd.res_down = true;
+                    } else {
+                        return fail(PACK_ESHAPE, who + "shortcut shapes neither agree nor halve");
+                    }
+                    nd.relu = true;
+                    ++i;
+                }
+                o.relu_out = nd.relu;
+                m.tensors.push_back(o);
+                nd.out_t = (int)m.tensors.size() - 1;
+                m.nodes.push_back(nd);
+                cur = nd.out_t;
+                break;
+            }
+            case PACK_GAP: {
+                if (src.is_input) return fail(PACK_ESHAPE, who + "GAP directly on the input is not supported");
+                NodeInfo nd;
+                nd.kind = NODE_GAP;
+                nd.in_t = cur;
+                TensorInfo o;
+                o.n = src.n; o.h = o.w = 1; o.c = src.c;
+                m.tensors.push_back(o);
+                nd.out_t = (int)m.tensors.size() - 1;
+                m.nodes.push_back(nd);
+                cur = nd.out_t;
+                break;
+            }
+            case PACK_RES_BEGIN:
+                res_stack.push_back(cur);
+                break;
+            case PACK_RELU:
+                return fail(PACK_ESHAPE, who + "RELU must directly follow LINEAR or CONV3X3");
+            case PACK_RES_END:
+                return fail(PACK_ESHAPE, who + "RES_END must directly follow a CONV3X3");
+            default:
+                return fail(PACK_EINVAL, who + "unknown op " + std::to_string(L.op));
+        }
+    }
+    if (!res_stack.empty()) return fail(PACK_ESHAPE, who + "RES_BEGIN without RES_END");
+    if (m.nodes.empty() || m.nodes.back().kind != NODE_LINEAR || m.nodes.back().relu)
+        return fail(PACK_ESHAPE, who + "the layer list must end in a LINEAR layer producing the logits");
+    m.tensors[cur].f32 = true;
+    m.C = m.tensors[cur].c;
+    m.n_params = blob_off;
+    // which tensors have parameters upstream
+    for (NodeInfo& nd : m.nodes) {
+        bool ng = (nd.kind != NODE_GAP) || m.tensors[nd.in_t].needs_grad;
+        if (nd.res_src >= 0 && m.tensors[nd.res_src].needs_grad) ng = true;
+        m.tensors[nd.out_t].needs_grad = ng;
+    }
+    return PACK_OK;
+}
+
+// ---- plan building ---------------------------------------------------------------------------------
+struct DescBuilder {
+    std::vector<char> bytes;
+    size_t add(const void* p, size_t n) {
+        const size_t off = align_up(bytes.size(), 64);
+        bytes.resize(off + n);
+        if (n) std::memcpy(bytes.data() + off, p, n);
+        return off;
+    }
+};
+
+struct TileOrder { int prob, tm, tn, ks; };
+
+// Places logical tile t on the workgroup index that the hardware's round-robin distribution of
+// workgroups over the 8 XCDs sends to XCD t / (n/8): neighbours in the logical order (which share
+// an operand tile) then share one XCD's L2.
+std::vector<TileRef> xcd_order(const std::vector<TileOrder>& logical) {
+    const size_t n = align_up(std::max<size_t>(logical.size(), 1), 8);
+    const size_t per = n / 8;
+    std::vector<TileRef> out(n, TileRef{-1, 0, 0, 0});
+    for (size_t t = 0; t < logical.size(); ++t) {
+        const size_t xcd = t / per, slot = t % per;
+        out[slot * 8 + xcd] = TileRef{logical[t].prob, logical[t].tm, logical[t].tn, logical[t].ks};
+    }
+    return out;
+}
+
+void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<GemmProb>& probs) {
+    if (probs.empty()) return;
+    std::vector<TileOrder> logical;
+    for (size_t i = 0; i < probs.size(); ++i) {
+        const GemmProb& g = probs[i];
+        const int tms = (g.R + GEMM_BM - 1) / GEMM_BM, tns = (g.Q + GEMM_BN - 1) / GEMM_BN;
+        const int S = (g.Kd + g.ksplit - 1) / g.ksplit;
+        for (int ks = 0; ks < std::max(S, 1); ++ks) {
+            if (mode == CONV_FWD || mode == CONV_DX) {
+                for (int tm = 0; tm < tms; ++tm)
+                    for (int tn = 0; tn < tns; ++tn) logical.push_back({(int)i, tm, tn, ks});
+            } else {
+                for (int tn = 0; tn < tns; ++tn)
+                    for (int tm = 0; tm < tms; ++tm) logical.push_back({(int)i, tm, tn, ks});
+            }
+        }
+    }
+    const std::vector<TileRef> tiles = xcd_order(logical);
+    Launch L;
+    L.kind = L_GEMM;
+    L.mode = mode;
+    L.desc_off = db.add(probs.data(), probs.size() * sizeof(GemmProb));
+    L.map_off = db.add(tiles.data(), tiles.size() * sizeof(TileRef));
+    L.n = (int)tiles.size();
+    p->plan.push_back(L);
+}
+
+template <typename P>
+void add_mapped_launch(pack_ctx* p, DescBuilder& db, int kind, const std::vector<P>& probs,
+                       const std::vector<int>& blocks_per_prob) {
+    if (probs.empty()) return;
+    std::vector<int2> map;
+    for (size_t i = 0; i < probs.size(); ++i)
+        for (int b = 0; b < blocks_per_prob[i]; ++b) map.push_back(int2{(int)i, b});
+    if (map.empty()) return;
+    Launch L;
+    L.kind = kind;
+    L.desc_off = db.add(probs.data(), probs.size() * sizeof(P));
+    L.map_off = db.add(map.data(), map.size() * sizeof(int2));
+    L.n = (int)map.size();
+    p->plan.push_back(L);
+}
+
+inline int elem_vec(bool bf16) { return bf16 ? 8 : 4; }
+
+// Builds the whole launch sequence.  Workspace offsets are relative; `ws_need` returns the size.
+void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
+    const bool bf = p->bf16;
+    const int V = elem_vec(bf);
+    const size_t esz = bf ? 2 : 4;
+    size_t max_nodes = 0;
+    for (const ModelInfo& m : p->models) max_nodes = std::max(max_nodes, m.nodes.size());
+    ws_need = 0;
+    char* const ws = p->workspace;   // null during the sizing pass; offsets are added to it later
+
+    auto weight_ptr = [&](const NodeInfo& nd) -> const void* {
+        return bf ? (const void*)((const char*)p->shadow + nd.w_off * 2) : (const void*)(p->master + nd.w_off);
+    };
+
+    // ---------------- forward ----------------
+    for (size_t s = 0; s < max_nodes; ++s) {
+        std::vector<GemmProb> lin, conv;
+        std::vector<GapProb> gaps;
+        std::vector<int> gap_blocks;
+        for (ModelInfo& m : p->models) {
+            if (s >= m.nodes.size()) continue;
+            const NodeInfo& nd = m.nodes[s];
+            const TensorInfo& ti = m.tensors[nd.in_t];
+            const TensorInfo& to = m.tensors[nd.out_t];
+            if (nd.kind == NODE_GAP) {
+                GapProb g{};
+                g.in = ti.act; g.out = to.act; g.n = ti.n; g.hw = ti.h * ti.w; g.c = ti.c;
+                gaps.push_back(g);
+                gap_blocks.push_back((ti.n * ti.c + 255) / 256);
+                continue;
+            }
+            GemmProb g{};
+            g.A = ti.is_input ? nullptr : ti.act;
+            g.B = weight_ptr(nd);
+            g.C = to.act;
+            g.bias = p->master + nd.b_off;
+            g.flags = (nd.relu ? F_RELU : 0) | (to.f32 ? F_OUT_F32 : 0) | (ti.is_input ? F_A_INPUT : 0);
+            if (nd.kind == NODE_LINEAR) {
+                g.R = ti.n; g.Q = nd.out; g.Kd = nd.fan_in;
+                g.lda = nd.fan_in; g.ldb = nd.fan_in; g.ldc = nd.out;
+                if (g.Kd % V == 0) g.flags |= F_VEC_A | F_VEC_B;
+                g.ksplit = g.Kd;
+                lin.push_back(g);
+            } else {
+                g.H = ti.h; g.W = ti.w; g.Cin = ti.c; g.Ho = to.h; g.Wo = to.w; g.Cout = to.c; g.stride = nd.stride;
+                g.R = to.n * to.h * to.w; g.Q = to.c; g.Kd = 9 * ti.c;
+                g.lda = ti.c; g.ldb = 9 * ti.c; g.ldc = to.c;
+                if (ti.c % V == 0) g.flags |= F_VEC_A | F_VEC_B;
+                if (nd.res_src >= 0) {
+                    const TensorInfo& rs = m.tensors[nd.res_src];
+                    g.aux = rs.is_input ? nullptr : rs.act;
+                    if (rs.is_input) g.flags |= F_AUX_INPUT;
+                    g.flags |= nd.res_down ? F_RES_DOWN : F_RES_ID;
+                    g.resH = rs.h; g.resW = rs.w; g.resC = rs.c;
+                }
+                g.ksplit = g.Kd;
+                conv.push_back(g);
+            }
+        }
+        add_gemm_launch(p, db, LIN_FWD, lin);
+        add_gemm_launch(p, db, CONV_FWD, conv);
+        add_mapped_launch(p, db, L_GAP_FWD, gaps, gap_blocks);
+    }
+
+    // ---------------- loss ----------------
+    {
+        std::vector<CeProb> ce;
+        for (ModelInfo& m : p->models) {
+            const TensorInfo& lg = m.tensors[m.nodes.back().out_t];
+            CeProb c{};
+            c.logits = (const float*)lg.act; c.dlogits = lg.dz; c.pred = m.pred; c.loss = m.loss;
+            c.rows = m.batch; c.C = m.C; c.ld = m.C; c.ldd = m.C;
+            ce.push_back(c);
+        }
+        Launch L;
+        L.kind = L_CE;
+        L.desc_off = db.add(ce.data(), ce.size() * sizeof(CeProb));
+        L.n = (int)ce.size();
+        p->plan.push_back(L);
+    }
+
+    // ---------------- backward ----------------
+    for (ModelInfo& m : p->models)
+        for (TensorInfo& t : m.tensors) t.grad_written = false;
+    for (size_t s = max_nodes; s-- > 0;) {
+        std::vector<ColsumProb> cs;
+        std::vector<int> cs_blocks;
+        std::vector<ReduceProb> cs_red, dw_red;
+        std::vector<int> cs_red_blocks, dw_red_blocks;
+        std::vector<GemmProb> lin_dw, conv_dw, lin_dx, conv_dx;
+        std::vector<GapProb> gaps;
+        std::vector<int> gap_blocks;
+        std::vector<ShortcutProb> scs;
+        std::vector<int> sc_blocks;
+        size_t ws_off = 0;
+        for (ModelInfo& m : p->models) {
+            if (s >= m.nodes.size()) continue;
+            const NodeInfo& nd = m.nodes[s];
+            TensorInfo& ti = m.tensors[nd.in_t];
+            const TensorInfo& to = m.tensors[nd.out_t];
+            if (nd.kind == NODE_GAP) {
+                if (!ti.needs_grad) continue;
+                GapProb g{};
+                g.in = ti.act; g.dz_out = to.dz; g.dz_in = ti.dz; g.n = ti.n; g.hw = ti.h * ti.w; g.c = ti.c;
+                g.mask = ti.relu_out; g.accum = ti.grad_written;
+                ti.grad_written = true;
+                gaps.push_back(g);
+                gap_blocks.push_back((int)((ti.elems() + ELEMWISE_PER_BLOCK - 1) / ELEMWISE_PER_BLOCK));
+                continue;
+            }
+            const int rows = (nd.kind == NODE_LINEAR) ? to.n : to.n * to.h * to.w;
+            // bias gradient
+            {
+                ColsumProb c{};
+                c.dz = to.dz; c.M = rows; c.N = nd.out; c.ld = nd.out;
+                c.rows_per_chunk = 2048;
+                c.nchunk = (rows + c.rows_per_chunk - 1) / c.rows_per_chunk;
+                float* dst = p->grad + nd.b_off;
+                if (c.nchunk > 1) {
+                    c.out = (float*)(ws + ws_off);
+                    ReduceProb r{};
+                    r.in = c.out; r.out = dst; r.stride = nd.out; r.n = nd.out; r.S = c.nchunk;
+                    cs_red.push_back(r);
+                    cs_red_blocks.push_back((nd.out + 1023) / 1024);
+                    ws_off += align_up((size_t)c.nchunk * nd.out * 4, 256);
+                } else {
+                    c.out = dst;
+                }
+                cs.push_back(c);
+                cs_blocks.push_back(c.nchunk * ((nd.out + COLSUM_COLS - 1) / COLSUM_COLS));
+            }
+            // weight gradient
+            {
+                GemmProb g{};
+                g.A = to.dz;
+                g.B = ti.is_input ? nullptr : ti.act;
+                g.flags = ti.is_input ? F_B_INPUT : 0;
+                g.R = nd.out; g.Q = nd.fan_in; g.Kd = rows;
+                g.lda = nd.out; g.ldc = nd.fan_in;
+                if (nd.out % V == 0) g.flags |= F_VEC_A;
+                float* dst = p->grad + nd.w_off;
+                if (nd.kind == NODE_LINEAR) {
+                    g.ldb = nd.fan_in;
+                    if (nd.fan_in % V == 0) g.flags |= F_VEC_B;
+                    g.ksplit = std::max(g.Kd, 1);
+                    g.C = dst;
+                    lin_dw.push_back(g);
+                } else {
+                    g.H = ti.h; g.W = ti.w; g.Cin = ti.c; g.Ho = to.h; g.Wo = to.w; g.Cout = to.c; g.stride = nd.stride;
+                    g.ldb = ti.c;
+                    if (ti.c % V == 0) g.flags |= F_VEC_B;
+                    int S = std::min(256, std::max(1, (rows + 2047) / 2048));
+                    g.ksplit = (int)align_up((size_t)(rows + S - 1) / S, 64);
+                    S = (rows + g.ksplit - 1) / g.ksplit;
+                    if (S > 1) {
+                        g.C = ws + ws_off;
+                        g.split_stride = (long long)nd.w_elems;
+                        ReduceProb r{};
+                        r.in = (const float*)g.C; r.out = dst; r.stride = (long long)nd.w_elems; r.n = (int)nd.w_elems; r.S = S;
+                        dw_red.push_back(r);
+                        dw_red_blocks.push_back((int)((nd.w_elems + 1023) / 1024));
+                        ws_off += align_up((size_t)S * nd.w_elems * 4, 256);
+                    } else {
+                        g.C = dst;
+                    }
+                    conv_dw.push_back(g);
+                }
+            }
+            // input gradient
+            if (ti.needs_grad) {
+                GemmProb g{};
+                g.A = to.dz;
+                g.B = weight_ptr(nd);
+                g.C = ti.dz;
+                g.aux = ti.act;
+                g.flags = (ti.relu_out ? F_MASK : 0) | (ti.grad_written ? F_ACCUM : 0);
+                ti.grad_written = true;
+                if (nd.kind == NODE_LINEAR) {
+                    g.R = ti.n; g.Q = nd.fan_in; g.Kd = nd.out;
+                    g.lda = nd.out; g.ldb = nd.fan_in; g.ldc = nd.fan_in;
+                    if (nd.out % V == 0) g.flags |= F_VEC_A;
+                    if (nd.fan_in % V == 0) g.flags |= F_VEC_B;
+                    g.ksplit = g.Kd;
+                    lin_dx.push_back(g);
+                } else {
+                    g.H = ti.h; g.W = ti.w; g.Cin = ti.c; g.Ho = to.h; g.Wo = to.w; g.Cout = to.c; g.stride = nd.stride;
+                    g.R = ti.n * ti.h * ti.w; g.Q = ti.c; g.Kd = 9 * to.c;
+                    g.lda = to.c; g.ldb = ti.c; g.ldc = ti.c;
+                    if (to.c % V == 0) g.flags |= F_VEC_A;
+                    if (ti.c % V == 0) g.flags |= F_VEC_B;
+                    g.ksplit = g.Kd;
+                    conv_dx.push_back(g);
+                }
+            }
+            // gradient through the shortcut into the block input
+            if (nd.res_src >= 0 && m.tensors[nd.res_src].needs_grad) {
+                TensorInfo& rs = m.tensors[nd.res_src];
+                ShortcutProb sp{};
+                sp.dz_out = to.dz; sp.src = rs.act; sp.dz_src = rs.dz;
+                sp.n = rs.n; sp.H = rs.h; sp.W = rs.w; sp.C = rs.c; sp.Ho = to.h; sp.Wo = to.w; sp.Co = to.c;
+                sp.down = nd.res_down; sp.mask = rs.relu_out; sp.accum = rs.grad_written;
+                rs.grad_written = true;
+                scs.push_back(sp);
+                sc_blocks.push_back((int)((rs.elems() + ELEMWISE_PER_BLOCK - 1) / ELEMWISE_PER_BLOCK));
+            }
+        }
+        ws_need = std::max(ws_need, ws_off);
+        add_mapped_launch(p, db, L_COLSUM, cs, cs_blocks);
+        add_mapped_launch(p, db, L_REDUCE, cs_red, cs_red_blocks);
+        add_gemm_launch(p, db, LIN_DW, lin_dw);
+        add_gemm_launch(p, db, CONV_DW, conv_dw);
+        add_mapped_launch(p, db, L_REDUCE, dw_red, dw_red_blocks);
+        add_gemm_launch(p, db, LIN_DX, lin_dx);
+        add_gemm_launch(p, db, CONV_DX, conv_dx);
+        add_mapped_launch(p, db, L_SHORTCUT, scs, sc_blocks);
+        add_mapped_launch(p, db, L_GAP_BWD, gaps, gap_blocks);
+    }
+    (void)esz;
+
+    // ---------------- update ----------------
+    Launch L;
+    L.kind = L_SGD;
+    L.n = 1;
+    p->plan.push_back(L);
+}
+
+void release(pack_ctx* p) {
+    if (!p) return;
+    if (p->master) (void)hipFree(p->master);
+    if (p->grad) (void)hipFree(p->grad);
+    if (p->shadow) (void)hipFree(p->shadow);
+    if (p->seg_end) (void)hipFree(p->seg_end);
+    if (p->slab) (void)hipFree(p->slab);
+    if (p->workspace) (void)hipFree(p->workspace);
+    if (p->desc) (void)hipFree(p->desc);
+    delete p;
+}
+
+pack_status dev_alloc(void** ptr, size_t bytes, pack_ctx* p) {
+    bytes = align_up(std::max<size_t>(bytes, 256), 256);
+    hipError_t e = hipMalloc(ptr, bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        *ptr = nullptr;
+        return fail(e == hipErrorOutOfMemory ? PACK_ENOMEM : PACK_EDEVICE,
+                    std::string("hipMalloc of ") + std::to_string(bytes) + " bytes: " + hipGetErrorString(e));
+    }
+    p->device_bytes += bytes;
+    return PACK_OK;
+}
+
+pack_status upload_weights(pack_ctx* p, int k, const float* blob) {
+    ModelInfo& m = p->models[k];
+    std::vector<float> arena;
+    blob_to_arena(m, blob, arena);
+    HIP_TRY(hipStreamSynchronize(p->stream), PACK_EDEVICE);
+    HIP_TRY(hipMemcpy(p->master + m.arena_begin, arena.data(), arena.size() * sizeof(float), hipMemcpyHostToDevice), PACK_EDEVICE);
+    if (p->bf16) {
+        HIP_TRY(launch_cast_bf16(p->master + m.arena_begin, (char*)p->shadow + m.arena_begin * 2,
+                                 (long long)arena.size(), p->stream), PACK_EDEVICE);
+        HIP_TRY(hipStreamSynchronize(p->stream), PACK_EDEVICE);
+    }
+    return PACK_OK;
+}
+
+pack_status download(pack_ctx* p, int k, const float* dev_arena, float* host_dst, size_t n_floats) {
+    if (!p || !host_dst) return fail(PACK_EINVAL, "null argument");
+    if (k < 0 || k >= p->K) return fail(PACK_EINVAL, "member index out of range");
+    ModelInfo& m = p->models[k];
+    if (n_floats != m.n_params) return fail(PACK_EINVAL, "n_floats does not match pack_num_params");
+    std::vector<float> arena(m.arena_end - m.arena_begin);
+    HIP_TRY(hipStreamSynchronize(p->stream), PACK_EDEVICE);
+    HIP_TRY(hipMemcpy(arena.data(), dev_arena + m.arena_begin, arena.size() * sizeof(float), hipMemcpyDeviceToHost), PACK_EDEVICE);
+    arena_to_blob(m, arena, host_dst);
+    return PACK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* pack_last_error(void) { return g_err.c_str(); }
+
+pack_status pack_create(const pack_input_spec* input, const pack_model_spec* models, int32_t K,
+                        uint64_t seed, void* hip_stream, pack_t** out) {
+    if (out) *out = nullptr;
+    if (!input || !models || !out) return fail(PACK_EINVAL, "null argument");
+    if (K < 1 || K > PACK_MAX_MODELS) return fail(PACK_EINVAL, "K must be in [1, PACK_MAX_MODELS]");
+    if (input->B < 1 || input->in_h < 1 || input->in_w < 1 || input->in_c < 1) return fail(PACK_EINVAL, "bad input shape");
+    if (input->dtype != PACK_F32 && input->dtype != PACK_BF16) return fail(PACK_EINVAL, "unknown dtype");
+
+    pack_ctx* p = new (std::nothrow) pack_ctx();
+    if (!p) return fail(PACK_ENOMEM, "host allocation failed");
+    p->stream = (hipStream_t)hip_stream;
+    p->bf16 = (input->dtype == PACK_BF16);
+    p->K = K;
+    p->in = *input;
+    p->models.resize(K);
+    for (int k = 0; k < K; ++k) {
+        pack_status s = parse_model(*input, models[k], k, p->models[k]);
+        if (s != PACK_OK) { release(p); return s; }
+    }
+    if (hipGetDevice(&p->device) != hipSuccess) {
+        (void)hipGetLastError();
+        release(p);
+        return fail(PACK_EDEVICE, "no HIP device is current");
+    }
+
+    // parameter arena: members back to back, every tensor starting on a 64-element boundary
+    size_t off = 0;
+    for (ModelInfo& m : p->models) {
+        m.arena_begin = off;
+        for (NodeInfo& nd : m.nodes) {
+            if (nd.kind == NODE_GAP) continue;
+            nd.w_off = off;
+            off = align_up(off + nd.w_elems, 64);
+            nd.b_off = off;
+            off = align_up(off + (size_t)nd.out, 64);
+        }
+        m.arena_end = off;
+    }
+    p->arena_elems = off;
+    const size_t esz = p->bf16 ? 2 : 4;
+
+    pack_status s;
+#define TRY_ALLOC(ptr, bytes)                                         \
+    if ((s = dev_alloc((void**)&(ptr), (bytes), p)) != PACK_OK) {     \
+        release(p);                                                   \
+        return s;                                                     \
+    }
+    TRY_ALLOC(p->master, p->arena_elems * 4);
+    TRY_ALLOC(p->grad, p->arena_elems * 4);
+    if (p->bf16) TRY_ALLOC(p->shadow, p->arena_elems * 2);
+    TRY_ALLOC(p->seg_end, (size_t)K * sizeof(long long));
+
+    // one slab for activations, their gradients, predictions, losses and the label-error flag
+    size_t slab = 0;
+    auto reserve = [&](size_t bytes) { const size_t o = slab; slab += align_up(std::max<size_t>(bytes, 16), 256); return o; };
+    std::vector<std::pair<void**, size_t>> fix;
+    for (ModelInfo& m : p->models) {
+        for (TensorInfo& t : m.tensors) {
+            if (t.is_input) continue;
+            fix.push_back({&t.act, reserve(t.elems() * (t.f32 ? 4 : esz))});
+            fix.push_back({&t.dz, reserve(t.elems() * esz)});
+        }
+        fix.push_back({(void**)&m.pred, reserve((size_t)m.batch * 4)});
+    }
+    const size_t loss_off = reserve((size_t)K * 4);
+    const size_t err_off = reserve(4);
+    TRY_ALLOC(p->slab, slab);
+    p->slab_bytes = slab;
+    for (auto& f : fix) *f.first = p->slab + f.second;
+    p->loss_all = (float*)(p->slab + loss_off);
+    p->err_flag = (int*)(p->slab + err_off);
+    for (int k = 0; k < K; ++k) p->models[k].loss = p->loss_all + k;
+
+    // size the workspace with a dry run of the planner, then build the real plan
+    {
+        DescBuilder dry;
+        size_t need = 0;
+        build_plan(p, dry, need);
+        p->plan.clear();
+        p->workspace_bytes = need;
+        if (need) TRY_ALLOC(p->workspace, need);
+    }
+    DescBuilder db;
+    size_t need = 0;
+    build_plan(p, db, need);
+    TRY_ALLOC(p->desc, db.bytes.size());
+    p->desc_bytes = db.bytes.size();
+#undef TRY_ALLOC
+
+    hipError_t e = hipMemcpy(p->desc, db.bytes.data(), db.bytes.size(), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemset(p->slab, 0, p->slab_bytes);
+    if (e == hipSuccess) e = hipMemset(p->grad, 0, p->arena_elems * 4);
+    if (e == hipSuccess) e = hipMemset(p->master, 0, p->arena_elems * 4);
+    if (e == hipSuccess && p->shadow) e = hipMemset(p->shadow, 0, p->arena_elems * 2);
+    std::vector<long long> ends(K);
+    for (int k = 0; k < K; ++k) ends[k] = (long long)p->models[k].arena_end;
+    if (e == hipSuccess) e = hipMemcpy(p->seg_end, ends.data(), (size_t)K * sizeof(long long), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        release(p);
+        return fail(PACK_EDEVICE, std::string("initial upload: ") + hipGetErrorString(e));
+    }
+
+    // seeded initial weights
+    for (int k = 0; k < K; ++k) {
+        ModelInfo& m = p->models[k];
+        std::vector<float> blob(m.n_params);
+        int tensor = 0;
+        for (const NodeInfo& nd : m.nodes) {
+            if (nd.kind == NODE_GAP) continue;
+            const float bw = std::sqrt(6.0f / (float)nd.fan_in), bb = 1.0f / std::sqrt((float)nd.fan_in);
+            for (size_t i = 0; i < nd.w_elems; ++i) blob[nd.blob_off + i] = uniform_pm(seed, k, tensor, i, bw);
+            for (int i = 0; i < nd.out; ++i) blob[nd.blob_off + nd.w_elems + i] = uniform_pm(seed, k, tensor + 1, i, bb);
+            tensor += 2;
+        }
+        if (p->bf16) for (float& v : blob) v = round_to_bf16(v);
+        s = upload_weights(p, k, blob.data());
+        if (s != PACK_OK) { release(p); return s; }
+    }
+    *out = p;
+    return PACK_OK;
+}
+
+pack_status pack_write_weights(pack_t* p, int32_t k, const float* host_src, size_t n_floats) {
+    if (!p || !host_src) return fail(PACK_EINVAL, "null argument");
+    if (k < 0 || k >= p->K) return fail(PACK_EINVAL, "member index out of range");
+    if (n_floats != p->models[k].n_params) return fail(PACK_EINVAL, "n_floats does not match pack_num_params");
+    return upload_weights(p, k, host_src);
+}
+
+pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, const float* lr_host) {
+    if (!p || !x_dev || !labels_dev || !lr_host) return fail(PACK_EINVAL, "null argument");
+    if (((uintptr_t)x_dev & 15) || ((uintptr_t)labels_dev & 3)) return fail(PACK_EINVAL, "x_dev must be 16-byte aligned");
+    LrTable lr;
+    for (int k = 0; k < 256; ++k) lr.lr[k] = (k < p->K) ? lr_host[k] : 0.f;
+    const bool bf = p->bf16;
+    for (const Launch& L : p->plan) {
+        hipError_t e = hipSuccess;
+        const char* d = p->desc + L.desc_off;
+        const char* mp = p->desc + L.map_off;
+        switch (L.kind) {
+            case L_GEMM:
+                e = launch_gemm(L.mode, bf, (const GemmProb*)d, (const TileRef*)mp, L.n, x_dev, p->stream);
+                break;
+            case L_COLSUM: e = launch_colsum(bf, (const ColsumProb*)d, (const int2*)mp, L.n, p->stream); break;
+            case L_REDUCE: e = launch_reduce((const ReduceProb*)d, (const int2*)mp, L.n, p->stream); break;
+            case L_CE: e = launch_ce(bf, (const CeProb*)d, L.n, labels_dev, p->err_flag, p->stream); break;
+            case L_GAP_FWD: e = launch_gap(bf, false, (const GapProb*)d, (const int2*)mp, L.n, p->stream); break;
+            case L_GAP_BWD: e = launch_gap(bf, true, (const GapProb*)d, (const int2*)mp, L.n, p->stream); break;
+            case L_SHORTCUT: e = launch_shortcut_bwd(bf, (const ShortcutProb*)d, (const int2*)mp, L.n, p->stream); break;
+            case L_SGD:
+                e = launch_sgd(p->master, p->grad, p->shadow, (long long)p->arena_elems, p->seg_end, p->K, lr, p->stream);
+                break;
+        }
+        if (e != hipSuccess) return fail(PACK_EDEVICE, std::string("kernel launch: ") + hipGetErrorString(e));
+    }
+    return PACK_OK;
+}
+
+pack_status pack_read_loss(pack_t* p, float* host_dst) {
+    if (!p || !host_dst) return fail(PACK_EINVAL, "null argument");
+    HIP_TRY(hipStreamSynchronize(p->stream), PACK_EDEVICE);
+    HIP_TRY(hipMemcpy(host_dst, p->loss_all, (size_t)p->K * 4, hipMemcpyDeviceToHost), PACK_EDEVICE);
+    int flag = 0;
+    HIP_TRY(hipMemcpy(&flag, p->err_flag, 4, hipMemcpyDeviceToHost), PACK_EDEVICE);
+    if (flag) {
+        HIP_TRY(hipMemset(p->err_flag, 0, 4), PACK_EDEVICE);
+        return fail(PACK_ELABEL, "a label outside [0, C_k) was seen since the last pack_read_loss");
+    }
+    return PACK_OK;
+}
+
+pack_status pack_read_weights(pack_t* p, int32_t k, float* host_dst, size_t n_floats) {
+    return download(p, k, p ? p->master : nullptr, host_dst, n_floats);
+}
+
+pack_status pack_read_grads(pack_t* p, int32_t k, float* host_dst, size_t n_floats) {
+    return download(p, k, p ? p->grad : nullptr, host_dst, n_floats);
+}
+
+pack_status pack_read_pred(pack_t* p, int32_t k, int32_t* host_dst) {
+    if (!p || !host_dst) return fail(PACK_EINVAL, "null argument");
+    if (k < 0 || k >= p->K) return fail(PACK_EINVAL, "member index out of range");
+    HIP_TRY(hipStreamSynchronize(p->stream), PACK_EDEVICE);
+    HIP_TRY(hipMemcpy(host_dst, p->models[k].pred, (size_t)p->models[k].batch * 4, hipMemcpyDeviceToHost), PACK_EDEVICE);
+    return PACK_OK;
+}
+
+pack_status pack_read_logits(pack_t* p, int32_t k, float* host_dst, size_t n_floats) {
+    if (!p || !host_dst) return fail(PACK_EINVAL, "null argument");
+    if (k < 0 || k >= p->K) return fail(PACK_EINVAL, "member index out of range");
+    const ModelInfo& m = p->models[k];
+    if (n_floats != (size_t)m.batch * m.C) return fail(PACK_EINVAL, "n_floats must be b_k * C_k");
+    HIP_TRY(hipStreamSynchronize(p->stream), PACK_EDEVICE);
+    HIP_TRY(hipMemcpy(host_dst, m.tensors[m.nodes.back().out_t].act, n_floats * 4, hipMemcpyDeviceToHost), PACK_EDEVICE);
+    return PACK_OK;
+}
+
+size_t pack_num_params(const pack_t* p, int32_t k) {
+    if (!p || k < 0 || k >= p->K) return 0;
+    return p->models[k].n_params;
+}
+
+int32_t pack_num_classes(const pack_t* p, int32_t k) {
+    if (!p || k < 0 || k >= p->K) return 0;
+    return p->models[k].C;
+}
+
+int32_t pack_num_launches(const pack_t* p) { return p ? (int32_t)p->plan.size() : 0; }
+
+size_t pack_device_bytes(const pack_t* p) { return p ? p->device_bytes : 0; }
+
+void pack_destroy(pack_t* p) {
+    if (!p) return;
+    (void)hipStreamSynchronize(p->stream);
+    release(p);
+}
+
+}  // extern "C"

@@ -1,0 +1,119 @@
+// Internal interface between the host planner (pack_api.cpp) and the gfx950 kernels
+// (pack_kernels.hip).  Nothing here is part of the public ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace packk {
+
+// Every matrix product of the step is one instance of  OUT[r, q] = sum_k A(r, k) * B(q, k),
+// r in [0,R), q in [0,Q), k in [0,Kd), with the two operands fetched by a mode-specific
+// address rule.  MODE selects the rules and the epilogue.
+enum GemmMode : int {
+    LIN_FWD = 0,   // Z[m,n]   = sum_k H[m,k] W[n,k]                 (+bias, relu)
+    LIN_DX = 1,    // dH[m,k'] = sum_n dZ[m,n] W[n,k']               (mask, accumulate)
+    LIN_DW = 2,    // dW[o,i]  = sum_b dZ[b,o] H[b,i]
+    CONV_FWD = 3,  // Z[(b,i,j),o] = sum_(tap,c) In[b,s*i+u-1,s*j+v-1,c] W[o,tap,c]   (+bias, residual, relu)
+    CONV_DX = 4,   // dIn[(b,y,x),c] = sum_(tap,o) dZ[b,(y+1-u)/s,(x+1-v)/s,o] W[o,tap,c]  (mask, accumulate)
+    CONV_DW = 5    // dW[o,(tap,c)] = sum_(b,i,j) dZ[(b,i,j),o] In[b,s*i+u-1,s*j+v-1,c]   (split over the sum)
+};
+
+enum GemmFlags : int {
+    F_RELU = 1,        // forward: max(v, 0)
+    F_OUT_F32 = 2,     // forward: store float regardless of the pack dtype (logits)
+    F_ACCUM = 4,       // dX: add to what the output buffer already holds
+    F_MASK = 8,        // dX: zero where aux <= 0 (aux = the stored activation of the output tensor)
+    F_RES_ID = 16,     // forward: add aux[row, col] before the ReLU (identity shortcut)
+    F_RES_DOWN = 32,   // forward: add aux[b, 2i, 2j, col] for col < resC (subsampling shortcut)
+    F_VEC_A = 64,      // operand A may be fetched as aligned 16-byte vectors
+    F_VEC_B = 128,     // operand B likewise
+    F_A_INPUT = 256,   // operand A is the shared input batch handed to this step
+    F_B_INPUT = 512,   // operand B is the shared input batch
+    F_AUX_INPUT = 1024 // the shortcut source is the shared input batch
+};
+
+struct GemmProb {
+    const void* A;
+    const void* B;
+    void* C;
+    const float* bias;
+    const void* aux;
+    int R, Q, Kd;
+    int lda, ldb, ldc;
+    int H, W, Cin, Ho, Wo, Cout, stride;   // geometry of the forward convolution (conv modes)
+    int resH, resW, resC;                  // geometry of the shortcut source (F_RES_DOWN)
+    int flags;
+    int ksplit;                            // reduction indices per split (>= Kd when not split)
+    long long split_stride;                // elements between the partial outputs of two splits
+};
+
+struct TileRef {      // one workgroup's job; prob < 0 marks a filler slot
+    int prob;
+    int tm, tn, ks;
+};
+
+struct ColsumProb {   // db[n] = sum_m dz[m, n]
+    const void* dz;
+    float* out;       // final result (or partial sums when nchunk > 1: out[chunk * N + n])
+    int M, N, ld;
+    int rows_per_chunk, nchunk;
+};
+
+struct ReduceProb {   // out[e] = sum_{s < S} in[s * stride + e], fixed order
+    const float* in;
+    float* out;
+    long long stride;
+    int n, S;
+};
+
+struct CeProb {       // softmax cross-entropy of one member
+    const float* logits;   // [rows, ld]
+    void* dlogits;         // [rows, ldd] pack dtype
+    int* pred;             // [rows]
+    float* loss;           // scalar
+    int rows, C, ld, ldd;
+};
+
+struct GapProb {      // global average pool: in [n, hw, c] -> out [n, c]
+    const void* in;
+    void* out;
+    const void* dz_out;    // backward: gradient wrt out
+    void* dz_in;           // backward: gradient wrt in
+    int n, hw, c;
+    int mask;              // backward: zero where in <= 0
+    int accum;
+};
+
+struct ShortcutProb { // backward of the residual shortcut into the source tensor's gradient
+    const void* dz_out;    // [n, Ho, Wo, Co]
+    const void* src;       // stored activation of the source [n, H, W, C] (mask)
+    void* dz_src;
+    int n, H, W, C, Ho, Wo, Co;
+    int down;              // 0 identity, 1 subsample
+    int mask;
+    int accum;
+};
+
+struct LrTable { float lr[256]; };
+
+// launch wrappers; all enqueue on `st` and return the launch status -----------------------------
+hipError_t launch_gemm(int mode, bool bf16, const GemmProb* probs_dev, const TileRef* tiles_dev,
+                       int n_tiles, const void* x_dev, hipStream_t st);
+hipError_t launch_colsum(bool bf16, const ColsumProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);
+hipError_t launch_reduce(const ReduceProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);
+hipError_t launch_ce(bool bf16, const CeProb* probs_dev, int K, const int32_t* labels, int* err_flag, hipStream_t st);
+hipError_t launch_gap(bool bf16, bool backward, const GapProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);
+hipError_t launch_shortcut_bwd(bool bf16, const ShortcutProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);
+hipError_t launch_sgd(float* master, const float* grad, void* shadow_bf16, long long n,
+                      const long long* seg_end_dev, int K, const LrTable& lr, hipStream_t st);
+hipError_t launch_cast_bf16(const float* src, void* dst_bf16, long long n, hipStream_t st);
+hipError_t launch_fill_zero(void* dst, long long bytes, hipStream_t st);
+
+// tile geometry the planner needs
+constexpr int GEMM_BM = 128;
+constexpr int GEMM_BN = 128;
+constexpr int COLSUM_COLS = 64;
+constexpr int ELEMWISE_PER_BLOCK = 2048;   // elements one block of the elementwise kernels covers
+constexpr int SGD_PER_BLOCK = 4096;        // parameters one block of the update kernel covers
+
+}  // namespace packk

@@ -1,0 +1,246 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Tolerances: 1e-4 (fp32 packs) and 2e-2 (bf16 packs) maximum relative error; labels,
+argmax and everything integer must agree exactly."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+F32_TOL, BF16_TOL = pu.TOL[wl.F32], pu.TOL[wl.BF16]
+
+
+def _check_f32(w, steps=None):
+    gpu = pu.run_gpu(w, steps)
+    ref = pu.run_oracle(w, steps)
+    worst = pu.compare(w, gpu, ref, F32_TOL)
+    n, skipped = pu.compare_pred(w, gpu["pred_first"], gpu["logits"], ref["pred"][0], F32_TOL)
+    print(f"\n{w.name}: worst {worst}; argmax rows compared {n}, unresolvable {skipped}; launches {gpu['launches']}")
+    return gpu, ref
+
+
+def _check_bf16(w, steps=None):
+    """bf16 packs (bf16 inputs/weights, fp32 accumulate, fp32 master).  Three references:
+    - step 1 against the float64 oracle (the weights are bf16-representable, so the only
+      difference is the rounding of stored activations): loss within 2e-2;
+    - every step against the oracle that rounds where the device rounds: loss, step-1
+      gradients, displacement and weights within 2e-2 (without the matching rounding points a
+      ReLU unit within bf16 rounding of zero flips and moves a gradient entry by a whole summand);
+    - every step against the oracle that only rounds the per-step weight copy (the precision
+      the configuration itself fixes): loss within 2e-2 for every member whose loss the
+      oracle's own two roundings agree on to a quarter of that; the others are reported as
+      ill-conditioned (large learning rate on un-normalised inputs), not passed silently."""
+    steps = w.steps if steps is None else steps
+    gpu = pu.run_gpu(w, steps)
+    exact = pu.run_oracle(w, 1, mode="exact")
+    weights = pu.run_oracle(w, steps, mode="weights")
+    rounded = pu.run_oracle(w, steps, mode="rounded")
+    first = {"loss": gpu["loss"][:1], "blobs": gpu["blobs"], "grads": None}
+    w0 = pu.compare(w, first, exact, BF16_TOL, what=("loss",), label="exact step 1: ")
+    w2 = pu.compare(w, gpu, rounded, BF16_TOL, what=("loss", "grads", "disp", "weights"), label="rounded: ")
+    ill = []
+    worst = 0.0
+    for k in range(w.K):
+        sens = np.abs(weights["loss"][:, k] - rounded["loss"][:, k]) / np.abs(weights["loss"][:, k])
+        bad = np.maximum.accumulate(sens) > BF16_TOL / 4
+        err = np.abs(gpu["loss"][:, k] - weights["loss"][:, k]) / np.abs(weights["loss"][:, k])
+        if bad.any():
+            ill.append((k, float(sens.max()), float(err.max())))
+        if (~bad).any():
+            worst = max(worst, float(err[~bad].max()))
+            assert err[~bad].max() <= BF16_TOL, f"{w.name} member {k}: loss vs weight-rounding oracle {err}"
+    n, skipped = pu.compare_pred(w, gpu["pred_first"], gpu["logits"], rounded["pred"][0], BF16_TOL)
+    print(f"\n{w.name}: step-1 loss vs float64 {w0['loss']:.2e}; vs rounding oracle {w2}; "
+          f"loss vs weight-rounding oracle {worst:.2e}; ill-conditioned members (k, oracle sensitivity, gpu err): {ill}; "
+          f"argmax rows {n}, unresolvable {skipped}; launches {gpu['launches']}")
+    return gpu, weights, rounded
+
+
+# ------------------------------------------------------------------ MLPs, fp32
+def test_c1_two_mlps_fp32_full_size():
+    _check_f32(wl.config1())
+
+
+def test_mlp_fp32_ragged_shapes_and_batch_slices():
+    models = [wl.mlp([50], 7), wl.mlp([33, 130], 7), wl.mlp([129, 5, 64], 7), [("linear", 7)]]
+    w = wl.custom("ragged_f32", 5, wl.F32, 19, (1, 1, 37), models, batch=[19, 7, 1, 13], n_classes=7, steps=3)
+    _check_f32(w)
+
+
+def test_mlp_fp32_spans_several_tiles():
+    models = [wl.mlp([300, 260], 10), wl.mlp([140], 10)]
+    w = wl.custom("tiles_f32", 6, wl.F32, 300, (1, 1, 200), models, batch=[300, 150], n_classes=10, steps=2,
+                  lr=[0.05, 0.02])
+    _check_f32(w)
+
+
+# ------------------------------------------------------------------ MLPs, bf16
+def test_c2_reduced_bf16():
+    _check_bf16(wl.config2(B=64, D=256, hidden=(128, 136), K=3, steps=3))
+
+
+def test_c2_eight_mlps_bf16_full_size():
+    _check_bf16(wl.config2())
+
+
+def test_c4_reduced_heterogeneous_bf16():
+    _check_bf16(wl.config4(K=6, B=32, D=96, width_choices=(8, 16, 40, 64), steps=3))
+
+
+@pytest.mark.parametrize("n_classes", [10, 100])
+def test_c4_heterogeneous_bf16_full_size(n_classes):
+    _check_bf16(wl.config4(n_classes=n_classes))
+
+
+# ------------------------------------------------------------------ CNNs
+def test_c3_reduced_fp32():
+    _check_f32(wl.config3(K=2, B=5, size=10, widths=(8, 12, 20), steps=3))
+
+
+def test_c3_reduced_fp32_odd_sizes():
+    _check_f32(wl.config3(K=2, B=3, size=7, widths=(5, 9, 6), steps=2))
+
+
+def test_c3_four_cnns_fp32_full_size():
+    _check_f32(wl.config3(), steps=2)
+
+
+def test_c5_reduced_fp32_and_bf16():
+    _check_f32(wl.config5(K=2, B=3, size=12, widths=(8, 16, 24, 32), n_classes=10, steps=2, dtype=wl.F32))
+    _check_bf16(wl.config5(K=2, B=4, size=16, widths=(8, 16, 32, 64), n_classes=10, steps=2))
+
+
+def test_c5_resnet_style_bf16_full_width_reduced_images():
+    _check_bf16(wl.config5(K=2, B=8, size=16, steps=2))
+
+
+# ------------------------------------------------------------------ the paper's invariants on the device
+def _blobs_equal(a, b):
+    return all(np.array_equal(x, y) for x, y in zip(a, b))
+
+
+def test_singleton_pack_and_run_to_run_determinism():
+    w = wl.config2(B=32, D=128, hidden=(64, 64), K=1, steps=3)
+    a = pu.run_gpu(w)
+    b = pu.run_gpu(w)
+    assert _blobs_equal(a["blobs"], b["blobs"]) and np.array_equal(a["loss"], b["loss"])
+    _check_bf16(w)
+
+
+def test_member_result_does_not_depend_on_the_rest_of_the_pack():
+    # Section 2.2: a member trains as if alone -> bit-identical whether packed with others or not,
+    # whatever the others' learning rates, and wherever it sits in the pack.
+    w = wl.config4(K=5, B=64, D=160, width_choices=(24, 64, 136), steps=3)
+    full = pu.run_gpu(w)
+    for k in (0, 3):
+        solo = wl.PackWorkload(w.name, w.dtype, w.B, w.in_shape, [w.models[k]], [w.batch[k]], [w.weights[k]],
+                               w.lr[k:k + 1], w.x, w.labels, w.steps, w.n_classes)
+        one = pu.run_gpu(solo)
+        assert np.array_equal(one["blobs"][0], full["blobs"][k])
+        assert np.array_equal(one["loss"][:, 0], full["loss"][:, k])
+    lr2 = w.lr.copy()
+    lr2[1] *= 3.0
+    other = pu.run_gpu(w, lr=lr2)
+    for k in (0, 2, 3, 4):
+        assert np.array_equal(other["blobs"][k], full["blobs"][k])
+    assert not np.array_equal(other["blobs"][1], full["blobs"][1])
+    perm = [3, 1, 4, 0, 2]
+    wp = wl.PackWorkload(w.name, w.dtype, w.B, w.in_shape, [w.models[i] for i in perm], [w.batch[i] for i in perm],
+                         [w.weights[i] for i in perm], w.lr[perm], w.x, w.labels, w.steps, w.n_classes)
+    shuffled = pu.run_gpu(wp)
+    for j, i in enumerate(perm):
+        assert np.array_equal(shuffled["blobs"][j], full["blobs"][i])
+        assert np.array_equal(shuffled["pred"][j], full["pred"][i])
+
+
+def test_rows_beyond_a_members_batch_are_never_read():
+    w = wl.config4(K=4, B=32, D=64, width_choices=(16, 32), steps=2, dtype=wl.F32)
+    w.batch = [32, 8, 16, 5]
+    base = pu.run_gpu(w)
+    x2 = w.x.copy()
+    x2[16:] = 7.0
+    lab2 = w.labels.copy()
+    lab2[16:] = (lab2[16:] + 1) % w.n_classes
+    w2 = wl.PackWorkload(w.name, w.dtype, w.B, w.in_shape, w.models, w.batch, w.weights, w.lr, x2, lab2, w.steps, w.n_classes)
+    moved = pu.run_gpu(w2)
+    for k in (1, 2, 3):
+        assert np.array_equal(base["blobs"][k], moved["blobs"][k])
+    assert not np.array_equal(base["blobs"][0], moved["blobs"][0])
+
+
+def test_zero_learning_rate_leaves_weights_bit_identical():
+    w = wl.config3(K=2, B=4, size=8, widths=(8, 8, 8), steps=2)
+    out = pu.run_gpu(w, lr=[0.0, 0.01])
+    assert np.array_equal(out["blobs"][0], w.weights[0])
+    assert not np.array_equal(out["blobs"][1], w.weights[1])
+
+
+def test_exact_ties_in_the_logits_and_label_column():
+    # A linear-only member with zero weights: its logits are exactly its bias for every row, so
+    # ties are exact; argmax must return the lowest index and the loss must use column y.
+    C, D, B = 6, 16, 9
+    bias = np.array([1.0, 3.0, 3.0, 2.0, 3.0, -1.0], dtype=np.float32)
+    blob = np.concatenate([np.zeros(C * D, dtype=np.float32), bias])
+    for dtype in (wl.F32, wl.BF16):
+        w = wl.custom("ties", 9, dtype, B, (1, 1, D), [[("linear", C)]], n_classes=C, lr=[0.0])
+        w.weights = [blob]
+        gpu = pu.run_gpu(w)
+        ref = pu.run_oracle(w)
+        assert np.array_equal(gpu["pred"][0], np.ones(B, dtype=np.int32))
+        assert np.array_equal(gpu["pred"][0], ref["pred"][0][0])
+        assert np.array_equal(gpu["logits"][0], np.tile(bias, (B, 1)))
+        assert abs(gpu["loss"][0, 0] - ref["loss"][0, 0]) <= 1e-6 * ref["loss"][0, 0]
+        tol = 1e-6 if dtype == wl.F32 else 2.0 ** -8
+        assert pu.rel_inf(gpu["grads"][0].astype(np.float64), ref["grads"][0][0]) <= tol
+
+
+def test_out_of_range_label_is_reported_and_never_indexes_memory():
+    from paper_2002_02885_amd import binding
+    w = wl.config1(B=8, D=16, hidden=8)
+    lab = w.labels.copy()
+    lab[3] = 10
+    lab[5] = -1
+    pk = binding.Pack(w.B, w.in_shape, w.dtype, w.models, w.batch)
+    try:
+        for k in range(w.K):
+            pk.write_weights(k, w.weights[k])
+        x = torch.from_numpy(w.x).cuda()
+        y = torch.from_numpy(lab).cuda()
+        pk.step(x.data_ptr(), y.data_ptr(), w.lr)
+        loss = pk.read_loss(allow_label_error=True)
+        assert pk.last_status == binding.PACK_ELABEL and np.all(np.isfinite(loss))
+        ok = np.ones(8, dtype=bool)
+        ok[[3, 5]] = False
+        # rows with a bad label contribute nothing: same loss sum as the oracle on the good rows
+        from oracle import pack_oracle as po
+        for k in range(w.K):
+            net = po.Model(w.models[k], w.in_shape, w.weights[k].astype(np.float64))
+            l6, _, _ = net.loss_and_grads(w.x[ok].astype(np.float64), w.labels[ok])
+            assert abs(loss[k] - l6 * 6 / 8) <= 1e-4 * abs(l6)
+        y2 = torch.from_numpy(w.labels).cuda()
+        pk.step(x.data_ptr(), y2.data_ptr(), w.lr)
+        pk.read_loss()
+        assert pk.last_status == binding.PACK_OK
+    finally:
+        pk.destroy()
+
+
+def test_seeded_initialisation_is_reproducible_and_bounded():
+    from paper_2002_02885_amd import binding
+    models = [wl.small_cnn((8, 8, 8), 10)]
+    a = binding.Pack(2, (8, 8, 3), "f32", models, seed=42)
+    b = binding.Pack(2, (8, 8, 3), "f32", models, seed=42)
+    c = binding.Pack(2, (8, 8, 3), "f32", models, seed=43)
+    wa, wb, wc = a.read_weights(0), b.read_weights(0), c.read_weights(0)
+    a.destroy(); b.destroy(); c.destroy()
+    assert np.array_equal(wa, wb) and not np.array_equal(wa, wc)
+    off = 0
+    for kind, ws, bs, fan_in in wl.param_shapes(models[0], (8, 8, 3)):
+        nw, nb = int(np.prod(ws)), int(np.prod(bs))
+        W, bb = wa[off:off + nw], wa[off + nw:off + nw + nb]
+        off += nw + nb
+        assert np.max(np.abs(W)) <= np.sqrt(6.0 / fan_in) and np.max(np.abs(bb)) <= 1 / np.sqrt(fan_in)
+        assert np.max(np.abs(W)) > 0.8 * np.sqrt(6.0 / fan_in) and abs(W.mean()) < 0.2 * np.sqrt(6.0 / fan_in)

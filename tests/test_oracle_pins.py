@@ -568,3 +568,15 @@ def test_rounded_mode_is_close_to_exact_and_stores_bf16_operands():
     for rec in tape:
         if rec[0] == "relu":
             assert np.array_equal(po.q_bf16(rec[1]), rec[1])
+
+
+def test_weight_rounding_mode_equals_exact_while_weights_are_representable_then_lags():
+    # With bf16-representable initial weights the first step of "weights" mode IS the exact step;
+    # after the update the master is no longer representable and the operand copy lags behind it.
+    w = wl.config2(B=16, D=64, hidden=(32, 32), K=1)
+    args = (w.models, w.in_shape, [w.weights[0].astype(np.float64)], w.batch, [0.05], w.x.astype(np.float64), w.labels)
+    ex = po.train_pack(*args, steps=3, mode="exact", keep_grads=True)
+    wt = po.train_pack(*args, steps=3, mode="weights", keep_grads=True)
+    assert ex["loss"][0, 0] == wt["loss"][0, 0] and np.array_equal(ex["grads"][0][0], wt["grads"][0][0])
+    assert ex["loss"][1, 0] != wt["loss"][1, 0]
+    assert abs(ex["loss"][2, 0] - wt["loss"][2, 0]) < 0.05 * ex["loss"][2, 0]
