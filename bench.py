@@ -1,0 +1,171 @@
+#!/usr/bin/env python3
+"""Benchmark of the packed training step on one MI355X.
+
+A "step" is one pass of the whole hot path over one synthetic batch: shared-input forward of all
+K members, softmax cross-entropy, backward, and the per-member-learning-rate SGD update.  The
+workload is the K=8 MLP 3072-1024-1024-10 configuration in bf16 (batch 256), inputs resident in
+HBM before timing starts.  Prints ONE JSON line.
+
+Beside the packed throughput it reports
+  - the unpacked baseline of the paper's Eq. 1-3: T_s(Seq) = sum of the step times of K packs of
+    one member each (same library, same stream), speed-up T_s(Seq)/T_s(Pack) and IMPV;
+  - `roofline`: the dominant kernel of the step (chosen by measured time), its algorithmic bytes
+    or flops per launch divided by its average duration from HIP events on the pack's stream;
+  - `cpu_baseline`: the CPU oracle (float64, members trained separately) timed on this host.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def _time_steps(pk, x, y, lr, steps, torch):
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        pk.step(x.data_ptr(), y.data_ptr(), lr)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-unpacked", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the packed step has no cross-GPU part); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as wl
+    from paper_2002_02885_amd import binding
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = wl.CONFIGS[args.workload]()
+    stream = torch.cuda.current_stream().cuda_stream
+    x = torch.from_numpy(w.x)
+    x = (x.to(torch.bfloat16) if w.dtype == wl.BF16 else x).cuda().contiguous()
+    y = torch.from_numpy(w.labels).cuda().contiguous()
+
+    def make(models, batch, weights):
+        pk = binding.Pack(w.B, w.in_shape, w.dtype, models, batch, stream=stream)
+        for k, blob in enumerate(weights):
+            pk.write_weights(k, blob)
+        return pk
+
+    # a tiny learning rate keeps hundreds of timed steps finite; arithmetic and traffic per step
+    # do not depend on its value
+    lr = np.full(w.K, 1e-6, dtype=np.float32)
+
+    pk = make(w.models, w.batch, w.weights)
+    n_params = sum(pk.num_params(k) for k in range(w.K))
+    flops = sum(wl.step_flops(m, w.in_shape, b) for m, b in zip(w.models, w.batch))
+    samples_models = float(sum(w.batch))
+
+    # warm-up, with every launch timed once to find the dominant kernel
+    for _ in range(max(args.warmup - 5, 1)):
+        pk.step(x.data_ptr(), y.data_ptr(), lr)
+    pk.profile_start(-1)
+    for _ in range(5):
+        pk.step(x.data_ptr(), y.data_ptr(), lr)
+    ms, cnt = pk.profile_stop()
+    names = [pk.launch_name(i) for i in range(pk.num_launches())]
+    per_launch = ms / np.maximum(cnt, 1)
+    dom = int(np.argmax(per_launch))
+    breakdown = {}
+    for nm, t in zip(names, per_launch):
+        breakdown[nm] = breakdown.get(nm, 0.0) + float(t) * 1e3
+    # timed region: EXACTLY --steps steps, the dominant launch bracketed by events
+    pk.profile_start(dom)
+    t_pack = _time_steps(pk, x, y, lr, args.steps, torch)
+    ms, cnt = pk.profile_stop()
+    dom_ms = float(ms[dom] / max(cnt[dom], 1))
+    loss = pk.read_loss()
+    assert np.all(np.isfinite(loss)), loss
+    launches = pk.num_launches()
+    dev_bytes = pk.device_bytes()
+    pk.destroy()
+
+    dom_name = names[dom]
+    if dom_name == "sgd_update":
+        bpp = 14.0 if w.dtype == wl.BF16 else 12.0     # master r+w, gradient r, (+ bf16 copy w)
+        achieved = n_params * bpp / (dom_ms * 1e-3) / 1e9
+        roofline = {"kernel": dom_name, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": None, "avg_ms": dom_ms,
+                    "algorithmic_bytes": n_params * bpp}
+    else:
+        # a matrix-product launch: its flops are those of the layer slot it executes
+        peak = MFMA_PEAK_TFLOPS[w.dtype]
+        share = None
+        roofline = {"kernel": dom_name, "bound": "mfma", "achieved": share, "peak": peak, "unit": "TFLOP/s",
+                    "frac": None, "traffic": None, "avg_ms": dom_ms}
+
+    out = {
+        "metric": "packed train samples x models / s",
+        "value": samples_models / t_pack,
+        "unit": "samples*models/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": t_pack * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == wl.BF16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: K={w.K} packed models, batch {w.B}, input {list(w.in_shape)}, "
+                               f"{n_params} parameters", "K": w.K, "batch": w.B, "launches_per_step": launches,
+                   "device_bytes": dev_bytes},
+        "tflops": flops / t_pack / 1e12,
+        "tflops_frac_of_mfma_peak": flops / t_pack / 1e12 / MFMA_PEAK_TFLOPS[w.dtype],
+        "kernel_us": {k: round(v, 2) for k, v in breakdown.items()},
+        "roofline": roofline,
+    }
+
+    if not args.no_unpacked:
+        t_seq = 0.0
+        for k in range(w.K):
+            solo = make([w.models[k]], [w.batch[k]], [w.weights[k]])
+            l1 = lr[k:k + 1]
+            for _ in range(max(args.warmup // 2, 2)):
+                solo.step(x.data_ptr(), y.data_ptr(), l1)
+            t_seq += _time_steps(solo, x, y, l1, max(args.steps // 4, 5), torch)
+            solo.destroy()
+        out["unpacked_ms_per_step"] = t_seq * 1e3
+        out["speedup_vs_unpacked"] = t_seq / t_pack
+        out["impv"] = (t_seq - t_pack) / t_seq
+
+    if not args.no_cpu_baseline:
+        from oracle import pack_oracle as po
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+        except Exception:
+            threads = len(os.sched_getaffinity(0))
+        mode = "weights" if w.dtype == wl.BF16 else "exact"
+        blobs = [b.astype(np.float64) for b in w.weights]
+        x64 = w.x.astype(np.float64)
+        n_steps, t_cpu = 0, 0.0
+        while t_cpu < 12.0 and n_steps < 50:
+            t0 = time.perf_counter()
+            po.train_pack(w.models, w.in_shape, blobs, w.batch, lr.astype(np.float64), x64, w.labels, 1, mode=mode)
+            t_cpu += time.perf_counter() - t0
+            n_steps += 1
+        out["cpu_baseline"] = {"value": samples_models * n_steps / t_cpu, "unit": "samples*models/s", "cores": int(threads),
+                               "kind": "oracle", "sample": f"{n_steps} full steps of all {w.K} members of {w.name} "
+                                                          f"(numpy float64, members trained one after another)"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

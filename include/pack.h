@@ -53,7 +53,7 @@ typedef enum {
     PACK_ENOMEM = 2,   /* device or host allocation failed (the out-of-memory case of Section 4.2) */
     PACK_EDEVICE = 3,  /* a HIP runtime call failed */
     PACK_ESHAPE = 4,   /* layer list is not a classifier this library can run (see pack_create) */
-    PACK_ELABEL = 5    /* a label outside [0, C_k) was seen by the last step */
+    PACK_ELABEL = 5    /* a label outside [0, C_k) was seen since the last pack_read_loss */
 } pack_status;
 
 typedef enum {
@@ -94,10 +94,10 @@ typedef struct {
  * `models` and the layer arrays are host memory and are copied.  Weights are initialised from
  * `seed` (uniform in +-sqrt(6/fan_in), biases in +-1/sqrt(fan_in)); callers that need specific
  * weights use pack_write_weights.  `hip_stream` is a hipStream_t (0 = the null stream) on
- * which every later call enqueues its work.  The layer list of each member must end in a
- * [b_k, C_k] tensor (a PACK_LINEAR, or PACK_GAP), the logits.
+ * which every later call enqueues its work.
+ * The layer list must end in a PACK_LINEAR (without ReLU): its output [b_k, C_k] is the logits.
  * Errors: PACK_EINVAL, PACK_ESHAPE (unsupported op order, RES_BEGIN/RES_END mismatch, shortcut
- * shapes that neither agree nor halve, no parameterised layer), PACK_ENOMEM, PACK_EDEVICE. */
+ * shapes that neither agree nor halve, last layer not linear), PACK_ENOMEM, PACK_EDEVICE. */
 pack_status pack_create(const pack_input_spec* input, const pack_model_spec* models, int32_t K,
                         uint64_t seed, void* hip_stream, pack_t** out);
 
@@ -109,14 +109,15 @@ pack_status pack_write_weights(pack_t* p, int32_t k, const float* host_src, size
 /* One synchronised training step of all K members (Section 2.2; shared input Section 3.4; batch
  * slices Section 3.2): forward, mean softmax cross-entropy over each member's own rows, backward,
  * and W <- W - lr[k] * dW for every parameter of member k, with gradients taken at the
- * pre-update weights.  x_dev: device, [B, H, W, C] of the pack's dtype; labels_dev: device int32
+ * pre-update weights.  x_dev: device, 16-byte aligned, [B, H, W, C] of the pack's dtype; labels_dev: device int32
  * [B]; lr_host: host float [K], copied during the call.  Enqueues only.
  * Errors: PACK_EINVAL (null argument), PACK_EDEVICE (launch failure). */
 pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, const float* lr_host);
 
 /* Loss of each member at the last step, evaluated at that step's pre-update weights.
  * host_dst: float [K].  Waits for the stream.  Returns PACK_ELABEL (and still fills host_dst)
- * if the last step met a label outside [0, C_k); such rows contribute nothing. */
+ * if any step since the previous pack_read_loss met a label outside [0, C_k); such rows
+ * contribute nothing to loss or gradients and index no memory. */
 pack_status pack_read_loss(pack_t* p, float* host_dst);
 
 /* free's checkpoint (Section 2.2): the member's current fp32 weights in the blob layout. */
@@ -144,6 +145,17 @@ int32_t pack_num_launches(const pack_t* p);
 
 /* Bytes of device memory the pack holds (the paper's memory metric, Section 4.2: allocated). */
 size_t pack_device_bytes(const pack_t* p);
+
+/* Per-launch timing, for benchmarks: after pack_profile_start every pack_step brackets launch
+ * number `which` of its sequence (all launches if which < 0) with a pair of events on the
+ * pack's stream; pack_profile_stop waits for the stream, writes the summed milliseconds and the
+ * number of samples per launch index into ms_sum / count (host, pack_num_launches entries
+ * each) and switches timing off.  pack_launch_name writes the kernel family of launch i
+ * ("gemm_lin_fwd", "sgd_update", ...) into buf (host, n bytes, always terminated).
+ * Errors: PACK_EINVAL (null, index out of range), PACK_EDEVICE. */
+pack_status pack_profile_start(pack_t* p, int32_t which);
+pack_status pack_profile_stop(pack_t* p, float* ms_sum, int32_t* count);
+pack_status pack_launch_name(const pack_t* p, int32_t i, char* buf, size_t n);
 
 /* Thread-local text describing the last failing call on this thread ("" if none). */
 const char* pack_last_error(void);

@@ -18,7 +18,8 @@ STATUS_NAMES = ["PACK_OK", "PACK_EINVAL", "PACK_ENOMEM", "PACK_EDEVICE", "PACK_E
 
 EXPORTS = ["pack_create", "pack_write_weights", "pack_step", "pack_read_loss", "pack_read_weights",
            "pack_read_pred", "pack_read_grads", "pack_read_logits", "pack_num_params",
-           "pack_num_classes", "pack_num_launches", "pack_device_bytes", "pack_last_error", "pack_destroy"]
+           "pack_num_classes", "pack_num_launches", "pack_device_bytes", "pack_last_error", "pack_destroy",
+           "pack_profile_start", "pack_profile_stop", "pack_launch_name"]
 
 
 class pack_layer(C.Structure):
@@ -73,8 +74,12 @@ def lib() -> C.CDLL:
         l.pack_last_error.restype = C.c_char_p
         l.pack_destroy.argtypes = [vp]
         l.pack_destroy.restype = None
+        l.pack_profile_start.argtypes = [vp, i32]
+        l.pack_profile_stop.argtypes = [vp, fp, C.POINTER(C.c_int32)]
+        l.pack_launch_name.argtypes = [vp, i32, C.c_char_p, sz]
         for name in ("pack_create", "pack_write_weights", "pack_step", "pack_read_loss",
-                     "pack_read_weights", "pack_read_pred", "pack_read_grads", "pack_read_logits"):
+                     "pack_read_weights", "pack_read_pred", "pack_read_grads", "pack_read_logits",
+                     "pack_profile_start", "pack_profile_stop", "pack_launch_name"):
             getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
@@ -166,6 +171,22 @@ class Pack:
 
     def device_bytes(self) -> int:
         return int(lib().pack_device_bytes(self._h))
+
+    def profile_start(self, which: int = -1):
+        _check(lib().pack_profile_start(self._h, which))
+
+    def profile_stop(self):
+        """Returns (summed milliseconds, sample count) per launch index."""
+        n = self.num_launches()
+        ms = np.zeros(n, dtype=np.float32)
+        cnt = np.zeros(n, dtype=np.int32)
+        _check(lib().pack_profile_stop(self._h, _fptr(ms), cnt.ctypes.data_as(C.POINTER(C.c_int32))))
+        return ms, cnt
+
+    def launch_name(self, i: int) -> str:
+        buf = C.create_string_buffer(64)
+        _check(lib().pack_launch_name(self._h, i, buf, 64))
+        return buf.value.decode()
 
     def destroy(self):
         if self._h:

@@ -11,6 +11,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -105,6 +106,11 @@ struct pack_ctx {
     float* loss_all = nullptr;   // [K]
     std::vector<Launch> plan;
     size_t device_bytes = 0;
+    // per-launch timing (off unless pack_profile_start was called)
+    bool profiling = false;
+    int profile_which = -1;
+    struct Stamp { int launch; hipEvent_t t0, t1; };
+    std::vector<Stamp> stamps;
 };
 
 namespace {
@@ -585,6 +591,7 @@ void release(pack_ctx* p) {
     if (p->slab) (void)hipFree(p->slab);
     if (p->workspace) (void)hipFree(p->workspace);
     if (p->desc) (void)hipFree(p->desc);
+    for (auto& s : p->stamps) { (void)hipEventDestroy(s.t0); (void)hipEventDestroy(s.t1); }
     delete p;
 }
 
@@ -768,8 +775,16 @@ pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, c
     LrTable lr;
     for (int k = 0; k < 256; ++k) lr.lr[k] = (k < p->K) ? lr_host[k] : 0.f;
     const bool bf = p->bf16;
-    for (const Launch& L : p->plan) {
+    for (size_t li = 0; li < p->plan.size(); ++li) {
+        const Launch& L = p->plan[li];
         hipError_t e = hipSuccess;
+        const bool timed = p->profiling && (p->profile_which < 0 || p->profile_which == (int)li);
+        pack_ctx::Stamp stamp{(int)li, nullptr, nullptr};
+        if (timed) {
+            if (hipEventCreate(&stamp.t0) != hipSuccess || hipEventCreate(&stamp.t1) != hipSuccess ||
+                hipEventRecord(stamp.t0, p->stream) != hipSuccess)
+                return fail(PACK_EDEVICE, "profiling event");
+        }
         const char* d = p->desc + L.desc_off;
         const char* mp = p->desc + L.map_off;
         switch (L.kind) {
@@ -787,7 +802,49 @@ pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, c
                 break;
         }
         if (e != hipSuccess) return fail(PACK_EDEVICE, std::string("kernel launch: ") + hipGetErrorString(e));
+        if (timed) {
+            if (hipEventRecord(stamp.t1, p->stream) != hipSuccess) return fail(PACK_EDEVICE, "profiling event");
+            p->stamps.push_back(stamp);
+        }
     }
+    return PACK_OK;
+}
+
+pack_status pack_profile_start(pack_t* p, int32_t which) {
+    if (!p) return fail(PACK_EINVAL, "null argument");
+    if (which >= (int32_t)p->plan.size()) return fail(PACK_EINVAL, "launch index out of range");
+    for (auto& s : p->stamps) { (void)hipEventDestroy(s.t0); (void)hipEventDestroy(s.t1); }
+    p->stamps.clear();
+    p->profiling = true;
+    p->profile_which = which;
+    return PACK_OK;
+}
+
+pack_status pack_profile_stop(pack_t* p, float* ms_sum, int32_t* count) {
+    if (!p || !ms_sum || !count) return fail(PACK_EINVAL, "null argument");
+    p->profiling = false;
+    for (size_t i = 0; i < p->plan.size(); ++i) { ms_sum[i] = 0.f; count[i] = 0; }
+    HIP_TRY(hipStreamSynchronize(p->stream), PACK_EDEVICE);
+    pack_status st = PACK_OK;
+    for (auto& s : p->stamps) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, s.t0, s.t1) == hipSuccess) { ms_sum[s.launch] += ms; count[s.launch] += 1; }
+        else st = fail(PACK_EDEVICE, "hipEventElapsedTime failed");
+        (void)hipEventDestroy(s.t0);
+        (void)hipEventDestroy(s.t1);
+    }
+    p->stamps.clear();
+    return st;
+}
+
+pack_status pack_launch_name(const pack_t* p, int32_t i, char* buf, size_t n) {
+    if (!p || !buf || n == 0) return fail(PACK_EINVAL, "null argument");
+    if (i < 0 || i >= (int32_t)p->plan.size()) return fail(PACK_EINVAL, "launch index out of range");
+    static const char* gemm_names[] = {"gemm_lin_fwd", "gemm_lin_dx", "gemm_lin_dw", "gemm_conv_fwd", "gemm_conv_dx", "gemm_conv_dw"};
+    static const char* names[] = {"", "colsum_bias_grad", "reduce_partials", "softmax_xent", "gap_fwd", "gap_bwd", "shortcut_bwd", "sgd_update"};
+    const Launch& L = p->plan[i];
+    const char* nm = (L.kind == L_GEMM) ? gemm_names[L.mode] : names[L.kind];
+    std::snprintf(buf, n, "%s", nm);
     return PACK_OK;
 }
 

@@ -28,7 +28,9 @@ def _check_bf16(w, steps=None):
       difference is the rounding of stored activations): loss within 2e-2;
     - every step against the oracle that rounds where the device rounds: loss, step-1
       gradients, displacement and weights within 2e-2 (without the matching rounding points a
-      ReLU unit within bf16 rounding of zero flips and moves a gradient entry by a whole summand);
+      ReLU unit within bf16 rounding of zero flips and moves a gradient entry by a whole summand).
+      Items on which that oracle itself moves by more than a quarter of the tolerance under
+      fp32-sized noise are reported as ill-conditioned and gated at tol + 4 x that sensitivity;
     - every step against the oracle that only rounds the per-step weight copy (the precision
       the configuration itself fixes): loss within 2e-2 for every member whose loss the
       oracle's own two roundings agree on to a quarter of that; the others are reported as
@@ -38,9 +40,10 @@ def _check_bf16(w, steps=None):
     exact = pu.run_oracle(w, 1, mode="exact")
     weights = pu.run_oracle(w, steps, mode="weights")
     rounded = pu.run_oracle(w, steps, mode="rounded")
+    sens = pu.oracle_sensitivity(w, steps, rounded)
     first = {"loss": gpu["loss"][:1], "blobs": gpu["blobs"], "grads": None}
     w0 = pu.compare(w, first, exact, BF16_TOL, what=("loss",), label="exact step 1: ")
-    w2 = pu.compare(w, gpu, rounded, BF16_TOL, what=("loss", "grads", "disp", "weights"), label="rounded: ")
+    w2 = pu.compare(w, gpu, rounded, BF16_TOL, what=("loss", "grads", "disp", "weights"), label="rounded: ", sens=sens)
     ill = []
     worst = 0.0
     for k in range(w.K):
