@@ -79,9 +79,9 @@ def rel_l2(g, r):
 
 def measure(w: wl.PackWorkload, a: dict, ref: dict, what=("loss", "grads", "disp", "weights")):
     """Differences between run `a` and run `ref`, as {(kind, member, item): (error, allowance)}.
-    Gradients and the displacement W_T - W_0 are measured per tensor as max(inf-norm error,
-    2-norm error), both relative (raw weights barely move at small learning rates, so agreement
-    of raw weights alone would be vacuous).  `allowance` is what fp32 storage of the master
+    Gradients and the displacement W_T - W_0 are measured per tensor in the 2-norm and in the
+    infinity norm, both relative to the reference tensor's norm (raw weights barely move at
+    small learning rates, so agreement of raw weights alone would be vacuous).  `allowance` is what fp32 storage of the master
     weights alone may contribute (2^-24 of the weight per step)."""
     out = {}
     steps = min(a["loss"].shape[0], ref["loss"].shape[0])
@@ -95,14 +95,16 @@ def measure(w: wl.PackWorkload, a: dict, ref: dict, what=("loss", "grads", "disp
             r = ref["grads"][0][k]
             assert g.shape == r.shape
             for name, s in sl:
-                out[("grad", k, name)] = (max(rel_inf(g[s], r[s]), rel_l2(g[s], r[s])), 0.0)
+                out[("grad_l2", k, name)] = (rel_l2(g[s], r[s]), 0.0)
+                out[("grad_inf", k, name)] = (rel_inf(g[s], r[s]), 0.0)
         w0 = w.weights[k].astype(np.float64)
         gw, rw = np.asarray(a["blobs"][k], dtype=np.float64), ref["blobs"][k]
         if "disp" in what and float(w.lr[k]) != 0.0:
             for name, s in sl:
                 dg, dr = gw[s] - w0[s], rw[s] - w0[s]
                 floor = 2.0 ** -23 * steps * np.max(np.abs(w0[s])) / max(np.max(np.abs(dr)), 1e-300)
-                out[("disp", k, name)] = (max(rel_inf(dg, dr), rel_l2(dg, dr)), floor)
+                out[("disp_l2", k, name)] = (rel_l2(dg, dr), floor)
+                out[("disp_inf", k, name)] = (rel_inf(dg, dr), floor)
         if "weights" in what:
             scale = np.maximum(np.abs(rw), np.sqrt(np.mean(rw * rw)))
             out[("weights", k, "all")] = (float(np.max(np.abs(gw - rw) / scale)), 0.0)
@@ -136,10 +138,18 @@ def compare(w: wl.PackWorkload, gpu: dict, ref: dict, tol: float, what=("loss", 
     return worst
 
 
-def oracle_sensitivity(w: wl.PackWorkload, steps, base: dict, mode="rounded", trials=2, eps=1e-7):
+def accumulation_noise(w: wl.PackWorkload) -> float:
+    """Relative size of fp32 accumulation-order noise in a sum of `fan_in` products: the unit
+    roundoff 2^-24 times the square root of the longest reduction that feeds a rounding."""
+    fan = max(f for m in w.models for _, _, _, f in wl.param_shapes(m, w.in_shape))
+    return 2.0 ** -24 * float(np.sqrt(fan))
+
+
+def oracle_sensitivity(w: wl.PackWorkload, steps, base: dict, mode="rounded", trials=2, eps=None):
     """Runs the rounding oracle again with every value perturbed by a relative `eps` just before
-    it is rounded to bf16 (the size of fp32 accumulation-order noise) and measures how far the
-    results move.  The perturbation is planted in the oracle, on the CPU."""
+    it is rounded to bf16 (default: the size of fp32 accumulation-order noise) and measures how
+    far the results move.  The perturbation is planted in the oracle, on the CPU."""
+    eps = accumulation_noise(w) if eps is None else eps
     orig = po.q_bf16
     out = {}
     try:
