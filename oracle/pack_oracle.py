@@ -155,8 +155,13 @@ class Model:
     ("conv3x3", out, stride), ("relu",), ("gap",), ("res_begin",), ("res_end",); `blob` is the
     flat weight vector (linear W[out][in], b[out]; conv W[Cout][Cin][3][3], b[Cout])."""
 
-    def __init__(self, layers, in_shape, blob, mode="exact"):
+    def __init__(self, layers, in_shape, blob, mode="exact", acc_noise=None):
+        """`acc_noise`, if given, is a function applied to every matrix-product result a device
+        would hold in an fp32 accumulator (forward pre-activations, input gradients) before
+        anything else looks at it.  It is a sensitivity probe for tests - how far do the results
+        move when those sums carry accumulation-order noise - and is the identity by default."""
         assert mode in ("exact", "weights", "rounded")
+        self.acc = acc_noise if acc_noise is not None else _ident
         self.layers = [tuple(op) for op in layers]
         self.in_shape = tuple(in_shape)
         self.q = q_bf16 if mode == "rounded" else _ident          # stored activations / gradients
@@ -204,14 +209,14 @@ class Model:
                 W, b = self.params[pi]
                 cur = q(cur)                       # a stored operand is a rounded operand
                 flat = cur.reshape(cur.shape[0], -1)
-                z = flat @ self.qw(W).T + b
+                z = self.acc(flat @ self.qw(W).T) + b
                 tape.append(("linear", pi, cur))
                 cur = z.reshape(z.shape[0], 1, 1, z.shape[1])
                 pi += 1
             elif kind == "conv3x3":
                 W, b = self.params[pi]
                 cur = q(cur)
-                z = conv3x3_forward(cur, self.qw(W), b, op[2])
+                z = self.acc(conv3x3_forward(cur, self.qw(W), np.zeros_like(b), op[2])) + b
                 tape.append(("conv3x3", pi, cur, op[2]))
                 cur = z
                 pi += 1
@@ -260,13 +265,13 @@ class Model:
                 dz = q(g).reshape(g.shape[0], -1)
                 flat = inp.reshape(inp.shape[0], -1)
                 grads[pi] = [dz.T @ flat, dz.sum(axis=0)]
-                g = (dz @ self.qw(W)).reshape(inp.shape) if pi != first_param else None
+                g = self.acc(dz @ self.qw(W)).reshape(inp.shape) if pi != first_param else None
             elif kind == "conv3x3":
                 _, pi, inp, s = rec
                 W, _b = self.params[pi]
                 dW, db, dx = conv3x3_backward(inp, self.qw(W), s, q(g), need_dx=(pi != first_param))
                 grads[pi] = [dW, db]
-                g = dx
+                g = self.acc(dx) if dx is not None else None
             elif kind == "relu":
                 g = q(g * (rec[1] > 0.0))
             elif kind == "gap":
@@ -289,7 +294,8 @@ class Model:
         return loss, pred, grads
 
 
-def train_pack(models, in_shape, blobs, batch, lr, x, labels, steps, mode="exact", keep_grads=False):
+def train_pack(models, in_shape, blobs, batch, lr, x, labels, steps, mode="exact", keep_grads=False,
+               acc_noise=None):
     """Train K models separately on the shared batch: model k sees rows [0, batch[k]) of `x`
     and `labels` at every step (the same batch each step).  Returns a dict with
       loss  [steps, K]   pre-update losses,
@@ -297,7 +303,7 @@ def train_pack(models, in_shape, blobs, batch, lr, x, labels, steps, mode="exact
       blobs list of K flat float64 weight vectors after the last step,
       grads (when keep_grads) list over steps of list over models of flat float64 gradients."""
     K = len(models)
-    nets = [Model(models[k], in_shape, blobs[k], mode) for k in range(K)]
+    nets = [Model(models[k], in_shape, blobs[k], mode, acc_noise) for k in range(K)]
     loss = np.zeros((steps, K))
     preds, grads = [], []
     for t in range(steps):

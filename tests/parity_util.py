@@ -146,28 +146,25 @@ def accumulation_noise(w: wl.PackWorkload) -> float:
 
 
 def oracle_sensitivity(w: wl.PackWorkload, steps, base: dict, mode="rounded", trials=2, eps=None):
-    """Runs the rounding oracle again with every value perturbed by a relative `eps` just before
-    it is rounded to bf16 (default: the size of fp32 accumulation-order noise) and measures how
-    far the results move.  The perturbation is planted in the oracle, on the CPU."""
-    eps = accumulation_noise(w) if eps is None else eps
-    orig = po.q_bf16
+    """Runs the oracle again with every matrix-product result perturbed by a relative `eps`
+    (default: four times the size of fp32 accumulation-order noise) through the oracle's
+    `acc_noise` probe, and measures how far the results move.  A ReLU unit whose pre-activation
+    is that close to zero flips, and a value that close to a bf16 rounding boundary rounds the
+    other way; both move single gradient entries by whole summands.  The perturbation is
+    planted in the oracle, on the CPU."""
+    eps = 4.0 * accumulation_noise(w) if eps is None else eps
     out = {}
-    try:
-        for trial in range(trials):
-            rng = np.random.default_rng(1000 + trial)
+    for trial in range(trials):
+        rng = np.random.default_rng(1000 + trial)
 
-            def noisy(a):
-                a = np.asarray(a, dtype=np.float64)
-                return orig(a * (1.0 + eps * rng.standard_normal(a.shape)))
+        def noisy(a):
+            return a * (1.0 + eps * rng.standard_normal(a.shape))
 
-            po.q_bf16 = noisy
-            pert = run_oracle(w, steps, mode=mode)
-            po.q_bf16 = orig
-            pert_first = {"loss": pert["loss"], "blobs": pert["blobs"], "grads": pert["grads"]}
-            for key, (e, _) in measure(w, pert_first, base).items():
-                out[key] = (max(out.get(key, (0.0, 0.0))[0], e), 0.0)
-    finally:
-        po.q_bf16 = orig
+        pert = po.train_pack(w.models, w.in_shape, [b.astype(np.float64) for b in w.weights], w.batch,
+                             np.asarray(w.lr, dtype=np.float64), w.x.astype(np.float64), w.labels, steps,
+                             mode=mode, keep_grads=True, acc_noise=noisy)
+        for key, (e, _) in measure(w, pert, base).items():
+            out[key] = (max(out.get(key, (0.0, 0.0))[0], e), 0.0)
     return out
 
 

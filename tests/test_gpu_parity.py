@@ -13,16 +13,22 @@ pytestmark = pytest.mark.gpu
 F32_TOL, BF16_TOL = pu.TOL[wl.F32], pu.TOL[wl.BF16]
 
 
-def _check_f32(w, steps=None):
+def _check_f32(w, steps=None, trials=2):
+    """fp32 packs against the float64 oracle at 1e-4.  Items on which the oracle itself moves by
+    more than a quarter of that under fp32-sized accumulation noise (a ReLU unit within rounding
+    of zero flips and moves a gradient entry by a whole summand) are reported as
+    ill-conditioned and gated at tol + 4 x that sensitivity."""
+    steps = w.steps if steps is None else steps
     gpu = pu.run_gpu(w, steps)
     ref = pu.run_oracle(w, steps)
-    worst = pu.compare(w, gpu, ref, F32_TOL)
+    sens = pu.oracle_sensitivity(w, steps, ref, mode="exact", trials=trials)
+    worst = pu.compare(w, gpu, ref, F32_TOL, sens=sens)
     n, skipped = pu.compare_pred(w, gpu["pred_first"], gpu["logits"], ref["pred"][0], F32_TOL)
     print(f"\n{w.name}: worst {worst}; argmax rows compared {n}, unresolvable {skipped}; launches {gpu['launches']}")
     return gpu, ref
 
 
-def _check_bf16(w, steps=None):
+def _check_bf16(w, steps=None, trials=2):
     """bf16 packs (bf16 inputs/weights, fp32 accumulate, fp32 master).  Three references:
     - step 1 against the float64 oracle (the weights are bf16-representable, so the only
       difference is the rounding of stored activations): loss within 2e-2;
@@ -40,7 +46,7 @@ def _check_bf16(w, steps=None):
     exact = pu.run_oracle(w, 1, mode="exact")
     weights = pu.run_oracle(w, steps, mode="weights")
     rounded = pu.run_oracle(w, steps, mode="rounded")
-    sens = pu.oracle_sensitivity(w, steps, rounded)
+    sens = pu.oracle_sensitivity(w, steps, rounded, trials=trials)
     first = {"loss": gpu["loss"][:1], "blobs": gpu["blobs"], "grads": None}
     w0 = pu.compare(w, first, exact, BF16_TOL, what=("loss",), label="exact step 1: ")
     w2 = pu.compare(w, gpu, rounded, BF16_TOL, what=("loss", "grads", "disp", "weights"), label="rounded: ", sens=sens)
@@ -86,7 +92,7 @@ def test_c2_reduced_bf16():
 
 
 def test_c2_eight_mlps_bf16_full_size():
-    _check_bf16(wl.config2())
+    _check_bf16(wl.config2(), trials=1)
 
 
 def test_c4_reduced_heterogeneous_bf16():
@@ -95,7 +101,7 @@ def test_c4_reduced_heterogeneous_bf16():
 
 @pytest.mark.parametrize("n_classes", [10, 100])
 def test_c4_heterogeneous_bf16_full_size(n_classes):
-    _check_bf16(wl.config4(n_classes=n_classes))
+    _check_bf16(wl.config4(n_classes=n_classes), trials=1)
 
 
 # ------------------------------------------------------------------ CNNs
@@ -108,7 +114,7 @@ def test_c3_reduced_fp32_odd_sizes():
 
 
 def test_c3_four_cnns_fp32_full_size():
-    _check_f32(wl.config3(), steps=2)
+    _check_f32(wl.config3(), steps=1, trials=1)
 
 
 def test_c5_reduced_fp32_and_bf16():
