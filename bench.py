@@ -129,6 +129,7 @@ def main():
         "tflops": flops / t_pack / 1e12,
         "tflops_frac_of_mfma_peak": flops / t_pack / 1e12 / MFMA_PEAK_TFLOPS[w.dtype],
         "kernel_us": {k: round(v, 2) for k, v in breakdown.items()},
+        "launch_us": [[nm, round(float(t) * 1e3, 2)] for nm, t in zip(names, per_launch)],
         "roofline": roofline,
     }
 

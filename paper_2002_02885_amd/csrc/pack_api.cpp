@@ -73,10 +73,11 @@ struct ModelInfo {
     float* loss = nullptr;
 };
 
-enum LaunchKind { L_GEMM, L_COLSUM, L_REDUCE, L_CE, L_GAP_FWD, L_GAP_BWD, L_SHORTCUT, L_SGD };
+enum LaunchKind { L_GEMM, L_REDUCE, L_CE, L_GAP_FWD, L_GAP_BWD, L_SHORTCUT, L_SGD };
 
 struct Launch {
     int kind = 0, mode = 0;
+    int tile_cfg = 0;       // GEMM launches: index into GEMM_TILE_M / GEMM_TILE_N
     size_t desc_off = 0;    // byte offset of the problem array in the descriptor buffer
     size_t map_off = 0;     // byte offset of the tile / block map
     int n = 0;              // grid size
@@ -311,12 +312,28 @@ std::vector<TileRef> xcd_order(const std::vector<TileOrder>& logical) {
     return out;
 }
 
+size_t count_tiles(const std::vector<GemmProb>& probs, int cfg) {
+    size_t n = 0;
+    for (const GemmProb& g : probs) {
+        const size_t tms = (g.R + GEMM_TILE_M[cfg] - 1) / GEMM_TILE_M[cfg];
+        const size_t tns = (g.Q + GEMM_TILE_N[cfg] - 1) / GEMM_TILE_N[cfg];
+        n += tms * tns * std::max(1, (g.Kd + g.ksplit - 1) / g.ksplit);
+    }
+    return n;
+}
+
 void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<GemmProb>& probs) {
     if (probs.empty()) return;
+    // The tile shape is chosen per launch so that the grid fills the 256 compute units about
+    // twice; it only partitions the output, the summation order of an element does not depend
+    // on it, so a member's bits do not depend on who else is in the launch.
+    int cfg = 0;
+    while (cfg < 2 && count_tiles(probs, cfg) < 512) ++cfg;
+    const int BMc = GEMM_TILE_M[cfg], BNc = GEMM_TILE_N[cfg];
     std::vector<TileOrder> logical;
     for (size_t i = 0; i < probs.size(); ++i) {
         const GemmProb& g = probs[i];
-        const int tms = (g.R + GEMM_BM - 1) / GEMM_BM, tns = (g.Q + GEMM_BN - 1) / GEMM_BN;
+        const int tms = (g.R + BMc - 1) / BMc, tns = (g.Q + BNc - 1) / BNc;
         const int S = (g.Kd + g.ksplit - 1) / g.ksplit;
         for (int ks = 0; ks < std::max(S, 1); ++ks) {
             if (mode == CONV_FWD || mode == CONV_DX) {
@@ -332,6 +349,7 @@ void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<G
     Launch L;
     L.kind = L_GEMM;
     L.mode = mode;
+    L.tile_cfg = cfg;
     L.desc_off = db.add(probs.data(), probs.size() * sizeof(GemmProb));
     L.map_off = db.add(tiles.data(), tiles.size() * sizeof(TileRef));
     L.n = (int)tiles.size();
@@ -441,10 +459,8 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
     for (ModelInfo& m : p->models)
         for (TensorInfo& t : m.tensors) t.grad_written = false;
     for (size_t s = max_nodes; s-- > 0;) {
-        std::vector<ColsumProb> cs;
-        std::vector<int> cs_blocks;
-        std::vector<ReduceProb> cs_red, dw_red;
-        std::vector<int> cs_red_blocks, dw_red_blocks;
+        std::vector<ReduceProb> dw_red;
+        std::vector<int> dw_red_blocks;
         std::vector<GemmProb> lin_dw, conv_dw, lin_dx, conv_dx;
         std::vector<GapProb> gaps;
         std::vector<int> gap_blocks;
@@ -467,26 +483,6 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 continue;
             }
             const int rows = (nd.kind == NODE_LINEAR) ? to.n : to.n * to.h * to.w;
-            // bias gradient
-            {
-                ColsumProb c{};
-                c.dz = to.dz; c.M = rows; c.N = nd.out; c.ld = nd.out;
-                c.rows_per_chunk = 2048;
-                c.nchunk = (rows + c.rows_per_chunk - 1) / c.rows_per_chunk;
-                float* dst = p->grad + nd.b_off;
-                if (c.nchunk > 1) {
-                    c.out = (float*)(ws + ws_off);
-                    ReduceProb r{};
-                    r.in = c.out; r.out = dst; r.stride = nd.out; r.n = nd.out; r.S = c.nchunk;
-                    cs_red.push_back(r);
-                    cs_red_blocks.push_back((nd.out + 1023) / 1024);
-                    ws_off += align_up((size_t)c.nchunk * nd.out * 4, 256);
-                } else {
-                    c.out = dst;
-                }
-                cs.push_back(c);
-                cs_blocks.push_back(c.nchunk * ((nd.out + COLSUM_COLS - 1) / COLSUM_COLS));
-            }
             // weight gradient
             {
                 GemmProb g{};
@@ -502,6 +498,7 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                     if (nd.fan_in % V == 0) g.flags |= F_VEC_B;
                     g.ksplit = std::max(g.Kd, 1);
                     g.C = dst;
+                    g.dbias = p->grad + nd.b_off;
                     lin_dw.push_back(g);
                 } else {
                     g.H = ti.h; g.W = ti.w; g.Cin = ti.c; g.Ho = to.h; g.Wo = to.w; g.Cout = to.c; g.stride = nd.stride;
@@ -518,8 +515,15 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                         dw_red.push_back(r);
                         dw_red_blocks.push_back((int)((nd.w_elems + 1023) / 1024));
                         ws_off += align_up((size_t)S * nd.w_elems * 4, 256);
+                        g.dbias = (float*)(ws + ws_off);
+                        ReduceProb rb{};
+                        rb.in = g.dbias; rb.out = p->grad + nd.b_off; rb.stride = nd.out; rb.n = nd.out; rb.S = S;
+                        dw_red.push_back(rb);
+                        dw_red_blocks.push_back((nd.out + 1023) / 1024);
+                        ws_off += align_up((size_t)S * nd.out * 4, 256);
                     } else {
                         g.C = dst;
+                        g.dbias = p->grad + nd.b_off;
                     }
                     conv_dw.push_back(g);
                 }
@@ -563,8 +567,6 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
             }
         }
         ws_need = std::max(ws_need, ws_off);
-        add_mapped_launch(p, db, L_COLSUM, cs, cs_blocks);
-        add_mapped_launch(p, db, L_REDUCE, cs_red, cs_red_blocks);
         add_gemm_launch(p, db, LIN_DW, lin_dw);
         add_gemm_launch(p, db, CONV_DW, conv_dw);
         add_mapped_launch(p, db, L_REDUCE, dw_red, dw_red_blocks);
@@ -789,9 +791,8 @@ pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, c
         const char* mp = p->desc + L.map_off;
         switch (L.kind) {
             case L_GEMM:
-                e = launch_gemm(L.mode, bf, (const GemmProb*)d, (const TileRef*)mp, L.n, x_dev, p->stream);
+                e = launch_gemm(L.mode, bf, L.tile_cfg, (const GemmProb*)d, (const TileRef*)mp, L.n, x_dev, p->stream);
                 break;
-            case L_COLSUM: e = launch_colsum(bf, (const ColsumProb*)d, (const int2*)mp, L.n, p->stream); break;
             case L_REDUCE: e = launch_reduce((const ReduceProb*)d, (const int2*)mp, L.n, p->stream); break;
             case L_CE: e = launch_ce(bf, (const CeProb*)d, L.n, labels_dev, p->err_flag, p->stream); break;
             case L_GAP_FWD: e = launch_gap(bf, false, (const GapProb*)d, (const int2*)mp, L.n, p->stream); break;
@@ -841,7 +842,7 @@ pack_status pack_launch_name(const pack_t* p, int32_t i, char* buf, size_t n) {
     if (!p || !buf || n == 0) return fail(PACK_EINVAL, "null argument");
     if (i < 0 || i >= (int32_t)p->plan.size()) return fail(PACK_EINVAL, "launch index out of range");
     static const char* gemm_names[] = {"gemm_lin_fwd", "gemm_lin_dx", "gemm_lin_dw", "gemm_conv_fwd", "gemm_conv_dx", "gemm_conv_dw"};
-    static const char* names[] = {"", "colsum_bias_grad", "reduce_partials", "softmax_xent", "gap_fwd", "gap_bwd", "shortcut_bwd", "sgd_update"};
+    static const char* names[] = {"", "reduce_partials", "softmax_xent", "gap_fwd", "gap_bwd", "shortcut_bwd", "sgd_update"};
     const Launch& L = p->plan[i];
     const char* nm = (L.kind == L_GEMM) ? gemm_names[L.mode] : names[L.kind];
     std::snprintf(buf, n, "%s", nm);

@@ -38,6 +38,8 @@ struct GemmProb {
     void* C;
     const float* bias;
     const void* aux;
+    float* dbias;                          // weight-gradient modes: where the bias gradient goes
+                                           // (split ks writes dbias[ks * R + row]); null = skip
     int R, Q, Kd;
     int lda, ldb, ldc;
     int H, W, Cin, Ho, Wo, Cout, stride;   // geometry of the forward convolution (conv modes)
@@ -50,13 +52,6 @@ struct GemmProb {
 struct TileRef {      // one workgroup's job; prob < 0 marks a filler slot
     int prob;
     int tm, tn, ks;
-};
-
-struct ColsumProb {   // db[n] = sum_m dz[m, n]
-    const void* dz;
-    float* out;       // final result (or partial sums when nchunk > 1: out[chunk * N + n])
-    int M, N, ld;
-    int rows_per_chunk, nchunk;
 };
 
 struct ReduceProb {   // out[e] = sum_{s < S} in[s * stride + e], fixed order
@@ -97,9 +92,9 @@ struct ShortcutProb { // backward of the residual shortcut into the source tenso
 struct LrTable { float lr[256]; };
 
 // launch wrappers; all enqueue on `st` and return the launch status -----------------------------
-hipError_t launch_gemm(int mode, bool bf16, const GemmProb* probs_dev, const TileRef* tiles_dev,
+// tile_cfg: 0 = 128x128, 1 = 128x64, 2 = 64x64 output tile per workgroup
+hipError_t launch_gemm(int mode, bool bf16, int tile_cfg, const GemmProb* probs_dev, const TileRef* tiles_dev,
                        int n_tiles, const void* x_dev, hipStream_t st);
-hipError_t launch_colsum(bool bf16, const ColsumProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);
 hipError_t launch_reduce(const ReduceProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);
 hipError_t launch_ce(bool bf16, const CeProb* probs_dev, int K, const int32_t* labels, int* err_flag, hipStream_t st);
 hipError_t launch_gap(bool bf16, bool backward, const GapProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);
@@ -110,9 +105,8 @@ hipError_t launch_cast_bf16(const float* src, void* dst_bf16, long long n, hipSt
 hipError_t launch_fill_zero(void* dst, long long bytes, hipStream_t st);
 
 // tile geometry the planner needs
-constexpr int GEMM_BM = 128;
-constexpr int GEMM_BN = 128;
-constexpr int COLSUM_COLS = 64;
+constexpr int GEMM_TILE_M[3] = {128, 128, 64};
+constexpr int GEMM_TILE_N[3] = {128, 64, 64};
 constexpr int ELEMWISE_PER_BLOCK = 2048;   // elements one block of the elementwise kernels covers
 constexpr int SGD_PER_BLOCK = 4096;        // parameters one block of the update kernel covers
 

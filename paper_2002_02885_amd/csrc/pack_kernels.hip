@@ -115,76 +115,146 @@ template <int MODE> struct OperandLayout {
 // ------------------------------------------------------------------------------------------------
 // grouped MFMA GEMM
 // ------------------------------------------------------------------------------------------------
+// LDS tile of one operand: BR rows x BK reduction indices, each row padded by 16 bytes so that
+// the 16-byte fragment reads of 16 consecutive rows fall into 64 different banks.
 template <typename T, int BR>
 struct TileGeom {
     static constexpr int V = ET<T>::V;
     static constexpr int BK = ET<T>::BK;
-    static constexpr int LDS_LD = BK + V;             // 16 bytes of padding per row
-    static constexpr int SLOTS = BR * BK / V / 256;   // 16-byte vectors per thread per tile
-    static constexpr int VPR = BK / V;                // vectors per row (KC)
-    static constexpr int RPV = BR / V;                // row-vectors per reduction index (RC)
+    static constexpr int LDS_LD = BK + V;
+    static constexpr int VPR = BK / V;                 // KC: 16-byte vectors per row
+    static constexpr int KC_SLOTS = BR * BK / V / 256; // KC: vectors per thread
+    static constexpr int RPV = BR / V;                 // RC scalar fallback: row-vectors per reduction index
+    static constexpr int KQ = BK / 4;                  // RC: groups of 4 reduction indices
+    static constexpr int RC_BLOCKS = KQ * (BR / V);    // RC: (4 x V) blocks per tile, one per thread
+    static constexpr int SLOTS = 4;                    // registers reserved per operand (u32x4 each)
+    static_assert(KC_SLOTS <= SLOTS && RC_BLOCKS <= 256 && BR * BK / V / 256 >= 1, "tile too large or too small");
 };
 
+template <int MODE, typename T, bool IS_A>
+__device__ __forceinline__ const T* operand_addr(const GemmProb& p, int r, int k) {
+    if constexpr (IS_A) return addr_a<MODE, T>(p, r, k);
+    else return addr_b<MODE, T>(p, r, k);
+}
+
+// gathers V scalars into one 16-byte register group (slow path for unaligned shapes)
+template <int MODE, typename T, bool IS_A, bool KC>
+__device__ __forceinline__ u32x4_t fetch_scalars(const GemmProb& p, int r, int k, int kend) {
+    constexpr int V = ET<T>::V;
+    T tmp[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+        const int rr = KC ? r : r + e;
+        const int kk = KC ? k + e : k;
+        const T* ptr = (kk < kend) ? operand_addr<MODE, T, IS_A>(p, rr, kk) : nullptr;
+        tmp[e] = ptr ? *ptr : (T)0;
+    }
+    u32x4_t val;
+    if constexpr (sizeof(T) == 4) {
+        val.x = __float_as_uint(tmp[0]); val.y = __float_as_uint(tmp[1]);
+        val.z = __float_as_uint(tmp[2]); val.w = __float_as_uint(tmp[3]);
+    } else {
+        val.x = (unsigned)tmp[0] | ((unsigned)tmp[1] << 16);
+        val.y = (unsigned)tmp[2] | ((unsigned)tmp[3] << 16);
+        val.z = (unsigned)tmp[4] | ((unsigned)tmp[5] << 16);
+        val.w = (unsigned)tmp[6] | ((unsigned)tmp[7] << 16);
+    }
+    return val;
+}
+
+// Global -> registers.  KC operands: each thread takes 16-byte vectors along the reduction.
+// RC operands (contiguous along the row index): with `vec`, each thread takes a block of 4
+// reduction indices x V rows as four 16-byte vectors, thread index varying fastest along the
+// reduction so that the transposed LDS stores of a wave fall into distinct banks.
 template <int MODE, typename T, bool IS_A, int BR>
 __device__ __forceinline__ void fetch_tile(const GemmProb& p, int row0, int k0, int kend, bool vec,
-                                           u32x4_t (&regs)[TileGeom<T, BR>::SLOTS]) {
+                                           u32x4_t (&regs)[4]) {
     typedef TileGeom<T, BR> G;
     constexpr bool KC = IS_A ? OperandLayout<MODE>::A_KC : OperandLayout<MODE>::B_KC;
     const int tid = threadIdx.x;
+    if constexpr (KC) {
 #pragma unroll
-    for (int s = 0; s < G::SLOTS; ++s) {
-        const int vid = tid + 256 * s;
-        int r, k;
-        if constexpr (KC) {
-            r = row0 + vid / G::VPR;
-            k = k0 + (vid % G::VPR) * G::V;
-        } else {
-            k = k0 + vid / G::RPV;
-            r = row0 + (vid % G::RPV) * G::V;
-        }
-        u32x4_t val = {0u, 0u, 0u, 0u};
-        if (vec) {
-            const T* ptr = nullptr;
-            if (k < kend) ptr = IS_A ? addr_a<MODE, T>(p, r, k) : addr_b<MODE, T>(p, r, k);
-            if (ptr) val = *reinterpret_cast<const u32x4_t*>(ptr);
-        } else {
-            T tmp[G::V];
-#pragma unroll
-            for (int e = 0; e < G::V; ++e) {
-                const int rr = KC ? r : r + e;
-                const int kk = KC ? k + e : k;
-                const T* ptr = nullptr;
-                if (kk < kend) ptr = IS_A ? addr_a<MODE, T>(p, rr, kk) : addr_b<MODE, T>(p, rr, kk);
-                tmp[e] = ptr ? *ptr : (T)0;
-            }
-            if constexpr (sizeof(T) == 4) {
-                val.x = __float_as_uint(tmp[0]); val.y = __float_as_uint(tmp[1]);
-                val.z = __float_as_uint(tmp[2]); val.w = __float_as_uint(tmp[3]);
+        for (int s = 0; s < G::KC_SLOTS; ++s) {
+            const int vid = tid + 256 * s;
+            const int r = row0 + vid / G::VPR;
+            const int k = k0 + (vid % G::VPR) * G::V;
+            if (vec) {
+                const T* ptr = (k < kend) ? operand_addr<MODE, T, IS_A>(p, r, k) : nullptr;
+                regs[s] = ptr ? *reinterpret_cast<const u32x4_t*>(ptr) : u32x4_t{0u, 0u, 0u, 0u};
             } else {
-                val.x = (unsigned)tmp[0] | ((unsigned)tmp[1] << 16);
-                val.y = (unsigned)tmp[2] | ((unsigned)tmp[3] << 16);
-                val.z = (unsigned)tmp[4] | ((unsigned)tmp[5] << 16);
-                val.w = (unsigned)tmp[6] | ((unsigned)tmp[7] << 16);
+                regs[s] = fetch_scalars<MODE, T, IS_A, true>(p, r, k, kend);
             }
         }
-        regs[s] = val;
+    } else {
+        if (vec) {
+            if (tid < G::RC_BLOCKS) {
+                const int kq = tid % G::KQ, rv = tid / G::KQ;
+                const int r = row0 + rv * G::V;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int k = k0 + kq * 4 + e;
+                    const T* ptr = (k < kend) ? operand_addr<MODE, T, IS_A>(p, r, k) : nullptr;
+                    regs[e] = ptr ? *reinterpret_cast<const u32x4_t*>(ptr) : u32x4_t{0u, 0u, 0u, 0u};
+                }
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < G::KC_SLOTS; ++s) {
+                const int vid = tid + 256 * s;
+                const int k = k0 + vid / G::RPV;
+                const int r = row0 + (vid % G::RPV) * G::V;
+                regs[s] = fetch_scalars<MODE, T, IS_A, false>(p, r, k, kend);
+            }
+        }
     }
 }
 
+// Registers -> LDS, always as rows with the reduction index contiguous.
 template <int MODE, typename T, bool IS_A, int BR>
-__device__ __forceinline__ void stash_tile(T* __restrict__ Sbase,
-                                           const u32x4_t (&regs)[TileGeom<T, BR>::SLOTS]) {
+__device__ __forceinline__ void stash_tile(T* __restrict__ Sbase, bool vec, const u32x4_t (&regs)[4]) {
     typedef TileGeom<T, BR> G;
-    T(*S)[G::LDS_LD] = reinterpret_cast<T(*)[G::LDS_LD]>(Sbase);
     constexpr bool KC = IS_A ? OperandLayout<MODE>::A_KC : OperandLayout<MODE>::B_KC;
+    T(*S)[G::LDS_LD] = reinterpret_cast<T(*)[G::LDS_LD]>(Sbase);
     const int tid = threadIdx.x;
+    if constexpr (KC) {
 #pragma unroll
-    for (int s = 0; s < G::SLOTS; ++s) {
-        const int vid = tid + 256 * s;
-        if constexpr (KC) {
-            const int r = vid / G::VPR, kv = vid % G::VPR;
-            *reinterpret_cast<u32x4_t*>(&S[r][kv * G::V]) = regs[s];
-        } else {
+        for (int s = 0; s < G::KC_SLOTS; ++s) {
+            const int vid = tid + 256 * s;
+            *reinterpret_cast<u32x4_t*>(&S[vid / G::VPR][(vid % G::VPR) * G::V]) = regs[s];
+        }
+    } else if (vec) {
+        if (tid < G::RC_BLOCKS) {
+            const int kq = tid % G::KQ, rv = tid / G::KQ;
+            if constexpr (sizeof(T) == 4) {
+                // 4x4 transpose is a renaming of registers: row j gets component j of each vector
+                const u32x4_t c0 = {regs[0].x, regs[1].x, regs[2].x, regs[3].x};
+                const u32x4_t c1 = {regs[0].y, regs[1].y, regs[2].y, regs[3].y};
+                const u32x4_t c2 = {regs[0].z, regs[1].z, regs[2].z, regs[3].z};
+                const u32x4_t c3 = {regs[0].w, regs[1].w, regs[2].w, regs[3].w};
+                *reinterpret_cast<u32x4_t*>(&S[rv * 4 + 0][kq * 4]) = c0;
+                *reinterpret_cast<u32x4_t*>(&S[rv * 4 + 1][kq * 4]) = c1;
+                *reinterpret_cast<u32x4_t*>(&S[rv * 4 + 2][kq * 4]) = c2;
+                *reinterpret_cast<u32x4_t*>(&S[rv * 4 + 3][kq * 4]) = c3;
+            } else {
+                // 4 (reduction) x 8 (rows) block of 16-bit values: row j collects element j of
+                // each of the four vectors into 8 bytes
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const unsigned a0 = regs[0][d], a1 = regs[1][d], a2 = regs[2][d], a3 = regs[3][d];
+                    uint2 even, odd;
+                    even.x = (a0 & 0xffffu) | (a1 << 16);
+                    even.y = (a2 & 0xffffu) | (a3 << 16);
+                    odd.x = (a0 >> 16) | (a1 & 0xffff0000u);
+                    odd.y = (a2 >> 16) | (a3 & 0xffff0000u);
+                    *reinterpret_cast<uint2*>(&S[rv * 8 + 2 * d][kq * 4]) = even;
+                    *reinterpret_cast<uint2*>(&S[rv * 8 + 2 * d + 1][kq * 4]) = odd;
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int s = 0; s < G::KC_SLOTS; ++s) {
+            const int vid = tid + 256 * s;
             const int kk = vid / G::RPV, r = (vid % G::RPV) * G::V;
             const u32x4_t v = regs[s];
             if constexpr (sizeof(T) == 4) {
@@ -202,15 +272,18 @@ __device__ __forceinline__ void stash_tile(T* __restrict__ Sbase,
     }
 }
 
-template <int MODE, typename T>
+// One workgroup (4 waves, 2 x 2) computes a BM x BN tile of one problem.  Every output element is
+// the sum over the reduction in ascending chunks of BK, whatever BM and BN are, so the choice of
+// tile shape never changes a result bit.
+template <int MODE, typename T, int BM, int BN>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ probs,
                                                    const TileRef* __restrict__ tiles,
                                                    const void* __restrict__ x) {
-    constexpr int BM = GEMM_BM, BN = GEMM_BN;
     typedef TileGeom<T, BM> GA;
     typedef TileGeom<T, BN> GB;
     constexpr int V = ET<T>::V, BK = ET<T>::BK;
     constexpr int TM = BM / 64, TN = BN / 64;   // 32x32 MFMA blocks per wave in each direction
+    constexpr bool IS_DW = (MODE == LIN_DW || MODE == CONV_DW);
 
     const TileRef tr = tiles[blockIdx.x];
     if (tr.prob < 0) return;
@@ -229,6 +302,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
     const int kbeg = tr.ks * p.ksplit;
     const int kend = min(p.Kd, kbeg + p.ksplit);
     const bool vecA = (p.flags & F_VEC_A) != 0, vecB = (p.flags & F_VEC_B) != 0;
+    const bool do_bias_grad = IS_DW && tr.tn == 0 && p.dbias != nullptr;
 
     f32x16_t acc[TM][TN];
 #pragma unroll
@@ -237,20 +311,40 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
         for (int b = 0; b < TN; ++b)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+    float bias_grad = 0.f;
 
-    u32x4_t ra[GA::SLOTS], rb[GB::SLOTS];
+    u32x4_t ra[4], rb[4];
     if (kbeg < kend) {
         fetch_tile<MODE, T, true, BM>(p, row0, kbeg, kend, vecA, ra);
         fetch_tile<MODE, T, false, BN>(p, col0, kbeg, kend, vecB, rb);
     }
     for (int k0 = kbeg; k0 < kend; k0 += BK) {
         __syncthreads();   // all waves are done reading the previous tile
-        stash_tile<MODE, T, true, BM>(&As[0][0], ra);
-        stash_tile<MODE, T, false, BN>(&Bs[0][0], rb);
+        stash_tile<MODE, T, true, BM>(&As[0][0], vecA, ra);
+        stash_tile<MODE, T, false, BN>(&Bs[0][0], vecB, rb);
         __syncthreads();
         if (k0 + BK < kend) {   // next tile's global loads fly while this tile is multiplied
             fetch_tile<MODE, T, true, BM>(p, row0, k0 + BK, kend, vecA, ra);
             fetch_tile<MODE, T, false, BN>(p, col0, k0 + BK, kend, vecB, rb);
+        }
+        if constexpr (IS_DW) {
+            // bias gradient = sum of dz over the reduction: rows of the A tile, summed in order
+            if (do_bias_grad && threadIdx.x < BM) {
+#pragma unroll
+                for (int kk = 0; kk < BK; kk += V) {
+                    const u32x4_t v = *reinterpret_cast<const u32x4_t*>(&As[threadIdx.x][kk]);
+                    if constexpr (sizeof(T) == 4) {
+                        bias_grad += __uint_as_float(v.x); bias_grad += __uint_as_float(v.y);
+                        bias_grad += __uint_as_float(v.z); bias_grad += __uint_as_float(v.w);
+                    } else {
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            bias_grad += __uint_as_float(v[d] << 16);
+                            bias_grad += __uint_as_float(v[d] & 0xffff0000u);
+                        }
+                    }
+                }
+            }
         }
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2 * V) {
@@ -276,6 +370,11 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
                     }
                 }
         }
+    }
+
+    if constexpr (IS_DW) {
+        if (do_bias_grad && threadIdx.x < BM && row0 + (int)threadIdx.x < p.R)
+            p.dbias[(size_t)tr.ks * p.R + row0 + threadIdx.x] = bias_grad;
     }
 
     // epilogue: accumulator register e of a 32x32 block holds row 8*(e/4) + 4*(lane/32) + e%4,
@@ -317,59 +416,33 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
             }
 }
 
+template <int MODE, typename T>
+static void launch_gemm_tile(int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, hipStream_t st) {
+    switch (tile_cfg) {
+        case 0: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 128>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
+        case 1: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 64>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
+        default: hipLaunchKernelGGL((gemm_kernel<MODE, T, 64, 64>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
+    }
+}
+
 template <int MODE>
-static hipError_t launch_gemm_mode(bool bf16, const GemmProb* probs, const TileRef* tiles, int n, const void* x, hipStream_t st) {
-    if (bf16) hipLaunchKernelGGL((gemm_kernel<MODE, bf16_t>), dim3(n), dim3(256), 0, st, probs, tiles, x);
-    else hipLaunchKernelGGL((gemm_kernel<MODE, float>), dim3(n), dim3(256), 0, st, probs, tiles, x);
+static hipError_t launch_gemm_mode(bool bf16, int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, hipStream_t st) {
+    if (bf16) launch_gemm_tile<MODE, bf16_t>(tile_cfg, probs, tiles, n, x, st);
+    else launch_gemm_tile<MODE, float>(tile_cfg, probs, tiles, n, x, st);
     return hipGetLastError();
 }
 
-hipError_t launch_gemm(int mode, bool bf16, const GemmProb* probs, const TileRef* tiles, int n, const void* x, hipStream_t st) {
+hipError_t launch_gemm(int mode, bool bf16, int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, hipStream_t st) {
     if (n <= 0) return hipSuccess;
     switch (mode) {
-        case LIN_FWD: return launch_gemm_mode<LIN_FWD>(bf16, probs, tiles, n, x, st);
-        case LIN_DX: return launch_gemm_mode<LIN_DX>(bf16, probs, tiles, n, x, st);
-        case LIN_DW: return launch_gemm_mode<LIN_DW>(bf16, probs, tiles, n, x, st);
-        case CONV_FWD: return launch_gemm_mode<CONV_FWD>(bf16, probs, tiles, n, x, st);
-        case CONV_DX: return launch_gemm_mode<CONV_DX>(bf16, probs, tiles, n, x, st);
-        case CONV_DW: return launch_gemm_mode<CONV_DW>(bf16, probs, tiles, n, x, st);
+        case LIN_FWD: return launch_gemm_mode<LIN_FWD>(bf16, tile_cfg, probs, tiles, n, x, st);
+        case LIN_DX: return launch_gemm_mode<LIN_DX>(bf16, tile_cfg, probs, tiles, n, x, st);
+        case LIN_DW: return launch_gemm_mode<LIN_DW>(bf16, tile_cfg, probs, tiles, n, x, st);
+        case CONV_FWD: return launch_gemm_mode<CONV_FWD>(bf16, tile_cfg, probs, tiles, n, x, st);
+        case CONV_DX: return launch_gemm_mode<CONV_DX>(bf16, tile_cfg, probs, tiles, n, x, st);
+        case CONV_DW: return launch_gemm_mode<CONV_DW>(bf16, tile_cfg, probs, tiles, n, x, st);
         default: return hipErrorInvalidValue;
     }
-}
-
-// ------------------------------------------------------------------------------------------------
-// bias gradient: column sums of dz, fixed summation order
-// ------------------------------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(256) void colsum_kernel(const ColsumProb* __restrict__ probs, const int2* __restrict__ map) {
-    const int2 m = map[blockIdx.x];
-    const ColsumProb p = probs[m.x];
-    const int ncb = (p.N + COLSUM_COLS - 1) / COLSUM_COLS;
-    const int chunk = m.y / ncb, cb = m.y - chunk * ncb;
-    const int col = cb * COLSUM_COLS + (threadIdx.x & 63);
-    const int rl = threadIdx.x >> 6;
-    const int r0 = chunk * p.rows_per_chunk;
-    const int r1 = min(p.M, r0 + p.rows_per_chunk);
-    float s = 0.f;
-    if (col < p.N) {
-        const T* dz = (const T*)p.dz;
-        for (int r = r0 + rl; r < r1; r += 4) s += ET<T>::to_f(dz[(size_t)r * p.ld + col]);
-    }
-    __shared__ float part[4][64];
-    part[rl][threadIdx.x & 63] = s;
-    __syncthreads();
-    if (rl == 0 && col < p.N) {
-        const int c = threadIdx.x & 63;
-        const float t = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
-        p.out[(p.nchunk > 1 ? (size_t)chunk * p.N : (size_t)0) + col] = t;
-    }
-}
-
-hipError_t launch_colsum(bool bf16, const ColsumProb* probs, const int2* map, int n, hipStream_t st) {
-    if (n <= 0) return hipSuccess;
-    if (bf16) hipLaunchKernelGGL(colsum_kernel<bf16_t>, dim3(n), dim3(256), 0, st, probs, map);
-    else hipLaunchKernelGGL(colsum_kernel<float>, dim3(n), dim3(256), 0, st, probs, map);
-    return hipGetLastError();
 }
 
 // out[e] = sum over S partials, in order
