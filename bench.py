@@ -43,6 +43,9 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unpacked", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain elementwise copy of 256 MiB (reads 256 MiB, writes 256 MiB) five times, "
+                         "so that a hardware-counter run has a kernel of known traffic to scale by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the packed step has no cross-GPU part); "
@@ -132,6 +135,14 @@ def main():
         "launch_us": [[nm, round(float(t) * 1e3, 2)] for nm, t in zip(names, per_launch)],
         "roofline": roofline,
     }
+
+    if args.calibrate_copy:
+        a = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(5):
+            torch.add(a, 0.0, out=b)
+        torch.cuda.synchronize()
+        del a, b
 
     if not args.no_unpacked:
         t_seq = 0.0

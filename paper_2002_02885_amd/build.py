@@ -8,7 +8,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpack.so")
 SOURCES = ["pack_kernels.hip", "pack_api.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-         # no packed-fp32 instructions: see DESIGN.md ("build flags")
+         # do not generate packed-fp32 instructions (v_pk_*_f32)
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
