@@ -25,6 +25,18 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
+# HBM bytes per launch of the update kernel on workload c2 from hardware counters (FETCH_SIZE and
+# WRITE_SIZE, each scaled by a copy kernel of known size; profiles/c2_sgd_update_hbm_counters.txt),
+# valid only for the kernel source it was measured on (hash of the kernel's text).
+SGD_TRAFFIC = {"workload": "c2", "bytes": 471.2e6, "kernel_sha": "4a03ca8a66de6201"}
+
+
+def _sgd_kernel_sha():
+    import hashlib
+    src = open(os.path.join(ROOT, "paper_2002_02885_amd", "csrc", "pack_kernels.hip")).read()
+    a, b = src.index("template <bool SHADOW>"), src.index("hipError_t launch_sgd")
+    return hashlib.sha256(src[a:b].encode()).hexdigest()[:16]
+
 
 def _time_steps(pk, x, y, lr, steps, torch):
     torch.cuda.synchronize()
@@ -108,8 +120,14 @@ def main():
     if dom_name == "sgd_update":
         bpp = 14.0 if w.dtype == wl.BF16 else 12.0     # master r+w, gradient r, (+ bf16 copy w)
         achieved = n_params * bpp / (dom_ms * 1e-3) / 1e9
+        traffic = None
+        try:
+            if w.name == SGD_TRAFFIC["workload"] and _sgd_kernel_sha() == SGD_TRAFFIC["kernel_sha"]:
+                traffic = SGD_TRAFFIC["bytes"]
+        except (OSError, ValueError):
+            pass
         roofline = {"kernel": dom_name, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": None, "avg_ms": dom_ms,
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "avg_ms": dom_ms,
                     "algorithmic_bytes": n_params * bpp}
     else:
         # a matrix-product launch: its flops are those of the layer slot it executes
