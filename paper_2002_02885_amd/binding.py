@@ -9,7 +9,7 @@ from typing import List, Sequence, Tuple
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libpack.so")
+LIB_PATH = os.environ.get("PACK_LIB", os.path.join(_HERE, "libpack.so"))
 
 PACK_OK, PACK_EINVAL, PACK_ENOMEM, PACK_EDEVICE, PACK_ESHAPE, PACK_ELABEL = range(6)
 PACK_F32, PACK_BF16 = 0, 1

@@ -12,6 +12,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -105,6 +106,7 @@ struct pack_ctx {
     size_t desc_bytes = 0;
     int* err_flag = nullptr;
     float* loss_all = nullptr;   // [K]
+    void* zeros = nullptr;       // 256 bytes of zeros inside the slab (never written)
     std::vector<Launch> plan;
     size_t device_bytes = 0;
     // per-launch timing (off unless pack_profile_start was called)
@@ -329,6 +331,14 @@ void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<G
     // on it, so a member's bits do not depend on who else is in the launch.
     int cfg = 0;
     while (cfg < 2 && count_tiles(probs, cfg) < 512) ++cfg;
+    {   // tuning knob: PACK_GEMM_CFG_FWD / _DX / _DW = 0..2 forces the tile configuration of the
+        // linear-layer launches of that kind (results do not depend on it)
+        const char* names[3] = {"PACK_GEMM_CFG_FWD", "PACK_GEMM_CFG_DX", "PACK_GEMM_CFG_DW"};
+        if (mode <= LIN_DW) {
+            const char* v = std::getenv(names[mode]);
+            if (v && v[0] >= '0' && v[0] <= '2' && v[1] == 0) cfg = v[0] - '0';
+        }
+    }
     const int BMc = GEMM_TILE_M[cfg], BNc = GEMM_TILE_N[cfg];
     std::vector<TileOrder> logical;
     for (size_t i = 0; i < probs.size(); ++i) {
@@ -406,6 +416,7 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 continue;
             }
             GemmProb g{};
+                g.zeros = p->zeros;
             g.A = ti.is_input ? nullptr : ti.act;
             g.B = weight_ptr(nd);
             g.C = to.act;
@@ -486,6 +497,7 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
             // weight gradient
             {
                 GemmProb g{};
+                g.zeros = p->zeros;
                 g.A = to.dz;
                 g.B = ti.is_input ? nullptr : ti.act;
                 g.flags = ti.is_input ? F_B_INPUT : 0;
@@ -531,6 +543,7 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
             // input gradient
             if (ti.needs_grad) {
                 GemmProb g{};
+                g.zeros = p->zeros;
                 g.A = to.dz;
                 g.B = weight_ptr(nd);
                 g.C = ti.dz;
@@ -708,11 +721,13 @@ pack_status pack_create(const pack_input_spec* input, const pack_model_spec* mod
     }
     const size_t loss_off = reserve((size_t)K * 4);
     const size_t err_off = reserve(4);
+    const size_t zeros_off = reserve(256);
     TRY_ALLOC(p->slab, slab);
     p->slab_bytes = slab;
     for (auto& f : fix) *f.first = p->slab + f.second;
     p->loss_all = (float*)(p->slab + loss_off);
     p->err_flag = (int*)(p->slab + err_off);
+    p->zeros = p->slab + zeros_off;
     for (int k = 0; k < K; ++k) p->models[k].loss = p->loss_all + k;
 
     // size the workspace with a dry run of the planner, then build the real plan

@@ -38,6 +38,7 @@ struct GemmProb {
     void* C;
     const float* bias;
     const void* aux;
+    const void* zeros;                     // 256 bytes of zeros: what a missing operand element reads
     float* dbias;                          // weight-gradient modes: where the bias gradient goes
                                            // (split ks writes dbias[ks * R + row]); null = skip
     int R, Q, Kd;
@@ -92,7 +93,7 @@ struct ShortcutProb { // backward of the residual shortcut into the source tenso
 struct LrTable { float lr[256]; };
 
 // launch wrappers; all enqueue on `st` and return the launch status -----------------------------
-// tile_cfg: 0 = 128x128, 1 = 128x64, 2 = 64x64 output tile per workgroup
+// tile_cfg indexes GEMM_TILE_M / GEMM_TILE_N
 hipError_t launch_gemm(int mode, bool bf16, int tile_cfg, const GemmProb* probs_dev, const TileRef* tiles_dev,
                        int n_tiles, const void* x_dev, hipStream_t st);
 hipError_t launch_reduce(const ReduceProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);

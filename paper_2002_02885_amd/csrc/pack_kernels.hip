@@ -14,6 +14,8 @@
 // other members share the pack (the isolation guarantee of Section 2.2).
 #include "pack_internal.h"
 
+#include <type_traits>
+
 namespace packk {
 
 typedef unsigned short bf16_t;   // bfloat16 = upper half of an IEEE binary32
@@ -46,16 +48,19 @@ template <> struct ET<bf16_t> {
 };
 
 // ------------------------------------------------------------------------------------------------
-// operand address rules: element (row, k) of operand A / B for each mode, or null for "zero"
+// operand address rules: element (row, k) of operand A / B for each mode.  Each rule returns
+// whether the element exists (otherwise it reads as zero) and its element offset from the
+// operand's base; the offset is forced to 0 for missing elements so that the caller can always
+// issue the load (branch-free, so that many loads stay in flight) and discard the value.
 // ------------------------------------------------------------------------------------------------
-template <int MODE, typename T>
-__device__ __forceinline__ const T* addr_a(const GemmProb& p, int r, int k) {
-    if (r >= p.R || k >= p.Kd) return nullptr;
-    const T* A = (const T*)p.A;
+template <int MODE>
+__device__ __forceinline__ bool off_a(const GemmProb& p, int r, int k, size_t& off) {
+    bool ok = (r < p.R) && (k < p.Kd);
+    size_t o;
     if constexpr (MODE == LIN_FWD || MODE == LIN_DX) {
-        return A + (size_t)r * p.lda + k;
+        o = (size_t)r * p.lda + k;
     } else if constexpr (MODE == LIN_DW || MODE == CONV_DW) {
-        return A + (size_t)k * p.lda + r;
+        o = (size_t)k * p.lda + r;
     } else if constexpr (MODE == CONV_FWD) {
         const int hw = p.Ho * p.Wo;
         const int b = r / hw, rem = r - b * hw;
@@ -63,37 +68,39 @@ __device__ __forceinline__ const T* addr_a(const GemmProb& p, int r, int k) {
         const int tap = k / p.Cin, c = k - tap * p.Cin;
         const int u = tap / 3, v = tap - 3 * u;
         const int y = p.stride * i + u - 1, x = p.stride * j + v - 1;
-        if ((unsigned)y >= (unsigned)p.H || (unsigned)x >= (unsigned)p.W) return nullptr;
-        return A + ((size_t)(b * p.H + y) * p.W + x) * p.Cin + c;
+        ok = ok && ((unsigned)y < (unsigned)p.H) && ((unsigned)x < (unsigned)p.W);
+        o = ((size_t)(b * p.H + y) * p.W + x) * p.Cin + c;
     } else {  // CONV_DX: row = input pixel (b, y, x), k = (tap, o)
         const int hw = p.H * p.W;
         const int b = r / hw, rem = r - b * hw;
         const int y = rem / p.W, x = rem - y * p.W;
-        const int tap = k / p.Cout, o = k - tap * p.Cout;
+        const int tap = k / p.Cout, oc = k - tap * p.Cout;
         const int u = tap / 3, v = tap - 3 * u;
         int ty = y + 1 - u, tx = x + 1 - v;
-        if (ty < 0 || tx < 0) return nullptr;
+        ok = ok && (ty >= 0) && (tx >= 0);
         if (p.stride == 2) {
-            if ((ty | tx) & 1) return nullptr;
+            ok = ok && (((ty | tx) & 1) == 0);
             ty >>= 1;
             tx >>= 1;
         }
-        if (ty >= p.Ho || tx >= p.Wo) return nullptr;
-        return A + ((size_t)(b * p.Ho + ty) * p.Wo + tx) * p.Cout + o;
+        ok = ok && (ty < p.Ho) && (tx < p.Wo);
+        o = ((size_t)(b * p.Ho + ty) * p.Wo + tx) * p.Cout + oc;
     }
+    off = ok ? o : (size_t)0;
+    return ok;
 }
 
-template <int MODE, typename T>
-__device__ __forceinline__ const T* addr_b(const GemmProb& p, int q, int k) {
-    if (q >= p.Q || k >= p.Kd) return nullptr;
-    const T* B = (const T*)p.B;
+template <int MODE>
+__device__ __forceinline__ bool off_b(const GemmProb& p, int q, int k, size_t& off) {
+    bool ok = (q < p.Q) && (k < p.Kd);
+    size_t o;
     if constexpr (MODE == LIN_FWD || MODE == CONV_FWD) {
-        return B + (size_t)q * p.ldb + k;
+        o = (size_t)q * p.ldb + k;
     } else if constexpr (MODE == LIN_DX || MODE == LIN_DW) {
-        return B + (size_t)k * p.ldb + q;
+        o = (size_t)k * p.ldb + q;
     } else if constexpr (MODE == CONV_DX) {   // q = input channel c, k = (tap, o); W is [Cout][9][Cin]
-        const int tap = k / p.Cout, o = k - tap * p.Cout;
-        return B + ((size_t)o * 9 + tap) * p.Cin + q;
+        const int tap = k / p.Cout, oc = k - tap * p.Cout;
+        o = ((size_t)oc * 9 + tap) * p.Cin + q;
     } else {  // CONV_DW: q = (tap, c), k = output pixel (b, i, j)
         const int tap = q / p.Cin, c = q - tap * p.Cin;
         const int u = tap / 3, v = tap - 3 * u;
@@ -101,9 +108,11 @@ __device__ __forceinline__ const T* addr_b(const GemmProb& p, int q, int k) {
         const int b = k / hw, rem = k - b * hw;
         const int i = rem / p.Wo, j = rem - i * p.Wo;
         const int y = p.stride * i + u - 1, x = p.stride * j + v - 1;
-        if ((unsigned)y >= (unsigned)p.H || (unsigned)x >= (unsigned)p.W) return nullptr;
-        return B + ((size_t)(b * p.H + y) * p.W + x) * p.Cin + c;
+        ok = ok && ((unsigned)y < (unsigned)p.H) && ((unsigned)x < (unsigned)p.W);
+        o = ((size_t)(b * p.H + y) * p.W + x) * p.Cin + c;
     }
+    off = ok ? o : (size_t)0;
+    return ok;
 }
 
 // Which operands are contiguous along the reduction (KC) and which along their row index (RC).
@@ -117,37 +126,103 @@ template <int MODE> struct OperandLayout {
 // ------------------------------------------------------------------------------------------------
 // LDS tile of one operand: BR rows x BK reduction indices, each row padded by 16 bytes so that
 // the 16-byte fragment reads of 16 consecutive rows fall into 64 different banks.
-template <typename T, int BR>
+template <typename T, int BR, int BK_>
 struct TileGeom {
     static constexpr int V = ET<T>::V;
-    static constexpr int BK = ET<T>::BK;
+    static constexpr int BK = BK_;
     static constexpr int LDS_LD = BK + V;
     static constexpr int VPR = BK / V;                 // KC: 16-byte vectors per row
-    static constexpr int KC_SLOTS = BR * BK / V / 256; // KC: vectors per thread
-    static constexpr int RPV = BR / V;                 // RC scalar fallback: row-vectors per reduction index
-    static constexpr int KQ = BK / 4;                  // RC: groups of 4 reduction indices
-    static constexpr int RC_BLOCKS = KQ * (BR / V);    // RC: (4 x V) blocks per tile, one per thread
-    static constexpr int SLOTS = 4;                    // registers reserved per operand (u32x4 each)
-    static_assert(KC_SLOTS <= SLOTS && RC_BLOCKS <= 256 && BR * BK / V / 256 >= 1, "tile too large or too small");
+    static constexpr int NVEC = BR * BK / V;           // 16-byte vectors per tile
+    static constexpr int KC_SLOTS = (NVEC + 255) / 256;// vectors per thread
+    static constexpr int RPV = BR / V;                 // row-vectors per reduction index
+    // RC operands are moved as blocks of 4 reduction indices x V rows (four vectors per block).
+    // Block b: kq_lo = b % 16 (fastest, so that the transposed LDS stores of neighbouring lanes
+    // fall into different banks), rv = (b / 16) % RPV, kq_hi = b / (16 * RPV).
+    static constexpr int RC_BLOCKS = NVEC / 4;
+    static constexpr int RC_PER_THREAD = (RC_BLOCKS + 255) / 256;
+    static constexpr int NREG = (KC_SLOTS > 4 * RC_PER_THREAD) ? KC_SLOTS : 4 * RC_PER_THREAD;
+    static_assert(BK % 64 == 0 || sizeof(T) == 4, "bf16 tiles hold multiples of 64 reduction indices");
+    static_assert(BK % (16 * 4) == 0 || BK % 32 == 0, "reduction extent");
 };
 
+// bit m set: GEMM mode m issues its operand loads as assembly statements with hand-placed
+// waits (see load_vec); clear: ordinary loads, waits left to the compiler
+#ifndef PACK_ASM_MODES
+#define PACK_ASM_MODES 63
+#endif
+
+typedef const __attribute__((address_space(1))) u32x4_t* gvec_ptr;
+typedef const __attribute__((address_space(1))) unsigned short* gu16_ptr;
+typedef const __attribute__((address_space(1))) float* gf32_ptr;
+
+// One 16-byte vector of operand A or B at (r, k), zero where the element does not exist.  The
+// load is unconditional: a missing element is fetched from the problem's block of zeros, so
+// nothing has to look at the loaded value until it is stored to LDS and the load can stay in
+// flight across the multiplication of earlier chunks.
+// The load is written as an assembly statement on purpose: the compiler does not count it as
+// outstanding memory traffic, so it inserts no wait for it (left to itself it drains every
+// outstanding load once per unrolled group of chunks, which serialises the pipeline).  The
+// matching wait is wait_stage() below; loads of one type return in issue order, so "at most N
+// newer loads outstanding" implies that a stage issued before those N has landed.
+// `live` = false (a thread with no element of the tile) still issues the load, from the zeros
+// block: every wave must issue the same number of loads per chunk for the count to be right.
 template <int MODE, typename T, bool IS_A>
-__device__ __forceinline__ const T* operand_addr(const GemmProb& p, int r, int k) {
-    if constexpr (IS_A) return addr_a<MODE, T>(p, r, k);
-    else return addr_b<MODE, T>(p, r, k);
+__device__ __forceinline__ u32x4_t load_vec(const GemmProb& p, int r, int k, int kend, bool live = true) {
+    size_t off;
+    bool ok = IS_A ? off_a<MODE>(p, r, k, off) : off_b<MODE>(p, r, k, off);
+    ok = ok && (k < kend) && live;
+    const T* base = (const T*)(IS_A ? p.A : p.B);
+    const void* ptr = ok ? (const void*)(base + off) : p.zeros;
+    if constexpr ((PACK_ASM_MODES >> MODE) & 1) {
+        u32x4_t v;
+        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(ptr) : "memory");
+        return v;
+    } else {
+        return *(gvec_ptr)ptr;
+    }
+}
+
+// number of load_vec() calls fetch_tile<..., VEC = true> makes per thread and chunk
+template <int MODE, typename T, bool IS_A, int BR, int BK>
+struct LoadsPerChunk {
+    typedef TileGeom<T, BR, BK> G;
+    static constexpr bool KC = IS_A ? OperandLayout<MODE>::A_KC : OperandLayout<MODE>::B_KC;
+    static constexpr int value = KC ? G::KC_SLOTS : 4 * G::RC_PER_THREAD;
+};
+
+// Blocks until at most NEWER asm loads issued after the given registers' loads are outstanding.
+// The registers are in-out operands so that nothing that reads them can move above the wait.
+template <int NEWER, int N>
+__device__ __forceinline__ void wait_stage(u32x4_t (&regs)[N]) {
+    static_assert(NEWER >= 0 && NEWER < 64, "vmcnt is a 6-bit counter");
+    if constexpr (N == 1) asm volatile("s_waitcnt vmcnt(%1)" : "+v"(regs[0]) : "n"(NEWER));
+    else if constexpr (N == 2) asm volatile("s_waitcnt vmcnt(%2)" : "+v"(regs[0]), "+v"(regs[1]) : "n"(NEWER));
+    else if constexpr (N == 4)
+        asm volatile("s_waitcnt vmcnt(%4)" : "+v"(regs[0]), "+v"(regs[1]), "+v"(regs[2]), "+v"(regs[3]) : "n"(NEWER));
+    else if constexpr (N == 8)
+        asm volatile("s_waitcnt vmcnt(%8)"
+                     : "+v"(regs[0]), "+v"(regs[1]), "+v"(regs[2]), "+v"(regs[3]), "+v"(regs[4]), "+v"(regs[5]),
+                       "+v"(regs[6]), "+v"(regs[7])
+                     : "n"(NEWER));
+    else static_assert(N == 1 || N == 2 || N == 4 || N == 8, "unsupported register count");
 }
 
 // gathers V scalars into one 16-byte register group (slow path for unaligned shapes)
 template <int MODE, typename T, bool IS_A, bool KC>
 __device__ __forceinline__ u32x4_t fetch_scalars(const GemmProb& p, int r, int k, int kend) {
     constexpr int V = ET<T>::V;
+    const T* base = (const T*)(IS_A ? p.A : p.B);
     T tmp[V];
 #pragma unroll
     for (int e = 0; e < V; ++e) {
         const int rr = KC ? r : r + e;
         const int kk = KC ? k + e : k;
-        const T* ptr = (kk < kend) ? operand_addr<MODE, T, IS_A>(p, rr, kk) : nullptr;
-        tmp[e] = ptr ? *ptr : (T)0;
+        size_t off;
+        bool ok = IS_A ? off_a<MODE>(p, rr, kk, off) : off_b<MODE>(p, rr, kk, off);
+        ok = ok && (kk < kend);
+        const void* ptr = ok ? (const void*)(base + off) : p.zeros;
+        if constexpr (sizeof(T) == 4) tmp[e] = *(gf32_ptr)ptr;
+        else tmp[e] = *(gu16_ptr)ptr;
     }
     u32x4_t val;
     if constexpr (sizeof(T) == 4) {
@@ -162,14 +237,23 @@ __device__ __forceinline__ u32x4_t fetch_scalars(const GemmProb& p, int r, int k
     return val;
 }
 
+template <typename G>
+__device__ __forceinline__ void rc_block_coords(int b, int& kq, int& rv) {
+    constexpr int KQ_LO = (G::BK / 4 < 16) ? G::BK / 4 : 16;
+    const int lo = b % KQ_LO;
+    const int rest = b / KQ_LO;
+    rv = rest % G::RPV;
+    kq = (rest / G::RPV) * KQ_LO + lo;
+}
+
 // Global -> registers.  KC operands: each thread takes 16-byte vectors along the reduction.
-// RC operands (contiguous along the row index): with `vec`, each thread takes a block of 4
-// reduction indices x V rows as four 16-byte vectors, thread index varying fastest along the
-// reduction so that the transposed LDS stores of a wave fall into distinct banks.
-template <int MODE, typename T, bool IS_A, int BR>
-__device__ __forceinline__ void fetch_tile(const GemmProb& p, int row0, int k0, int kend, bool vec,
-                                           u32x4_t (&regs)[4]) {
-    typedef TileGeom<T, BR> G;
+// RC operands (contiguous along the row index): with `vec`, each thread takes blocks of 4
+// reduction indices x V rows as four 16-byte vectors each.
+template <int MODE, typename T, bool IS_A, int BR, int BK, bool VEC>
+__device__ __forceinline__ void fetch_tile(const GemmProb& p, int row0, int k0, int kend,
+                                           u32x4_t (&regs)[TileGeom<T, BR, BK>::NREG]) {
+    constexpr bool vec = VEC;
+    typedef TileGeom<T, BR, BK> G;
     constexpr bool KC = IS_A ? OperandLayout<MODE>::A_KC : OperandLayout<MODE>::B_KC;
     const int tid = threadIdx.x;
     if constexpr (KC) {
@@ -179,28 +263,30 @@ __device__ __forceinline__ void fetch_tile(const GemmProb& p, int row0, int k0, 
             const int r = row0 + vid / G::VPR;
             const int k = k0 + (vid % G::VPR) * G::V;
             if (vec) {
-                const T* ptr = (k < kend) ? operand_addr<MODE, T, IS_A>(p, r, k) : nullptr;
-                regs[s] = ptr ? *reinterpret_cast<const u32x4_t*>(ptr) : u32x4_t{0u, 0u, 0u, 0u};
+                regs[s] = load_vec<MODE, T, IS_A>(p, r, k, kend, vid < G::NVEC);
             } else {
+                if (G::NVEC % 256 != 0 && vid >= G::NVEC) break;
                 regs[s] = fetch_scalars<MODE, T, IS_A, true>(p, r, k, kend);
             }
         }
     } else {
         if (vec) {
-            if (tid < G::RC_BLOCKS) {
-                const int kq = tid % G::KQ, rv = tid / G::KQ;
+#pragma unroll
+            for (int j = 0; j < G::RC_PER_THREAD; ++j) {
+                const int b = tid + 256 * j;
+                int kq, rv;
+                rc_block_coords<G>(b, kq, rv);
                 const int r = row0 + rv * G::V;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const int k = k0 + kq * 4 + e;
-                    const T* ptr = (k < kend) ? operand_addr<MODE, T, IS_A>(p, r, k) : nullptr;
-                    regs[e] = ptr ? *reinterpret_cast<const u32x4_t*>(ptr) : u32x4_t{0u, 0u, 0u, 0u};
+                    regs[4 * j + e] = load_vec<MODE, T, IS_A>(p, r, k0 + kq * 4 + e, kend, b < G::RC_BLOCKS);
                 }
             }
         } else {
 #pragma unroll
             for (int s = 0; s < G::KC_SLOTS; ++s) {
                 const int vid = tid + 256 * s;
+                if (G::NVEC % 256 != 0 && vid >= G::NVEC) break;
                 const int k = k0 + vid / G::RPV;
                 const int r = row0 + (vid % G::RPV) * G::V;
                 regs[s] = fetch_scalars<MODE, T, IS_A, false>(p, r, k, kend);
@@ -210,9 +296,11 @@ __device__ __forceinline__ void fetch_tile(const GemmProb& p, int row0, int k0, 
 }
 
 // Registers -> LDS, always as rows with the reduction index contiguous.
-template <int MODE, typename T, bool IS_A, int BR>
-__device__ __forceinline__ void stash_tile(T* __restrict__ Sbase, bool vec, const u32x4_t (&regs)[4]) {
-    typedef TileGeom<T, BR> G;
+template <int MODE, typename T, bool IS_A, int BR, int BK, bool VEC>
+__device__ __forceinline__ void stash_tile(T* __restrict__ Sbase,
+                                           const u32x4_t (&regs)[TileGeom<T, BR, BK>::NREG]) {
+    constexpr bool vec = VEC;
+    typedef TileGeom<T, BR, BK> G;
     constexpr bool KC = IS_A ? OperandLayout<MODE>::A_KC : OperandLayout<MODE>::B_KC;
     T(*S)[G::LDS_LD] = reinterpret_cast<T(*)[G::LDS_LD]>(Sbase);
     const int tid = threadIdx.x;
@@ -220,27 +308,29 @@ __device__ __forceinline__ void stash_tile(T* __restrict__ Sbase, bool vec, cons
 #pragma unroll
         for (int s = 0; s < G::KC_SLOTS; ++s) {
             const int vid = tid + 256 * s;
+            if (G::NVEC % 256 != 0 && vid >= G::NVEC) break;
             *reinterpret_cast<u32x4_t*>(&S[vid / G::VPR][(vid % G::VPR) * G::V]) = regs[s];
         }
     } else if (vec) {
-        if (tid < G::RC_BLOCKS) {
-            const int kq = tid % G::KQ, rv = tid / G::KQ;
+#pragma unroll
+        for (int j = 0; j < G::RC_PER_THREAD; ++j) {
+            const int b = tid + 256 * j;
+            if (G::RC_BLOCKS % 256 != 0 && b >= G::RC_BLOCKS) break;
+            int kq, rv;
+            rc_block_coords<G>(b, kq, rv);
+            const u32x4_t r0 = regs[4 * j], r1 = regs[4 * j + 1], r2 = regs[4 * j + 2], r3 = regs[4 * j + 3];
             if constexpr (sizeof(T) == 4) {
-                // 4x4 transpose is a renaming of registers: row j gets component j of each vector
-                const u32x4_t c0 = {regs[0].x, regs[1].x, regs[2].x, regs[3].x};
-                const u32x4_t c1 = {regs[0].y, regs[1].y, regs[2].y, regs[3].y};
-                const u32x4_t c2 = {regs[0].z, regs[1].z, regs[2].z, regs[3].z};
-                const u32x4_t c3 = {regs[0].w, regs[1].w, regs[2].w, regs[3].w};
-                *reinterpret_cast<u32x4_t*>(&S[rv * 4 + 0][kq * 4]) = c0;
-                *reinterpret_cast<u32x4_t*>(&S[rv * 4 + 1][kq * 4]) = c1;
-                *reinterpret_cast<u32x4_t*>(&S[rv * 4 + 2][kq * 4]) = c2;
-                *reinterpret_cast<u32x4_t*>(&S[rv * 4 + 3][kq * 4]) = c3;
+                // 4x4 transpose is a renaming of registers: row i gets component i of each vector
+                *reinterpret_cast<u32x4_t*>(&S[rv * 4 + 0][kq * 4]) = u32x4_t{r0.x, r1.x, r2.x, r3.x};
+                *reinterpret_cast<u32x4_t*>(&S[rv * 4 + 1][kq * 4]) = u32x4_t{r0.y, r1.y, r2.y, r3.y};
+                *reinterpret_cast<u32x4_t*>(&S[rv * 4 + 2][kq * 4]) = u32x4_t{r0.z, r1.z, r2.z, r3.z};
+                *reinterpret_cast<u32x4_t*>(&S[rv * 4 + 3][kq * 4]) = u32x4_t{r0.w, r1.w, r2.w, r3.w};
             } else {
-                // 4 (reduction) x 8 (rows) block of 16-bit values: row j collects element j of
+                // 4 (reduction) x 8 (rows) block of 16-bit values: row i collects element i of
                 // each of the four vectors into 8 bytes
 #pragma unroll
                 for (int d = 0; d < 4; ++d) {
-                    const unsigned a0 = regs[0][d], a1 = regs[1][d], a2 = regs[2][d], a3 = regs[3][d];
+                    const unsigned a0 = r0[d], a1 = r1[d], a2 = r2[d], a3 = r3[d];
                     uint2 even, odd;
                     even.x = (a0 & 0xffffu) | (a1 << 16);
                     even.y = (a2 & 0xffffu) | (a3 << 16);
@@ -255,6 +345,7 @@ __device__ __forceinline__ void stash_tile(T* __restrict__ Sbase, bool vec, cons
 #pragma unroll
         for (int s = 0; s < G::KC_SLOTS; ++s) {
             const int vid = tid + 256 * s;
+            if (G::NVEC % 256 != 0 && vid >= G::NVEC) break;
             const int kk = vid / G::RPV, r = (vid % G::RPV) * G::V;
             const u32x4_t v = regs[s];
             if constexpr (sizeof(T) == 4) {
@@ -273,35 +364,36 @@ __device__ __forceinline__ void stash_tile(T* __restrict__ Sbase, bool vec, cons
 }
 
 // One workgroup (4 waves, 2 x 2) computes a BM x BN tile of one problem.  Every output element is
-// the sum over the reduction in ascending chunks of BK, whatever BM and BN are, so the choice of
-// tile shape never changes a result bit.
-template <int MODE, typename T, int BM, int BN>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ probs,
-                                                   const TileRef* __restrict__ tiles,
-                                                   const void* __restrict__ x) {
-    typedef TileGeom<T, BM> GA;
-    typedef TileGeom<T, BN> GB;
-    constexpr int V = ET<T>::V, BK = ET<T>::BK;
+// the sum over the reduction in ascending order, sixteen (bf16) or two (fp32) indices per MFMA,
+// whatever BM, BN and the LDS chunk BK are, so the choice of tile shape never changes a result bit.
+// BKM scales the LDS chunk: skinny problems (few rows, long reduction) are bound by the latency
+// of one global round trip per chunk, so they take chunks four times as long.
+template <int BM, int BN, int BKM>
+struct StageCount {   // register stages of prefetch per tile shape (bounded by the register file)
+    static constexpr int value = (BKM > 1) ? 2 : ((BM * BN >= 128 * 128) ? 2 : ((BM * BN >= 128 * 64) ? 3 : 4));
+};
+
+template <int MODE, typename T, int BM, int BN, int BKM, bool VEC>
+__device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, T* __restrict__ As_, T* __restrict__ Bs_) {
+    constexpr int V = ET<T>::V, BK = ET<T>::BK * BKM;
+    typedef TileGeom<T, BM, BK> GA;
+    typedef TileGeom<T, BN, BK> GB;
     constexpr int TM = BM / 64, TN = BN / 64;   // 32x32 MFMA blocks per wave in each direction
     constexpr bool IS_DW = (MODE == LIN_DW || MODE == CONV_DW);
-
-    const TileRef tr = tiles[blockIdx.x];
-    if (tr.prob < 0) return;
-    GemmProb p = probs[tr.prob];
-    // the shared input batch (Section 3.4) arrives per step; every member's first layer reads it
-    if (p.flags & F_A_INPUT) p.A = x;
-    if (p.flags & F_B_INPUT) p.B = x;
-    if (p.flags & F_AUX_INPUT) p.aux = x;
-
-    __shared__ __attribute__((aligned(16))) T As[BM][GA::LDS_LD];
-    __shared__ __attribute__((aligned(16))) T Bs[BN][GB::LDS_LD];
+    // Two LDS buffers (one barrier per chunk) and ST register stages: the global loads of chunk
+    // i + ST - 1 are issued before chunk i is multiplied, so ST - 1 round trips to memory are in
+    // flight per workgroup; a skinny layer has too few workgroups per compute unit to hide that
+    // latency by occupancy alone.
+    constexpr int ST = StageCount<BM, BN, BKM>::value;
+    T(*As)[BM][GA::LDS_LD] = reinterpret_cast<T(*)[BM][GA::LDS_LD]>(As_);
+    T(*Bs)[BN][GB::LDS_LD] = reinterpret_cast<T(*)[BN][GB::LDS_LD]>(Bs_);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int row0 = tr.tm * BM, col0 = tr.tn * BN;
     const int kbeg = tr.ks * p.ksplit;
     const int kend = min(p.Kd, kbeg + p.ksplit);
-    const bool vecA = (p.flags & F_VEC_A) != 0, vecB = (p.flags & F_VEC_B) != 0;
+    const int nk = (kend - kbeg + BK - 1) / BK;
     const bool do_bias_grad = IS_DW && tr.tn == 0 && p.dbias != nullptr;
 
     f32x16_t acc[TM][TN];
@@ -313,26 +405,47 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
             for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
     float bias_grad = 0.f;
 
-    u32x4_t ra[4], rb[4];
-    if (kbeg < kend) {
-        fetch_tile<MODE, T, true, BM>(p, row0, kbeg, kend, vecA, ra);
-        fetch_tile<MODE, T, false, BN>(p, col0, kbeg, kend, vecB, rb);
+    u32x4_t ra[ST][GA::NREG], rb[ST][GB::NREG];
+#pragma unroll
+    for (int s = 0; s < ST - 1; ++s) {
+        // always issued: a chunk beyond the reduction reads the block of zeros.  Keeping the
+        // loads unconditional keeps the loop body free of branches, which is what lets the
+        // compiler wait for the oldest stage only.
+        fetch_tile<MODE, T, true, BM, BK, VEC>(p, row0, kbeg + s * BK, kend, ra[s]);
+        fetch_tile<MODE, T, false, BN, BK, VEC>(p, col0, kbeg + s * BK, kend, rb[s]);
+        __builtin_amdgcn_sched_barrier(0);   // keep the stages' loads in issue order
     }
-    for (int k0 = kbeg; k0 < kend; k0 += BK) {
-        __syncthreads();   // all waves are done reading the previous tile
-        stash_tile<MODE, T, true, BM>(&As[0][0], vecA, ra);
-        stash_tile<MODE, T, false, BN>(&Bs[0][0], vecB, rb);
-        __syncthreads();
-        if (k0 + BK < kend) {   // next tile's global loads fly while this tile is multiplied
-            fetch_tile<MODE, T, true, BM>(p, row0, k0 + BK, kend, vecA, ra);
-            fetch_tile<MODE, T, false, BN>(p, col0, k0 + BK, kend, vecB, rb);
+    // one chunk: (optionally) issue the loads of chunk it + ST - 1 into the stage that has just
+    // been consumed, store stage S to LDS buffer it & 1, barrier, multiply
+    constexpr int LOADS = LoadsPerChunk<MODE, T, true, BM, BK>::value + LoadsPerChunk<MODE, T, false, BN, BK>::value;
+    auto chunk = [&](auto S, const int it, auto FETCH) {
+        constexpr int s = decltype(S)::value;
+        constexpr bool fetching = decltype(FETCH)::value;
+        if constexpr (fetching) {
+            fetch_tile<MODE, T, true, BM, BK, VEC>(p, row0, kbeg + (it + ST - 1) * BK, kend, ra[(s + ST - 1) % ST]);
+            fetch_tile<MODE, T, false, BN, BK, VEC>(p, col0, kbeg + (it + ST - 1) * BK, kend, rb[(s + ST - 1) % ST]);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        T(*Ab)[GA::LDS_LD] = As[it & 1];
+        T(*Bb)[GB::LDS_LD] = Bs[it & 1];
+        if constexpr (VEC && ((PACK_ASM_MODES >> MODE) & 1)) {
+            // steady state: ST - 1 newer stages are in flight behind stage s; in the tail (no
+            // more loads are issued) simply drain everything
+            constexpr int NEWER = fetching ? (ST - 1) * LOADS : 0;
+            wait_stage<NEWER>(ra[s]);
+            wait_stage<NEWER>(rb[s]);
+        }
+        // buffer it&1 was last read while chunk it-2 was multiplied; every wave has passed the
+        // barrier of chunk it-1 since, so it is free
+        stash_tile<MODE, T, true, BM, BK, VEC>(&Ab[0][0], ra[s]);
+        stash_tile<MODE, T, false, BN, BK, VEC>(&Bb[0][0], rb[s]);
+        __syncthreads();
         if constexpr (IS_DW) {
             // bias gradient = sum of dz over the reduction: rows of the A tile, summed in order
             if (do_bias_grad && threadIdx.x < BM) {
 #pragma unroll
                 for (int kk = 0; kk < BK; kk += V) {
-                    const u32x4_t v = *reinterpret_cast<const u32x4_t*>(&As[threadIdx.x][kk]);
+                    const u32x4_t v = *reinterpret_cast<const u32x4_t*>(&Ab[threadIdx.x][kk]);
                     if constexpr (sizeof(T) == 4) {
                         bias_grad += __uint_as_float(v.x); bias_grad += __uint_as_float(v.y);
                         bias_grad += __uint_as_float(v.z); bias_grad += __uint_as_float(v.w);
@@ -351,10 +464,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
             u32x4_t fa[TM], fb[TN];
 #pragma unroll
             for (int a = 0; a < TM; ++a)
-                fa[a] = *reinterpret_cast<const u32x4_t*>(&As[wm * (BM / 2) + a * 32 + (lane & 31)][kk + (lane >> 5) * V]);
+                fa[a] = *reinterpret_cast<const u32x4_t*>(&Ab[wm * (BM / 2) + a * 32 + (lane & 31)][kk + (lane >> 5) * V]);
 #pragma unroll
             for (int b = 0; b < TN; ++b)
-                fb[b] = *reinterpret_cast<const u32x4_t*>(&Bs[wn * (BN / 2) + b * 32 + (lane & 31)][kk + (lane >> 5) * V]);
+                fb[b] = *reinterpret_cast<const u32x4_t*>(&Bb[wn * (BN / 2) + b * 32 + (lane & 31)][kk + (lane >> 5) * V]);
 #pragma unroll
             for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -370,6 +483,27 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
                     }
                 }
         }
+    };
+    using std::integral_constant;
+    typedef integral_constant<bool, true> Yes;
+    typedef integral_constant<bool, false> No;
+    // full groups of ST chunks: a branch-free body, so that the compiler waits only for the
+    // oldest register stage; then up to ST - 1 remaining chunks, which need no further loads
+    int it0 = 0;
+    for (; it0 + ST <= nk; it0 += ST) {
+        chunk(integral_constant<int, 0>{}, it0, Yes{});
+        if constexpr (ST > 1) chunk(integral_constant<int, 1 % ST>{}, it0 + 1, Yes{});
+        if constexpr (ST > 2) chunk(integral_constant<int, 2 % ST>{}, it0 + 2, Yes{});
+        if constexpr (ST > 3) chunk(integral_constant<int, 3 % ST>{}, it0 + 3, Yes{});
+    }
+    if (it0 < nk) chunk(integral_constant<int, 0>{}, it0, No{});
+    if constexpr (ST > 2) { if (it0 + 1 < nk) chunk(integral_constant<int, 1 % ST>{}, it0 + 1, No{}); }
+    if constexpr (ST > 3) { if (it0 + 2 < nk) chunk(integral_constant<int, 2 % ST>{}, it0 + 2, No{}); }
+    if constexpr (VEC && ((PACK_ASM_MODES >> MODE) & 1)) {
+        // The last full group prefetched chunks beyond the reduction (reads of the zeros block).
+        // Those loads are invisible to the compiler and still target the stage registers, which
+        // it is about to reuse for the epilogue: drain them first.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
 
     if constexpr (IS_DW) {
@@ -416,12 +550,31 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
             }
 }
 
+template <int MODE, typename T, int BM, int BN, int BKM>
+__global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ probs,
+                                                   const TileRef* __restrict__ tiles,
+                                                   const void* __restrict__ x) {
+    constexpr int BK = ET<T>::BK * BKM;
+    const TileRef tr = tiles[blockIdx.x];
+    if (tr.prob < 0) return;
+    GemmProb p = probs[tr.prob];
+    // the shared input batch (Section 3.4) arrives per step; every member's first layer reads it
+    if (p.flags & F_A_INPUT) p.A = x;
+    if (p.flags & F_B_INPUT) p.B = x;
+    if (p.flags & F_AUX_INPUT) p.aux = x;
+    __shared__ __attribute__((aligned(16))) T As[2 * BM * TileGeom<T, BM, BK>::LDS_LD];
+    __shared__ __attribute__((aligned(16))) T Bs[2 * BN * TileGeom<T, BN, BK>::LDS_LD];
+    // aligned shapes take 16-byte loads for both operands; anything else takes the scalar gather
+    if ((p.flags & F_VEC_A) && (p.flags & F_VEC_B)) gemm_body<MODE, T, BM, BN, BKM, true>(p, tr, As, Bs);
+    else gemm_body<MODE, T, BM, BN, BKM, false>(p, tr, As, Bs);
+}
+
 template <int MODE, typename T>
 static void launch_gemm_tile(int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, hipStream_t st) {
     switch (tile_cfg) {
-        case 0: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 128>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
-        case 1: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 64>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
-        default: hipLaunchKernelGGL((gemm_kernel<MODE, T, 64, 64>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
+        case 0: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 128, 1>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
+        case 1: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 64, 1>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
+        default: hipLaunchKernelGGL((gemm_kernel<MODE, T, 64, 64, 1>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
     }
 }
 
