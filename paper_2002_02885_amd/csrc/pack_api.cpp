@@ -300,17 +300,21 @@ struct DescBuilder {
 
 struct TileOrder { int prob, tm, tn, ks; };
 
-// Places logical tile t on the workgroup index that the hardware's round-robin distribution of
-// workgroups over the 8 XCDs sends to XCD t / (n/8): neighbours in the logical order (which share
-// an operand tile) then share one XCD's L2.
+// Hardware deals consecutive workgroup indices round-robin over the 8 XCDs, each with its own L2.
+// Logical neighbours (which share an operand tile) are kept together in runs of XCD_RUN tiles on
+// one XCD; runs are dealt over the XCDs in rotation so that problems of different cost in one
+// launch spread evenly instead of landing on one XCD each.
+constexpr size_t XCD_RUN = 8;
 std::vector<TileRef> xcd_order(const std::vector<TileOrder>& logical) {
-    const size_t n = align_up(std::max<size_t>(logical.size(), 1), 8);
-    const size_t per = n / 8;
+    const size_t n = align_up(std::max<size_t>(logical.size(), 1), 8 * XCD_RUN);
     std::vector<TileRef> out(n, TileRef{-1, 0, 0, 0});
     for (size_t t = 0; t < logical.size(); ++t) {
-        const size_t xcd = t / per, slot = t % per;
+        const size_t run = t / XCD_RUN, in_run = t % XCD_RUN;
+        const size_t xcd = run % 8, slot = (run / 8) * XCD_RUN + in_run;
         out[slot * 8 + xcd] = TileRef{logical[t].prob, logical[t].tm, logical[t].tn, logical[t].ks};
     }
+    while (out.size() > 8 && std::all_of(out.end() - 8, out.end(), [](const TileRef& r) { return r.prob < 0; }))
+        out.resize(out.size() - 8);
     return out;
 }
 
@@ -469,15 +473,19 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
     // ---------------- backward ----------------
     for (ModelInfo& m : p->models)
         for (TensorInfo& t : m.tensors) t.grad_written = false;
+    // Weight gradients need only dz and the stored activations, not each other, so all of them
+    // run in ONE launch (per kernel kind) after the chain of input gradients: the small layers
+    // fill the gaps the big ones leave instead of each paying a launch of its own.
+    std::vector<ReduceProb> dw_red;
+    std::vector<int> dw_red_blocks;
+    std::vector<GemmProb> lin_dw, conv_dw;
+    size_t ws_off = 0;
     for (size_t s = max_nodes; s-- > 0;) {
-        std::vector<ReduceProb> dw_red;
-        std::vector<int> dw_red_blocks;
-        std::vector<GemmProb> lin_dw, conv_dw, lin_dx, conv_dx;
+        std::vector<GemmProb> lin_dx, conv_dx;
         std::vector<GapProb> gaps;
         std::vector<int> gap_blocks;
         std::vector<ShortcutProb> scs;
         std::vector<int> sc_blocks;
-        size_t ws_off = 0;
         for (ModelInfo& m : p->models) {
             if (s >= m.nodes.size()) continue;
             const NodeInfo& nd = m.nodes[s];
@@ -579,15 +587,25 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 sc_blocks.push_back((int)((rs.elems() + ELEMWISE_PER_BLOCK - 1) / ELEMWISE_PER_BLOCK));
             }
         }
-        ws_need = std::max(ws_need, ws_off);
-        add_gemm_launch(p, db, LIN_DW, lin_dw);
-        add_gemm_launch(p, db, CONV_DW, conv_dw);
-        add_mapped_launch(p, db, L_REDUCE, dw_red, dw_red_blocks);
         add_gemm_launch(p, db, LIN_DX, lin_dx);
         add_gemm_launch(p, db, CONV_DX, conv_dx);
         add_mapped_launch(p, db, L_SHORTCUT, scs, sc_blocks);
         add_mapped_launch(p, db, L_GAP_BWD, gaps, gap_blocks);
     }
+    ws_need = ws_off;
+    // a grid drains best when its slowest tiles start first: unaligned problems (scalar gather),
+    // then long reductions, then large outputs
+    auto slow_first = [](const GemmProb& a, const GemmProb& b) {
+        const bool va = (a.flags & F_VEC_A) && (a.flags & F_VEC_B), vb = (b.flags & F_VEC_A) && (b.flags & F_VEC_B);
+        if (va != vb) return !va;
+        if (a.ksplit != b.ksplit) return std::min(a.ksplit, a.Kd) > std::min(b.ksplit, b.Kd);
+        return (long long)a.R * a.Q > (long long)b.R * b.Q;
+    };
+    std::stable_sort(lin_dw.begin(), lin_dw.end(), slow_first);
+    std::stable_sort(conv_dw.begin(), conv_dw.end(), slow_first);
+    add_gemm_launch(p, db, LIN_DW, lin_dw);
+    add_gemm_launch(p, db, CONV_DW, conv_dw);
+    add_mapped_launch(p, db, L_REDUCE, dw_red, dw_red_blocks);
     (void)esz;
 
     // ---------------- update ----------------
