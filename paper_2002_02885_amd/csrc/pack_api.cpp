@@ -333,8 +333,18 @@ void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<G
     // The tile shape is chosen per launch so that the grid fills the 256 compute units about
     // twice; it only partitions the output, the summation order of an element does not depend
     // on it, so a member's bits do not depend on who else is in the launch.
+    // ... preferring, among shapes that give enough workgroups, the one that multiplies the
+    // fewest padding elements (a 64-channel layer wastes half of a 128-wide tile)
+    auto padded_work = [&](int c) {
+        double w = 0;
+        for (const GemmProb& g : probs) {
+            const double tms = (g.R + GEMM_TILE_M[c] - 1) / GEMM_TILE_M[c], tns = (g.Q + GEMM_TILE_N[c] - 1) / GEMM_TILE_N[c];
+            w += tms * GEMM_TILE_M[c] * tns * GEMM_TILE_N[c] * (double)g.Kd;
+        }
+        return w;
+    };
     int cfg = 0;
-    while (cfg < 2 && count_tiles(probs, cfg) < 512) ++cfg;
+    while (cfg < 2 && (count_tiles(probs, cfg) < 512 || padded_work(cfg + 1) < 0.8 * padded_work(cfg))) ++cfg;
     {   // tuning knob: PACK_GEMM_CFG_FWD / _DX / _DW = 0..2 forces the tile configuration of the
         // linear-layer launches of that kind (results do not depend on it)
         const char* names[3] = {"PACK_GEMM_CFG_FWD", "PACK_GEMM_CFG_DX", "PACK_GEMM_CFG_DW"};
@@ -388,10 +398,16 @@ void add_mapped_launch(pack_ctx* p, DescBuilder& db, int kind, const std::vector
 
 inline int elem_vec(bool bf16) { return bf16 ? 8 : 4; }
 
+// the gather kernels index with 32-bit element offsets
+inline bool small_tensors(const TensorInfo& a, const TensorInfo& b) {
+    return a.elems() < (size_t)1 << 30 && b.elems() < (size_t)1 << 30;
+}
+
 // Builds the whole launch sequence.  Workspace offsets are relative; `ws_need` returns the size.
 void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
     const bool bf = p->bf16;
     const int V = elem_vec(bf);
+    const int BKc = bf ? 64 : 32;   // reduction indices per LDS chunk (ET<T>::BK of the kernels)
     const size_t esz = bf ? 2 : 4;
     size_t max_nodes = 0;
     for (const ModelInfo& m : p->models) max_nodes = std::max(max_nodes, m.nodes.size());
@@ -436,7 +452,8 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 g.H = ti.h; g.W = ti.w; g.Cin = ti.c; g.Ho = to.h; g.Wo = to.w; g.Cout = to.c; g.stride = nd.stride;
                 g.R = to.n * to.h * to.w; g.Q = to.c; g.Kd = 9 * ti.c;
                 g.lda = ti.c; g.ldb = 9 * ti.c; g.ldc = to.c;
-                if (ti.c % V == 0) g.flags |= F_VEC_A | F_VEC_B;
+                // vector path of the gathered operand: a chunk must stay inside one tap
+                if (ti.c % BKc == 0 && small_tensors(ti, to)) g.flags |= F_VEC_A | F_VEC_B;
                 if (nd.res_src >= 0) {
                     const TensorInfo& rs = m.tensors[nd.res_src];
                     g.aux = rs.is_input ? nullptr : rs.act;
@@ -523,7 +540,11 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 } else {
                     g.H = ti.h; g.W = ti.w; g.Cin = ti.c; g.Ho = to.h; g.Wo = to.w; g.Cout = to.c; g.stride = nd.stride;
                     g.ldb = ti.c;
-                    if (ti.c % V == 0) g.flags |= F_VEC_B;
+                    // vector path of the gathered input: chunks of output pixels must stay inside
+                    // one image and rows must decode by shifts
+                    const bool pow2 = (to.w & (to.w - 1)) == 0;
+                    if (ti.c % V == 0 && pow2 && (to.h * to.w) % BKc == 0 && small_tensors(ti, to)) g.flags |= F_VEC_B;
+                    else g.flags &= ~F_VEC_A;
                     int S = std::min(256, std::max(1, (rows + 2047) / 2048));
                     g.ksplit = (int)align_up((size_t)(rows + S - 1) / S, 64);
                     S = (rows + g.ksplit - 1) / g.ksplit;
@@ -569,8 +590,7 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                     g.H = ti.h; g.W = ti.w; g.Cin = ti.c; g.Ho = to.h; g.Wo = to.w; g.Cout = to.c; g.stride = nd.stride;
                     g.R = ti.n * ti.h * ti.w; g.Q = ti.c; g.Kd = 9 * to.c;
                     g.lda = to.c; g.ldb = ti.c; g.ldc = ti.c;
-                    if (to.c % V == 0) g.flags |= F_VEC_A;
-                    if (ti.c % V == 0) g.flags |= F_VEC_B;
+                    if (to.c % BKc == 0 && ti.c % V == 0 && small_tensors(ti, to)) g.flags |= F_VEC_A | F_VEC_B;
                     g.ksplit = g.Kd;
                     conv_dx.push_back(g);
                 }

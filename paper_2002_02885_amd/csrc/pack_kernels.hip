@@ -368,6 +368,161 @@ __device__ __forceinline__ void stash_tile(T* __restrict__ Sbase,
 // whatever BM, BN and the LDS chunk BK are, so the choice of tile shape never changes a result bit.
 // BKM scales the LDS chunk: skinny problems (few rows, long reduction) are bound by the latency
 // of one global round trip per chunk, so they take chunks four times as long.
+// issues one assembly load of 16 bytes from `ptr` (see load_vec for why it is assembly)
+__device__ __forceinline__ u32x4_t asm_load16(const void* ptr) {
+    u32x4_t v;
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(ptr) : "memory");
+    return v;
+}
+
+// Per-thread operand fetcher of one tile.  The generic form recomputes addresses from (row, k)
+// for every load.  The gathered convolution operands get a form that decodes each thread's rows
+// (pixel coordinates, border validity of the nine taps) ONCE per tile and then needs only an
+// add and a bit test per load; it relies on the alignment the planner checks before it marks a
+// convolution problem as vectorisable: a chunk of BK reduction indices never straddles a tap
+// (forward: Cin % BK == 0, input gradient: Cout % BK == 0) or an image (weight gradient:
+// Ho*Wo % BK == 0 with Wo a power of two), and tensors have fewer than 2^31 elements.
+template <int MODE, typename T, bool IS_A, int BR, int BK, bool VEC>
+struct Fetcher {
+    typedef TileGeom<T, BR, BK> G;
+    static constexpr bool KC = IS_A ? OperandLayout<MODE>::A_KC : OperandLayout<MODE>::B_KC;
+    static constexpr bool ASM = ((PACK_ASM_MODES >> MODE) & 1) != 0;
+    static constexpr bool GATHER_KC = VEC && ASM && IS_A && (MODE == CONV_FWD || MODE == CONV_DX);
+    static constexpr bool WEIGHT_RC = VEC && ASM && !IS_A && MODE == CONV_DX;
+    static constexpr bool GATHER_RC = VEC && ASM && !IS_A && MODE == CONV_DW;
+    static constexpr int NS = GATHER_KC ? G::KC_SLOTS : ((WEIGHT_RC || GATHER_RC) ? G::RC_PER_THREAD : 1);
+
+    int row0;
+    int base[NS];        // element offset of the thread's row / block, without the per-chunk part
+    unsigned mask[NS];   // GATHER_KC: bit t = tap t reads inside the image; others: bit 0 = live
+    int aux0[NS], aux1[NS], aux2[NS];   // GATHER_RC: u - 1, v - 1, first reduction index of the block
+
+    __device__ __forceinline__ void init(const GemmProb& p, int row0_) {
+        row0 = row0_;
+        const int tid = threadIdx.x;
+        if constexpr (GATHER_KC) {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                const int vid = tid + 256 * s;
+                const int r = row0 + vid / G::VPR;
+                const int kv = (vid % G::VPR) * G::V;
+                const bool live = (vid < G::NVEC) && (r < p.R);
+                unsigned m = 0;
+                if constexpr (MODE == CONV_FWD) {
+                    const int hw = p.Ho * p.Wo;
+                    const int b = r / hw, rem = r - b * hw;
+                    const int i = rem / p.Wo, j = rem - i * p.Wo;
+                    const int y0 = p.stride * i - 1, x0 = p.stride * j - 1;
+                    base[s] = ((b * p.H + y0) * p.W + x0) * p.Cin + kv;
+#pragma unroll
+                    for (int t = 0; t < 9; ++t) {
+                        const int y = y0 + t / 3, x = x0 + t % 3;
+                        if ((unsigned)y < (unsigned)p.H && (unsigned)x < (unsigned)p.W) m |= 1u << t;
+                    }
+                } else {   // CONV_DX: rows are input pixels, the gather reads dz
+                    const int hw = p.H * p.W;
+                    const int b = r / hw, rem = r - b * hw;
+                    const int y = rem / p.W, x = rem - y * p.W;
+                    const int yy = y + 1, xx = x + 1;
+                    const int sh = (p.stride == 2) ? 1 : 0;
+                    base[s] = ((b * p.Ho + (yy >> sh)) * p.Wo + (xx >> sh)) * p.Cout + kv;
+#pragma unroll
+                    for (int t = 0; t < 9; ++t) {
+                        const int ty = yy - t / 3, tx = xx - t % 3;
+                        bool ok = (ty >= 0) && (tx >= 0);
+                        if (sh) ok = ok && (((ty | tx) & 1) == 0);
+                        ok = ok && ((ty >> sh) < p.Ho) && ((tx >> sh) < p.Wo);
+                        if (ok) m |= 1u << t;
+                    }
+                }
+                mask[s] = live ? m : 0u;
+            }
+        } else if constexpr (WEIGHT_RC) {
+#pragma unroll
+            for (int j = 0; j < NS; ++j) {
+                const int b = tid + 256 * j;
+                int kq, rv;
+                rc_block_coords<G>(b, kq, rv);
+                const int q = row0 + rv * G::V;
+                base[j] = kq * 4 * 9 * p.Cin + q;
+                mask[j] = ((b < G::RC_BLOCKS) && (q < p.Q)) ? 1u : 0u;
+            }
+        } else if constexpr (GATHER_RC) {
+#pragma unroll
+            for (int j = 0; j < NS; ++j) {
+                const int b = tid + 256 * j;
+                int kq, rv;
+                rc_block_coords<G>(b, kq, rv);
+                const int q = row0 + rv * G::V;
+                const int tap = q / p.Cin, c = q - tap * p.Cin;
+                aux0[j] = tap / 3 - 1;
+                aux1[j] = tap % 3 - 1;
+                aux2[j] = kq * 4;
+                base[j] = (aux0[j] * p.W + aux1[j]) * p.Cin + c;
+                mask[j] = ((b < G::RC_BLOCKS) && (q < p.Q)) ? 1u : 0u;
+            }
+        }
+    }
+
+    __device__ __forceinline__ void fetch(const GemmProb& p, int k0, int kend, u32x4_t (&regs)[G::NREG]) const {
+        const T* src = (const T*)(IS_A ? p.A : p.B);
+        if constexpr (GATHER_KC) {
+            // the whole chunk lies in one tap: its offset is the same for every thread
+            const int span = (MODE == CONV_FWD) ? p.Cin : p.Cout;
+            const int tap = k0 / span, c0 = k0 - tap * span;
+            const int u = tap / 3, v = tap - 3 * u;
+            int toff;
+            if constexpr (MODE == CONV_FWD) {
+                toff = (u * p.W + v) * p.Cin + c0;
+            } else {
+                const int sh = (p.stride == 2) ? 1 : 0;
+                toff = c0 - ((u >> sh) * p.Wo + (v >> sh)) * p.Cout;
+            }
+            const bool in_range = k0 < kend;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                const bool ok = in_range && ((mask[s] >> tap) & 1u);
+                const void* ptr = ok ? (const void*)(src + (base[s] + toff)) : p.zeros;
+                regs[s] = asm_load16(ptr);
+            }
+        } else if constexpr (WEIGHT_RC) {
+            const int tap = k0 / p.Cout, o0 = k0 - tap * p.Cout;
+            const int toff = (o0 * 9 + tap) * p.Cin;
+            const bool in_range = k0 < kend;
+#pragma unroll
+            for (int j = 0; j < NS; ++j) {
+                const bool ok = in_range && mask[j];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const void* ptr = ok ? (const void*)(src + (base[j] + toff + e * 9 * p.Cin)) : p.zeros;
+                    regs[4 * j + e] = asm_load16(ptr);
+                }
+            }
+        } else if constexpr (GATHER_RC) {
+            // reduction index = output pixel; the chunk lies inside one image
+            const int hw = p.Ho * p.Wo;
+            const int img = k0 / hw, p0 = k0 - img * hw;
+            const int lw = 31 - __builtin_clz(p.Wo);
+            const int ibase = img * p.H * p.W * p.Cin;
+#pragma unroll
+            for (int j = 0; j < NS; ++j) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int pidx = p0 + aux2[j] + e;
+                    const int i = pidx >> lw, jx = pidx & (p.Wo - 1);
+                    const int yb = p.stride * i, xb = p.stride * jx;
+                    const bool ok = mask[j] && (k0 + aux2[j] + e < kend) &&
+                                    ((unsigned)(yb + aux0[j]) < (unsigned)p.H) && ((unsigned)(xb + aux1[j]) < (unsigned)p.W);
+                    const void* ptr = ok ? (const void*)(src + (ibase + (yb * p.W + xb) * p.Cin + base[j])) : p.zeros;
+                    regs[4 * j + e] = asm_load16(ptr);
+                }
+            }
+        } else {
+            fetch_tile<MODE, T, IS_A, BR, BK, VEC>(p, row0, k0, kend, regs);
+        }
+    }
+};
+
 template <int BM, int BN, int BKM>
 struct StageCount {   // register stages of prefetch per tile shape (bounded by the register file)
     static constexpr int value = (BKM > 1) ? 2 : ((BM * BN >= 128 * 128) ? 2 : ((BM * BN >= 128 * 64) ? 3 : 4));
@@ -406,13 +561,17 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
     float bias_grad = 0.f;
 
     u32x4_t ra[ST][GA::NREG], rb[ST][GB::NREG];
+    Fetcher<MODE, T, true, BM, BK, VEC> fa;
+    Fetcher<MODE, T, false, BN, BK, VEC> fb;
+    fa.init(p, row0);
+    fb.init(p, col0);
 #pragma unroll
     for (int s = 0; s < ST - 1; ++s) {
         // always issued: a chunk beyond the reduction reads the block of zeros.  Keeping the
         // loads unconditional keeps the loop body free of branches, which is what lets the
         // compiler wait for the oldest stage only.
-        fetch_tile<MODE, T, true, BM, BK, VEC>(p, row0, kbeg + s * BK, kend, ra[s]);
-        fetch_tile<MODE, T, false, BN, BK, VEC>(p, col0, kbeg + s * BK, kend, rb[s]);
+        fa.fetch(p, kbeg + s * BK, kend, ra[s]);
+        fb.fetch(p, kbeg + s * BK, kend, rb[s]);
         __builtin_amdgcn_sched_barrier(0);   // keep the stages' loads in issue order
     }
     // one chunk: (optionally) issue the loads of chunk it + ST - 1 into the stage that has just
@@ -422,8 +581,8 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
         constexpr int s = decltype(S)::value;
         constexpr bool fetching = decltype(FETCH)::value;
         if constexpr (fetching) {
-            fetch_tile<MODE, T, true, BM, BK, VEC>(p, row0, kbeg + (it + ST - 1) * BK, kend, ra[(s + ST - 1) % ST]);
-            fetch_tile<MODE, T, false, BN, BK, VEC>(p, col0, kbeg + (it + ST - 1) * BK, kend, rb[(s + ST - 1) % ST]);
+            fa.fetch(p, kbeg + (it + ST - 1) * BK, kend, ra[(s + ST - 1) % ST]);
+            fb.fetch(p, kbeg + (it + ST - 1) * BK, kend, rb[(s + ST - 1) % ST]);
             __builtin_amdgcn_sched_barrier(0);
         }
         T(*Ab)[GA::LDS_LD] = As[it & 1];
@@ -502,8 +661,13 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
     if constexpr (VEC && ((PACK_ASM_MODES >> MODE) & 1)) {
         // The last full group prefetched chunks beyond the reduction (reads of the zeros block).
         // Those loads are invisible to the compiler and still target the stage registers, which
-        // it is about to reuse for the epilogue: drain them first.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // it would otherwise reuse for the epilogue at once: drain them, with every stage
+        // register as an operand of the wait so that none of them counts as free before it.
+#pragma unroll
+        for (int s = 0; s < ST; ++s) {
+            wait_stage<0>(ra[s]);
+            wait_stage<0>(rb[s]);
+        }
     }
 
     if constexpr (IS_DW) {
@@ -511,43 +675,157 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
             p.dbias[(size_t)tr.ks * p.R + row0 + threadIdx.x] = bias_grad;
     }
 
-    // epilogue: accumulator register e of a 32x32 block holds row 8*(e/4) + 4*(lane/32) + e%4,
-    // column lane%32
+    // ---- epilogue ----
+    // Accumulators go through LDS (as fp32) so that global memory is touched with 16-byte
+    // vectors along rows: the bias, the residual / mask source and the previous value are read
+    // and the result is written as full vectors instead of one element per lane.
+    // Accumulator register e of a 32x32 block holds row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
+    constexpr int SLD = BN + 8;   // 4 rows apart = 32 banks apart: the two half-waves do not collide
+    static_assert((size_t)BM * SLD * 4 <= (size_t)2 * (BM * GA::LDS_LD + BN * GB::LDS_LD) * sizeof(T), "staging tile must fit");
+    float(*stage)[SLD] = reinterpret_cast<float(*)[SLD]>(As_);
+    __syncthreads();   // every wave is done with the operand tiles
 #pragma unroll
     for (int a = 0; a < TM; ++a)
 #pragma unroll
         for (int b = 0; b < TN; ++b)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int row = row0 + wm * (BM / 2) + a * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                const int col = col0 + wn * (BN / 2) + b * 32 + (lane & 31);
-                if (row >= p.R || col >= p.Q) continue;
-                float v = acc[a][b][e];
-                const size_t off = (size_t)row * p.ldc + col;
-                if constexpr (MODE == LIN_FWD || MODE == CONV_FWD) {
-                    v += p.bias[col];
-                    if (p.flags & F_RES_ID) v += ET<T>::to_f(((const T*)p.aux)[off]);
-                    if (p.flags & F_RES_DOWN) {
-                        if (col < p.resC) {
-                            const int hw = p.Ho * p.Wo;
-                            const int bb = row / hw, rem = row - bb * hw;
-                            const int i = rem / p.Wo, j = rem - i * p.Wo;
-                            v += ET<T>::to_f(((const T*)p.aux)[((size_t)(bb * p.resH + 2 * i) * p.resW + 2 * j) * p.resC + col]);
-                        }
-                    }
-                    if (p.flags & F_RELU) v = fmaxf(v, 0.f);
-                    if (p.flags & F_OUT_F32) ((float*)p.C)[off] = v;
-                    else ((T*)p.C)[off] = ET<T>::from_f(v);
-                } else if constexpr (MODE == LIN_DX || MODE == CONV_DX) {
-                    if (p.flags & F_MASK) {
-                        if (!(ET<T>::to_f(((const T*)p.aux)[off]) > 0.f)) v = 0.f;
-                    }
-                    if (p.flags & F_ACCUM) v += ET<T>::to_f(((const T*)p.C)[off]);
-                    ((T*)p.C)[off] = ET<T>::from_f(v);
-                } else {
-                    ((float*)p.C)[(size_t)tr.ks * p.split_stride + off] = v;
+            for (int e = 0; e < 16; ++e)
+                stage[wm * (BM / 2) + a * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)][wn * (BN / 2) + b * 32 + (lane & 31)] = acc[a][b][e];
+    __syncthreads();
+
+    constexpr bool IS_FWD = (MODE == LIN_FWD || MODE == CONV_FWD);
+    const bool out_f32 = IS_DW || (IS_FWD && (p.flags & F_OUT_F32));
+    // element-wise tail of one output element; `v` comes from the staging tile
+    auto finish = [&](float v, int row, int col, size_t off) -> float {
+        if constexpr (IS_FWD) {
+            v += p.bias[col];
+            if (p.flags & F_RES_ID) v += ET<T>::to_f(((const T*)p.aux)[off]);
+            if (p.flags & F_RES_DOWN) {
+                if (col < p.resC) {
+                    const int hw = p.Ho * p.Wo;
+                    const int bb = row / hw, rem = row - bb * hw;
+                    const int i = rem / p.Wo, j = rem - i * p.Wo;
+                    v += ET<T>::to_f(((const T*)p.aux)[((size_t)(bb * p.resH + 2 * i) * p.resW + 2 * j) * p.resC + col]);
                 }
             }
+            if (p.flags & F_RELU) v = fmaxf(v, 0.f);
+        } else if constexpr (!IS_DW) {
+            if (p.flags & F_MASK) {
+                if (!(ET<T>::to_f(((const T*)p.aux)[off]) > 0.f)) v = 0.f;
+            }
+            if (p.flags & F_ACCUM) v += ET<T>::to_f(((const T*)p.C)[off]);
+        }
+        return v;
+    };
+    float* const cf = (float*)p.C + (IS_DW ? (size_t)tr.ks * p.split_stride : (size_t)0);
+
+    // vector form: 8 consecutive columns per thread (two 16-byte LDS reads); needs aligned rows
+    const bool vec_out = (p.ldc % 8 == 0) && (!(p.flags & F_RES_DOWN) || (p.resC % 8 == 0));
+    if (vec_out) {
+        constexpr int GROUPS = BN / 8;
+#pragma unroll 2
+        for (int idx = threadIdx.x; idx < BM * GROUPS; idx += 256) {
+            const int lr = idx / GROUPS, lc = (idx % GROUPS) * 8;
+            const int row = row0 + lr, col = col0 + lc;
+            if (row >= p.R || col >= p.Q) continue;
+            float v[8];
+            {
+                const f32x4_t s0 = *reinterpret_cast<const f32x4_t*>(&stage[lr][lc]);
+                const f32x4_t s1 = *reinterpret_cast<const f32x4_t*>(&stage[lr][lc + 4]);
+                v[0] = s0.x; v[1] = s0.y; v[2] = s0.z; v[3] = s0.w;
+                v[4] = s1.x; v[5] = s1.y; v[6] = s1.z; v[7] = s1.w;
+            }
+            const size_t off = (size_t)row * p.ldc + col;
+            if (col + 8 > p.Q) {   // ragged right edge: element by element
+                for (int e = 0; e < 8 && col + e < p.Q; ++e) {
+                    const float r = finish(v[e], row, col + e, off + e);
+                    if (out_f32) cf[off + e] = r;
+                    else ((T*)p.C)[off + e] = ET<T>::from_f(r);
+                }
+                continue;
+            }
+            if constexpr (IS_FWD) {
+                const f32x4_t b0 = *reinterpret_cast<const f32x4_t*>(p.bias + col);
+                const f32x4_t b1 = *reinterpret_cast<const f32x4_t*>(p.bias + col + 4);
+                v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
+                v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
+                const T* res = nullptr;
+                if (p.flags & F_RES_ID) {
+                    res = (const T*)p.aux + off;
+                } else if ((p.flags & F_RES_DOWN) && col < p.resC) {
+                    const int hw = p.Ho * p.Wo;
+                    const int bb = row / hw, rem = row - bb * hw;
+                    const int i = rem / p.Wo, j = rem - i * p.Wo;
+                    res = (const T*)p.aux + ((size_t)(bb * p.resH + 2 * i) * p.resW + 2 * j) * p.resC + col;
+                }
+                if (res) {
+                    if constexpr (sizeof(T) == 2) {
+                        const u32x4_t rv = *reinterpret_cast<const u32x4_t*>(res);
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            v[2 * d] += __uint_as_float(rv[d] << 16);
+                            v[2 * d + 1] += __uint_as_float(rv[d] & 0xffff0000u);
+                        }
+                    } else {
+                        const f32x4_t r0 = *reinterpret_cast<const f32x4_t*>(res);
+                        const f32x4_t r1 = *reinterpret_cast<const f32x4_t*>(res + 4);
+                        v[0] += r0.x; v[1] += r0.y; v[2] += r0.z; v[3] += r0.w;
+                        v[4] += r1.x; v[5] += r1.y; v[6] += r1.z; v[7] += r1.w;
+                    }
+                }
+                if (p.flags & F_RELU) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+                }
+            } else if constexpr (!IS_DW) {
+                float mk[8], old[8];
+                const bool masked = (p.flags & F_MASK) != 0, accum = (p.flags & F_ACCUM) != 0;
+                if constexpr (sizeof(T) == 2) {
+                    const u32x4_t z = {0u, 0u, 0u, 0u};
+                    const u32x4_t mv = masked ? *reinterpret_cast<const u32x4_t*>((const T*)p.aux + off) : z;
+                    const u32x4_t ov = accum ? *reinterpret_cast<const u32x4_t*>((const T*)p.C + off) : z;
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        mk[2 * d] = __uint_as_float(mv[d] << 16); mk[2 * d + 1] = __uint_as_float(mv[d] & 0xffff0000u);
+                        old[2 * d] = __uint_as_float(ov[d] << 16); old[2 * d + 1] = __uint_as_float(ov[d] & 0xffff0000u);
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        mk[e] = masked ? ((const float*)p.aux)[off + e] : 1.f;
+                        old[e] = accum ? ((const float*)p.C)[off + e] : 0.f;
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    if (masked && !(mk[e] > 0.f)) v[e] = 0.f;
+                    if (accum) v[e] += old[e];
+                }
+            }
+            if (out_f32) {
+                *reinterpret_cast<f32x4_t*>(cf + off) = f32x4_t{v[0], v[1], v[2], v[3]};
+                *reinterpret_cast<f32x4_t*>(cf + off + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
+            } else if constexpr (sizeof(T) == 2) {
+                u32x4_t o;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) o[d] = (unsigned)f2bf(v[2 * d]) | ((unsigned)f2bf(v[2 * d + 1]) << 16);
+                *reinterpret_cast<u32x4_t*>((T*)p.C + off) = o;
+            } else {
+                *reinterpret_cast<f32x4_t*>((float*)p.C + off) = f32x4_t{v[0], v[1], v[2], v[3]};
+                *reinterpret_cast<f32x4_t*>((float*)p.C + off + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
+            }
+        }
+    } else {
+        for (int idx = threadIdx.x; idx < BM * BN; idx += 256) {
+            const int lr = idx / BN, lc = idx % BN;
+            const int row = row0 + lr, col = col0 + lc;
+            if (row >= p.R || col >= p.Q) continue;
+            const size_t off = (size_t)row * p.ldc + col;
+            const float r = finish(stage[lr][lc], row, col, off);
+            if (out_f32) cf[off] = r;
+            else ((T*)p.C)[off] = ET<T>::from_f(r);
+        }
+    }
 }
 
 template <int MODE, typename T, int BM, int BN, int BKM>
@@ -562,8 +840,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
     if (p.flags & F_A_INPUT) p.A = x;
     if (p.flags & F_B_INPUT) p.B = x;
     if (p.flags & F_AUX_INPUT) p.aux = x;
-    __shared__ __attribute__((aligned(16))) T As[2 * BM * TileGeom<T, BM, BK>::LDS_LD];
-    __shared__ __attribute__((aligned(16))) T Bs[2 * BN * TileGeom<T, BN, BK>::LDS_LD];
+    // one block: operand tiles A (two buffers) then B (two buffers); the epilogue reuses it
+    __shared__ __attribute__((aligned(16))) T lds[2 * BM * TileGeom<T, BM, BK>::LDS_LD + 2 * BN * TileGeom<T, BN, BK>::LDS_LD];
+    T* const As = lds;
+    T* const Bs = lds + 2 * BM * TileGeom<T, BM, BK>::LDS_LD;
     // aligned shapes take 16-byte loads for both operands; anything else takes the scalar gather
     if ((p.flags & F_VEC_A) && (p.flags & F_VEC_B)) gemm_body<MODE, T, BM, BN, BKM, true>(p, tr, As, Bs);
     else gemm_body<MODE, T, BM, BN, BKM, false>(p, tr, As, Bs);

@@ -126,6 +126,13 @@ def test_c5_resnet_style_bf16_full_width_reduced_images():
     _check_bf16(wl.config5(K=2, B=8, size=16, steps=2))
 
 
+def test_c5_resnet_style_full_width_32px_bf16_and_fp32():
+    # power-of-two maps of 32, 16, 8 and 4 pixels at the full channel widths: the aligned
+    # (vector gather) forms of all three convolution products, both element types
+    _check_bf16(wl.config5(K=2, B=4, size=32, steps=1), trials=1)
+    _check_f32(wl.config5(K=1, B=4, size=32, steps=1, dtype=wl.F32), trials=1)
+
+
 # ------------------------------------------------------------------ the paper's invariants on the device
 def _blobs_equal(a, b):
     return all(np.array_equal(x, y) for x, y in zip(a, b))
