@@ -545,7 +545,7 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                     const bool pow2 = (to.w & (to.w - 1)) == 0;
                     if (ti.c % V == 0 && pow2 && (to.h * to.w) % BKc == 0 && small_tensors(ti, to)) g.flags |= F_VEC_B;
                     else g.flags &= ~F_VEC_A;
-                    int S = std::min(256, std::max(1, (rows + 2047) / 2048));
+                    int S = std::min(64, std::max(1, (rows + 8191) / 8192));   // depends on the layer shape only
                     g.ksplit = (int)align_up((size_t)(rows + S - 1) / S, 64);
                     S = (rows + g.ksplit - 1) / g.ksplit;
                     if (S > 1) {

@@ -902,49 +902,120 @@ hipError_t launch_reduce(const ReduceProb* probs, const int2* map, int n, hipStr
 // ------------------------------------------------------------------------------------------------
 // softmax cross-entropy, its gradient, and the argmax: one workgroup per member
 // ------------------------------------------------------------------------------------------------
+constexpr int CE_WAVES = 16;   // wavefronts per workgroup
+constexpr int CE_PER_LANE = 4;  // classes a lane keeps in registers (fast path: C <= 4 * lanes per row)
+
+// One workgroup per member.  A row is handled by a group of `lpr` lanes (a power of two, at
+// least min(C, 64)), so a wavefront handles 64 / lpr rows at once and the logits of a row are
+// read from memory exactly once, into registers.  Row maximum (lowest index among equals), sum
+// of exponentials and argmax are combined by a fixed butterfly inside the group; each group
+// adds its rows' losses in row order and the groups' sums are added in a fixed order, so the
+// loss is reproducible bit for bit and depends on nothing but the member's own rows.
 template <typename T>
-__global__ __launch_bounds__(256) void ce_kernel(const CeProb* __restrict__ probs, const int32_t* __restrict__ labels,
-                                                 int* __restrict__ err_flag) {
+__global__ __launch_bounds__(64 * CE_WAVES) void ce_kernel(const CeProb* __restrict__ probs,
+                                                            const int32_t* __restrict__ labels,
+                                                            int* __restrict__ err_flag) {
     const CeProb p = probs[blockIdx.x];
+    int lpr = 1;
+    while (lpr < 64 && lpr < p.C) lpr <<= 1;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int rpw = 64 / lpr, sub = lane / lpr, sl = lane - sub * lpr;
+    const int rows_per_pass = CE_WAVES * rpw;
     const float inv_rows = 1.f / (float)p.rows;
-    float local = 0.f;
-    for (int row = threadIdx.x; row < p.rows; row += 256) {
-        const float* z = p.logits + (size_t)row * p.ld;
-        float mx = z[0];
-        int arg = 0;
-        for (int c = 1; c < p.C; ++c) {
-            const float v = z[c];
-            if (v > mx) { mx = v; arg = c; }   // strict: the lowest index wins ties
+    const bool in_regs = p.C <= CE_PER_LANE * lpr;
+    float group_loss = 0.f;
+    for (int row0 = 0; row0 < p.rows; row0 += rows_per_pass) {
+        const int row = row0 + wave * rpw + sub;
+        const bool active = row < p.rows;
+        const float* z = p.logits + (size_t)(active ? row : 0) * p.ld;
+        const int y = active ? labels[row] : 0;
+        float zv[CE_PER_LANE];
+        float mx = -INFINITY;
+        int arg = 0x7fffffff;
+        if (in_regs) {
+#pragma unroll
+            for (int i = 0; i < CE_PER_LANE; ++i) {
+                const int c = sl + i * lpr;
+                zv[i] = (c < p.C) ? z[c] : -INFINITY;
+            }
+#pragma unroll
+            for (int i = 0; i < CE_PER_LANE; ++i)
+                if (zv[i] > mx) { mx = zv[i]; arg = sl + i * lpr; }   // ascending class index
+        } else {
+            for (int c = sl; c < p.C; c += lpr) {
+                const float v = z[c];
+                if (v > mx) { mx = v; arg = c; }
+            }
         }
+        for (int m = lpr >> 1; m > 0; m >>= 1) {
+            const float om = __shfl_xor(mx, m, 64);
+            const int oa = __shfl_xor(arg, m, 64);
+            if (om > mx || (om == mx && oa < arg)) { mx = om; arg = oa; }
+        }
+        float ev[CE_PER_LANE];
         float s = 0.f;
-        for (int c = 0; c < p.C; ++c) s += expf(z[c] - mx);
-        const int y = labels[row];
-        const bool ok = (y >= 0 && y < p.C);
-        if (!ok) atomicOr(err_flag, 1);
-        const float lse = mx + logf(s);
-        if (ok) local += lse - z[y];
-        const float inv_s = 1.f / s;
-        T* d = (T*)p.dlogits + (size_t)row * p.ldd;
-        for (int c = 0; c < p.C; ++c) {
-            float g = 0.f;
-            if (ok) g = (expf(z[c] - mx) * inv_s - (c == y ? 1.f : 0.f)) * inv_rows;
-            d[c] = ET<T>::from_f(g);
+        if (in_regs) {
+#pragma unroll
+            for (int i = 0; i < CE_PER_LANE; ++i) {
+                ev[i] = (sl + i * lpr < p.C) ? expf(zv[i] - mx) : 0.f;
+                s += ev[i];
+            }
+        } else {
+            for (int c = sl; c < p.C; c += lpr) s += expf(z[c] - mx);
         }
-        p.pred[row] = arg;
+        for (int m = lpr >> 1; m > 0; m >>= 1) s += __shfl_xor(s, m, 64);
+        const bool ok = (y >= 0 && y < p.C);
+        if (active && !ok && sl == 0) atomicOr(err_flag, 1);
+        // the logit of the label: held by lane y % lpr of the group, slot y / lpr
+        float zy = 0.f;
+        if (in_regs) {
+            const int yy = ok ? y : 0;
+            float cand = zv[0];
+#pragma unroll
+            for (int i = 1; i < CE_PER_LANE; ++i)
+                if (yy / lpr == i) cand = zv[i];
+            zy = __shfl(cand, sub * lpr + (yy & (lpr - 1)), 64);
+        } else if (ok && active) {
+            zy = z[y];
+        }
+        if (active && ok) group_loss += (mx + logf(s)) - zy;
+        const float inv_s = 1.f / s;
+        T* d = (T*)p.dlogits + (size_t)(active ? row : 0) * p.ldd;
+        if (active) {
+            if (in_regs) {
+#pragma unroll
+                for (int i = 0; i < CE_PER_LANE; ++i) {
+                    const int c = sl + i * lpr;
+                    if (c < p.C) {
+                        const float g = ok ? (ev[i] * inv_s - (c == y ? 1.f : 0.f)) * inv_rows : 0.f;
+                        d[c] = ET<T>::from_f(g);
+                    }
+                }
+            } else {
+                for (int c = sl; c < p.C; c += lpr) {
+                    const float g = ok ? (expf(z[c] - mx) * inv_s - (c == y ? 1.f : 0.f)) * inv_rows : 0.f;
+                    d[c] = ET<T>::from_f(g);
+                }
+            }
+            if (sl == 0) p.pred[row] = arg;
+        }
     }
-    __shared__ float red[256];
-    red[threadIdx.x] = local;
+    // groups of one wave by a fixed butterfly over the group index, then the waves in order
+    float wsum = (sl == 0) ? group_loss : 0.f;
+    for (int m = 32; m >= lpr; m >>= 1) wsum += __shfl_xor(wsum, m, 64);
+    __shared__ float part[CE_WAVES];
+    if (lane == 0) part[wave] = wsum;
     __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
-        __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.f;
+        for (int w = 0; w < CE_WAVES; ++w) t += part[w];
+        *p.loss = t * inv_rows;
     }
-    if (threadIdx.x == 0) *p.loss = red[0] * inv_rows;
 }
 
 hipError_t launch_ce(bool bf16, const CeProb* probs, int K, const int32_t* labels, int* err_flag, hipStream_t st) {
-    if (bf16) hipLaunchKernelGGL(ce_kernel<bf16_t>, dim3(K), dim3(256), 0, st, probs, labels, err_flag);
-    else hipLaunchKernelGGL(ce_kernel<float>, dim3(K), dim3(256), 0, st, probs, labels, err_flag);
+    if (bf16) hipLaunchKernelGGL(ce_kernel<bf16_t>, dim3(K), dim3(64 * CE_WAVES), 0, st, probs, labels, err_flag);
+    else hipLaunchKernelGGL(ce_kernel<float>, dim3(K), dim3(64 * CE_WAVES), 0, st, probs, labels, err_flag);
     return hipGetLastError();
 }
 
@@ -1003,6 +1074,43 @@ __global__ __launch_bounds__(256) void shortcut_bwd_kernel(const ShortcutProb* _
     const int2 m = map[blockIdx.x];
     const ShortcutProb p = probs[m.x];
     const long long total = (long long)p.n * p.H * p.W * p.C;
+    constexpr int V = ET<T>::V;
+    if (p.C % V == 0 && p.Co % V == 0) {
+        // 16-byte vectors: V consecutive channels of one pixel
+        for (int vi = threadIdx.x; vi < ELEMWISE_PER_BLOCK / V; vi += 256) {
+        const long long e = ((long long)m.y * (ELEMWISE_PER_BLOCK / V) + vi) * V;
+        if (e >= total) break;
+        u32x4_t g = {0u, 0u, 0u, 0u};
+        if (!p.down) {
+            g = *reinterpret_cast<const u32x4_t*>((const T*)p.dz_out + e);
+        } else {
+            const int c = (int)(e % p.C);
+            long long t = e / p.C;
+            const int x = (int)(t % p.W);
+            t /= p.W;
+            const int y = (int)(t % p.H);
+            const int n = (int)(t / p.H);
+            if (((x | y) & 1) == 0 && (y >> 1) < p.Ho && (x >> 1) < p.Wo)
+                g = *reinterpret_cast<const u32x4_t*>((const T*)p.dz_out + ((size_t)(n * p.Ho + (y >> 1)) * p.Wo + (x >> 1)) * p.Co + c);
+        }
+        T gv[V], sv[V], ov[V];
+        __builtin_memcpy(gv, &g, 16);
+        if (p.mask) { const u32x4_t t = *reinterpret_cast<const u32x4_t*>((const T*)p.src + e); __builtin_memcpy(sv, &t, 16); }
+        if (p.accum) { const u32x4_t t = *reinterpret_cast<const u32x4_t*>((const T*)p.dz_src + e); __builtin_memcpy(ov, &t, 16); }
+        T out[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            float v = ET<T>::to_f(gv[i]);
+            if (p.mask && !(ET<T>::to_f(sv[i]) > 0.f)) v = 0.f;
+            if (p.accum) v += ET<T>::to_f(ov[i]);
+            out[i] = ET<T>::from_f(v);
+        }
+        u32x4_t o;
+        __builtin_memcpy(&o, out, 16);
+        *reinterpret_cast<u32x4_t*>((T*)p.dz_src + e) = o;
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < ELEMWISE_PER_BLOCK / 256; ++i) {
         const long long e = (long long)m.y * ELEMWISE_PER_BLOCK + i * 256 + threadIdx.x;
