@@ -592,7 +592,26 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                     g.lda = to.c; g.ldb = ti.c; g.ldc = ti.c;
                     if (to.c % BKc == 0 && ti.c % V == 0 && small_tensors(ti, to)) g.flags |= F_VEC_A | F_VEC_B;
                     g.ksplit = g.Kd;
-                    conv_dx.push_back(g);
+                    if (nd.stride == 2 && (g.flags & F_VEC_A)) {
+                        // An input pixel of a stride-2 convolution receives gradient through the
+                        // taps whose parity matches its own only (1, 2, 2 or 4 of the 9): one
+                        // problem per parity class multiplies no structural zeros.  The surviving
+                        // products are added in the same order as in the undivided sum.
+                        for (int py = 0; py < 2; ++py)
+                            for (int px = 0; px < 2; ++px) {
+                                GemmProb c = g;
+                                c.flags |= F_ROWMAP;
+                                c.cls_py = py; c.cls_px = px;
+                                c.cls_h = py ? (ti.h + 1) / 2 : ti.h / 2;
+                                c.cls_w = px ? (ti.w + 1) / 2 : ti.w / 2;
+                                c.R = ti.n * c.cls_h * c.cls_w;
+                                c.Kd = (py ? 1 : 2) * (px ? 1 : 2) * to.c;
+                                c.ksplit = c.Kd;
+                                if (c.R > 0) conv_dx.push_back(c);
+                            }
+                    } else {
+                        conv_dx.push_back(g);
+                    }
                 }
             }
             // gradient through the shortcut into the block input

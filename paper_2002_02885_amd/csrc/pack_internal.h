@@ -29,7 +29,10 @@ enum GemmFlags : int {
     F_VEC_B = 128,     // operand B likewise
     F_A_INPUT = 256,   // operand A is the shared input batch handed to this step
     F_B_INPUT = 512,   // operand B is the shared input batch
-    F_AUX_INPUT = 1024 // the shortcut source is the shared input batch
+    F_AUX_INPUT = 1024,// the shortcut source is the shared input batch
+    F_ROWMAP = 2048    // stride-2 input gradient, one parity class of input pixels: output row r is
+                       // pixel (b, 2*yc + 1 - cls_py, 2*xc + 1 - cls_px) and the reduction runs over the
+                       // taps of that class only (u = 1 or u in {0, 2}, likewise v)
 };
 
 struct GemmProb {
@@ -45,6 +48,7 @@ struct GemmProb {
     int lda, ldb, ldc;
     int H, W, Cin, Ho, Wo, Cout, stride;   // geometry of the forward convolution (conv modes)
     int resH, resW, resC;                  // geometry of the shortcut source (F_RES_DOWN)
+    int cls_py, cls_px, cls_h, cls_w;      // F_ROWMAP: parity class and its extent in pixels
     int flags;
     int ksplit;                            // reduction indices per split (>= Kd when not split)
     long long split_stride;                // elements between the partial outputs of two splits

@@ -368,6 +368,32 @@ __device__ __forceinline__ void stash_tile(T* __restrict__ Sbase,
 // whatever BM, BN and the LDS chunk BK are, so the choice of tile shape never changes a result bit.
 // BKM scales the LDS chunk: skinny problems (few rows, long reduction) are bound by the latency
 // of one global round trip per chunk, so they take chunks four times as long.
+// F_ROWMAP problems (one parity class of a stride-2 input gradient): the tap that reduction
+// block `tc` of the class stands for, and the pixel an output row stands for
+__device__ __forceinline__ int class_tap(const GemmProb& p, int tc) {
+    const int ntx = p.cls_px ? 1 : 2;
+    const int iu = tc / ntx, iv = tc - iu * ntx;
+    const int u = p.cls_py ? 1 : 2 * iu, v = p.cls_px ? 1 : 2 * iv;
+    return u * 3 + v;
+}
+__device__ __forceinline__ void class_pixel(const GemmProb& p, int r, int& b, int& y, int& x) {
+    const int hw = p.cls_h * p.cls_w;
+    b = r / hw;
+    const int rem = r - b * hw;
+    const int yc = rem / p.cls_w, xc = rem - yc * p.cls_w;
+    y = 2 * yc + 1 - p.cls_py;
+    x = 2 * xc + 1 - p.cls_px;
+}
+// element offset of output row `row` (times the leading dimension) for the epilogue
+__device__ __forceinline__ size_t out_row_base(const GemmProb& p, int row) {
+    if (p.flags & F_ROWMAP) {
+        int b, y, x;
+        class_pixel(p, row, b, y, x);
+        return ((size_t)(b * p.H + y) * p.W + x) * p.ldc;
+    }
+    return (size_t)row * p.ldc;
+}
+
 // issues one assembly load of 16 bytes from `ptr` (see load_vec for why it is assembly)
 __device__ __forceinline__ u32x4_t asm_load16(const void* ptr) {
     u32x4_t v;
@@ -420,9 +446,16 @@ struct Fetcher {
                         if ((unsigned)y < (unsigned)p.H && (unsigned)x < (unsigned)p.W) m |= 1u << t;
                     }
                 } else {   // CONV_DX: rows are input pixels, the gather reads dz
-                    const int hw = p.H * p.W;
-                    const int b = r / hw, rem = r - b * hw;
-                    const int y = rem / p.W, x = rem - y * p.W;
+                    int b, y, x;
+                    if (p.flags & F_ROWMAP) {
+                        class_pixel(p, r, b, y, x);
+                    } else {
+                        const int hw = p.H * p.W;
+                        b = r / hw;
+                        const int rem = r - b * hw;
+                        y = rem / p.W;
+                        x = rem - y * p.W;
+                    }
                     const int yy = y + 1, xx = x + 1;
                     const int sh = (p.stride == 2) ? 1 : 0;
                     base[s] = ((b * p.Ho + (yy >> sh)) * p.Wo + (xx >> sh)) * p.Cout + kv;
@@ -469,7 +502,8 @@ struct Fetcher {
         if constexpr (GATHER_KC) {
             // the whole chunk lies in one tap: its offset is the same for every thread
             const int span = (MODE == CONV_FWD) ? p.Cin : p.Cout;
-            const int tap = k0 / span, c0 = k0 - tap * span;
+            const int tc = k0 / span, c0 = k0 - tc * span;
+            const int tap = (MODE == CONV_DX && (p.flags & F_ROWMAP)) ? class_tap(p, tc) : tc;
             const int u = tap / 3, v = tap - 3 * u;
             int toff;
             if constexpr (MODE == CONV_FWD) {
@@ -486,7 +520,8 @@ struct Fetcher {
                 regs[s] = asm_load16(ptr);
             }
         } else if constexpr (WEIGHT_RC) {
-            const int tap = k0 / p.Cout, o0 = k0 - tap * p.Cout;
+            const int tc = k0 / p.Cout, o0 = k0 - tc * p.Cout;
+            const int tap = (p.flags & F_ROWMAP) ? class_tap(p, tc) : tc;
             const int toff = (o0 * 9 + tap) * p.Cin;
             const bool in_range = k0 < kend;
 #pragma unroll
@@ -735,7 +770,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                 v[0] = s0.x; v[1] = s0.y; v[2] = s0.z; v[3] = s0.w;
                 v[4] = s1.x; v[5] = s1.y; v[6] = s1.z; v[7] = s1.w;
             }
-            const size_t off = (size_t)row * p.ldc + col;
+            const size_t off = out_row_base(p, row) + col;
             if (col + 8 > p.Q) {   // ragged right edge: element by element
                 for (int e = 0; e < 8 && col + e < p.Q; ++e) {
                     const float r = finish(v[e], row, col + e, off + e);
@@ -820,7 +855,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
             const int lr = idx / BN, lc = idx % BN;
             const int row = row0 + lr, col = col0 + lc;
             if (row >= p.R || col >= p.Q) continue;
-            const size_t off = (size_t)row * p.ldc + col;
+            const size_t off = out_row_base(p, row) + col;
             const float r = finish(stage[lr][lc], row, col, off);
             if (out_f32) cf[off] = r;
             else ((T*)p.C)[off] = ET<T>::from_f(r);
