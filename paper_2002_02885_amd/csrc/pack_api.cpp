@@ -59,7 +59,10 @@ struct NodeInfo {
     int res_src = -1;        // tensor index of the shortcut source, -1 if none
     bool res_down = false;
     size_t w_off = 0, b_off = 0;   // element offsets into the parameter arena
-    size_t w_elems = 0;
+    size_t w_elems = 0;      // weights in the public blob
+    size_t w_arena = 0;      // weights in the arena (rows padded to `kp` for im2col convolutions)
+    int kp = 0;              // > 0: first-layer convolution executed over the shared im2col buffer
+    int im2col_idx = -1;     // which shared buffer (pack_ctx::im2col)
     int fan_in = 0;
     size_t blob_off = 0;     // float offset of W in the member's public blob
 };
@@ -74,7 +77,7 @@ struct ModelInfo {
     float* loss = nullptr;
 };
 
-enum LaunchKind { L_GEMM, L_REDUCE, L_CE, L_GAP_FWD, L_GAP_BWD, L_SHORTCUT, L_SGD };
+enum LaunchKind { L_GEMM, L_REDUCE, L_CE, L_GAP_FWD, L_GAP_BWD, L_SHORTCUT, L_SGD, L_IM2COL };
 
 struct Launch {
     int kind = 0, mode = 0;
@@ -107,6 +110,7 @@ struct pack_ctx {
     int* err_flag = nullptr;
     float* loss_all = nullptr;   // [K]
     void* zeros = nullptr;       // 256 bytes of zeros inside the slab (never written)
+    std::vector<Im2colProb> im2col;   // shared-input loaders, one per first-layer stride in use
     std::vector<Launch> plan;
     size_t device_bytes = 0;
     // per-launch timing (off unless pack_profile_start was called)
@@ -153,10 +157,11 @@ void blob_to_arena(const ModelInfo& m, const float* blob, std::vector<float>& ar
             std::memcpy(W, src, nd.w_elems * sizeof(float));
         } else {
             const int cin = nd.fan_in / 9;
+            const size_t row = nd.kp ? (size_t)nd.kp : (size_t)nd.fan_in;   // padding stays zero
             for (int o = 0; o < nd.out; ++o)
                 for (int c = 0; c < cin; ++c)
                     for (int t = 0; t < 9; ++t)
-                        W[((size_t)o * 9 + t) * cin + c] = src[((size_t)o * cin + c) * 9 + t];
+                        W[(size_t)o * row + (size_t)t * cin + c] = src[((size_t)o * cin + c) * 9 + t];
         }
         std::memcpy(b, src + nd.w_elems, (size_t)nd.out * sizeof(float));
     }
@@ -172,10 +177,11 @@ void arena_to_blob(const ModelInfo& m, const std::vector<float>& arena, float* b
             std::memcpy(dst, W, nd.w_elems * sizeof(float));
         } else {
             const int cin = nd.fan_in / 9;
+            const size_t row = nd.kp ? (size_t)nd.kp : (size_t)nd.fan_in;
             for (int o = 0; o < nd.out; ++o)
                 for (int c = 0; c < cin; ++c)
                     for (int t = 0; t < 9; ++t)
-                        dst[((size_t)o * cin + c) * 9 + t] = W[((size_t)o * 9 + t) * cin + c];
+                        dst[((size_t)o * cin + c) * 9 + t] = W[(size_t)o * row + (size_t)t * cin + c];
         }
         std::memcpy(dst + nd.w_elems, b, (size_t)nd.out * sizeof(float));
     }
@@ -220,6 +226,11 @@ pack_status parse_model(const pack_input_spec& in, const pack_model_spec& spec, 
                 }
                 o.c = L.out;
                 nd.w_elems = (size_t)L.out * nd.fan_in;
+                nd.w_arena = nd.w_elems;
+                if (L.op == PACK_CONV3X3 && src.is_input && nd.fan_in <= 32) {
+                    nd.kp = 32;   // few input channels: run over the shared im2col buffer
+                    nd.w_arena = (size_t)L.out * nd.kp;
+                }
                 nd.blob_off = blob_off;
                 blob_off += nd.w_elems + L.out;
                 if (next_op == PACK_RELU) {
@@ -328,31 +339,13 @@ size_t count_tiles(const std::vector<GemmProb>& probs, int cfg) {
     return n;
 }
 
-void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<GemmProb>& probs) {
-    if (probs.empty()) return;
-    // The tile shape is chosen per launch so that the grid fills the 256 compute units about
-    // twice; it only partitions the output, the summation order of an element does not depend
-    // on it, so a member's bits do not depend on who else is in the launch.
-    // ... preferring, among shapes that give enough workgroups, the one that multiplies the
-    // fewest padding elements (a 64-channel layer wastes half of a 128-wide tile)
-    auto padded_work = [&](int c) {
-        double w = 0;
-        for (const GemmProb& g : probs) {
-            const double tms = (g.R + GEMM_TILE_M[c] - 1) / GEMM_TILE_M[c], tns = (g.Q + GEMM_TILE_N[c] - 1) / GEMM_TILE_N[c];
-            w += tms * GEMM_TILE_M[c] * tns * GEMM_TILE_N[c] * (double)g.Kd;
-        }
-        return w;
-    };
-    int cfg = 0;
-    while (cfg < 2 && (count_tiles(probs, cfg) < 512 || padded_work(cfg + 1) < 0.8 * padded_work(cfg))) ++cfg;
-    {   // tuning knob: PACK_GEMM_CFG_FWD / _DX / _DW = 0..2 forces the tile configuration of the
-        // linear-layer launches of that kind (results do not depend on it)
-        const char* names[3] = {"PACK_GEMM_CFG_FWD", "PACK_GEMM_CFG_DX", "PACK_GEMM_CFG_DW"};
-        if (mode <= LIN_DW) {
-            const char* v = std::getenv(names[mode]);
-            if (v && v[0] >= '0' && v[0] <= '2' && v[1] == 0) cfg = v[0] - '0';
-        }
-    }
+double padded_work(const GemmProb& g, int c) {
+    const double tms = (g.R + GEMM_TILE_M[c] - 1) / GEMM_TILE_M[c], tns = (g.Q + GEMM_TILE_N[c] - 1) / GEMM_TILE_N[c];
+    return tms * GEMM_TILE_M[c] * tns * GEMM_TILE_N[c] * (double)std::min(g.Kd, g.ksplit) *
+           std::max(1, (g.Kd + g.ksplit - 1) / g.ksplit);
+}
+
+void emit_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, int cfg, const std::vector<GemmProb>& probs) {
     const int BMc = GEMM_TILE_M[cfg], BNc = GEMM_TILE_N[cfg];
     std::vector<TileOrder> logical;
     for (size_t i = 0; i < probs.size(); ++i) {
@@ -378,6 +371,49 @@ void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<G
     L.map_off = db.add(tiles.data(), tiles.size() * sizeof(TileRef));
     L.n = (int)tiles.size();
     p->plan.push_back(L);
+}
+
+void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<GemmProb>& probs) {
+    if (probs.empty()) return;
+    // The tile shape only partitions the output; the summation order of an element does not
+    // depend on it, so a member's bits do not depend on who else is in the launch.  Each problem
+    // prefers the shape that multiplies the fewest padding elements (a 64-channel layer wastes
+    // half of a 128-wide tile); the launch as a whole needs enough workgroups to fill the 256
+    // compute units about twice.  Problems whose preferred shape carries little of the work
+    // ride along in the main launch rather than paying for a launch of their own.
+    int floor_cfg = 0;
+    while (floor_cfg < 2 && count_tiles(probs, floor_cfg) < 512) ++floor_cfg;
+    std::vector<int> want(probs.size());
+    double work[3] = {0, 0, 0}, total = 0;
+    for (size_t i = 0; i < probs.size(); ++i) {
+        int c = floor_cfg;
+        while (c < 2 && padded_work(probs[i], c + 1) < 0.8 * padded_work(probs[i], c)) ++c;
+        want[i] = c;
+        work[c] += padded_work(probs[i], c);
+        total += padded_work(probs[i], c);
+    }
+    int main_cfg = 0;
+    for (int c = 1; c < 3; ++c)
+        if (work[c] > work[main_cfg]) main_cfg = c;
+    {   // tuning knob: PACK_GEMM_CFG_FWD / _DX / _DW = 0..2 forces the tile configuration of the
+        // linear-layer launches of that kind (results do not depend on it)
+        const char* names[3] = {"PACK_GEMM_CFG_FWD", "PACK_GEMM_CFG_DX", "PACK_GEMM_CFG_DW"};
+        if (mode <= LIN_DW) {
+            const char* v = std::getenv(names[mode]);
+            if (v && v[0] >= '0' && v[0] <= '2' && v[1] == 0) {
+                emit_gemm_launch(p, db, mode, v[0] - '0', probs);
+                return;
+            }
+        }
+    }
+    for (int c = 0; c < 3; ++c) {
+        std::vector<GemmProb> group;
+        for (size_t i = 0; i < probs.size(); ++i) {
+            const int eff = (work[want[i]] < 0.15 * total) ? main_cfg : want[i];
+            if (eff == c) group.push_back(probs[i]);
+        }
+        if (!group.empty()) emit_gemm_launch(p, db, mode, c, group);
+    }
 }
 
 template <typename P>
@@ -418,6 +454,15 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
         return bf ? (const void*)((const char*)p->shadow + nd.w_off * 2) : (const void*)(p->master + nd.w_off);
     };
 
+    // ---------------- shared-input loader ----------------
+    for (size_t i = 0; i < p->im2col.size(); ++i) {
+        Launch L;
+        L.kind = L_IM2COL;
+        L.mode = (int)i;
+        L.n = 1;
+        p->plan.push_back(L);
+    }
+
     // ---------------- forward ----------------
     for (size_t s = 0; s < max_nodes; ++s) {
         std::vector<GemmProb> lin, conv;
@@ -446,6 +491,23 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 g.R = ti.n; g.Q = nd.out; g.Kd = nd.fan_in;
                 g.lda = nd.fan_in; g.ldb = nd.fan_in; g.ldc = nd.out;
                 if (g.Kd % V == 0) g.flags |= F_VEC_A | F_VEC_B;
+                g.ksplit = g.Kd;
+                lin.push_back(g);
+            } else if (nd.kp) {
+                // first convolution over the shared im2col buffer: a dense product, rows = pixels
+                g.A = p->im2col[nd.im2col_idx].out;
+                g.flags &= ~F_A_INPUT;
+                g.H = ti.h; g.W = ti.w; g.Cin = ti.c; g.Ho = to.h; g.Wo = to.w; g.Cout = to.c; g.stride = nd.stride;
+                g.R = to.n * to.h * to.w; g.Q = to.c; g.Kd = nd.kp;
+                g.lda = nd.kp; g.ldb = nd.kp; g.ldc = to.c;
+                g.flags |= F_VEC_A | F_VEC_B;
+                if (nd.res_src >= 0) {
+                    const TensorInfo& rs = m.tensors[nd.res_src];
+                    g.aux = rs.is_input ? nullptr : rs.act;
+                    if (rs.is_input) g.flags |= F_AUX_INPUT;
+                    g.flags |= nd.res_down ? F_RES_DOWN : F_RES_ID;
+                    g.resH = rs.h; g.resW = rs.w; g.resC = rs.c;
+                }
                 g.ksplit = g.Kd;
                 lin.push_back(g);
             } else {
@@ -526,17 +588,19 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 g.A = to.dz;
                 g.B = ti.is_input ? nullptr : ti.act;
                 g.flags = ti.is_input ? F_B_INPUT : 0;
-                g.R = nd.out; g.Q = nd.fan_in; g.Kd = rows;
-                g.lda = nd.out; g.ldc = nd.fan_in;
+                const int q_dim = nd.kp ? nd.kp : nd.fan_in;   // columns of the weight matrix in the arena
+                g.R = nd.out; g.Q = q_dim; g.Kd = rows;
+                g.lda = nd.out; g.ldc = q_dim;
                 if (nd.out % V == 0) g.flags |= F_VEC_A;
                 float* dst = p->grad + nd.w_off;
-                if (nd.kind == NODE_LINEAR) {
-                    g.ldb = nd.fan_in;
-                    if (nd.fan_in % V == 0) g.flags |= F_VEC_B;
-                    g.ksplit = std::max(g.Kd, 1);
-                    g.C = dst;
-                    g.dbias = p->grad + nd.b_off;
-                    lin_dw.push_back(g);
+                const bool dense = (nd.kind == NODE_LINEAR) || nd.kp;
+                if (dense) {
+                    g.ldb = q_dim;
+                    if (nd.kp) {
+                        g.B = p->im2col[nd.im2col_idx].out;
+                        g.flags &= ~F_B_INPUT;
+                    }
+                    if (q_dim % V == 0) g.flags |= F_VEC_B;
                 } else {
                     g.H = ti.h; g.W = ti.w; g.Cin = ti.c; g.Ho = to.h; g.Wo = to.w; g.Cout = to.c; g.stride = nd.stride;
                     g.ldb = ti.c;
@@ -545,29 +609,35 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                     const bool pow2 = (to.w & (to.w - 1)) == 0;
                     if (ti.c % V == 0 && pow2 && (to.h * to.w) % BKc == 0 && small_tensors(ti, to)) g.flags |= F_VEC_B;
                     else g.flags &= ~F_VEC_A;
-                    int S = std::min(64, std::max(1, (rows + 8191) / 8192));   // depends on the layer shape only
-                    g.ksplit = (int)align_up((size_t)(rows + S - 1) / S, 64);
-                    S = (rows + g.ksplit - 1) / g.ksplit;
-                    if (S > 1) {
-                        g.C = ws + ws_off;
-                        g.split_stride = (long long)nd.w_elems;
-                        ReduceProb r{};
-                        r.in = (const float*)g.C; r.out = dst; r.stride = (long long)nd.w_elems; r.n = (int)nd.w_elems; r.S = S;
-                        dw_red.push_back(r);
-                        dw_red_blocks.push_back((int)((nd.w_elems + 1023) / 1024));
-                        ws_off += align_up((size_t)S * nd.w_elems * 4, 256);
-                        g.dbias = (float*)(ws + ws_off);
-                        ReduceProb rb{};
-                        rb.in = g.dbias; rb.out = p->grad + nd.b_off; rb.stride = nd.out; rb.n = nd.out; rb.S = S;
-                        dw_red.push_back(rb);
-                        dw_red_blocks.push_back((nd.out + 1023) / 1024);
-                        ws_off += align_up((size_t)S * nd.out * 4, 256);
-                    } else {
-                        g.C = dst;
-                        g.dbias = p->grad + nd.b_off;
-                    }
-                    conv_dw.push_back(g);
                 }
+                // long reductions (many pixels) are split over workgroups; the split length
+                // depends on the layer shape only, partial results are summed in split order
+                const int out_tiles = ((nd.out + 127) / 128) * ((q_dim + 127) / 128);
+                const int chunk = (out_tiles == 1) ? 1024 : 8192;   // a one-tile output gets its parallelism from splits
+                int S = std::min(128, std::max(1, (rows + chunk - 1) / chunk));
+                g.ksplit = (int)align_up((size_t)(rows + S - 1) / S, 64);
+                S = (rows + g.ksplit - 1) / g.ksplit;
+                if (S > 1) {
+                    g.C = ws + ws_off;
+                    g.split_stride = (long long)nd.w_arena;
+                    ReduceProb r{};
+                    r.in = (const float*)g.C; r.out = dst; r.stride = (long long)nd.w_arena; r.n = (int)nd.w_arena; r.S = S;
+                    dw_red.push_back(r);
+                    dw_red_blocks.push_back((int)((nd.w_arena + 1023) / 1024));
+                    ws_off += align_up((size_t)S * nd.w_arena * 4, 256);
+                    g.dbias = (float*)(ws + ws_off);
+                    ReduceProb rb{};
+                    rb.in = g.dbias; rb.out = p->grad + nd.b_off; rb.stride = nd.out; rb.n = nd.out; rb.S = S;
+                    dw_red.push_back(rb);
+                    dw_red_blocks.push_back((nd.out + 1023) / 1024);
+                    ws_off += align_up((size_t)S * nd.out * 4, 256);
+                } else {
+                    g.ksplit = std::max(g.Kd, 1);
+                    g.C = dst;
+                    g.dbias = p->grad + nd.b_off;
+                }
+                if (dense) lin_dw.push_back(g);
+                else conv_dw.push_back(g);
             }
             // input gradient
             if (ti.needs_grad) {
@@ -744,7 +814,7 @@ pack_status pack_create(const pack_input_spec* input, const pack_model_spec* mod
         for (NodeInfo& nd : m.nodes) {
             if (nd.kind == NODE_GAP) continue;
             nd.w_off = off;
-            off = align_up(off + nd.w_elems, 64);
+            off = align_up(off + nd.w_arena, 64);
             nd.b_off = off;
             off = align_up(off + (size_t)nd.out, 64);
         }
@@ -768,6 +838,24 @@ pack_status pack_create(const pack_input_spec* input, const pack_model_spec* mod
     size_t slab = 0;
     auto reserve = [&](size_t bytes) { const size_t o = slab; slab += align_up(std::max<size_t>(bytes, 16), 256); return o; };
     std::vector<std::pair<void**, size_t>> fix;
+    // shared im2col buffers: one per stride used by a first-layer convolution over few channels
+    for (ModelInfo& m : p->models) {
+        NodeInfo& nd = m.nodes[0];
+        if (!nd.kp) continue;
+        for (size_t i = 0; i < p->im2col.size(); ++i)
+            if (p->im2col[i].stride == nd.stride) nd.im2col_idx = (int)i;
+        if (nd.im2col_idx < 0) {
+            Im2colProb ip{};
+            ip.B = input->B; ip.H = input->in_h; ip.W = input->in_w; ip.C = input->in_c;
+            ip.stride = nd.stride; ip.Kp = nd.kp;
+            ip.Ho = (ip.H - 1) / nd.stride + 1; ip.Wo = (ip.W - 1) / nd.stride + 1;
+            p->im2col.push_back(ip);
+            nd.im2col_idx = (int)p->im2col.size() - 1;
+        }
+    }
+    p->im2col.reserve(p->im2col.size());
+    for (Im2colProb& ip : p->im2col)
+        fix.push_back({&ip.out, reserve((size_t)ip.B * ip.Ho * ip.Wo * ip.Kp * esz)});
     for (ModelInfo& m : p->models) {
         for (TensorInfo& t : m.tensors) {
             if (t.is_input) continue;
@@ -870,6 +958,7 @@ pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, c
             case L_GAP_FWD: e = launch_gap(bf, false, (const GapProb*)d, (const int2*)mp, L.n, p->stream); break;
             case L_GAP_BWD: e = launch_gap(bf, true, (const GapProb*)d, (const int2*)mp, L.n, p->stream); break;
             case L_SHORTCUT: e = launch_shortcut_bwd(bf, (const ShortcutProb*)d, (const int2*)mp, L.n, p->stream); break;
+            case L_IM2COL: e = launch_im2col(bf, p->im2col[L.mode], x_dev, p->stream); break;
             case L_SGD:
                 e = launch_sgd(p->master, p->grad, p->shadow, (long long)p->arena_elems, p->seg_end, p->K, lr, p->stream);
                 break;
@@ -914,7 +1003,7 @@ pack_status pack_launch_name(const pack_t* p, int32_t i, char* buf, size_t n) {
     if (!p || !buf || n == 0) return fail(PACK_EINVAL, "null argument");
     if (i < 0 || i >= (int32_t)p->plan.size()) return fail(PACK_EINVAL, "launch index out of range");
     static const char* gemm_names[] = {"gemm_lin_fwd", "gemm_lin_dx", "gemm_lin_dw", "gemm_conv_fwd", "gemm_conv_dx", "gemm_conv_dw"};
-    static const char* names[] = {"", "reduce_partials", "softmax_xent", "gap_fwd", "gap_bwd", "shortcut_bwd", "sgd_update"};
+    static const char* names[] = {"", "reduce_partials", "softmax_xent", "gap_fwd", "gap_bwd", "shortcut_bwd", "sgd_update", "im2col_shared_input"};
     const Launch& L = p->plan[i];
     const char* nm = (L.kind == L_GEMM) ? gemm_names[L.mode] : names[L.kind];
     std::snprintf(buf, n, "%s", nm);

@@ -94,6 +94,11 @@ struct ShortcutProb { // backward of the residual shortcut into the source tenso
     int accum;
 };
 
+struct Im2colProb {   // shared-input loader: x [B,H,W,C] -> xcol [B*Ho*Wo, Kp], k = tap*C + c, zero beyond 9*C
+    void* out;
+    int B, H, W, C, Ho, Wo, stride, Kp;
+};
+
 struct LrTable { float lr[256]; };
 
 // launch wrappers; all enqueue on `st` and return the launch status -----------------------------
@@ -106,6 +111,7 @@ hipError_t launch_gap(bool bf16, bool backward, const GapProb* probs_dev, const 
 hipError_t launch_shortcut_bwd(bool bf16, const ShortcutProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);
 hipError_t launch_sgd(float* master, const float* grad, void* shadow_bf16, long long n,
                       const long long* seg_end_dev, int K, const LrTable& lr, hipStream_t st);
+hipError_t launch_im2col(bool bf16, const Im2colProb& p, const void* x_dev, hipStream_t st);
 hipError_t launch_cast_bf16(const float* src, void* dst_bf16, long long n, hipStream_t st);
 hipError_t launch_fill_zero(void* dst, long long bytes, hipStream_t st);
 

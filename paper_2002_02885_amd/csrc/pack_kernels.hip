@@ -921,8 +921,16 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceProb* __restric
     for (int i = 0; i < 4; ++i) {
         const int e = m.y * 1024 + i * 256 + threadIdx.x;
         if (e < p.n) {
+            // partials are added in split order; eight loads are issued before their adds so
+            // that the (strided) reads overlap instead of paying one round trip each
             float s = 0.f;
-            for (int k = 0; k < p.S; ++k) s += p.in[(size_t)k * p.stride + e];
+            for (int k0 = 0; k0 < p.S; k0 += 8) {
+                float v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = (k0 + j < p.S) ? p.in[(size_t)(k0 + j) * p.stride + e] : 0.f;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) s += v[j];
+            }
             p.out[e] = s;
         }
     }
@@ -1065,8 +1073,15 @@ __global__ __launch_bounds__(256) void gap_fwd_kernel(const GapProb* __restrict_
     if (e >= p.n * p.c) return;
     const int n = e / p.c, c = e - n * p.c;
     const T* in = (const T*)p.in + (size_t)n * p.hw * p.c + c;
+    // pixels are added in order; eight loads are issued before their adds so that they overlap
     float s = 0.f;
-    for (int i = 0; i < p.hw; ++i) s += ET<T>::to_f(in[(size_t)i * p.c]);
+    for (int i0 = 0; i0 < p.hw; i0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = (i0 + j < p.hw) ? ET<T>::to_f(in[(size_t)(i0 + j) * p.c]) : 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += v[j];
+    }
     ((T*)p.out)[e] = ET<T>::from_f(s / (float)p.hw);
 }
 
@@ -1238,6 +1253,51 @@ hipError_t launch_sgd(float* master, const float* grad, void* shadow, long long 
     const int blocks = (int)((n + SGD_PER_BLOCK - 1) / SGD_PER_BLOCK);
     if (shadow) hipLaunchKernelGGL(sgd_kernel<true>, dim3(blocks), dim3(256), 0, st, master, grad, (bf16_t*)shadow, n, seg_end, K, lr);
     else hipLaunchKernelGGL(sgd_kernel<false>, dim3(blocks), dim3(256), 0, st, master, grad, (bf16_t*)nullptr, n, seg_end, K, lr);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Shared-input loader for packs whose first layer is a convolution over few channels (paper
+// Section 3.4: the members read ONE input).  The nine shifted views of the batch are written
+// once per step as a dense matrix xcol[(b,i,j), tap*C + c] (zero for taps outside the image and
+// for the padding columns up to Kp); every member's first convolution and its weight gradient
+// are then plain aligned matrix products over that one buffer, instead of each member gathering
+// 3-channel pixels element by element.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void im2col_kernel(Im2colProb p, const T* __restrict__ x) {
+    constexpr int V = ET<T>::V;
+    const int groups = p.Kp / V;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long rows = (long long)p.B * p.Ho * p.Wo;
+    if (idx >= rows * groups) return;
+    const int g = (int)(idx % groups);
+    const long long r = idx / groups;
+    const int hw = p.Ho * p.Wo;
+    const int b = (int)(r / hw), rem = (int)(r - (long long)b * hw);
+    const int i = rem / p.Wo, j = rem - i * p.Wo;
+    T vals[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+        const int k = g * V + e;
+        const int tap = k / p.C, c = k - tap * p.C;
+        const int y = p.stride * i + tap / 3 - 1, xx = p.stride * j + tap % 3 - 1;
+        T v = (T)0;
+        if (tap < 9 && (unsigned)y < (unsigned)p.H && (unsigned)xx < (unsigned)p.W)
+            v = x[((size_t)(b * p.H + y) * p.W + xx) * p.C + c];
+        vals[e] = v;
+    }
+    u32x4_t o;
+    __builtin_memcpy(&o, vals, 16);
+    *reinterpret_cast<u32x4_t*>((T*)p.out + (size_t)r * p.Kp + g * V) = o;
+}
+
+hipError_t launch_im2col(bool bf16, const Im2colProb& p, const void* x_dev, hipStream_t st) {
+    const long long items = (long long)p.B * p.Ho * p.Wo * (p.Kp / (bf16 ? 8 : 4));
+    const int blocks = (int)((items + 255) / 256);
+    if (blocks <= 0) return hipSuccess;
+    if (bf16) hipLaunchKernelGGL(im2col_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, p, (const bf16_t*)x_dev);
+    else hipLaunchKernelGGL(im2col_kernel<float>, dim3(blocks), dim3(256), 0, st, p, (const float*)x_dev);
     return hipGetLastError();
 }
 
