@@ -9,19 +9,58 @@ LIB = os.path.join(HERE, "libpack.so")
 SOURCES = ["pack_kernels.hip", "pack_api.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # do not generate packed-fp32 instructions (v_pk_*_f32)
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # per-kernel register report, checked below
+         "-Rpass-analysis=kernel-resource-usage"]
+
+
+def check_no_spills(report: str) -> int:
+    """The GEMM kernels issue their operand loads as assembly statements whose completion the
+    compiler does not track.  That is only sound while no register such a load targets is
+    spilled or copied before the hand-placed wait, so the build refuses kernels that spill:
+    scratch must be 0 and the accumulation registers (AGPRs) must hold the MFMA accumulators
+    only: 16 per 32x32 block, (BM/64) * (BN/64) blocks per wave.  Returns the number of GEMM
+    kernels checked."""
+    import re
+    name, checked = None, 0
+    agprs = None
+    for line in report.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name, agprs = m.group(1), None
+            continue
+        if name is None or "gemm_kernel" not in name:
+            continue
+        m = re.search(r"AGPRs: (\d+)", line)
+        if m:
+            agprs = int(m.group(1))
+        m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
+        if m:
+            t = re.search(r"gemm_kernelILi\d+E[tf]Li(\d+)ELi(\d+)E", name)
+            want = 16 * (int(t.group(1)) // 64) * (int(t.group(2)) // 64)
+            if int(m.group(1)) != 0 or agprs != want:
+                raise RuntimeError(f"{name}: scratch {m.group(1)} bytes, {agprs} AGPRs (accumulators need {want}): "
+                                   "the kernel spills; the assembly-load pipeline would be unsound")
+            checked += 1
+            name = None
+    return checked
 
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB + ".tmp"]
     res = subprocess.run(cmd, capture_output=True, text=True)
-    noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    noise = ("is not a recognized feature for this target", "-Rpass-analysis=kernel-resource-usage")
+    err = "\n".join(l for l in res.stderr.splitlines() if not any(n in l for n in noise))
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + err)
-    if verbose and err.strip():
-        print(err, file=sys.stderr)
+    n = check_no_spills(res.stderr)
+    if n < 36:
+        raise RuntimeError(f"register report covered only {n} GEMM kernels")
+    if verbose:
+        for line in err.splitlines():
+            if "warning:" in line or "error:" in line:
+                print(line, file=sys.stderr)
     os.replace(LIB + ".tmp", LIB)
     return LIB
 
