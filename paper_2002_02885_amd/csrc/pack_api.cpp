@@ -46,6 +46,7 @@ struct TensorInfo {
     bool relu_out = false;   // produced through a ReLU: gradients written to it are masked
     bool needs_grad = false;
     bool grad_written = false;
+    int ld_dz = 0;           // leading dimension of dz when padded (logits), 0 = c
     void* act = nullptr;
     void* dz = nullptr;
     size_t elems() const { return (size_t)n * h * w * c; }
@@ -65,6 +66,8 @@ struct NodeInfo {
     int im2col_idx = -1;     // which shared buffer (pack_ctx::im2col)
     int fan_in = 0;
     size_t blob_off = 0;     // float offset of W in the member's public blob
+    bool has_wt = false;     // convolution with an input gradient: a transposed copy of W is kept per step
+    size_t wt_off = 0;       // element offset of that copy in pack_ctx::wt
 };
 
 struct ModelInfo {
@@ -77,7 +80,7 @@ struct ModelInfo {
     float* loss = nullptr;
 };
 
-enum LaunchKind { L_GEMM, L_REDUCE, L_CE, L_GAP_FWD, L_GAP_BWD, L_SHORTCUT, L_SGD, L_IM2COL };
+enum LaunchKind { L_GEMM, L_REDUCE, L_CE, L_GAP_FWD, L_GAP_BWD, L_SHORTCUT, L_SGD, L_IM2COL, L_WTRANS };
 
 struct Launch {
     int kind = 0, mode = 0;
@@ -100,6 +103,7 @@ struct pack_ctx {
     float* grad = nullptr;       // same layout
     void* shadow = nullptr;      // bf16 copy of the arena (bf16 packs)
     size_t arena_elems = 0;
+    void* wt = nullptr;          // per-step transposed copies [Cin][9][Cout] of convolution weights (operand type)
     long long* seg_end = nullptr;
     char* slab = nullptr;        // activations, gradients wrt activations, loss, predictions
     size_t slab_bytes = 0;
@@ -287,6 +291,10 @@ pack_status parse_model(const pack_input_spec& in, const pack_model_spec& spec, 
     if (m.nodes.empty() || m.nodes.back().kind != NODE_LINEAR || m.nodes.back().relu)
         return fail(PACK_ESHAPE, who + "the layer list must end in a LINEAR layer producing the logits");
     m.tensors[cur].f32 = true;
+    // The gradient wrt the logits keeps its rows padded to whole 16-byte vectors; the padding is
+    // zeroed once at creation and never written, so the classifier's backward products read it
+    // with aligned vector loads whatever the number of classes.
+    m.tensors[cur].ld_dz = (int)align_up((size_t)m.tensors[cur].c, in.dtype == PACK_BF16 ? 8 : 4);
     m.C = m.tensors[cur].c;
     m.n_params = blob_off;
     // which tensors have parameters upstream
@@ -373,7 +381,12 @@ void emit_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, int cfg, const std
     p->plan.push_back(L);
 }
 
-void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<GemmProb>& probs) {
+void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<GemmProb>& all_probs) {
+    // problems whose operands are not aligned for 16-byte loads go to the scalar-gather kernel
+    std::vector<GemmProb> probs, scalar;
+    for (const GemmProb& g : all_probs)
+        ((g.flags & F_VEC_A) && (g.flags & F_VEC_B) ? probs : scalar).push_back(g);
+    if (!scalar.empty()) emit_gemm_launch(p, db, mode, GEMM_CFG_SCALAR, scalar);
     if (probs.empty()) return;
     // The tile shape only partitions the output; the summation order of an element does not
     // depend on it, so a member's bits do not depend on who else is in the launch.  Each problem
@@ -539,7 +552,7 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
             const TensorInfo& lg = m.tensors[m.nodes.back().out_t];
             CeProb c{};
             c.logits = (const float*)lg.act; c.dlogits = lg.dz; c.pred = m.pred; c.loss = m.loss;
-            c.rows = m.batch; c.C = m.C; c.ld = m.C; c.ldd = m.C;
+            c.rows = m.batch; c.C = m.C; c.ld = m.C; c.ldd = lg.ld_dz;
             ce.push_back(c);
         }
         Launch L;
@@ -555,6 +568,22 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
     // Weight gradients need only dz and the stored activations, not each other, so all of them
     // run in ONE launch (per kernel kind) after the chain of input gradients: the small layers
     // fill the gaps the big ones leave instead of each paying a launch of its own.
+    {
+        std::vector<TransposeProb> tps;
+        std::vector<int> tp_blocks;
+        for (ModelInfo& m : p->models)
+            for (const NodeInfo& nd : m.nodes) {
+                if (!nd.has_wt) continue;
+                TransposeProb t{};
+                t.src = weight_ptr(nd);
+                t.dst = (char*)p->wt + nd.wt_off * esz;
+                t.Cin = m.tensors[nd.in_t].c; t.Cout = nd.out;
+                t.tiles_ci = (t.Cin + 63) / 64; t.tiles_co = (t.Cout + 63) / 64;
+                tps.push_back(t);
+                tp_blocks.push_back(9 * t.tiles_ci * t.tiles_co);
+            }
+        add_mapped_launch(p, db, L_WTRANS, tps, tp_blocks);
+    }
     std::vector<ReduceProb> dw_red;
     std::vector<int> dw_red_blocks;
     std::vector<GemmProb> lin_dw, conv_dw;
@@ -590,8 +619,8 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 g.flags = ti.is_input ? F_B_INPUT : 0;
                 const int q_dim = nd.kp ? nd.kp : nd.fan_in;   // columns of the weight matrix in the arena
                 g.R = nd.out; g.Q = q_dim; g.Kd = rows;
-                g.lda = nd.out; g.ldc = q_dim;
-                if (nd.out % V == 0) g.flags |= F_VEC_A;
+                g.lda = to.ld_dz ? to.ld_dz : nd.out; g.ldc = q_dim;
+                if (g.lda % V == 0) g.flags |= F_VEC_A;
                 float* dst = p->grad + nd.w_off;
                 const bool dense = (nd.kind == NODE_LINEAR) || nd.kp;
                 if (dense) {
@@ -651,15 +680,16 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 ti.grad_written = true;
                 if (nd.kind == NODE_LINEAR) {
                     g.R = ti.n; g.Q = nd.fan_in; g.Kd = nd.out;
-                    g.lda = nd.out; g.ldb = nd.fan_in; g.ldc = nd.fan_in;
-                    if (nd.out % V == 0) g.flags |= F_VEC_A;
+                    g.lda = to.ld_dz ? to.ld_dz : nd.out; g.ldb = nd.fan_in; g.ldc = nd.fan_in;
+                    if (g.lda % V == 0) g.flags |= F_VEC_A;
                     if (nd.fan_in % V == 0) g.flags |= F_VEC_B;
                     g.ksplit = g.Kd;
                     lin_dx.push_back(g);
                 } else {
                     g.H = ti.h; g.W = ti.w; g.Cin = ti.c; g.Ho = to.h; g.Wo = to.w; g.Cout = to.c; g.stride = nd.stride;
                     g.R = ti.n * ti.h * ti.w; g.Q = ti.c; g.Kd = 9 * to.c;
-                    g.lda = to.c; g.ldb = ti.c; g.ldc = ti.c;
+                    g.B = (const char*)p->wt + nd.wt_off * esz;   // transposed copy [Cin][9][Cout]
+                    g.lda = to.c; g.ldb = 9 * to.c; g.ldc = ti.c;
                     if (to.c % BKc == 0 && ti.c % V == 0 && small_tensors(ti, to)) g.flags |= F_VEC_A | F_VEC_B;
                     g.ksplit = g.Kd;
                     if (nd.stride == 2 && (g.flags & F_VEC_A)) {
@@ -715,7 +745,6 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
     add_gemm_launch(p, db, LIN_DW, lin_dw);
     add_gemm_launch(p, db, CONV_DW, conv_dw);
     add_mapped_launch(p, db, L_REDUCE, dw_red, dw_red_blocks);
-    (void)esz;
 
     // ---------------- update ----------------
     Launch L;
@@ -729,6 +758,7 @@ void release(pack_ctx* p) {
     if (p->master) (void)hipFree(p->master);
     if (p->grad) (void)hipFree(p->grad);
     if (p->shadow) (void)hipFree(p->shadow);
+    if (p->wt) (void)hipFree(p->wt);
     if (p->seg_end) (void)hipFree(p->seg_end);
     if (p->slab) (void)hipFree(p->slab);
     if (p->workspace) (void)hipFree(p->workspace);
@@ -833,6 +863,17 @@ pack_status pack_create(const pack_input_spec* input, const pack_model_spec* mod
     TRY_ALLOC(p->grad, p->arena_elems * 4);
     if (p->bf16) TRY_ALLOC(p->shadow, p->arena_elems * 2);
     TRY_ALLOC(p->seg_end, (size_t)K * sizeof(long long));
+    {
+        size_t wt_elems = 0;
+        for (ModelInfo& m : p->models)
+            for (NodeInfo& nd : m.nodes) {
+                if (nd.kind != NODE_CONV || nd.kp || !m.tensors[nd.in_t].needs_grad) continue;
+                nd.has_wt = true;
+                nd.wt_off = wt_elems;
+                wt_elems = align_up(wt_elems + nd.w_elems, 64);
+            }
+        if (wt_elems) TRY_ALLOC(p->wt, wt_elems * esz);
+    }
 
     // one slab for activations, their gradients, predictions, losses and the label-error flag
     size_t slab = 0;
@@ -860,7 +901,7 @@ pack_status pack_create(const pack_input_spec* input, const pack_model_spec* mod
         for (TensorInfo& t : m.tensors) {
             if (t.is_input) continue;
             fix.push_back({&t.act, reserve(t.elems() * (t.f32 ? 4 : esz))});
-            fix.push_back({&t.dz, reserve(t.elems() * esz)});
+            fix.push_back({&t.dz, reserve((t.ld_dz ? (size_t)t.n * t.ld_dz : t.elems()) * esz)});
         }
         fix.push_back({(void**)&m.pred, reserve((size_t)m.batch * 4)});
     }
@@ -959,6 +1000,7 @@ pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, c
             case L_GAP_BWD: e = launch_gap(bf, true, (const GapProb*)d, (const int2*)mp, L.n, p->stream); break;
             case L_SHORTCUT: e = launch_shortcut_bwd(bf, (const ShortcutProb*)d, (const int2*)mp, L.n, p->stream); break;
             case L_IM2COL: e = launch_im2col(bf, p->im2col[L.mode], x_dev, p->stream); break;
+            case L_WTRANS: e = launch_wtranspose(bf, (const TransposeProb*)d, (const int2*)mp, L.n, p->stream); break;
             case L_SGD:
                 e = launch_sgd(p->master, p->grad, p->shadow, (long long)p->arena_elems, p->seg_end, p->K, lr, p->stream);
                 break;
@@ -1003,7 +1045,7 @@ pack_status pack_launch_name(const pack_t* p, int32_t i, char* buf, size_t n) {
     if (!p || !buf || n == 0) return fail(PACK_EINVAL, "null argument");
     if (i < 0 || i >= (int32_t)p->plan.size()) return fail(PACK_EINVAL, "launch index out of range");
     static const char* gemm_names[] = {"gemm_lin_fwd", "gemm_lin_dx", "gemm_lin_dw", "gemm_conv_fwd", "gemm_conv_dx", "gemm_conv_dw"};
-    static const char* names[] = {"", "reduce_partials", "softmax_xent", "gap_fwd", "gap_bwd", "shortcut_bwd", "sgd_update", "im2col_shared_input"};
+    static const char* names[] = {"", "reduce_partials", "softmax_xent", "gap_fwd", "gap_bwd", "shortcut_bwd", "sgd_update", "im2col_shared_input", "transpose_conv_weights"};
     const Launch& L = p->plan[i];
     const char* nm = (L.kind == L_GEMM) ? gemm_names[L.mode] : names[L.kind];
     std::snprintf(buf, n, "%s", nm);

@@ -99,6 +99,12 @@ struct Im2colProb {   // shared-input loader: x [B,H,W,C] -> xcol [B*Ho*Wo, Kp],
     int B, H, W, C, Ho, Wo, stride, Kp;
 };
 
+struct TransposeProb {   // convolution weights [Cout][9][Cin] -> [Cin][9][Cout], both of the pack's operand type
+    const void* src;
+    void* dst;
+    int Cin, Cout, tiles_ci, tiles_co;   // 64 x 64 tiles per tap
+};
+
 struct LrTable { float lr[256]; };
 
 // launch wrappers; all enqueue on `st` and return the launch status -----------------------------
@@ -112,12 +118,15 @@ hipError_t launch_shortcut_bwd(bool bf16, const ShortcutProb* probs_dev, const i
 hipError_t launch_sgd(float* master, const float* grad, void* shadow_bf16, long long n,
                       const long long* seg_end_dev, int K, const LrTable& lr, hipStream_t st);
 hipError_t launch_im2col(bool bf16, const Im2colProb& p, const void* x_dev, hipStream_t st);
+hipError_t launch_wtranspose(bool bf16, const TransposeProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);
 hipError_t launch_cast_bf16(const float* src, void* dst_bf16, long long n, hipStream_t st);
 hipError_t launch_fill_zero(void* dst, long long bytes, hipStream_t st);
 
 // tile geometry the planner needs
-constexpr int GEMM_TILE_M[3] = {128, 128, 64};
-constexpr int GEMM_TILE_N[3] = {128, 64, 64};
+// configurations 0..2: aligned problems (16-byte operand loads); 3: the scalar gather for any shape
+constexpr int GEMM_TILE_M[4] = {128, 128, 64, 64};
+constexpr int GEMM_TILE_N[4] = {128, 64, 64, 64};
+constexpr int GEMM_CFG_SCALAR = 3;
 constexpr int ELEMWISE_PER_BLOCK = 2048;   // elements one block of the elementwise kernels covers
 constexpr int SGD_PER_BLOCK = 4096;        // parameters one block of the update kernel covers
 

@@ -15,6 +15,7 @@
 #include "pack_internal.h"
 
 #include <type_traits>
+#include <utility>
 
 namespace packk {
 
@@ -46,6 +47,32 @@ template <> struct ET<bf16_t> {
     static __device__ __forceinline__ float to_f(bf16_t v) { return bf2f(v); }
     static __device__ __forceinline__ bf16_t from_f(float v) { return f2bf(v); }
 };
+
+// F_ROWMAP problems (one parity class of a stride-2 input gradient): the tap that reduction
+// block `tc` of the class stands for, and the pixel an output row stands for
+__device__ __forceinline__ int class_tap(const GemmProb& p, int tc) {
+    const int ntx = p.cls_px ? 1 : 2;
+    const int iu = tc / ntx, iv = tc - iu * ntx;
+    const int u = p.cls_py ? 1 : 2 * iu, v = p.cls_px ? 1 : 2 * iv;
+    return u * 3 + v;
+}
+__device__ __forceinline__ void class_pixel(const GemmProb& p, int r, int& b, int& y, int& x) {
+    const int hw = p.cls_h * p.cls_w;
+    b = r / hw;
+    const int rem = r - b * hw;
+    const int yc = rem / p.cls_w, xc = rem - yc * p.cls_w;
+    y = 2 * yc + 1 - p.cls_py;
+    x = 2 * xc + 1 - p.cls_px;
+}
+// element offset of output row `row` (times the leading dimension) for the epilogue
+__device__ __forceinline__ size_t out_row_base(const GemmProb& p, int row) {
+    if (p.flags & F_ROWMAP) {
+        int b, y, x;
+        class_pixel(p, row, b, y, x);
+        return ((size_t)(b * p.H + y) * p.W + x) * p.ldc;
+    }
+    return (size_t)row * p.ldc;
+}
 
 // ------------------------------------------------------------------------------------------------
 // operand address rules: element (row, k) of operand A / B for each mode.  Each rule returns
@@ -98,9 +125,15 @@ __device__ __forceinline__ bool off_b(const GemmProb& p, int q, int k, size_t& o
         o = (size_t)q * p.ldb + k;
     } else if constexpr (MODE == LIN_DX || MODE == LIN_DW) {
         o = (size_t)k * p.ldb + q;
-    } else if constexpr (MODE == CONV_DX) {   // q = input channel c, k = (tap, o); W is [Cout][9][Cin]
-        const int tap = k / p.Cout, oc = k - tap * p.Cout;
-        o = ((size_t)oc * 9 + tap) * p.Cin + q;
+    } else if constexpr (MODE == CONV_DX) {
+        // q = input channel c, k = (tap, o); the operand is the per-step transposed copy of the
+        // weights, [Cin][9][Cout], so the reduction is contiguous (ldb = 9 * Cout)
+        int kk = k;
+        if (p.flags & F_ROWMAP) {
+            const int tc = k / p.Cout;
+            kk = class_tap(p, tc) * p.Cout + (k - tc * p.Cout);
+        }
+        o = (size_t)q * p.ldb + kk;
     } else {  // CONV_DW: q = (tap, c), k = output pixel (b, i, j)
         const int tap = q / p.Cin, c = q - tap * p.Cin;
         const int u = tap / 3, v = tap - 3 * u;
@@ -118,7 +151,7 @@ __device__ __forceinline__ bool off_b(const GemmProb& p, int q, int k, size_t& o
 // Which operands are contiguous along the reduction (KC) and which along their row index (RC).
 template <int MODE> struct OperandLayout {
     static constexpr bool A_KC = (MODE == LIN_FWD || MODE == LIN_DX || MODE == CONV_FWD || MODE == CONV_DX);
-    static constexpr bool B_KC = (MODE == LIN_FWD || MODE == CONV_FWD);
+    static constexpr bool B_KC = (MODE == LIN_FWD || MODE == CONV_FWD || MODE == CONV_DX);
 };
 
 // ------------------------------------------------------------------------------------------------
@@ -368,32 +401,6 @@ __device__ __forceinline__ void stash_tile(T* __restrict__ Sbase,
 // whatever BM, BN and the LDS chunk BK are, so the choice of tile shape never changes a result bit.
 // BKM scales the LDS chunk: skinny problems (few rows, long reduction) are bound by the latency
 // of one global round trip per chunk, so they take chunks four times as long.
-// F_ROWMAP problems (one parity class of a stride-2 input gradient): the tap that reduction
-// block `tc` of the class stands for, and the pixel an output row stands for
-__device__ __forceinline__ int class_tap(const GemmProb& p, int tc) {
-    const int ntx = p.cls_px ? 1 : 2;
-    const int iu = tc / ntx, iv = tc - iu * ntx;
-    const int u = p.cls_py ? 1 : 2 * iu, v = p.cls_px ? 1 : 2 * iv;
-    return u * 3 + v;
-}
-__device__ __forceinline__ void class_pixel(const GemmProb& p, int r, int& b, int& y, int& x) {
-    const int hw = p.cls_h * p.cls_w;
-    b = r / hw;
-    const int rem = r - b * hw;
-    const int yc = rem / p.cls_w, xc = rem - yc * p.cls_w;
-    y = 2 * yc + 1 - p.cls_py;
-    x = 2 * xc + 1 - p.cls_px;
-}
-// element offset of output row `row` (times the leading dimension) for the epilogue
-__device__ __forceinline__ size_t out_row_base(const GemmProb& p, int row) {
-    if (p.flags & F_ROWMAP) {
-        int b, y, x;
-        class_pixel(p, row, b, y, x);
-        return ((size_t)(b * p.H + y) * p.W + x) * p.ldc;
-    }
-    return (size_t)row * p.ldc;
-}
-
 // issues one assembly load of 16 bytes from `ptr` (see load_vec for why it is assembly)
 __device__ __forceinline__ u32x4_t asm_load16(const void* ptr) {
     u32x4_t v;
@@ -414,9 +421,9 @@ struct Fetcher {
     static constexpr bool KC = IS_A ? OperandLayout<MODE>::A_KC : OperandLayout<MODE>::B_KC;
     static constexpr bool ASM = ((PACK_ASM_MODES >> MODE) & 1) != 0;
     static constexpr bool GATHER_KC = VEC && ASM && IS_A && (MODE == CONV_FWD || MODE == CONV_DX);
-    static constexpr bool WEIGHT_RC = VEC && ASM && !IS_A && MODE == CONV_DX;
+    static constexpr bool WEIGHT_KC = VEC && ASM && !IS_A && MODE == CONV_DX;
     static constexpr bool GATHER_RC = VEC && ASM && !IS_A && MODE == CONV_DW;
-    static constexpr int NS = GATHER_KC ? G::KC_SLOTS : ((WEIGHT_RC || GATHER_RC) ? G::RC_PER_THREAD : 1);
+    static constexpr int NS = (GATHER_KC || WEIGHT_KC) ? G::KC_SLOTS : (GATHER_RC ? G::RC_PER_THREAD : 1);
 
     int row0;
     int base[NS];        // element offset of the thread's row / block, without the per-chunk part
@@ -470,15 +477,13 @@ struct Fetcher {
                 }
                 mask[s] = live ? m : 0u;
             }
-        } else if constexpr (WEIGHT_RC) {
+        } else if constexpr (WEIGHT_KC) {
 #pragma unroll
-            for (int j = 0; j < NS; ++j) {
-                const int b = tid + 256 * j;
-                int kq, rv;
-                rc_block_coords<G>(b, kq, rv);
-                const int q = row0 + rv * G::V;
-                base[j] = kq * 4 * 9 * p.Cin + q;
-                mask[j] = ((b < G::RC_BLOCKS) && (q < p.Q)) ? 1u : 0u;
+            for (int s = 0; s < NS; ++s) {
+                const int vid = tid + 256 * s;
+                const int q = row0 + vid / G::VPR;
+                base[s] = q * p.ldb + (vid % G::VPR) * G::V;
+                mask[s] = ((vid < G::NVEC) && (q < p.Q)) ? 1u : 0u;
             }
         } else if constexpr (GATHER_RC) {
 #pragma unroll
@@ -519,19 +524,17 @@ struct Fetcher {
                 const void* ptr = ok ? (const void*)(src + (base[s] + toff)) : p.zeros;
                 regs[s] = asm_load16(ptr);
             }
-        } else if constexpr (WEIGHT_RC) {
+        } else if constexpr (WEIGHT_KC) {
+            // transposed weights [Cin][9][Cout]: the chunk lies in one tap
             const int tc = k0 / p.Cout, o0 = k0 - tc * p.Cout;
             const int tap = (p.flags & F_ROWMAP) ? class_tap(p, tc) : tc;
-            const int toff = (o0 * 9 + tap) * p.Cin;
+            const int toff = tap * p.Cout + o0;
             const bool in_range = k0 < kend;
 #pragma unroll
-            for (int j = 0; j < NS; ++j) {
-                const bool ok = in_range && mask[j];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const void* ptr = ok ? (const void*)(src + (base[j] + toff + e * 9 * p.Cin)) : p.zeros;
-                    regs[4 * j + e] = asm_load16(ptr);
-                }
+            for (int s = 0; s < NS; ++s) {
+                const bool ok = in_range && mask[s];
+                const void* ptr = ok ? (const void*)(src + (base[s] + toff)) : p.zeros;
+                regs[s] = asm_load16(ptr);
             }
         } else if constexpr (GATHER_RC) {
             // reduction index = output pixel; the chunk lies inside one image
@@ -558,9 +561,24 @@ struct Fetcher {
     }
 };
 
-template <int BM, int BN, int BKM>
+template <int... Is, typename F>
+__device__ __forceinline__ void for_each_stage(std::integer_sequence<int, Is...>, F&& f) {
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+
+#ifndef PACK_ST_64x64
+#define PACK_ST_64x64 4
+#endif
+#ifndef PACK_ST_128x64
+#define PACK_ST_128x64 3
+#endif
+#ifndef PACK_ST_128x128
+#define PACK_ST_128x128 2
+#endif
+
+template <int BM, int BN, int BKM, bool VEC>
 struct StageCount {   // register stages of prefetch per tile shape (bounded by the register file)
-    static constexpr int value = (BKM > 1) ? 2 : ((BM * BN >= 128 * 128) ? 2 : ((BM * BN >= 128 * 64) ? 3 : 4));
+    static constexpr int value = (BKM > 1 || !VEC) ? 2 : ((BM * BN >= 128 * 128) ? PACK_ST_128x128 : ((BM * BN >= 128 * 64) ? PACK_ST_128x64 : PACK_ST_64x64));
 };
 
 template <int MODE, typename T, int BM, int BN, int BKM, bool VEC>
@@ -574,7 +592,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
     // i + ST - 1 are issued before chunk i is multiplied, so ST - 1 round trips to memory are in
     // flight per workgroup; a skinny layer has too few workgroups per compute unit to hide that
     // latency by occupancy alone.
-    constexpr int ST = StageCount<BM, BN, BKM>::value;
+    constexpr int ST = StageCount<BM, BN, BKM, VEC>::value;
     T(*As)[BM][GA::LDS_LD] = reinterpret_cast<T(*)[BM][GA::LDS_LD]>(As_);
     T(*Bs)[BN][GB::LDS_LD] = reinterpret_cast<T(*)[BN][GB::LDS_LD]>(Bs_);
 
@@ -684,15 +702,11 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
     // full groups of ST chunks: a branch-free body, so that the compiler waits only for the
     // oldest register stage; then up to ST - 1 remaining chunks, which need no further loads
     int it0 = 0;
-    for (; it0 + ST <= nk; it0 += ST) {
-        chunk(integral_constant<int, 0>{}, it0, Yes{});
-        if constexpr (ST > 1) chunk(integral_constant<int, 1 % ST>{}, it0 + 1, Yes{});
-        if constexpr (ST > 2) chunk(integral_constant<int, 2 % ST>{}, it0 + 2, Yes{});
-        if constexpr (ST > 3) chunk(integral_constant<int, 3 % ST>{}, it0 + 3, Yes{});
-    }
-    if (it0 < nk) chunk(integral_constant<int, 0>{}, it0, No{});
-    if constexpr (ST > 2) { if (it0 + 1 < nk) chunk(integral_constant<int, 1 % ST>{}, it0 + 1, No{}); }
-    if constexpr (ST > 3) { if (it0 + 2 < nk) chunk(integral_constant<int, 2 % ST>{}, it0 + 2, No{}); }
+    for (; it0 + ST <= nk; it0 += ST)
+        for_each_stage(std::make_integer_sequence<int, ST>{}, [&](auto S) { chunk(S, it0 + decltype(S)::value, Yes{}); });
+    for_each_stage(std::make_integer_sequence<int, ST - 1>{}, [&](auto S) {
+        if (it0 + decltype(S)::value < nk) chunk(S, it0 + decltype(S)::value, No{});
+    });
     if constexpr (VEC && ((PACK_ASM_MODES >> MODE) & 1)) {
         // The last full group prefetched chunks beyond the reduction (reads of the zeros block).
         // Those loads are invisible to the compiler and still target the stage registers, which
@@ -863,7 +877,11 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
     }
 }
 
-template <int MODE, typename T, int BM, int BN, int BKM>
+// VEC = true: every problem of the launch has both operands aligned for 16-byte loads (the planner
+// sorts problems into launches by that); VEC = false: the element-by-element gather for any shape.
+// They are separate kernels because the gather needs many more registers, which would halve the
+// occupancy of the aligned path if both lived in one kernel.
+template <int MODE, typename T, int BM, int BN, int BKM, bool VEC>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ probs,
                                                    const TileRef* __restrict__ tiles,
                                                    const void* __restrict__ x) {
@@ -879,17 +897,16 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
     __shared__ __attribute__((aligned(16))) T lds[2 * BM * TileGeom<T, BM, BK>::LDS_LD + 2 * BN * TileGeom<T, BN, BK>::LDS_LD];
     T* const As = lds;
     T* const Bs = lds + 2 * BM * TileGeom<T, BM, BK>::LDS_LD;
-    // aligned shapes take 16-byte loads for both operands; anything else takes the scalar gather
-    if ((p.flags & F_VEC_A) && (p.flags & F_VEC_B)) gemm_body<MODE, T, BM, BN, BKM, true>(p, tr, As, Bs);
-    else gemm_body<MODE, T, BM, BN, BKM, false>(p, tr, As, Bs);
+    gemm_body<MODE, T, BM, BN, BKM, VEC>(p, tr, As, Bs);
 }
 
 template <int MODE, typename T>
 static void launch_gemm_tile(int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, hipStream_t st) {
     switch (tile_cfg) {
-        case 0: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 128, 1>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
-        case 1: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 64, 1>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
-        default: hipLaunchKernelGGL((gemm_kernel<MODE, T, 64, 64, 1>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
+        case 0: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 128, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
+        case 1: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 64, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
+        case 2: hipLaunchKernelGGL((gemm_kernel<MODE, T, 64, 64, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
+        default: hipLaunchKernelGGL((gemm_kernel<MODE, T, 64, 64, 1, false>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
     }
 }
 
@@ -1298,6 +1315,42 @@ hipError_t launch_im2col(bool bf16, const Im2colProb& p, const void* x_dev, hipS
     if (blocks <= 0) return hipSuccess;
     if (bf16) hipLaunchKernelGGL(im2col_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, p, (const bf16_t*)x_dev);
     else hipLaunchKernelGGL(im2col_kernel<float>, dim3(blocks), dim3(256), 0, st, p, (const float*)x_dev);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Per-tap transpose of convolution weights, once per step: [Cout][9][Cin] -> [Cin][9][Cout].
+// The input gradient of a convolution is itself a convolution of dz with these transposed
+// weights; with the copy both of its operands are contiguous along the reduction, like the
+// forward pass.  One block moves a 64 x 64 (Cout x Cin) tile of one tap through LDS.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void wtranspose_kernel(const TransposeProb* __restrict__ probs, const int2* __restrict__ map) {
+    __shared__ T tile[64][64 + 4 / sizeof(T)];
+    const int2 pb = map[blockIdx.x];
+    const TransposeProb p = probs[pb.x];
+    const int tap = pb.y % 9, rest = pb.y / 9;
+    const int ci0 = (rest % p.tiles_ci) * 64, co0 = (rest / p.tiles_ci) * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const T* __restrict__ src = (const T*)p.src;
+    T* __restrict__ dst = (T*)p.dst;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int co = co0 + ty + 4 * i, ci = ci0 + tx;
+        if (co < p.Cout && ci < p.Cin) tile[ty + 4 * i][tx] = src[((size_t)co * 9 + tap) * p.Cin + ci];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int ci = ci0 + ty + 4 * i, co = co0 + tx;
+        if (co < p.Cout && ci < p.Cin) dst[((size_t)ci * 9 + tap) * p.Cout + co] = tile[tx][ty + 4 * i];
+    }
+}
+
+hipError_t launch_wtranspose(bool bf16, const TransposeProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st) {
+    if (n_blocks <= 0) return hipSuccess;
+    if (bf16) hipLaunchKernelGGL(wtranspose_kernel<bf16_t>, dim3(n_blocks), dim3(256), 0, st, probs_dev, map_dev);
+    else hipLaunchKernelGGL(wtranspose_kernel<float>, dim3(n_blocks), dim3(256), 0, st, probs_dev, map_dev);
     return hipGetLastError();
 }
 
