@@ -337,6 +337,16 @@ std::vector<TileRef> xcd_order(const std::vector<TileOrder>& logical) {
     return out;
 }
 
+// rows of the problem are pixels of a w-wide, hw-pixel image plane
+void set_row_space(GemmProb& g, int w, int hw) {
+    g.row_w = w;
+    g.row_hw = hw;
+    auto lg = [](int v) { int l = 0; while ((1 << l) < v) ++l; return ((1 << l) == v) ? l : -1; };
+    g.lg_row_w = lg(w);
+    g.lg_row_hw = lg(hw);
+    if (g.lg_row_w < 0 || g.lg_row_hw < 0) g.lg_row_w = g.lg_row_hw = -1;
+}
+
 size_t count_tiles(const std::vector<GemmProb>& probs, int cfg) {
     size_t n = 0;
     for (const GemmProb& g : probs) {
@@ -512,6 +522,7 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 g.flags &= ~F_A_INPUT;
                 g.H = ti.h; g.W = ti.w; g.Cin = ti.c; g.Ho = to.h; g.Wo = to.w; g.Cout = to.c; g.stride = nd.stride;
                 g.R = to.n * to.h * to.w; g.Q = to.c; g.Kd = nd.kp;
+                set_row_space(g, to.w, to.h * to.w);
                 g.lda = nd.kp; g.ldb = nd.kp; g.ldc = to.c;
                 g.flags |= F_VEC_A | F_VEC_B;
                 if (nd.res_src >= 0) {
@@ -526,6 +537,7 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
             } else {
                 g.H = ti.h; g.W = ti.w; g.Cin = ti.c; g.Ho = to.h; g.Wo = to.w; g.Cout = to.c; g.stride = nd.stride;
                 g.R = to.n * to.h * to.w; g.Q = to.c; g.Kd = 9 * ti.c;
+                set_row_space(g, to.w, to.h * to.w);
                 g.lda = ti.c; g.ldb = 9 * ti.c; g.ldc = to.c;
                 // vector path of the gathered operand: a chunk must stay inside one tap
                 if (ti.c % BKc == 0 && small_tensors(ti, to)) g.flags |= F_VEC_A | F_VEC_B;
@@ -688,6 +700,7 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 } else {
                     g.H = ti.h; g.W = ti.w; g.Cin = ti.c; g.Ho = to.h; g.Wo = to.w; g.Cout = to.c; g.stride = nd.stride;
                     g.R = ti.n * ti.h * ti.w; g.Q = ti.c; g.Kd = 9 * to.c;
+                    set_row_space(g, ti.w, ti.h * ti.w);
                     g.B = (const char*)p->wt + nd.wt_off * esz;   // transposed copy [Cin][9][Cout]
                     g.lda = to.c; g.ldb = 9 * to.c; g.ldc = ti.c;
                     if (to.c % BKc == 0 && ti.c % V == 0 && small_tensors(ti, to)) g.flags |= F_VEC_A | F_VEC_B;
@@ -705,6 +718,7 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                                 c.cls_h = py ? (ti.h + 1) / 2 : ti.h / 2;
                                 c.cls_w = px ? (ti.w + 1) / 2 : ti.w / 2;
                                 c.R = ti.n * c.cls_h * c.cls_w;
+                                set_row_space(c, c.cls_w, c.cls_h * c.cls_w);
                                 c.Kd = (py ? 1 : 2) * (px ? 1 : 2) * to.c;
                                 c.ksplit = c.Kd;
                                 if (c.R > 0) conv_dx.push_back(c);

@@ -49,6 +49,8 @@ struct GemmProb {
     int H, W, Cin, Ho, Wo, Cout, stride;   // geometry of the forward convolution (conv modes)
     int resH, resW, resC;                  // geometry of the shortcut source (F_RES_DOWN)
     int cls_py, cls_px, cls_h, cls_w;      // F_ROWMAP: parity class and its extent in pixels
+    int row_w, row_hw;                     // conv problems whose rows are pixels: row r = (image, r % row_hw / row_w, r % row_w)
+    int lg_row_w, lg_row_hw;               // their base-2 logarithms when both are powers of two, else -1
     int flags;
     int ksplit;                            // reduction indices per split (>= Kd when not split)
     long long split_stride;                // elements between the partial outputs of two splits

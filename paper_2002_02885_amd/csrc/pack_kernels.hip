@@ -25,13 +25,16 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
 
-// round to nearest, ties to even; NaN stays NaN (quiet)
-__device__ __forceinline__ bf16_t f2bf(float f) {
-    unsigned int u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+
+// float -> bfloat16, round to nearest with ties to even, NaN stays NaN: the hardware conversion
+// (one instruction per pair of values)
+__device__ __forceinline__ unsigned pack2bf(float lo, float hi) {
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
 }
+__device__ __forceinline__ bf16_t f2bf(float f) { return (bf16_t)(pack2bf(f, 0.f) & 0xffffu); }
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((unsigned int)h) << 16); }
 
 template <typename T> struct ET;
@@ -56,11 +59,24 @@ __device__ __forceinline__ int class_tap(const GemmProb& p, int tc) {
     const int u = p.cls_py ? 1 : 2 * iu, v = p.cls_px ? 1 : 2 * iv;
     return u * 3 + v;
 }
+// row index of a problem whose rows are pixels -> (image, pixel row, pixel column); shifts when the
+// extents are powers of two (uniform branch), divisions otherwise
+__device__ __forceinline__ void decode_row(const GemmProb& p, int r, int& b, int& i, int& j) {
+    if (p.lg_row_hw >= 0) {
+        b = r >> p.lg_row_hw;
+        const int rem = r & (p.row_hw - 1);
+        i = rem >> p.lg_row_w;
+        j = rem & (p.row_w - 1);
+    } else {
+        b = r / p.row_hw;
+        const int rem = r - b * p.row_hw;
+        i = rem / p.row_w;
+        j = rem - i * p.row_w;
+    }
+}
 __device__ __forceinline__ void class_pixel(const GemmProb& p, int r, int& b, int& y, int& x) {
-    const int hw = p.cls_h * p.cls_w;
-    b = r / hw;
-    const int rem = r - b * hw;
-    const int yc = rem / p.cls_w, xc = rem - yc * p.cls_w;
+    int yc, xc;
+    decode_row(p, r, b, yc, xc);
     y = 2 * yc + 1 - p.cls_py;
     x = 2 * xc + 1 - p.cls_px;
 }
@@ -441,40 +457,34 @@ struct Fetcher {
                 const int kv = (vid % G::VPR) * G::V;
                 const bool live = (vid < G::NVEC) && (r < p.R);
                 unsigned m = 0;
+                // tap (u, v) is inside the image iff row condition u and column condition v hold:
+                // three bits each, combined into the nine-bit mask
+                unsigned rb = 0, cb = 0;
                 if constexpr (MODE == CONV_FWD) {
-                    const int hw = p.Ho * p.Wo;
-                    const int b = r / hw, rem = r - b * hw;
-                    const int i = rem / p.Wo, j = rem - i * p.Wo;
+                    int b, i, j;
+                    decode_row(p, r, b, i, j);
                     const int y0 = p.stride * i - 1, x0 = p.stride * j - 1;
                     base[s] = ((b * p.H + y0) * p.W + x0) * p.Cin + kv;
 #pragma unroll
-                    for (int t = 0; t < 9; ++t) {
-                        const int y = y0 + t / 3, x = x0 + t % 3;
-                        if ((unsigned)y < (unsigned)p.H && (unsigned)x < (unsigned)p.W) m |= 1u << t;
+                    for (int t = 0; t < 3; ++t) {
+                        if ((unsigned)(y0 + t) < (unsigned)p.H) rb |= 1u << t;
+                        if ((unsigned)(x0 + t) < (unsigned)p.W) cb |= 1u << t;
                     }
                 } else {   // CONV_DX: rows are input pixels, the gather reads dz
                     int b, y, x;
-                    if (p.flags & F_ROWMAP) {
-                        class_pixel(p, r, b, y, x);
-                    } else {
-                        const int hw = p.H * p.W;
-                        b = r / hw;
-                        const int rem = r - b * hw;
-                        y = rem / p.W;
-                        x = rem - y * p.W;
-                    }
+                    if (p.flags & F_ROWMAP) class_pixel(p, r, b, y, x);
+                    else decode_row(p, r, b, y, x);
                     const int yy = y + 1, xx = x + 1;
                     const int sh = (p.stride == 2) ? 1 : 0;
                     base[s] = ((b * p.Ho + (yy >> sh)) * p.Wo + (xx >> sh)) * p.Cout + kv;
 #pragma unroll
-                    for (int t = 0; t < 9; ++t) {
-                        const int ty = yy - t / 3, tx = xx - t % 3;
-                        bool ok = (ty >= 0) && (tx >= 0);
-                        if (sh) ok = ok && (((ty | tx) & 1) == 0);
-                        ok = ok && ((ty >> sh) < p.Ho) && ((tx >> sh) < p.Wo);
-                        if (ok) m |= 1u << t;
+                    for (int t = 0; t < 3; ++t) {
+                        const int ty = yy - t, tx = xx - t;
+                        if (ty >= 0 && !(ty & sh) && (ty >> sh) < p.Ho) rb |= 1u << t;
+                        if (tx >= 0 && !(tx & sh) && (tx >> sh) < p.Wo) cb |= 1u << t;
                     }
                 }
+                m = ((rb & 1u) ? cb : 0u) | ((rb & 2u) ? cb << 3 : 0u) | ((rb & 4u) ? cb << 6 : 0u);
                 mask[s] = live ? m : 0u;
             }
         } else if constexpr (WEIGHT_KC) {
@@ -751,9 +761,8 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
             if (p.flags & F_RES_ID) v += ET<T>::to_f(((const T*)p.aux)[off]);
             if (p.flags & F_RES_DOWN) {
                 if (col < p.resC) {
-                    const int hw = p.Ho * p.Wo;
-                    const int bb = row / hw, rem = row - bb * hw;
-                    const int i = rem / p.Wo, j = rem - i * p.Wo;
+                    int bb, i, j;
+                    decode_row(p, row, bb, i, j);
                     v += ET<T>::to_f(((const T*)p.aux)[((size_t)(bb * p.resH + 2 * i) * p.resW + 2 * j) * p.resC + col]);
                 }
             }
@@ -802,9 +811,8 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                 if (p.flags & F_RES_ID) {
                     res = (const T*)p.aux + off;
                 } else if ((p.flags & F_RES_DOWN) && col < p.resC) {
-                    const int hw = p.Ho * p.Wo;
-                    const int bb = row / hw, rem = row - bb * hw;
-                    const int i = rem / p.Wo, j = rem - i * p.Wo;
+                    int bb, i, j;
+                    decode_row(p, row, bb, i, j);
                     res = (const T*)p.aux + ((size_t)(bb * p.resH + 2 * i) * p.resW + 2 * j) * p.resC + col;
                 }
                 if (res) {
@@ -857,7 +865,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
             } else if constexpr (sizeof(T) == 2) {
                 u32x4_t o;
 #pragma unroll
-                for (int d = 0; d < 4; ++d) o[d] = (unsigned)f2bf(v[2 * d]) | ((unsigned)f2bf(v[2 * d + 1]) << 16);
+                for (int d = 0; d < 4; ++d) o[d] = pack2bf(v[2 * d], v[2 * d + 1]);
                 *reinterpret_cast<u32x4_t*>((T*)p.C + off) = o;
             } else {
                 *reinterpret_cast<f32x4_t*>((float*)p.C + off) = f32x4_t{v[0], v[1], v[2], v[3]};
@@ -1256,8 +1264,8 @@ __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ w, const f
             *reinterpret_cast<f32x4_t*>(w + idx[i]) = o;
             if constexpr (SHADOW) {
                 uint2 pk;
-                pk.x = (unsigned)f2bf(o.x) | ((unsigned)f2bf(o.y) << 16);
-                pk.y = (unsigned)f2bf(o.z) | ((unsigned)f2bf(o.w) << 16);
+                pk.x = pack2bf(o.x, o.y);
+                pk.y = pack2bf(o.z, o.w);
                 *reinterpret_cast<uint2*>(shadow + idx[i]) = pk;
             }
         }
@@ -1359,8 +1367,8 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict_
     if (i >= n) return;
     const f32x4_t v = *reinterpret_cast<const f32x4_t*>(src + i);
     uint2 pk;
-    pk.x = (unsigned)f2bf(v.x) | ((unsigned)f2bf(v.y) << 16);
-    pk.y = (unsigned)f2bf(v.z) | ((unsigned)f2bf(v.w) << 16);
+    pk.x = pack2bf(v.x, v.y);
+    pk.y = pack2bf(v.z, v.w);
     *reinterpret_cast<uint2*>(dst + i) = pk;
 }
 
