@@ -628,6 +628,19 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
     Fetcher<MODE, T, false, BN, BK, VEC> fb;
     fa.init(p, row0);
     fb.init(p, col0);
+    // the epilogue's vector form, decided now so that the forward bias of the thread's eight
+    // columns is requested before the main loop instead of at its end
+    const bool vec_out = (p.ldc % 8 == 0) && (!(p.flags & F_RES_DOWN) || (p.resC % 8 == 0));
+    float bias_v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if constexpr (MODE == LIN_FWD || MODE == CONV_FWD) {
+        const int bcol = col0 + (int)(threadIdx.x % (BN / 8)) * 8;
+        if (vec_out && bcol + 8 <= p.Q) {
+            const f32x4_t b0 = *reinterpret_cast<const f32x4_t*>(p.bias + bcol);
+            const f32x4_t b1 = *reinterpret_cast<const f32x4_t*>(p.bias + bcol + 4);
+            bias_v[0] = b0.x; bias_v[1] = b0.y; bias_v[2] = b0.z; bias_v[3] = b0.w;
+            bias_v[4] = b1.x; bias_v[5] = b1.y; bias_v[6] = b1.z; bias_v[7] = b1.w;
+        }
+    }
 #pragma unroll
     for (int s = 0; s < ST - 1; ++s) {
         // always issued: a chunk beyond the reduction reads the block of zeros.  Keeping the
@@ -637,25 +650,21 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
         fb.fetch(p, kbeg + s * BK, kend, rb[s]);
         __builtin_amdgcn_sched_barrier(0);   // keep the stages' loads in issue order
     }
-    // one chunk: (optionally) issue the loads of chunk it + ST - 1 into the stage that has just
-    // been consumed, store stage S to LDS buffer it & 1, barrier, multiply
+    // one chunk: issue the loads of chunk it + ST - 1 into the stage that has just been consumed,
+    // store stage S to LDS buffer it & 1, barrier, multiply
     constexpr int LOADS = LoadsPerChunk<MODE, T, true, BM, BK>::value + LoadsPerChunk<MODE, T, false, BN, BK>::value;
-    auto chunk = [&](auto S, const int it, auto FETCH) {
+    auto chunk = [&](auto S, auto PAR, const int it) {
         constexpr int s = decltype(S)::value;
-        constexpr bool fetching = decltype(FETCH)::value;
-        if constexpr (fetching) {
-            fa.fetch(p, kbeg + (it + ST - 1) * BK, kend, ra[(s + ST - 1) % ST]);
-            fb.fetch(p, kbeg + (it + ST - 1) * BK, kend, rb[(s + ST - 1) % ST]);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        T(*Ab)[GA::LDS_LD] = As[it & 1];
-        T(*Bb)[GB::LDS_LD] = Bs[it & 1];
+        constexpr int par = decltype(PAR)::value;   // LDS buffer of this chunk (= it & 1, known statically)
+        fa.fetch(p, kbeg + (it + ST - 1) * BK, kend, ra[(s + ST - 1) % ST]);
+        fb.fetch(p, kbeg + (it + ST - 1) * BK, kend, rb[(s + ST - 1) % ST]);
+        __builtin_amdgcn_sched_barrier(0);
+        T(*Ab)[GA::LDS_LD] = As[par];
+        T(*Bb)[GB::LDS_LD] = Bs[par];
         if constexpr (VEC && ((PACK_ASM_MODES >> MODE) & 1)) {
-            // steady state: ST - 1 newer stages are in flight behind stage s; in the tail (no
-            // more loads are issued) simply drain everything
-            constexpr int NEWER = fetching ? (ST - 1) * LOADS : 0;
-            wait_stage<NEWER>(ra[s]);
-            wait_stage<NEWER>(rb[s]);
+            // ST - 1 newer stages are in flight behind stage s
+            wait_stage<(ST - 1) * LOADS>(ra[s]);
+            wait_stage<(ST - 1) * LOADS>(rb[s]);
         }
         // buffer it&1 was last read while chunk it-2 was multiplied; every wave has passed the
         // barrier of chunk it-1 since, so it is free
@@ -707,15 +716,20 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
         }
     };
     using std::integral_constant;
-    typedef integral_constant<bool, true> Yes;
-    typedef integral_constant<bool, false> No;
-    // full groups of ST chunks: a branch-free body, so that the compiler waits only for the
-    // oldest register stage; then up to ST - 1 remaining chunks, which need no further loads
+    // Chunks run in groups of G (a multiple of the stage count and of the two LDS buffers), so
+    // that stage and buffer of every chunk in the unrolled body are compile-time constants and
+    // the body is free of branches.  Every chunk prefetches, also the last ones, whose prefetch
+    // lies beyond the reduction and reads the block of zeros.
+    constexpr int G = (ST % 2 == 0) ? ST : 2 * ST;
     int it0 = 0;
-    for (; it0 + ST <= nk; it0 += ST)
-        for_each_stage(std::make_integer_sequence<int, ST>{}, [&](auto S) { chunk(S, it0 + decltype(S)::value, Yes{}); });
-    for_each_stage(std::make_integer_sequence<int, ST - 1>{}, [&](auto S) {
-        if (it0 + decltype(S)::value < nk) chunk(S, it0 + decltype(S)::value, No{});
+    for (; it0 + G <= nk; it0 += G)
+        for_each_stage(std::make_integer_sequence<int, G>{}, [&](auto J) {
+            constexpr int j = decltype(J)::value;
+            chunk(integral_constant<int, j % ST>{}, integral_constant<int, j & 1>{}, it0 + j);
+        });
+    for_each_stage(std::make_integer_sequence<int, G - 1>{}, [&](auto J) {
+        constexpr int j = decltype(J)::value;
+        if (it0 + j < nk) chunk(integral_constant<int, j % ST>{}, integral_constant<int, j & 1>{}, it0 + j);
     });
     if constexpr (VEC && ((PACK_ASM_MODES >> MODE) & 1)) {
         // The last full group prefetched chunks beyond the reduction (reads of the zeros block).
@@ -777,99 +791,123 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
     };
     float* const cf = (float*)p.C + (IS_DW ? (size_t)tr.ks * p.split_stride : (size_t)0);
 
-    // vector form: 8 consecutive columns per thread (two 16-byte LDS reads); needs aligned rows
-    const bool vec_out = (p.ldc % 8 == 0) && (!(p.flags & F_RES_DOWN) || (p.resC % 8 == 0));
+    // vector form: 8 consecutive columns per thread (two 16-byte LDS reads); needs aligned rows.
+    // A thread keeps its column group for all its rows.  What the tail reads from global memory
+    // (shortcut source, mask source, previous value) is requested for a batch of rows before any
+    // of it is used, so a batch costs one round trip instead of one per row.
     if (vec_out) {
-        constexpr int GROUPS = BN / 8;
-#pragma unroll 2
-        for (int idx = threadIdx.x; idx < BM * GROUPS; idx += 256) {
-            const int lr = idx / GROUPS, lc = (idx % GROUPS) * 8;
-            const int row = row0 + lr, col = col0 + lc;
-            if (row >= p.R || col >= p.Q) continue;
-            float v[8];
-            {
-                const f32x4_t s0 = *reinterpret_cast<const f32x4_t*>(&stage[lr][lc]);
-                const f32x4_t s1 = *reinterpret_cast<const f32x4_t*>(&stage[lr][lc + 4]);
-                v[0] = s0.x; v[1] = s0.y; v[2] = s0.z; v[3] = s0.w;
-                v[4] = s1.x; v[5] = s1.y; v[6] = s1.z; v[7] = s1.w;
-            }
-            const size_t off = out_row_base(p, row) + col;
-            if (col + 8 > p.Q) {   // ragged right edge: element by element
-                for (int e = 0; e < 8 && col + e < p.Q; ++e) {
-                    const float r = finish(v[e], row, col + e, off + e);
-                    if (out_f32) cf[off + e] = r;
-                    else ((T*)p.C)[off + e] = ET<T>::from_f(r);
+        constexpr int GROUPS = BN / 8, NIT = BM * GROUPS / 256, RSTEP = 256 / GROUPS;
+        constexpr int BATCH = (NIT < 4) ? NIT : 4;
+        static_assert(256 % GROUPS == 0 && NIT % BATCH == 0, "tile shape");
+        const int lc = (threadIdx.x % GROUPS) * 8, lr0 = threadIdx.x / GROUPS;
+        const int col = col0 + lc;
+        const bool full = col + 8 <= p.Q;
+        typedef typename std::conditional<sizeof(T) == 2, u32x4_t, f32x4_t>::type ev_t;   // 8 bf16 or 4 floats
+        constexpr int EV = (sizeof(T) == 2) ? 1 : 2;   // vectors per 8 elements
+        if (col < p.Q) {
+#pragma unroll 1
+            for (int n0 = 0; n0 < NIT; n0 += BATCH) {
+                size_t off[BATCH];
+                bool live[BATCH];
+                ev_t auxv[BATCH][EV], oldv[BATCH][EV];
+#pragma unroll
+                for (int n = 0; n < BATCH; ++n) {
+                    const int row = row0 + lr0 + (n0 + n) * RSTEP;
+                    live[n] = row < p.R;
+                    off[n] = out_row_base(p, live[n] ? row : row0) + col;
+                    const T* ap = nullptr;
+                    const T* op = nullptr;
+                    if (live[n] && full) {
+                        if constexpr (IS_FWD) {
+                            if (p.flags & F_RES_ID) {
+                                ap = (const T*)p.aux + off[n];
+                            } else if ((p.flags & F_RES_DOWN) && col < p.resC) {
+                                int bb, i, j;
+                                decode_row(p, row, bb, i, j);
+                                ap = (const T*)p.aux + ((size_t)(bb * p.resH + 2 * i) * p.resW + 2 * j) * p.resC + col;
+                            }
+                        } else if constexpr (!IS_DW) {
+                            if (p.flags & F_MASK) ap = (const T*)p.aux + off[n];
+                            if (p.flags & F_ACCUM) op = (const T*)p.C + off[n];
+                        }
+                    }
+#pragma unroll
+                    for (int h = 0; h < EV; ++h) {
+                        // absent source: zeros for the shortcut and the previous value, ones for the mask
+                        const float fill = (!IS_FWD && !IS_DW) ? 1.f : 0.f;
+                        ev_t fz;
+                        if constexpr (sizeof(T) == 2) fz = u32x4_t{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+                        else fz = f32x4_t{fill, fill, fill, fill};
+                        if constexpr (sizeof(T) == 2) { if (IS_FWD) fz = u32x4_t{0u, 0u, 0u, 0u}; }
+                        auxv[n][h] = ap ? *reinterpret_cast<const ev_t*>(ap + h * 4) : fz;
+                        ev_t oz;
+                        if constexpr (sizeof(T) == 2) oz = u32x4_t{0u, 0u, 0u, 0u};
+                        else oz = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                        oldv[n][h] = op ? *reinterpret_cast<const ev_t*>(op + h * 4) : oz;
+                    }
                 }
-                continue;
-            }
-            if constexpr (IS_FWD) {
-                const f32x4_t b0 = *reinterpret_cast<const f32x4_t*>(p.bias + col);
-                const f32x4_t b1 = *reinterpret_cast<const f32x4_t*>(p.bias + col + 4);
-                v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
-                v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
-                const T* res = nullptr;
-                if (p.flags & F_RES_ID) {
-                    res = (const T*)p.aux + off;
-                } else if ((p.flags & F_RES_DOWN) && col < p.resC) {
-                    int bb, i, j;
-                    decode_row(p, row, bb, i, j);
-                    res = (const T*)p.aux + ((size_t)(bb * p.resH + 2 * i) * p.resW + 2 * j) * p.resC + col;
-                }
-                if (res) {
+#pragma unroll
+                for (int n = 0; n < BATCH; ++n) {
+                    if (!live[n]) continue;
+                    const int lr = lr0 + (n0 + n) * RSTEP;
+                    const int row = row0 + lr;
+                    float v[8];
+                    {
+                        const f32x4_t s0 = *reinterpret_cast<const f32x4_t*>(&stage[lr][lc]);
+                        const f32x4_t s1 = *reinterpret_cast<const f32x4_t*>(&stage[lr][lc + 4]);
+                        v[0] = s0.x; v[1] = s0.y; v[2] = s0.z; v[3] = s0.w;
+                        v[4] = s1.x; v[5] = s1.y; v[6] = s1.z; v[7] = s1.w;
+                    }
+                    if (!full) {   // ragged right edge: element by element
+                        for (int e = 0; e < 8 && col + e < p.Q; ++e) {
+                            const float r = finish(v[e], row, col + e, off[n] + e);
+                            if (out_f32) cf[off[n] + e] = r;
+                            else ((T*)p.C)[off[n] + e] = ET<T>::from_f(r);
+                        }
+                        continue;
+                    }
+                    float ax[8], old[8];
                     if constexpr (sizeof(T) == 2) {
-                        const u32x4_t rv = *reinterpret_cast<const u32x4_t*>(res);
 #pragma unroll
                         for (int d = 0; d < 4; ++d) {
-                            v[2 * d] += __uint_as_float(rv[d] << 16);
-                            v[2 * d + 1] += __uint_as_float(rv[d] & 0xffff0000u);
+                            ax[2 * d] = __uint_as_float(auxv[n][0][d] << 16); ax[2 * d + 1] = __uint_as_float(auxv[n][0][d] & 0xffff0000u);
+                            old[2 * d] = __uint_as_float(oldv[n][0][d] << 16); old[2 * d + 1] = __uint_as_float(oldv[n][0][d] & 0xffff0000u);
                         }
                     } else {
-                        const f32x4_t r0 = *reinterpret_cast<const f32x4_t*>(res);
-                        const f32x4_t r1 = *reinterpret_cast<const f32x4_t*>(res + 4);
-                        v[0] += r0.x; v[1] += r0.y; v[2] += r0.z; v[3] += r0.w;
-                        v[4] += r1.x; v[5] += r1.y; v[6] += r1.z; v[7] += r1.w;
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            ax[d] = auxv[n][0][d]; ax[4 + d] = auxv[n][EV - 1][d];
+                            old[d] = oldv[n][0][d]; old[4 + d] = oldv[n][EV - 1][d];
+                        }
+                    }
+                    if constexpr (IS_FWD) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = (v[e] + bias_v[e]) + ax[e];
+                        if (p.flags & F_RELU) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+                        }
+                    } else if constexpr (!IS_DW) {
+                        const bool accum = (p.flags & F_ACCUM) != 0;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            if (!(ax[e] > 0.f)) v[e] = 0.f;
+                            if (accum) v[e] += old[e];
+                        }
+                    }
+                    if (out_f32) {
+                        *reinterpret_cast<f32x4_t*>(cf + off[n]) = f32x4_t{v[0], v[1], v[2], v[3]};
+                        *reinterpret_cast<f32x4_t*>(cf + off[n] + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
+                    } else if constexpr (sizeof(T) == 2) {
+                        u32x4_t o;
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) o[d] = pack2bf(v[2 * d], v[2 * d + 1]);
+                        *reinterpret_cast<u32x4_t*>((T*)p.C + off[n]) = o;
+                    } else {
+                        *reinterpret_cast<f32x4_t*>((float*)p.C + off[n]) = f32x4_t{v[0], v[1], v[2], v[3]};
+                        *reinterpret_cast<f32x4_t*>((float*)p.C + off[n] + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
                     }
                 }
-                if (p.flags & F_RELU) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
-                }
-            } else if constexpr (!IS_DW) {
-                float mk[8], old[8];
-                const bool masked = (p.flags & F_MASK) != 0, accum = (p.flags & F_ACCUM) != 0;
-                if constexpr (sizeof(T) == 2) {
-                    const u32x4_t z = {0u, 0u, 0u, 0u};
-                    const u32x4_t mv = masked ? *reinterpret_cast<const u32x4_t*>((const T*)p.aux + off) : z;
-                    const u32x4_t ov = accum ? *reinterpret_cast<const u32x4_t*>((const T*)p.C + off) : z;
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) {
-                        mk[2 * d] = __uint_as_float(mv[d] << 16); mk[2 * d + 1] = __uint_as_float(mv[d] & 0xffff0000u);
-                        old[2 * d] = __uint_as_float(ov[d] << 16); old[2 * d + 1] = __uint_as_float(ov[d] & 0xffff0000u);
-                    }
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        mk[e] = masked ? ((const float*)p.aux)[off + e] : 1.f;
-                        old[e] = accum ? ((const float*)p.C)[off + e] : 0.f;
-                    }
-                }
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    if (masked && !(mk[e] > 0.f)) v[e] = 0.f;
-                    if (accum) v[e] += old[e];
-                }
-            }
-            if (out_f32) {
-                *reinterpret_cast<f32x4_t*>(cf + off) = f32x4_t{v[0], v[1], v[2], v[3]};
-                *reinterpret_cast<f32x4_t*>(cf + off + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
-            } else if constexpr (sizeof(T) == 2) {
-                u32x4_t o;
-#pragma unroll
-                for (int d = 0; d < 4; ++d) o[d] = pack2bf(v[2 * d], v[2 * d + 1]);
-                *reinterpret_cast<u32x4_t*>((T*)p.C + off) = o;
-            } else {
-                *reinterpret_cast<f32x4_t*>((float*)p.C + off) = f32x4_t{v[0], v[1], v[2], v[3]};
-                *reinterpret_cast<f32x4_t*>((float*)p.C + off + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
             }
         }
     } else {
