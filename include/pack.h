@@ -146,14 +146,15 @@ int32_t pack_num_launches(const pack_t* p);
 /* Bytes of device memory the pack holds (the paper's memory metric, Section 4.2: allocated). */
 size_t pack_device_bytes(const pack_t* p);
 
-/* Per-launch timing, for benchmarks: after pack_profile_start every pack_step brackets launch
- * number `which` of its sequence (all launches if which < 0) with a pair of events on the
- * pack's stream; pack_profile_stop waits for the stream, writes the summed milliseconds and the
+/* Per-launch timing, for benchmarks: after pack_profile_start every `every`-th pack_step (the
+ * first one included; every >= 1) brackets launch number `which` of its sequence (all launches
+ * if which < 0) with a pair of events on the pack's stream.  An event costs a few microseconds
+ * of stream time, which is why a long timed run samples its steps.  pack_profile_stop waits for the stream, writes the summed milliseconds and the
  * number of samples per launch index into ms_sum / count (host, pack_num_launches entries
  * each) and switches timing off.  pack_launch_name writes the kernel family of launch i
  * ("gemm_lin_fwd", "sgd_update", ...) into buf (host, n bytes, always terminated).
  * Errors: PACK_EINVAL (null, index out of range), PACK_EDEVICE. */
-pack_status pack_profile_start(pack_t* p, int32_t which);
+pack_status pack_profile_start(pack_t* p, int32_t which, int32_t every);
 pack_status pack_profile_stop(pack_t* p, float* ms_sum, int32_t* count);
 pack_status pack_launch_name(const pack_t* p, int32_t i, char* buf, size_t n);
 

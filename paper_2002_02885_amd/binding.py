@@ -74,7 +74,7 @@ def lib() -> C.CDLL:
         l.pack_last_error.restype = C.c_char_p
         l.pack_destroy.argtypes = [vp]
         l.pack_destroy.restype = None
-        l.pack_profile_start.argtypes = [vp, i32]
+        l.pack_profile_start.argtypes = [vp, i32, i32]
         l.pack_profile_stop.argtypes = [vp, fp, C.POINTER(C.c_int32)]
         l.pack_launch_name.argtypes = [vp, i32, C.c_char_p, sz]
         for name in ("pack_create", "pack_write_weights", "pack_step", "pack_read_loss",
@@ -172,8 +172,8 @@ class Pack:
     def device_bytes(self) -> int:
         return int(lib().pack_device_bytes(self._h))
 
-    def profile_start(self, which: int = -1):
-        _check(lib().pack_profile_start(self._h, which))
+    def profile_start(self, which: int = -1, every: int = 1):
+        _check(lib().pack_profile_start(self._h, which, every))
 
     def profile_stop(self):
         """Returns (summed milliseconds, sample count) per launch index."""

@@ -120,6 +120,8 @@ struct pack_ctx {
     // per-launch timing (off unless pack_profile_start was called)
     bool profiling = false;
     int profile_which = -1;
+    int profile_every = 1;       // time the chosen launch in every n-th step only
+    long long profile_step = 0;  // steps since pack_profile_start
     struct Stamp { int launch; hipEvent_t t0, t1; };
     std::vector<Stamp> stamps;
 };
@@ -398,6 +400,16 @@ void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<G
         ((g.flags & F_VEC_A) && (g.flags & F_VEC_B) ? probs : scalar).push_back(g);
     if (!scalar.empty()) emit_gemm_launch(p, db, mode, GEMM_CFG_SCALAR, scalar);
     if (probs.empty()) return;
+    if (std::getenv("PACK_GEMM_ONE_PER_LAUNCH")) {
+        // measuring aid: every problem in a launch of its own, so that per-launch timing shows
+        // each layer separately (results do not depend on it)
+        for (const GemmProb& g : probs) {
+            int c = 0;
+            while (c < 2 && padded_work(g, c + 1) < 0.8 * padded_work(g, c)) ++c;
+            emit_gemm_launch(p, db, mode, c, std::vector<GemmProb>(1, g));
+        }
+        return;
+    }
     // The tile shape only partitions the output; the summation order of an element does not
     // depend on it, so a member's bits do not depend on who else is in the launch.  Each problem
     // prefers the shape that multiplies the fewest padding elements (a 64-channel layer wastes
@@ -418,15 +430,15 @@ void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<G
     int main_cfg = 0;
     for (int c = 1; c < 3; ++c)
         if (work[c] > work[main_cfg]) main_cfg = c;
-    {   // tuning knob: PACK_GEMM_CFG_FWD / _DX / _DW = 0..2 forces the tile configuration of the
-        // linear-layer launches of that kind (results do not depend on it)
-        const char* names[3] = {"PACK_GEMM_CFG_FWD", "PACK_GEMM_CFG_DX", "PACK_GEMM_CFG_DW"};
-        if (mode <= LIN_DW) {
-            const char* v = std::getenv(names[mode]);
-            if (v && v[0] >= '0' && v[0] <= '2' && v[1] == 0) {
-                emit_gemm_launch(p, db, mode, v[0] - '0', probs);
-                return;
-            }
+    {   // tuning knob: PACK_GEMM_CFG_FWD / _DX / _DW (linear layers) and PACK_GEMM_CFG_CONV_FWD /
+        // _CONV_DX / _CONV_DW = 0..2 force the tile configuration of the launches of that kind
+        // (results do not depend on it)
+        const char* names[6] = {"PACK_GEMM_CFG_FWD", "PACK_GEMM_CFG_DX", "PACK_GEMM_CFG_DW",
+                                "PACK_GEMM_CFG_CONV_FWD", "PACK_GEMM_CFG_CONV_DX", "PACK_GEMM_CFG_CONV_DW"};
+        const char* v = std::getenv(names[mode]);
+        if (v && v[0] >= '0' && v[0] <= '2' && v[1] == 0) {
+            emit_gemm_launch(p, db, mode, v[0] - '0', probs);
+            return;
         }
     }
     for (int c = 0; c < 3; ++c) {
@@ -990,12 +1002,13 @@ pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, c
     if (!p || !x_dev || !labels_dev || !lr_host) return fail(PACK_EINVAL, "null argument");
     if (((uintptr_t)x_dev & 15) || ((uintptr_t)labels_dev & 3)) return fail(PACK_EINVAL, "x_dev must be 16-byte aligned");
     LrTable lr;
-    for (int k = 0; k < 256; ++k) lr.lr[k] = (k < p->K) ? lr_host[k] : 0.f;
+    for (int k = 0; k < PACK_LR_N; ++k) lr.lr[k] = (k < p->K) ? lr_host[k] : 0.f;
     const bool bf = p->bf16;
+    const bool timed_step = p->profiling && (p->profile_step++ % p->profile_every == 0);
     for (size_t li = 0; li < p->plan.size(); ++li) {
         const Launch& L = p->plan[li];
         hipError_t e = hipSuccess;
-        const bool timed = p->profiling && (p->profile_which < 0 || p->profile_which == (int)li);
+        const bool timed = timed_step && (p->profile_which < 0 || p->profile_which == (int)li);
         pack_ctx::Stamp stamp{(int)li, nullptr, nullptr};
         if (timed) {
             if (hipEventCreate(&stamp.t0) != hipSuccess || hipEventCreate(&stamp.t1) != hipSuccess ||
@@ -1028,13 +1041,15 @@ pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, c
     return PACK_OK;
 }
 
-pack_status pack_profile_start(pack_t* p, int32_t which) {
-    if (!p) return fail(PACK_EINVAL, "null argument");
+pack_status pack_profile_start(pack_t* p, int32_t which, int32_t every) {
+    if (!p || every < 1) return fail(PACK_EINVAL, "null argument or every < 1");
     if (which >= (int32_t)p->plan.size()) return fail(PACK_EINVAL, "launch index out of range");
     for (auto& s : p->stamps) { (void)hipEventDestroy(s.t0); (void)hipEventDestroy(s.t1); }
     p->stamps.clear();
     p->profiling = true;
     p->profile_which = which;
+    p->profile_every = every;
+    p->profile_step = 0;
     return PACK_OK;
 }
 

@@ -107,7 +107,10 @@ struct TransposeProb {   // convolution weights [Cout][9][Cin] -> [Cin][9][Cout]
     int Cin, Cout, tiles_ci, tiles_co;   // 64 x 64 tiles per tap
 };
 
-struct LrTable { float lr[256]; };
+#ifndef PACK_LR_N
+#define PACK_LR_N 256
+#endif
+struct LrTable { float lr[PACK_LR_N]; };
 
 // launch wrappers; all enqueue on `st` and return the launch status -----------------------------
 // tile_cfg indexes GEMM_TILE_M / GEMM_TILE_N

@@ -599,8 +599,8 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
     constexpr int TM = BM / 64, TN = BN / 64;   // 32x32 MFMA blocks per wave in each direction
     constexpr bool IS_DW = (MODE == LIN_DW || MODE == CONV_DW);
     // Two LDS buffers (one barrier per chunk) and ST register stages: the global loads of chunk
-    // i + ST - 1 are issued before chunk i is multiplied, so ST - 1 round trips to memory are in
-    // flight per workgroup; a skinny layer has too few workgroups per compute unit to hide that
+    // i + ST are issued when chunk i starts to be multiplied, so ST - 1 round trips to memory are
+    // in flight per workgroup; a skinny layer has too few workgroups per compute unit to hide that
     // latency by occupancy alone.
     constexpr int ST = StageCount<BM, BN, BKM, VEC>::value;
     T(*As)[BM][GA::LDS_LD] = reinterpret_cast<T(*)[BM][GA::LDS_LD]>(As_);
@@ -641,36 +641,42 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
             bias_v[4] = b1.x; bias_v[5] = b1.y; bias_v[6] = b1.z; bias_v[7] = b1.w;
         }
     }
+    constexpr int LOADS = LoadsPerChunk<MODE, T, true, BM, BK>::value + LoadsPerChunk<MODE, T, false, BN, BK>::value;
+    constexpr bool ASM_WAITS = VEC && ((PACK_ASM_MODES >> MODE) & 1);
 #pragma unroll
-    for (int s = 0; s < ST - 1; ++s) {
+    for (int s = 0; s < ST; ++s) {
         // always issued: a chunk beyond the reduction reads the block of zeros.  Keeping the
-        // loads unconditional keeps the loop body free of branches, which is what lets the
-        // compiler wait for the oldest stage only.
+        // loads unconditional keeps the loop body free of branches.
         fa.fetch(p, kbeg + s * BK, kend, ra[s]);
         fb.fetch(p, kbeg + s * BK, kend, rb[s]);
         __builtin_amdgcn_sched_barrier(0);   // keep the stages' loads in issue order
     }
-    // one chunk: issue the loads of chunk it + ST - 1 into the stage that has just been consumed,
-    // store stage S to LDS buffer it & 1, barrier, multiply
-    constexpr int LOADS = LoadsPerChunk<MODE, T, true, BM, BK>::value + LoadsPerChunk<MODE, T, false, BN, BK>::value;
+    // chunk 0 goes to LDS buffer 0 ahead of the loop
+    if constexpr (ASM_WAITS) {
+        wait_stage<(ST - 1) * LOADS>(ra[0]);
+        wait_stage<(ST - 1) * LOADS>(rb[0]);
+    }
+    stash_tile<MODE, T, true, BM, BK, VEC>(&As[0][0][0], ra[0]);
+    stash_tile<MODE, T, false, BN, BK, VEC>(&Bs[0][0][0], rb[0]);
+    // One chunk `it` (register stage s = it % ST, LDS buffer par = it & 1, both static in the
+    // unrolled body).  At its barrier chunk `it` is complete in buffer par (stored during the
+    // previous chunk) and nobody reads buffer par ^ 1 any more.  Then, in this order:
+    //   - stage s, emptied by the previous chunk, is refilled with the loads of chunk it + ST;
+    //   - the first MFMA step of chunk `it` is issued from buffer par;
+    //   - chunk it + 1 (stage s + 1, with ST - 1 newer stages in flight behind it) is stored to
+    //     buffer par ^ 1 while those MFMAs run: the wait for global memory and the LDS store
+    //     latency hide under the multiplication instead of standing between two barriers;
+    //   - the remaining MFMA steps.
     auto chunk = [&](auto S, auto PAR, const int it) {
         constexpr int s = decltype(S)::value;
-        constexpr int par = decltype(PAR)::value;   // LDS buffer of this chunk (= it & 1, known statically)
-        fa.fetch(p, kbeg + (it + ST - 1) * BK, kend, ra[(s + ST - 1) % ST]);
-        fb.fetch(p, kbeg + (it + ST - 1) * BK, kend, rb[(s + ST - 1) % ST]);
+        constexpr int par = decltype(PAR)::value;
+        constexpr int sn = (s + 1) % ST;
+        __syncthreads();
+        fa.fetch(p, kbeg + (it + ST) * BK, kend, ra[s]);
+        fb.fetch(p, kbeg + (it + ST) * BK, kend, rb[s]);
         __builtin_amdgcn_sched_barrier(0);
         T(*Ab)[GA::LDS_LD] = As[par];
         T(*Bb)[GB::LDS_LD] = Bs[par];
-        if constexpr (VEC && ((PACK_ASM_MODES >> MODE) & 1)) {
-            // ST - 1 newer stages are in flight behind stage s
-            wait_stage<(ST - 1) * LOADS>(ra[s]);
-            wait_stage<(ST - 1) * LOADS>(rb[s]);
-        }
-        // buffer it&1 was last read while chunk it-2 was multiplied; every wave has passed the
-        // barrier of chunk it-1 since, so it is free
-        stash_tile<MODE, T, true, BM, BK, VEC>(&Ab[0][0], ra[s]);
-        stash_tile<MODE, T, false, BN, BK, VEC>(&Bb[0][0], rb[s]);
-        __syncthreads();
         if constexpr (IS_DW) {
             // bias gradient = sum of dz over the reduction: rows of the A tile, summed in order
             if (do_bias_grad && threadIdx.x < BM) {
@@ -713,6 +719,14 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                         acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[a].w), __uint_as_float(fb[b].w), acc[a][b], 0, 0, 0);
                     }
                 }
+            if (kk == 0) {
+                if constexpr (ASM_WAITS) {
+                    wait_stage<(ST - 1) * LOADS>(ra[sn]);
+                    wait_stage<(ST - 1) * LOADS>(rb[sn]);
+                }
+                stash_tile<MODE, T, true, BM, BK, VEC>(&As[par ^ 1][0][0], ra[sn]);
+                stash_tile<MODE, T, false, BN, BK, VEC>(&Bs[par ^ 1][0][0], rb[sn]);
+            }
         }
     };
     using std::integral_constant;
@@ -732,7 +746,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
         if (it0 + j < nk) chunk(integral_constant<int, j % ST>{}, integral_constant<int, j & 1>{}, it0 + j);
     });
     if constexpr (VEC && ((PACK_ASM_MODES >> MODE) & 1)) {
-        // The last full group prefetched chunks beyond the reduction (reads of the zeros block).
+        // The last chunks prefetched beyond the reduction (reads of the zeros block).
         // Those loads are invisible to the compiler and still target the stage registers, which
         // it would otherwise reuse for the epilogue at once: drain them, with every stage
         // register as an operand of the wait so that none of them counts as free before it.
