@@ -20,6 +20,17 @@ The paper fixes none of the layer numerics; the readings used here are:
     pre-update weights; the reported loss is the pre-update loss;
   * every linear / conv layer has a bias; conv is 3x3, zero padding 1, stride 1 or 2;
   * ReLU derivative is 0 at 0 (mask z > 0, taken after the bias add);
+  * the other activations of the paper's search space (Table 3): sigmoid 1/(1+e^-z), tanh, and
+    leaky ReLU max(z, a*z) with a = 0.2 (the default slope of the framework the paper ran on;
+    the paper names no slope); derivative of leaky ReLU at 0 is a;
+  * the other optimisers of Table 3, each with state "stored with the model" (Section 2.2), all
+    applied to gradients taken at the pre-update weights:
+      momentum  acc <- mu*acc + g;  W <- W - lr*acc                       (acc starts at 0)
+      adagrad   acc <- acc + g*g;   W <- W - lr*g/sqrt(acc)               (acc starts at acc0 > 0)
+      adam      m <- b1*m + (1-b1)*g;  v <- b2*v + (1-b2)*g*g;  t <- t+1;
+                W <- W - lr * (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps)      (m, v, t start at 0)
+    The paper prints no update formula; these are the published definitions of the methods it
+    names (heavy-ball momentum; Duchi et al. without damping term; Kingma & Ba, Algorithm 1);
   * residual block: y = relu(branch(x) + shortcut(x)); the shortcut is the identity when shapes
     agree, otherwise the parameter-free form sc[b,i,j,c] = x[b,2i,2j,c] for c < Cin, 0 above;
   * argmax returns the smallest index attaining the maximum;
@@ -53,7 +64,9 @@ from __future__ import annotations
 
 import numpy as np
 
-__all__ = ["q_bf16", "Model", "train_pack", "softmax_xent"]
+__all__ = ["q_bf16", "Model", "train_pack", "softmax_xent", "apply_update", "new_opt_state", "LEAKY_SLOPE"]
+
+LEAKY_SLOPE = 0.2
 
 
 def q_bf16(a):
@@ -88,6 +101,77 @@ def softmax_xent(logits, y):
     p = ex / s
     p[np.arange(b), y] -= 1.0
     return loss, p / b, np.argmax(logits, axis=1).astype(np.int32)
+
+
+def _act_forward(kind, z):
+    if kind == "relu":
+        return np.maximum(z, 0.0)
+    if kind == "leaky_relu":
+        return np.where(z > 0.0, z, LEAKY_SLOPE * z)
+    if kind == "sigmoid":
+        return 1.0 / (1.0 + np.exp(-z))
+    if kind == "tanh":
+        return np.tanh(z)
+    raise ValueError(kind)
+
+
+def _act_derivative(kind, out):
+    """f'(z) written in terms of the stored output out = f(z)."""
+    if kind == "relu":
+        return (out > 0.0).astype(np.float64)
+    if kind == "leaky_relu":
+        return np.where(out > 0.0, 1.0, LEAKY_SLOPE)
+    if kind == "sigmoid":
+        return out * (1.0 - out)
+    if kind == "tanh":
+        return 1.0 - out * out
+    raise ValueError(kind)
+
+
+ACTIVATIONS = ("relu", "leaky_relu", "sigmoid", "tanh")
+
+
+def new_opt_state(opt, shape):
+    """Fresh optimiser state for one parameter tensor: a list of arrays (possibly empty)."""
+    kind = opt["kind"]
+    if kind == "sgd":
+        return []
+    if kind == "momentum":
+        return [np.zeros(shape)]
+    if kind == "adagrad":
+        return [np.full(shape, float(opt.get("acc0", 0.1)))]
+    if kind == "adam":
+        return [np.zeros(shape), np.zeros(shape)]
+    raise ValueError(kind)
+
+
+def apply_update(opt, w, g, state, lr, t):
+    """One optimiser step on one tensor, in place.  `t` is the number of this step (1 for the
+    first); `state` comes from new_opt_state.  Formulas as listed in the module header."""
+    kind = opt["kind"]
+    if kind == "sgd":
+        w -= lr * g
+    elif kind == "momentum":
+        acc, = state
+        acc *= float(opt.get("mu", 0.9))
+        acc += g
+        w -= lr * acc
+    elif kind == "adagrad":
+        acc, = state
+        acc += g * g
+        w -= lr * g / np.sqrt(acc)
+    elif kind == "adam":
+        m, v = state
+        b1, b2, eps = float(opt.get("beta1", 0.9)), float(opt.get("beta2", 0.999)), float(opt.get("eps", 1e-8))
+        m *= b1
+        m += (1.0 - b1) * g
+        v *= b2
+        v += (1.0 - b2) * g * g
+        mhat = m / (1.0 - b1 ** t)
+        vhat = v / (1.0 - b2 ** t)
+        w -= lr * mhat / (np.sqrt(vhat) + eps)
+    else:
+        raise ValueError(kind)
 
 
 def _conv_out(n, s):
@@ -152,10 +236,13 @@ def shortcut_backward(dsc, x_shape):
 
 class Model:
     """One network trained alone.  `layers` is a list of tuples ("linear", out),
-    ("conv3x3", out, stride), ("relu",), ("gap",), ("res_begin",), ("res_end",); `blob` is the
-    flat weight vector (linear W[out][in], b[out]; conv W[Cout][Cin][3][3], b[Cout])."""
+    ("conv3x3", out, stride), ("relu",) / ("leaky_relu",) / ("sigmoid",) / ("tanh",), ("gap",),
+    ("res_begin",), ("res_end",); `blob` is the flat weight vector (linear W[out][in], b[out];
+    conv W[Cout][Cin][3][3], b[Cout]).  `opt` is the optimiser: {"kind": "sgd"} (default),
+    {"kind": "momentum", "mu": 0.9}, {"kind": "adagrad", "acc0": 0.1} or
+    {"kind": "adam", "beta1": 0.9, "beta2": 0.999, "eps": 1e-8}."""
 
-    def __init__(self, layers, in_shape, blob, mode="exact", acc_noise=None):
+    def __init__(self, layers, in_shape, blob, mode="exact", acc_noise=None, opt=None):
         """`acc_noise`, if given, is a function applied to every matrix-product result a device
         would hold in an fp32 accumulator (forward pre-activations, input gradients) before
         anything else looks at it.  It is a sensitivity probe for tests - how far do the results
@@ -188,6 +275,9 @@ class Model:
             self.params.append([W, b])
         assert off == blob.size, "weight blob does not match the layer list"
         self.n_classes = c
+        self.opt = dict(opt) if opt is not None else {"kind": "sgd"}
+        self.opt_state = [[new_opt_state(self.opt, W.shape), new_opt_state(self.opt, b.shape)] for W, b in self.params]
+        self.t = 0
 
     # -- flat views ---------------------------------------------------------------------------
     def blob(self):
@@ -220,9 +310,9 @@ class Model:
                 tape.append(("conv3x3", pi, cur, op[2]))
                 cur = z
                 pi += 1
-            elif kind == "relu":
-                cur = q(np.maximum(cur, 0.0))
-                tape.append(("relu", cur))
+            elif kind in ACTIVATIONS:
+                cur = q(_act_forward(kind, cur))
+                tape.append((kind, cur))
             elif kind == "gap":
                 cur = q(cur)
                 tape.append(("gap", cur.shape))
@@ -272,8 +362,8 @@ class Model:
                 dW, db, dx = conv3x3_backward(inp, self.qw(W), s, q(g), need_dx=(pi != first_param))
                 grads[pi] = [dW, db]
                 g = self.acc(dx) if dx is not None else None
-            elif kind == "relu":
-                g = q(g * (rec[1] > 0.0))
+            elif kind in ACTIVATIONS:
+                g = q(g * _act_derivative(kind, rec[1]))
             elif kind == "gap":
                 shp = rec[1]
                 g = np.broadcast_to(q(g) / (shp[1] * shp[2]), shp).copy()
@@ -286,24 +376,33 @@ class Model:
         return loss, pred, grads
 
     def sgd_step(self, X, y, lr):
-        """One step of plain mini-batch SGD; returns (pre-update loss, predictions, grads)."""
+        """One training step with the model's optimiser (plain mini-batch SGD unless `opt` says
+        otherwise); returns (pre-update loss, predictions, grads)."""
         loss, pred, grads = self.loss_and_grads(X, y)
-        for (W, b), (dW, db) in zip(self.params, grads):
-            W -= lr * dW
-            b -= lr * db
+        self.t += 1
+        for (W, b), (dW, db), (sW, sb) in zip(self.params, grads, self.opt_state):
+            apply_update(self.opt, W, dW, sW, lr, self.t)
+            apply_update(self.opt, b, db, sb, lr, self.t)
         return loss, pred, grads
+
+    def opt_state_blob(self, slot):
+        """State array `slot` (0 or 1) of every tensor, flattened in the blob layout."""
+        return np.concatenate([np.concatenate([sW[slot].ravel(), sb[slot].ravel()]) for sW, sb in self.opt_state])
 
 
 def train_pack(models, in_shape, blobs, batch, lr, x, labels, steps, mode="exact", keep_grads=False,
-               acc_noise=None):
+               acc_noise=None, optimizers=None):
     """Train K models separately on the shared batch: model k sees rows [0, batch[k]) of `x`
     and `labels` at every step (the same batch each step).  Returns a dict with
       loss  [steps, K]   pre-update losses,
       pred  list over steps of list over models of int32 [b_k],
       blobs list of K flat float64 weight vectors after the last step,
-      grads (when keep_grads) list over steps of list over models of flat float64 gradients."""
+      grads (when keep_grads) list over steps of list over models of flat float64 gradients,
+      nets  the K trained Model objects (optimiser state included).
+    `optimizers`, if given, is a list of K optimiser dicts (see Model)."""
     K = len(models)
-    nets = [Model(models[k], in_shape, blobs[k], mode, acc_noise) for k in range(K)]
+    nets = [Model(models[k], in_shape, blobs[k], mode, acc_noise, opt=(optimizers[k] if optimizers else None))
+            for k in range(K)]
     loss = np.zeros((steps, K))
     preds, grads = [], []
     for t in range(steps):
@@ -316,7 +415,7 @@ def train_pack(models, in_shape, blobs, batch, lr, x, labels, steps, mode="exact
             preds[-1].append(p)
             if keep_grads:
                 grads[-1].append(Model.flatten_grads(g))
-    out = {"loss": loss, "pred": preds, "blobs": [n.blob() for n in nets]}
+    out = {"loss": loss, "pred": preds, "blobs": [n.blob() for n in nets], "nets": nets}
     if keep_grads:
         out["grads"] = grads
     return out

@@ -133,6 +133,6 @@ constexpr int GEMM_TILE_M[4] = {128, 128, 64, 64};
 constexpr int GEMM_TILE_N[4] = {128, 64, 64, 64};
 constexpr int GEMM_CFG_SCALAR = 3;
 constexpr int ELEMWISE_PER_BLOCK = 2048;   // elements one block of the elementwise kernels covers
-constexpr int SGD_PER_BLOCK = 4096;        // parameters one block of the update kernel covers
+constexpr int SGD_PER_BLOCK = 2048;        // parameters one block of the update kernel covers (measured best of 1024..8192)
 
 }  // namespace packk

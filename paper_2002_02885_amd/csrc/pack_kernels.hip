@@ -1313,12 +1313,11 @@ __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ w, const f
             o.y = wv[i].y - r * gv[i].y;
             o.z = wv[i].z - r * gv[i].z;
             o.w = wv[i].w - r * gv[i].w;
-            *reinterpret_cast<f32x4_t*>(w + idx[i]) = o;
+            // streaming stores: nothing re-reads these lines before they leave the caches
+            __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t*>(w + idx[i]));
             if constexpr (SHADOW) {
-                uint2 pk;
-                pk.x = pack2bf(o.x, o.y);
-                pk.y = pack2bf(o.z, o.w);
-                *reinterpret_cast<uint2*>(shadow + idx[i]) = pk;
+                typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
+                __builtin_nontemporal_store(u32x2_t{pack2bf(o.x, o.y), pack2bf(o.z, o.w)}, reinterpret_cast<u32x2_t*>(shadow + idx[i]));
             }
         }
     }

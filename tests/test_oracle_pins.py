@@ -233,6 +233,12 @@ NETS = {
                              ("conv3x3", 5, 1), ("res_end",), ("res_begin",), ("conv3x3", 5, 1), ("relu",),
                              ("conv3x3", 5, 1), ("res_end",), ("gap",), ("linear", 4)]),
     "conv_flatten_fc": ((3, 3, 2), [("conv3x3", 3, 1), ("relu",), ("linear", 3)]),
+    # the other activations of the paper's search space (Table 3)
+    "mlp_tanh": ((1, 1, 5), [("linear", 4), ("tanh",), ("linear", 4), ("tanh",), ("linear", 3)]),
+    "mlp_sigmoid": ((1, 1, 5), [("linear", 4), ("sigmoid",), ("linear", 3)]),
+    "mlp_leaky": ((1, 1, 6), [("linear", 5), ("leaky_relu",), ("linear", 4), ("leaky_relu",), ("linear", 3)]),
+    "cnn_mixed_act": ((6, 6, 2), [("conv3x3", 3, 1), ("leaky_relu",), ("conv3x3", 4, 2), ("tanh",), ("gap",),
+                                  ("linear", 4), ("sigmoid",), ("linear", 3)]),
 }
 
 
@@ -264,6 +270,12 @@ def _min_abs_preact(net, x):
             cur = po.conv3x3_forward(cur, W, b, op[2])
         elif op[0] == "relu":
             m = min(m, np.abs(cur).min()); cur = np.maximum(cur, 0)
+        elif op[0] == "leaky_relu":
+            m = min(m, np.abs(cur).min()); cur = np.where(cur > 0, cur, po.LEAKY_SLOPE * cur)
+        elif op[0] == "sigmoid":
+            cur = 1.0 / (1.0 + np.exp(-cur))
+        elif op[0] == "tanh":
+            cur = np.tanh(cur)
         elif op[0] == "gap":
             cur = cur.mean(axis=(1, 2), keepdims=True)
         elif op[0] == "res_begin":
@@ -316,6 +328,12 @@ def _torch_loss(layers, in_shape, blob_t, x, y):
             cur = F.conv2d(cur.permute(0, 3, 1, 2), W, b, stride=op[2], padding=1).permute(0, 2, 3, 1)
         elif op[0] == "relu":
             cur = torch.relu(cur)
+        elif op[0] == "leaky_relu":
+            cur = F.leaky_relu(cur, negative_slope=0.2)
+        elif op[0] == "sigmoid":
+            cur = torch.sigmoid(cur)
+        elif op[0] == "tanh":
+            cur = torch.tanh(cur)
         elif op[0] == "gap":
             cur = cur.mean(dim=(1, 2), keepdim=True)
         elif op[0] == "res_begin":

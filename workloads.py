@@ -81,7 +81,7 @@ def param_shapes(layers: Sequence[Layer], in_shape: Tuple[int, int, int]):
             h, w, c = conv_out_size(h, op[2]), conv_out_size(w, op[2]), op[1]
         elif kind == "gap":
             h, w = 1, 1
-        elif kind in ("relu", "res_begin", "res_end"):
+        elif kind in ("relu", "leaky_relu", "sigmoid", "tanh", "res_begin", "res_end"):
             pass
         else:
             raise ValueError(f"unknown layer {op!r}")
