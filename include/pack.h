@@ -62,12 +62,37 @@ typedef enum {
     PACK_RELU = 2,      /* max(z, 0); must directly follow PACK_LINEAR or PACK_CONV3X3 */
     PACK_GAP = 3,       /* global average pool over H x W */
     PACK_RES_BEGIN = 4, /* the current tensor becomes the shortcut source of a residual block */
-    PACK_RES_END = 5    /* y = relu(current + shortcut(source)); must directly follow PACK_CONV3X3.
+    PACK_RES_END = 5,   /* y = relu(current + shortcut(source)); must directly follow PACK_CONV3X3.
                            shortcut = identity when shapes agree; otherwise source[b,2i,2j,c] for
                            c < Cin and 0 for the remaining channels (parameter-free) */
+    /* the other activations of the paper's search space (Section 6, Table 3); like PACK_RELU each
+       must directly follow PACK_LINEAR or PACK_CONV3X3 */
+    PACK_SIGMOID = 6,   /* 1 / (1 + exp(-z)) */
+    PACK_TANH = 7,      /* tanh(z) */
+    PACK_LEAKY_RELU = 8 /* z > 0 ? z : 0.2 z (the paper names no slope; 0.2 is the default of the
+                           framework it ran on) */
 } pack_op;
 
 typedef enum { PACK_F32 = 0, PACK_BF16 = 1 } pack_dtype;
+
+/* Optimisers of the paper's search space (Section 6, Table 3).  A member's optimiser is one of its
+ * hyper-parameters (Section 2.2, task trait (a)); members of one pack may differ (Table 2,
+ * "Optimizer: Different").  The paper prints no update formula; the library follows the published
+ * definitions of the methods it names, always with gradients taken at the pre-update weights:
+ *   PACK_OPT_SGD       W <- W - lr*g
+ *   PACK_OPT_MOMENTUM  acc <- mu*acc + g;  W <- W - lr*acc                    (acc starts at 0)
+ *   PACK_OPT_ADAGRAD   acc <- acc + g*g;   W <- W - lr*g/sqrt(acc)            (acc starts at acc0)
+ *   PACK_OPT_ADAM      m <- beta1*m + (1-beta1)*g;  v <- beta2*v + (1-beta2)*g*g;  t <- t+1;
+ *                      W <- W - lr * (m/(1-beta1^t)) / (sqrt(v/(1-beta2^t)) + eps)   (m, v, t start at 0) */
+typedef enum { PACK_OPT_SGD = 0, PACK_OPT_MOMENTUM = 1, PACK_OPT_ADAGRAD = 2, PACK_OPT_ADAM = 3 } pack_opt_kind;
+
+typedef struct {
+    int32_t kind;        /* pack_opt_kind */
+    float mu;            /* PACK_OPT_MOMENTUM: in [0, 1) */
+    float acc0;          /* PACK_OPT_ADAGRAD: initial accumulator, > 0 */
+    float beta1, beta2;  /* PACK_OPT_ADAM: in [0, 1) */
+    float eps;           /* PACK_OPT_ADAM: > 0 */
+} pack_opt_spec;
 
 #define PACK_MAX_MODELS 256
 
@@ -113,6 +138,21 @@ pack_status pack_write_weights(pack_t* p, int32_t k, const float* host_src, size
  * [B]; lr_host: host float [K], copied during the call.  Enqueues only.
  * Errors: PACK_EINVAL (null argument), PACK_EDEVICE (launch failure). */
 pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, const float* lr_host);
+
+/* Choose member k's optimiser (default: PACK_OPT_SGD).  Resets the member's optimiser state to its
+ * starting values and its step counter to 0; the weights are untouched.  Fields that the chosen
+ * kind does not use are ignored.  Waits for the stream.  The learning rate stays the per-step
+ * argument of pack_step.
+ * Errors: PACK_EINVAL (null, k out of range, unknown kind, parameter outside its range), PACK_ENOMEM. */
+pack_status pack_set_optimizer(pack_t* p, int32_t k, const pack_opt_spec* spec);
+
+/* The optimiser part of free's checkpoint (Section 2.2: the state is stored with the model): state
+ * array `slot` of member k in the blob layout of the weights (slot 0: momentum / Adagrad accumulator
+ * or Adam's first moment; slot 1: Adam's second moment) and, if `steps` is not null, the number of
+ * steps the optimiser has taken.  pack_write_opt_state restores both (the load of a checkpoint).
+ * Errors: PACK_EINVAL (null, k out of range, n_floats mismatch, slot the member's optimiser does not have). */
+pack_status pack_read_opt_state(pack_t* p, int32_t k, int32_t slot, float* host_dst, size_t n_floats, int64_t* steps);
+pack_status pack_write_opt_state(pack_t* p, int32_t k, int32_t slot, const float* host_src, size_t n_floats, int64_t steps);
 
 /* Loss of each member at the last step, evaluated at that step's pre-update weights.
  * host_dst: float [K].  Waits for the stream.  Returns PACK_ELABEL (and still fills host_dst)

@@ -13,13 +13,21 @@ LIB_PATH = os.environ.get("PACK_LIB", os.path.join(_HERE, "libpack.so"))
 
 PACK_OK, PACK_EINVAL, PACK_ENOMEM, PACK_EDEVICE, PACK_ESHAPE, PACK_ELABEL = range(6)
 PACK_F32, PACK_BF16 = 0, 1
-OPS = {"linear": 0, "conv3x3": 1, "relu": 2, "gap": 3, "res_begin": 4, "res_end": 5}
+OPS = {"linear": 0, "conv3x3": 1, "relu": 2, "gap": 3, "res_begin": 4, "res_end": 5,
+       "sigmoid": 6, "tanh": 7, "leaky_relu": 8}
+OPT_KINDS = {"sgd": 0, "momentum": 1, "adagrad": 2, "adam": 3}
 STATUS_NAMES = ["PACK_OK", "PACK_EINVAL", "PACK_ENOMEM", "PACK_EDEVICE", "PACK_ESHAPE", "PACK_ELABEL"]
 
 EXPORTS = ["pack_create", "pack_write_weights", "pack_step", "pack_read_loss", "pack_read_weights",
            "pack_read_pred", "pack_read_grads", "pack_read_logits", "pack_num_params",
            "pack_num_classes", "pack_num_launches", "pack_device_bytes", "pack_last_error", "pack_destroy",
-           "pack_profile_start", "pack_profile_stop", "pack_launch_name"]
+           "pack_profile_start", "pack_profile_stop", "pack_launch_name",
+           "pack_set_optimizer", "pack_read_opt_state", "pack_write_opt_state"]
+
+
+class pack_opt_spec(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("mu", C.c_float), ("acc0", C.c_float), ("beta1", C.c_float),
+                ("beta2", C.c_float), ("eps", C.c_float)]
 
 
 class pack_layer(C.Structure):
@@ -77,9 +85,13 @@ def lib() -> C.CDLL:
         l.pack_profile_start.argtypes = [vp, i32, i32]
         l.pack_profile_stop.argtypes = [vp, fp, C.POINTER(C.c_int32)]
         l.pack_launch_name.argtypes = [vp, i32, C.c_char_p, sz]
+        l.pack_set_optimizer.argtypes = [vp, i32, C.POINTER(pack_opt_spec)]
+        l.pack_read_opt_state.argtypes = [vp, i32, i32, fp, sz, C.POINTER(C.c_int64)]
+        l.pack_write_opt_state.argtypes = [vp, i32, i32, fp, sz, C.c_int64]
         for name in ("pack_create", "pack_write_weights", "pack_step", "pack_read_loss",
                      "pack_read_weights", "pack_read_pred", "pack_read_grads", "pack_read_logits",
-                     "pack_profile_start", "pack_profile_stop", "pack_launch_name"):
+                     "pack_profile_start", "pack_profile_stop", "pack_launch_name",
+                     "pack_set_optimizer", "pack_read_opt_state", "pack_write_opt_state"):
             getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
@@ -97,8 +109,8 @@ def _fptr(a: np.ndarray):
 
 class Pack:
     """One packed model on the current GPU.  `models` is a list of layer lists of tuples
-    ("linear", out) / ("conv3x3", out, stride) / ("relu",) / ("gap",) / ("res_begin",) /
-    ("res_end",); `batch[k]` is the number of leading rows of the shared batch member k uses."""
+    ("linear", out) / ("conv3x3", out, stride) / ("relu",) / ("sigmoid",) / ("tanh",) /
+    ("leaky_relu",) / ("gap",) / ("res_begin",) / ("res_end",); `batch[k]` is the number of leading rows of the shared batch member k uses."""
 
     def __init__(self, B: int, in_shape: Tuple[int, int, int], dtype: str, models: List[list],
                  batch: Sequence[int] = None, seed: int = 0, stream: int = 0):
@@ -133,6 +145,24 @@ class Pack:
         lr = np.ascontiguousarray(lr, dtype=np.float32)
         assert lr.size == self.K
         _check(lib().pack_step(self._h, C.c_void_p(x_ptr), C.c_void_p(labels_ptr), _fptr(lr)))
+
+    def set_optimizer(self, k: int, opt: dict):
+        """`opt` as in the oracle: {"kind": "sgd" | "momentum" | "adagrad" | "adam", and optionally
+        "mu", "acc0", "beta1", "beta2", "eps"}."""
+        spec = pack_opt_spec(OPT_KINDS[opt["kind"]], float(opt.get("mu", 0.9)), float(opt.get("acc0", 0.1)),
+                             float(opt.get("beta1", 0.9)), float(opt.get("beta2", 0.999)), float(opt.get("eps", 1e-8)))
+        _check(lib().pack_set_optimizer(self._h, k, C.byref(spec)))
+
+    def read_opt_state(self, k: int, slot: int):
+        """Returns (state array in the blob layout, steps taken)."""
+        out = np.empty(self.num_params(k), dtype=np.float32)
+        steps = C.c_int64(0)
+        _check(lib().pack_read_opt_state(self._h, k, slot, _fptr(out), out.size, C.byref(steps)))
+        return out, int(steps.value)
+
+    def write_opt_state(self, k: int, slot: int, state: np.ndarray, steps: int):
+        state = np.ascontiguousarray(state, dtype=np.float32)
+        _check(lib().pack_write_opt_state(self._h, k, slot, _fptr(state), state.size, steps))
 
     def read_loss(self, allow_label_error: bool = False) -> np.ndarray:
         out = np.empty(self.K, dtype=np.float32)

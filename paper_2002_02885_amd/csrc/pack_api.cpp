@@ -43,7 +43,7 @@ struct TensorInfo {
     int n = 0, h = 0, w = 0, c = 0;
     bool is_input = false;
     bool f32 = false;        // logits are stored as float whatever the pack dtype
-    bool relu_out = false;   // produced through a ReLU: gradients written to it are masked
+    int act_out = 0;         // ActKind the tensor was produced through: gradients written to it take its derivative
     bool needs_grad = false;
     bool grad_written = false;
     int ld_dz = 0;           // leading dimension of dz when padded (logits), 0 = c
@@ -56,7 +56,7 @@ struct NodeInfo {
     int kind = 0;
     int in_t = -1, out_t = -1;
     int out = 0, stride = 1;
-    bool relu = false;
+    int act = 0;             // ActKind fused into the layer
     int res_src = -1;        // tensor index of the shortcut source, -1 if none
     bool res_down = false;
     size_t w_off = 0, b_off = 0;   // element offsets into the parameter arena
@@ -103,6 +103,13 @@ struct pack_ctx {
     float* grad = nullptr;       // same layout
     void* shadow = nullptr;      // bf16 copy of the arena (bf16 packs)
     size_t arena_elems = 0;
+    // optimisers other than SGD (all SGD: none of this is allocated or launched)
+    std::vector<pack_opt_spec> opt;      // per member
+    std::vector<long long> opt_t;        // steps taken per member
+    bool any_opt = false;
+    float* opt_m = nullptr;              // arena-shaped: momentum / Adagrad accumulator / Adam first moment
+    float* opt_v = nullptr;              // arena-shaped: Adam second moment
+    OptStatic* opt_params = nullptr;     // device, [K]
     void* wt = nullptr;          // per-step transposed copies [Cin][9][Cout] of convolution weights (operand type)
     long long* seg_end = nullptr;
     char* slab = nullptr;        // activations, gradients wrt activations, loss, predictions
@@ -239,8 +246,9 @@ pack_status parse_model(const pack_input_spec& in, const pack_model_spec& spec, 
                 }
                 nd.blob_off = blob_off;
                 blob_off += nd.w_elems + L.out;
-                if (next_op == PACK_RELU) {
-                    nd.relu = true;
+                if (next_op == PACK_RELU || next_op == PACK_SIGMOID || next_op == PACK_TANH || next_op == PACK_LEAKY_RELU) {
+                    nd.act = next_op == PACK_RELU ? ACT_RELU : next_op == PACK_SIGMOID ? ACT_SIGMOID
+                           : next_op == PACK_TANH ? ACT_TANH : ACT_LEAKY;
                     ++i;
                 } else if (next_op == PACK_RES_END) {
                     if (L.op != PACK_CONV3X3) return fail(PACK_ESHAPE, who + "RES_END must directly follow a CONV3X3");
@@ -255,10 +263,10 @@ pack_status parse_model(const pack_input_spec& in, const pack_model_spec& spec, 
                     } else {
                         return fail(PACK_ESHAPE, who + "shortcut shapes neither agree nor halve");
                     }
-                    nd.relu = true;
+                    nd.act = ACT_RELU;
                     ++i;
                 }
-                o.relu_out = nd.relu;
+                o.act_out = nd.act;
                 m.tensors.push_back(o);
                 nd.out_t = (int)m.tensors.size() - 1;
                 m.nodes.push_back(nd);
@@ -282,7 +290,10 @@ pack_status parse_model(const pack_input_spec& in, const pack_model_spec& spec, 
                 res_stack.push_back(cur);
                 break;
             case PACK_RELU:
-                return fail(PACK_ESHAPE, who + "RELU must directly follow LINEAR or CONV3X3");
+            case PACK_SIGMOID:
+            case PACK_TANH:
+            case PACK_LEAKY_RELU:
+                return fail(PACK_ESHAPE, who + "an activation must directly follow LINEAR or CONV3X3");
             case PACK_RES_END:
                 return fail(PACK_ESHAPE, who + "RES_END must directly follow a CONV3X3");
             default:
@@ -290,7 +301,7 @@ pack_status parse_model(const pack_input_spec& in, const pack_model_spec& spec, 
         }
     }
     if (!res_stack.empty()) return fail(PACK_ESHAPE, who + "RES_BEGIN without RES_END");
-    if (m.nodes.empty() || m.nodes.back().kind != NODE_LINEAR || m.nodes.back().relu)
+    if (m.nodes.empty() || m.nodes.back().kind != NODE_LINEAR || m.nodes.back().act)
         return fail(PACK_ESHAPE, who + "the layer list must end in a LINEAR layer producing the logits");
     m.tensors[cur].f32 = true;
     // The gradient wrt the logits keeps its rows padded to whole 16-byte vectors; the padding is
@@ -521,7 +532,8 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
             g.B = weight_ptr(nd);
             g.C = to.act;
             g.bias = p->master + nd.b_off;
-            g.flags = (nd.relu ? F_RELU : 0) | (to.f32 ? F_OUT_F32 : 0) | (ti.is_input ? F_A_INPUT : 0);
+            g.flags = (nd.act == ACT_RELU ? F_RELU : 0) | (to.f32 ? F_OUT_F32 : 0) | (ti.is_input ? F_A_INPUT : 0);
+            g.act = nd.act;
             if (nd.kind == NODE_LINEAR) {
                 g.R = ti.n; g.Q = nd.out; g.Kd = nd.fan_in;
                 g.lda = nd.fan_in; g.ldb = nd.fan_in; g.ldc = nd.out;
@@ -627,7 +639,7 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 if (!ti.needs_grad) continue;
                 GapProb g{};
                 g.in = ti.act; g.dz_out = to.dz; g.dz_in = ti.dz; g.n = ti.n; g.hw = ti.h * ti.w; g.c = ti.c;
-                g.mask = ti.relu_out; g.accum = ti.grad_written;
+                g.mask = ti.act_out; g.accum = ti.grad_written;
                 ti.grad_written = true;
                 gaps.push_back(g);
                 gap_blocks.push_back((int)((ti.elems() + ELEMWISE_PER_BLOCK - 1) / ELEMWISE_PER_BLOCK));
@@ -700,7 +712,8 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 g.B = weight_ptr(nd);
                 g.C = ti.dz;
                 g.aux = ti.act;
-                g.flags = (ti.relu_out ? F_MASK : 0) | (ti.grad_written ? F_ACCUM : 0);
+                g.flags = (ti.act_out ? F_MASK : 0) | (ti.grad_written ? F_ACCUM : 0);
+                g.mask_act = ti.act_out;
                 ti.grad_written = true;
                 if (nd.kind == NODE_LINEAR) {
                     g.R = ti.n; g.Q = nd.fan_in; g.Kd = nd.out;
@@ -746,7 +759,7 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 ShortcutProb sp{};
                 sp.dz_out = to.dz; sp.src = rs.act; sp.dz_src = rs.dz;
                 sp.n = rs.n; sp.H = rs.h; sp.W = rs.w; sp.C = rs.c; sp.Ho = to.h; sp.Wo = to.w; sp.Co = to.c;
-                sp.down = nd.res_down; sp.mask = rs.relu_out; sp.accum = rs.grad_written;
+                sp.down = nd.res_down; sp.mask = rs.act_out; sp.accum = rs.grad_written;
                 rs.grad_written = true;
                 scs.push_back(sp);
                 sc_blocks.push_back((int)((rs.elems() + ELEMWISE_PER_BLOCK - 1) / ELEMWISE_PER_BLOCK));
@@ -785,6 +798,9 @@ void release(pack_ctx* p) {
     if (p->grad) (void)hipFree(p->grad);
     if (p->shadow) (void)hipFree(p->shadow);
     if (p->wt) (void)hipFree(p->wt);
+    if (p->opt_m) (void)hipFree(p->opt_m);
+    if (p->opt_v) (void)hipFree(p->opt_v);
+    if (p->opt_params) (void)hipFree(p->opt_params);
     if (p->seg_end) (void)hipFree(p->seg_end);
     if (p->slab) (void)hipFree(p->slab);
     if (p->workspace) (void)hipFree(p->workspace);
@@ -853,6 +869,8 @@ pack_status pack_create(const pack_input_spec* input, const pack_model_spec* mod
     p->K = K;
     p->in = *input;
     p->models.resize(K);
+    p->opt.assign(K, pack_opt_spec{PACK_OPT_SGD, 0.f, 0.f, 0.f, 0.f, 0.f});
+    p->opt_t.assign(K, 0);
     for (int k = 0; k < K; ++k) {
         pack_status s = parse_model(*input, models[k], k, p->models[k]);
         if (s != PACK_OK) { release(p); return s; }
@@ -1029,7 +1047,24 @@ pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, c
             case L_IM2COL: e = launch_im2col(bf, p->im2col[L.mode], x_dev, p->stream); break;
             case L_WTRANS: e = launch_wtranspose(bf, (const TransposeProb*)d, (const int2*)mp, L.n, p->stream); break;
             case L_SGD:
-                e = launch_sgd(p->master, p->grad, p->shadow, (long long)p->arena_elems, p->seg_end, p->K, lr, p->stream);
+                if (!p->any_opt) {
+                    e = launch_sgd(p->master, p->grad, p->shadow, (long long)p->arena_elems, p->seg_end, p->K, lr, p->stream);
+                } else {
+                    OptTable tab;
+                    for (int k = 0; k < 256; ++k) {
+                        tab.lr[k] = (k < p->K) ? lr_host[k] : 0.f;
+                        tab.c1[k] = tab.c2[k] = 1.f;
+                        if (k < p->K && p->opt[k].kind == PACK_OPT_ADAM) {
+                            const double t = (double)(p->opt_t[k] + 1);
+                            tab.c1[k] = (float)(1.0 / (1.0 - std::pow((double)p->opt[k].beta1, t)));
+                            tab.c2[k] = (float)(1.0 / (1.0 - std::pow((double)p->opt[k].beta2, t)));
+                        }
+                    }
+                    e = launch_opt(p->master, p->grad, p->shadow, p->opt_m, p->opt_v, (long long)p->arena_elems,
+                                   p->seg_end, p->opt_params, p->K, tab, p->stream);
+                    if (e == hipSuccess)
+                        for (int k = 0; k < p->K; ++k) ++p->opt_t[k];
+                }
                 break;
         }
         if (e != hipSuccess) return fail(PACK_EDEVICE, std::string("kernel launch: ") + hipGetErrorString(e));
@@ -1078,6 +1113,95 @@ pack_status pack_launch_name(const pack_t* p, int32_t i, char* buf, size_t n) {
     const Launch& L = p->plan[i];
     const char* nm = (L.kind == L_GEMM) ? gemm_names[L.mode] : names[L.kind];
     std::snprintf(buf, n, "%s", nm);
+    return PACK_OK;
+}
+
+pack_status pack_set_optimizer(pack_t* p, int32_t k, const pack_opt_spec* spec) {
+    if (!p || !spec) return fail(PACK_EINVAL, "null argument");
+    if (k < 0 || k >= p->K) return fail(PACK_EINVAL, "member index out of range");
+    const pack_opt_spec o = *spec;
+    auto unit = [](float v) { return v >= 0.f && v < 1.f; };
+    switch (o.kind) {
+        case PACK_OPT_SGD: break;
+        case PACK_OPT_MOMENTUM: if (!unit(o.mu)) return fail(PACK_EINVAL, "momentum must be in [0, 1)"); break;
+        case PACK_OPT_ADAGRAD: if (!(o.acc0 > 0.f)) return fail(PACK_EINVAL, "initial accumulator must be > 0"); break;
+        case PACK_OPT_ADAM:
+            if (!unit(o.beta1) || !unit(o.beta2) || !(o.eps > 0.f)) return fail(PACK_EINVAL, "beta1, beta2 in [0, 1) and eps > 0");
+            break;
+        default: return fail(PACK_EINVAL, "unknown optimiser kind");
+    }
+    HIP_TRY(hipStreamSynchronize(p->stream), PACK_EDEVICE);
+    pack_status st;
+    if (o.kind != PACK_OPT_SGD && !p->opt_m) {
+        if ((st = dev_alloc((void**)&p->opt_m, p->arena_elems * 4, p)) != PACK_OK) return st;
+        HIP_TRY(hipMemset(p->opt_m, 0, p->arena_elems * 4), PACK_EDEVICE);
+    }
+    if (o.kind == PACK_OPT_ADAM && !p->opt_v) {
+        if ((st = dev_alloc((void**)&p->opt_v, p->arena_elems * 4, p)) != PACK_OK) return st;
+        HIP_TRY(hipMemset(p->opt_v, 0, p->arena_elems * 4), PACK_EDEVICE);
+    }
+    if (!p->opt_params) {
+        if ((st = dev_alloc((void**)&p->opt_params, (size_t)p->K * sizeof(OptStatic), p)) != PACK_OK) return st;
+    }
+    p->opt[k] = o;
+    p->opt_t[k] = 0;
+    // starting state over the member's whole arena segment (alignment gaps included: their gradient
+    // is always zero, and a positive Adagrad accumulator there keeps 0 / sqrt(acc) well defined)
+    const ModelInfo& m = p->models[k];
+    const size_t seg = m.arena_end - m.arena_begin;
+    if (p->opt_m) {
+        std::vector<float> init(seg, o.kind == PACK_OPT_ADAGRAD ? o.acc0 : 0.f);
+        HIP_TRY(hipMemcpy(p->opt_m + m.arena_begin, init.data(), seg * 4, hipMemcpyHostToDevice), PACK_EDEVICE);
+    }
+    if (p->opt_v) HIP_TRY(hipMemset(p->opt_v + m.arena_begin, 0, seg * 4), PACK_EDEVICE);
+    p->any_opt = false;
+    std::vector<OptStatic> par(p->K);
+    for (int i = 0; i < p->K; ++i) {
+        par[i] = OptStatic{p->opt[i].kind, p->opt[i].mu, p->opt[i].beta1, p->opt[i].beta2, p->opt[i].eps};
+        if (p->opt[i].kind != PACK_OPT_SGD) p->any_opt = true;
+    }
+    HIP_TRY(hipMemcpy(p->opt_params, par.data(), par.size() * sizeof(OptStatic), hipMemcpyHostToDevice), PACK_EDEVICE);
+    return PACK_OK;
+}
+
+static pack_status opt_slot(pack_t* p, int32_t k, int32_t slot, float** arena) {
+    if (!p) return fail(PACK_EINVAL, "null argument");
+    if (k < 0 || k >= p->K) return fail(PACK_EINVAL, "member index out of range");
+    const int kind = p->opt[k].kind;
+    const bool has = (slot == 0 && kind != PACK_OPT_SGD) || (slot == 1 && kind == PACK_OPT_ADAM);
+    if (!has) return fail(PACK_EINVAL, "the member's optimiser has no such state array");
+    *arena = slot == 0 ? p->opt_m : p->opt_v;
+    return PACK_OK;
+}
+
+pack_status pack_read_opt_state(pack_t* p, int32_t k, int32_t slot, float* host_dst, size_t n_floats, int64_t* steps) {
+    float* arena = nullptr;
+    pack_status st = opt_slot(p, k, slot, &arena);
+    if (st != PACK_OK) return st;
+    st = download(p, k, arena, host_dst, n_floats);
+    if (st == PACK_OK && steps) *steps = p->opt_t[k];
+    return st;
+}
+
+pack_status pack_write_opt_state(pack_t* p, int32_t k, int32_t slot, const float* host_src, size_t n_floats, int64_t steps) {
+    float* arena = nullptr;
+    pack_status st = opt_slot(p, k, slot, &arena);
+    if (st != PACK_OK) return st;
+    if (!host_src || steps < 0) return fail(PACK_EINVAL, "null argument or negative step count");
+    ModelInfo& m = p->models[k];
+    if (n_floats != m.n_params) return fail(PACK_EINVAL, "n_floats does not match pack_num_params");
+    std::vector<float> seg;
+    blob_to_arena(m, host_src, seg);
+    if (p->opt[k].kind == PACK_OPT_ADAGRAD && slot == 0) {
+        // positions outside the blob (alignment gaps, padded columns) keep a positive accumulator
+        std::vector<float> ones(m.n_params, 1.f), mark;
+        blob_to_arena(m, ones.data(), mark);
+        for (size_t i = 0; i < seg.size(); ++i)
+            if (mark[i] == 0.f) seg[i] = p->opt[k].acc0;
+    }
+    HIP_TRY(hipStreamSynchronize(p->stream), PACK_EDEVICE);
+    HIP_TRY(hipMemcpy(arena + m.arena_begin, seg.data(), seg.size() * 4, hipMemcpyHostToDevice), PACK_EDEVICE);
+    p->opt_t[k] = steps;
     return PACK_OK;
 }
 

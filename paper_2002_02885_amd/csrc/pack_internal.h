@@ -35,6 +35,9 @@ enum GemmFlags : int {
                        // taps of that class only (u = 1 or u in {0, 2}, likewise v)
 };
 
+// activation kinds (paper Table 3); the value is also what GemmProb::act / mask_act hold
+enum ActKind { ACT_NONE = 0, ACT_RELU = 1, ACT_LEAKY = 2, ACT_SIGMOID = 3, ACT_TANH = 4 };
+
 struct GemmProb {
     const void* A;
     const void* B;
@@ -51,6 +54,8 @@ struct GemmProb {
     int cls_py, cls_px, cls_h, cls_w;      // F_ROWMAP: parity class and its extent in pixels
     int row_w, row_hw;                     // conv problems whose rows are pixels: row r = (image, r % row_hw / row_w, r % row_w)
     int lg_row_w, lg_row_hw;               // their base-2 logarithms when both are powers of two, else -1
+    int act;                               // forward modes: activation applied after bias and shortcut (ActKind)
+    int mask_act;                          // input-gradient modes with F_MASK: activation that produced `aux`
     int flags;
     int ksplit;                            // reduction indices per split (>= Kd when not split)
     long long split_stride;                // elements between the partial outputs of two splits
@@ -82,7 +87,7 @@ struct GapProb {      // global average pool: in [n, hw, c] -> out [n, c]
     const void* dz_out;    // backward: gradient wrt out
     void* dz_in;           // backward: gradient wrt in
     int n, hw, c;
-    int mask;              // backward: zero where in <= 0
+    int mask;              // backward: ActKind that produced `in` (its derivative multiplies the gradient)
     int accum;
 };
 
@@ -92,7 +97,7 @@ struct ShortcutProb { // backward of the residual shortcut into the source tenso
     void* dz_src;
     int n, H, W, C, Ho, Wo, Co;
     int down;              // 0 identity, 1 subsample
-    int mask;
+    int mask;              // ActKind that produced `src`
     int accum;
 };
 
@@ -122,6 +127,11 @@ hipError_t launch_gap(bool bf16, bool backward, const GapProb* probs_dev, const 
 hipError_t launch_shortcut_bwd(bool bf16, const ShortcutProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);
 hipError_t launch_sgd(float* master, const float* grad, void* shadow_bf16, long long n,
                       const long long* seg_end_dev, int K, const LrTable& lr, hipStream_t st);
+// per-member optimiser description (device memory, one entry per member) and per-step table (by value)
+struct OptStatic { int kind; float mu, beta1, beta2, eps; };
+struct OptTable { float lr[256]; float c1[256]; float c2[256]; };   // c1, c2: Adam's 1/(1-beta1^t), 1/(1-beta2^t)
+hipError_t launch_opt(float* master, const float* grad, void* shadow_bf16, float* m, float* v, long long n,
+                      const long long* seg_end_dev, const OptStatic* params_dev, int K, const OptTable& tab, hipStream_t st);
 hipError_t launch_im2col(bool bf16, const Im2colProb& p, const void* x_dev, hipStream_t st);
 hipError_t launch_wtranspose(bool bf16, const TransposeProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);
 hipError_t launch_cast_bf16(const float* src, void* dst_bf16, long long n, hipStream_t st);

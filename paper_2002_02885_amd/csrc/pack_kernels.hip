@@ -37,6 +37,28 @@ __device__ __forceinline__ unsigned pack2bf(float lo, float hi) {
 __device__ __forceinline__ bf16_t f2bf(float f) { return (bf16_t)(pack2bf(f, 0.f) & 0xffffu); }
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((unsigned int)h) << 16); }
 
+// activations of the paper's search space (Table 3) and their derivatives written in terms of the
+// stored output (what the backward pass has at hand); leaky ReLU slope 0.2
+constexpr float LEAKY_SLOPE = 0.2f;
+__device__ __forceinline__ float act_apply(int kind, float z) {
+    switch (kind) {
+        case ACT_RELU: return fmaxf(z, 0.f);
+        case ACT_LEAKY: return z > 0.f ? z : LEAKY_SLOPE * z;
+        case ACT_SIGMOID: return 1.f / (1.f + expf(-z));
+        case ACT_TANH: return tanhf(z);
+        default: return z;
+    }
+}
+__device__ __forceinline__ float act_deriv(int kind, float out) {
+    switch (kind) {
+        case ACT_RELU: return out > 0.f ? 1.f : 0.f;
+        case ACT_LEAKY: return out > 0.f ? 1.f : LEAKY_SLOPE;
+        case ACT_SIGMOID: return out * (1.f - out);
+        case ACT_TANH: return 1.f - out * out;
+        default: return 1.f;
+    }
+}
+
 template <typename T> struct ET;
 template <> struct ET<float> {
     static constexpr int V = 4;    // elements per 16-byte vector
@@ -795,9 +817,12 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                 }
             }
             if (p.flags & F_RELU) v = fmaxf(v, 0.f);
+            else if (p.act > ACT_RELU) v = act_apply(p.act, v);
         } else if constexpr (!IS_DW) {
             if (p.flags & F_MASK) {
-                if (!(ET<T>::to_f(((const T*)p.aux)[off]) > 0.f)) v = 0.f;
+                const float a = ET<T>::to_f(((const T*)p.aux)[off]);
+                if (p.mask_act == ACT_RELU) { if (!(a > 0.f)) v = 0.f; }
+                else v *= act_deriv(p.mask_act, a);
             }
             if (p.flags & F_ACCUM) v += ET<T>::to_f(((const T*)p.C)[off]);
         }
@@ -900,14 +925,23 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                         if (p.flags & F_RELU) {
 #pragma unroll
                             for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+                        } else if (p.act > ACT_RELU) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[e] = act_apply(p.act, v[e]);
                         }
                     } else if constexpr (!IS_DW) {
                         const bool accum = (p.flags & F_ACCUM) != 0;
+                        if (!(p.flags & F_MASK) || p.mask_act == ACT_RELU) {   // absent mask source reads as ones
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            if (!(ax[e] > 0.f)) v[e] = 0.f;
-                            if (accum) v[e] += old[e];
+                            for (int e = 0; e < 8; ++e)
+                                if (!(ax[e] > 0.f)) v[e] = 0.f;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[e] *= act_deriv(p.mask_act, ax[e]);
                         }
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (accum) v[e] += old[e];
                     }
                     if (out_f32) {
                         *reinterpret_cast<f32x4_t*>(cf + off[n]) = f32x4_t{v[0], v[1], v[2], v[3]};
@@ -1175,7 +1209,8 @@ __global__ __launch_bounds__(256) void gap_bwd_kernel(const GapProb* __restrict_
         const int c = (int)(e % p.c);
         const int n = (int)(e / ((long long)p.hw * p.c));
         float g = ET<T>::to_f(((const T*)p.dz_out)[(size_t)n * p.c + c]) * inv;
-        if (p.mask && !(ET<T>::to_f(((const T*)p.in)[e]) > 0.f)) g = 0.f;
+        if (p.mask == ACT_RELU) { if (!(ET<T>::to_f(((const T*)p.in)[e]) > 0.f)) g = 0.f; }
+        else if (p.mask) g *= act_deriv(p.mask, ET<T>::to_f(((const T*)p.in)[e]));
         if (p.accum) g += ET<T>::to_f(((const T*)p.dz_in)[e]);
         ((T*)p.dz_in)[e] = ET<T>::from_f(g);
     }
@@ -1228,7 +1263,8 @@ __global__ __launch_bounds__(256) void shortcut_bwd_kernel(const ShortcutProb* _
 #pragma unroll
         for (int i = 0; i < V; ++i) {
             float v = ET<T>::to_f(gv[i]);
-            if (p.mask && !(ET<T>::to_f(sv[i]) > 0.f)) v = 0.f;
+            if (p.mask == ACT_RELU) { if (!(ET<T>::to_f(sv[i]) > 0.f)) v = 0.f; }
+            else if (p.mask) v *= act_deriv(p.mask, ET<T>::to_f(sv[i]));
             if (p.accum) v += ET<T>::to_f(ov[i]);
             out[i] = ET<T>::from_f(v);
         }
@@ -1256,7 +1292,8 @@ __global__ __launch_bounds__(256) void shortcut_bwd_kernel(const ShortcutProb* _
             if (((x | y) & 1) == 0 && (y >> 1) < p.Ho && (x >> 1) < p.Wo)
                 g = ET<T>::to_f(((const T*)p.dz_out)[((size_t)(n * p.Ho + (y >> 1)) * p.Wo + (x >> 1)) * p.Co + c]);
         }
-        if (p.mask && !(ET<T>::to_f(((const T*)p.src)[e]) > 0.f)) g = 0.f;
+        if (p.mask == ACT_RELU) { if (!(ET<T>::to_f(((const T*)p.src)[e]) > 0.f)) g = 0.f; }
+        else if (p.mask) g *= act_deriv(p.mask, ET<T>::to_f(((const T*)p.src)[e]));
         if (p.accum) g += ET<T>::to_f(((const T*)p.dz_src)[e]);
         ((T*)p.dz_src)[e] = ET<T>::from_f(g);
     }
@@ -1329,6 +1366,102 @@ hipError_t launch_sgd(float* master, const float* grad, void* shadow, long long 
     const int blocks = (int)((n + SGD_PER_BLOCK - 1) / SGD_PER_BLOCK);
     if (shadow) hipLaunchKernelGGL(sgd_kernel<true>, dim3(blocks), dim3(256), 0, st, master, grad, (bf16_t*)shadow, n, seg_end, K, lr);
     else hipLaunchKernelGGL(sgd_kernel<false>, dim3(blocks), dim3(256), 0, st, master, grad, (bf16_t*)nullptr, n, seg_end, K, lr);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// The other optimisers of the paper's search space (Table 3), each member with its own kind,
+// hyper-parameters and state (the state is "stored with the model", Section 2.2):
+//   momentum  acc <- mu*acc + g;  W <- W - lr*acc
+//   adagrad   acc <- acc + g*g;   W <- W - lr*g/sqrt(acc)
+//   adam      m <- b1*m + (1-b1)*g;  v <- b2*v + (1-b2)*g*g;  W <- W - lr*(m*c1)/(sqrt(v*c2) + eps),
+//             c1 = 1/(1-b1^t), c2 = 1/(1-b2^t) for step number t (computed on the host in double)
+// `m` holds the momentum / Adagrad accumulator or Adam's first moment, `v` Adam's second moment.
+// Streams 20-22 bytes per parameter for momentum and Adagrad, 28-30 for Adam.  Packs whose members
+// all use plain SGD never launch this kernel.
+// ------------------------------------------------------------------------------------------------
+enum OptKind { OPT_SGD = 0, OPT_MOMENTUM = 1, OPT_ADAGRAD = 2, OPT_ADAM = 3 };
+
+template <bool SHADOW>
+__global__ __launch_bounds__(256) void opt_kernel(float* __restrict__ w, const float* __restrict__ g,
+                                                  bf16_t* __restrict__ shadow, float* __restrict__ ms,
+                                                  float* __restrict__ vs, long long n,
+                                                  const long long* __restrict__ seg_end,
+                                                  const OptStatic* __restrict__ params, int K, OptTable tab) {
+    __shared__ float s_lr[256], s_c1[256], s_c2[256];
+    __shared__ long long s_end[256];
+    __shared__ OptStatic s_par[256];
+    for (int i = threadIdx.x; i < K; i += 256) {
+        s_lr[i] = tab.lr[i];
+        s_c1[i] = tab.c1[i];
+        s_c2[i] = tab.c2[i];
+        s_end[i] = seg_end[i];
+        s_par[i] = params[i];
+    }
+    __syncthreads();
+    const long long base = (long long)blockIdx.x * SGD_PER_BLOCK;
+    int lo = 0, hi = K - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (s_end[mid] > base) hi = mid; else lo = mid + 1;
+    }
+    int mdl = lo;
+    constexpr int IT = SGD_PER_BLOCK / 1024;
+#pragma unroll
+    for (int i = 0; i < IT; ++i) {
+        const long long idx = base + i * 1024 + threadIdx.x * 4;
+        if (idx >= n) break;
+        while (mdl < K - 1 && idx >= s_end[mdl]) ++mdl;
+        const OptStatic o = s_par[mdl];
+        const float lr = s_lr[mdl];
+        f32x4_t wv = *reinterpret_cast<const f32x4_t*>(w + idx);
+        const f32x4_t gv = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(g + idx));
+        if (o.kind == OPT_SGD) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) wv[e] = wv[e] - lr * gv[e];
+        } else if (o.kind == OPT_MOMENTUM) {
+            f32x4_t a = *reinterpret_cast<const f32x4_t*>(ms + idx);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                a[e] = o.mu * a[e] + gv[e];
+                wv[e] = wv[e] - lr * a[e];
+            }
+            __builtin_nontemporal_store(a, reinterpret_cast<f32x4_t*>(ms + idx));
+        } else if (o.kind == OPT_ADAGRAD) {
+            f32x4_t a = *reinterpret_cast<const f32x4_t*>(ms + idx);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                a[e] = a[e] + gv[e] * gv[e];
+                wv[e] = wv[e] - lr * (gv[e] / sqrtf(a[e]));
+            }
+            __builtin_nontemporal_store(a, reinterpret_cast<f32x4_t*>(ms + idx));
+        } else {
+            f32x4_t a = *reinterpret_cast<const f32x4_t*>(ms + idx);
+            f32x4_t b = *reinterpret_cast<const f32x4_t*>(vs + idx);
+            const float c1 = s_c1[mdl], c2 = s_c2[mdl];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                a[e] = o.beta1 * a[e] + (1.f - o.beta1) * gv[e];
+                b[e] = o.beta2 * b[e] + (1.f - o.beta2) * (gv[e] * gv[e]);
+                wv[e] = wv[e] - lr * ((a[e] * c1) / (sqrtf(b[e] * c2) + o.eps));
+            }
+            __builtin_nontemporal_store(a, reinterpret_cast<f32x4_t*>(ms + idx));
+            __builtin_nontemporal_store(b, reinterpret_cast<f32x4_t*>(vs + idx));
+        }
+        __builtin_nontemporal_store(wv, reinterpret_cast<f32x4_t*>(w + idx));
+        if constexpr (SHADOW) {
+            typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
+            __builtin_nontemporal_store(u32x2_t{pack2bf(wv.x, wv.y), pack2bf(wv.z, wv.w)}, reinterpret_cast<u32x2_t*>(shadow + idx));
+        }
+    }
+}
+
+hipError_t launch_opt(float* master, const float* grad, void* shadow, float* m, float* v, long long n,
+                      const long long* seg_end, const OptStatic* params, int K, const OptTable& tab, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    const int blocks = (int)((n + SGD_PER_BLOCK - 1) / SGD_PER_BLOCK);
+    if (shadow) hipLaunchKernelGGL(opt_kernel<true>, dim3(blocks), dim3(256), 0, st, master, grad, (bf16_t*)shadow, m, v, n, seg_end, params, K, tab);
+    else hipLaunchKernelGGL(opt_kernel<false>, dim3(blocks), dim3(256), 0, st, master, grad, (bf16_t*)nullptr, m, v, n, seg_end, params, K, tab);
     return hipGetLastError();
 }
 

@@ -29,6 +29,10 @@ def run_gpu(w: wl.PackWorkload, steps=None, lr=None, x_dev=None, y_dev=None, kee
     try:
         for k in range(w.K):
             pk.write_weights(k, w.weights[k])
+        opts = w.meta.get("optimizers")
+        if opts:
+            for k in range(w.K):
+                pk.set_optimizer(k, opts[k])
         if x_dev is None:
             x_dev, y_dev = device_inputs(w)
         loss = np.zeros((steps, w.K), dtype=np.float64)
@@ -44,6 +48,9 @@ def run_gpu(w: wl.PackWorkload, steps=None, lr=None, x_dev=None, y_dev=None, kee
                "pred": [pk.read_pred(k) for k in range(w.K)],
                "blobs": [pk.read_weights(k) for k in range(w.K)],
                "launches": pk.num_launches(), "device_bytes": pk.device_bytes()}
+        if opts:
+            out["opt_state"] = [[pk.read_opt_state(k, s) for s in range({"sgd": 0, "momentum": 1, "adagrad": 1, "adam": 2}[opts[k]["kind"]])]
+                                for k in range(w.K)]
     finally:
         pk.destroy()
     return out
@@ -54,7 +61,7 @@ def run_oracle(w: wl.PackWorkload, steps=None, mode="exact", lr=None):
     lr = w.lr if lr is None else lr
     return po.train_pack(w.models, w.in_shape, [b.astype(np.float64) for b in w.weights], w.batch,
                          np.asarray(lr, dtype=np.float64), w.x.astype(np.float64), w.labels, steps,
-                         mode=mode, keep_grads=True)
+                         mode=mode, keep_grads=True, optimizers=w.meta.get("optimizers"))
 
 
 def tensor_slices(layers, in_shape):
@@ -162,7 +169,7 @@ def oracle_sensitivity(w: wl.PackWorkload, steps, base: dict, mode="rounded", tr
 
         pert = po.train_pack(w.models, w.in_shape, [b.astype(np.float64) for b in w.weights], w.batch,
                              np.asarray(w.lr, dtype=np.float64), w.x.astype(np.float64), w.labels, steps,
-                             mode=mode, keep_grads=True, acc_noise=noisy)
+                             mode=mode, keep_grads=True, acc_noise=noisy, optimizers=w.meta.get("optimizers"))
         for key, (e, _) in measure(w, pert, base).items():
             out[key] = (max(out.get(key, (0.0, 0.0))[0], e), 0.0)
     return out

@@ -260,3 +260,117 @@ def test_seeded_initialisation_is_reproducible_and_bounded():
         off += nw + nb
         assert np.max(np.abs(W)) <= np.sqrt(6.0 / fan_in) and np.max(np.abs(bb)) <= 1 / np.sqrt(fan_in)
         assert np.max(np.abs(W)) > 0.8 * np.sqrt(6.0 / fan_in) and abs(W.mean()) < 0.2 * np.sqrt(6.0 / fan_in)
+
+
+# ------------------------------------------------------------------ the rest of the paper's search space (Table 3)
+ADAM = {"kind": "adam", "beta1": 0.9, "beta2": 0.999, "eps": 1e-8}
+MOMENTUM = {"kind": "momentum", "mu": 0.9}
+ADAGRAD = {"kind": "adagrad", "acc0": 0.1}
+SGD = {"kind": "sgd"}
+
+
+def _act_mlp(widths, act, C=10):
+    layers = []
+    for h in widths:
+        layers += [("linear", h), (act,)]
+    return layers + [("linear", C)]
+
+
+def _check_opt_state(w, gpu, ref, tol):
+    """Optimiser state after the last step against the oracle's, per member and state array,
+    relative to the largest entry (Adam's second moment spans many orders of magnitude)."""
+    for k, opt in enumerate(w.meta["optimizers"]):
+        for slot, (state, steps) in enumerate(gpu["opt_state"][k]):
+            want = ref["nets"][k].opt_state_blob(slot)
+            assert steps == ref["nets"][k].t
+            err = np.max(np.abs(state - want)) / max(np.max(np.abs(want)), 1e-300)
+            assert err <= tol, f"{w.name} member {k} {opt['kind']} state {slot}: {err}"
+
+
+def test_activations_and_optimisers_mlp_fp32():
+    """One pack whose members differ in activation AND optimiser (Table 2 'Optimizer: Different',
+    Table 3), ragged widths and batch slices, several steps."""
+    models = [_act_mlp([96, 40], "tanh"), _act_mlp([130], "sigmoid"), _act_mlp([64, 64, 24], "leaky_relu"),
+              _act_mlp([72], "relu"), _act_mlp([50, 30], "tanh")]
+    w = wl.custom("acts_opts_f32", 41, wl.F32, 48, (1, 1, 200), models, batch=[48, 40, 48, 17, 48],
+                  lr=lambda r: np.array([1e-3, 5e-2, 2e-2, 5e-2, 1e-2]), steps=4)
+    w.meta["optimizers"] = [ADAM, MOMENTUM, ADAGRAD, SGD, {"kind": "adam", "beta1": 0.8, "beta2": 0.95, "eps": 1e-6}]
+    gpu, ref = _check_f32(w)
+    _check_opt_state(w, gpu, ref, F32_TOL)
+
+
+def test_activations_and_optimisers_cnn_fp32():
+    cnn = lambda a, b: [("conv3x3", 8, 1), (a,), ("conv3x3", 16, 2), (b,), ("gap",), ("linear", 10)]
+    models = [cnn("tanh", "leaky_relu"), cnn("sigmoid", "relu"), cnn("leaky_relu", "tanh")]
+    w = wl.custom("acts_opts_cnn_f32", 42, wl.F32, 12, (10, 10, 3), models, lr=lambda r: np.array([2e-3, 3e-2, 3e-2]),
+                  pixel="uniform", steps=3)
+    w.meta["optimizers"] = [ADAM, ADAGRAD, MOMENTUM]
+    gpu, ref = _check_f32(w)
+    _check_opt_state(w, gpu, ref, F32_TOL)
+
+
+def test_activations_and_optimisers_bf16():
+    models = [_act_mlp([128, 64], "tanh"), _act_mlp([128], "sigmoid"), _act_mlp([64, 64], "leaky_relu"), _act_mlp([128], "relu")]
+    w = wl.custom("acts_opts_bf16", 43, wl.BF16, 64, (1, 1, 256), models, lr=lambda r: np.array([1e-3, 2e-2, 2e-2, 2e-2]), steps=4)
+    w.meta["optimizers"] = [ADAM, MOMENTUM, ADAGRAD, MOMENTUM]
+    gpu, weights, rounded = _check_bf16(w)
+    _check_opt_state(w, gpu, rounded, BF16_TOL)
+
+
+def test_optimiser_checkpoint_round_trip_continues_the_same_trajectory():
+    """free's checkpoint carries the optimiser state (Section 2.2): train 2 steps, read weights and
+    state, load them into a fresh pack, train 2 more; bit-identical to 4 uninterrupted steps."""
+    from paper_2002_02885_amd import binding
+    models = [_act_mlp([64], "tanh"), _act_mlp([32, 32], "relu")]
+    w = wl.custom("ckpt", 44, wl.F32, 16, (1, 1, 40), models, lr=lambda r: np.array([1e-2, 1e-2]), steps=4)
+    opts = [ADAM, MOMENTUM]
+    x_dev, y_dev = pu.device_inputs(w)
+
+    def fresh():
+        pk = binding.Pack(w.B, w.in_shape, w.dtype, w.models, w.batch)
+        for k in range(w.K):
+            pk.write_weights(k, w.weights[k])
+            pk.set_optimizer(k, opts[k])
+        return pk
+
+    a = fresh()
+    for _ in range(4):
+        a.step(x_dev.data_ptr(), y_dev.data_ptr(), w.lr)
+    want = [a.read_weights(k) for k in range(w.K)]
+    a.destroy()
+    b = fresh()
+    for _ in range(2):
+        b.step(x_dev.data_ptr(), y_dev.data_ptr(), w.lr)
+    ckpt = [(b.read_weights(k), [b.read_opt_state(k, s) for s in range(2 if opts[k]["kind"] == "adam" else 1)]) for k in range(w.K)]
+    b.destroy()
+    c = fresh()
+    for k, (blob, states) in enumerate(ckpt):
+        c.write_weights(k, blob)
+        for s, (arr, steps) in enumerate(states):
+            assert steps == 2
+            c.write_opt_state(k, s, arr, steps)
+    for _ in range(2):
+        c.step(x_dev.data_ptr(), y_dev.data_ptr(), w.lr)
+    got = [c.read_weights(k) for k in range(w.K)]
+    c.destroy()
+    for k in range(w.K):
+        assert np.array_equal(got[k], want[k])
+
+
+def test_optimiser_argument_errors():
+    from paper_2002_02885_amd import binding
+    pk = binding.Pack(4, (1, 1, 8), wl.F32, [[("linear", 3)]], [4])
+    try:
+        for bad in ({"kind": "momentum", "mu": 1.0}, {"kind": "adagrad", "acc0": 0.0}, {"kind": "adam", "eps": 0.0},
+                    {"kind": "adam", "beta2": 1.5}):
+            with pytest.raises(binding.PackError) as e:
+                pk.set_optimizer(0, bad)
+            assert e.value.status == binding.PACK_EINVAL
+        with pytest.raises(binding.PackError):
+            pk.read_opt_state(0, 0)            # plain SGD has no state
+        pk.set_optimizer(0, MOMENTUM)
+        with pytest.raises(binding.PackError):
+            pk.read_opt_state(0, 1)            # momentum has one state array
+        assert pk.read_opt_state(0, 0)[1] == 0
+    finally:
+        pk.destroy()
