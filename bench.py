@@ -53,6 +53,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--optimizer", default="sgd", choices=["sgd", "momentum", "adagrad", "adam"],
+                    help="optimiser of every member (the headline workload uses plain SGD)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unpacked", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -81,6 +83,8 @@ def main():
         pk = binding.Pack(w.B, w.in_shape, w.dtype, models, batch, stream=stream)
         for k, blob in enumerate(weights):
             pk.write_weights(k, blob)
+            if args.optimizer != "sgd":
+                pk.set_optimizer(k, {"kind": args.optimizer})
         return pk
 
     # a tiny learning rate keeps hundreds of timed steps finite; arithmetic and traffic per step
@@ -115,15 +119,18 @@ def main():
     assert np.all(np.isfinite(loss)), loss
     launches = pk.num_launches()
     dev_bytes = pk.device_bytes()
+    dom_flops = pk.launch_flops(dom)
     pk.destroy()
 
     dom_name = names[dom]
-    if dom_name == "sgd_update":
-        bpp = 14.0 if w.dtype == wl.BF16 else 12.0     # master r+w, gradient r, (+ bf16 copy w)
+    if dom_name in ("sgd_update", "optimizer_update"):
+        # master r+w, gradient r, each state array r+w, (+ bf16 copy w)
+        bpp = 12.0 + 8.0 * {"sgd": 0, "momentum": 1, "adagrad": 1, "adam": 2}[args.optimizer] + (2.0 if w.dtype == wl.BF16 else 0.0)
         achieved = n_params * bpp / (dom_ms * 1e-3) / 1e9
         traffic = None
         try:
-            if w.name == SGD_TRAFFIC["workload"] and _sgd_kernel_sha() == SGD_TRAFFIC["kernel_sha"]:
+            if (args.optimizer == "sgd" and w.name == SGD_TRAFFIC["workload"]
+                    and _sgd_kernel_sha() == SGD_TRAFFIC["kernel_sha"]):
                 traffic = SGD_TRAFFIC["bytes"]
         except (OSError, ValueError):
             pass
@@ -133,9 +140,9 @@ def main():
     else:
         # a matrix-product launch: its flops are those of the layer slot it executes
         peak = MFMA_PEAK_TFLOPS[w.dtype]
-        share = None
-        roofline = {"kernel": dom_name, "bound": "mfma", "achieved": share, "peak": peak, "unit": "TFLOP/s",
-                    "frac": None, "traffic": None, "avg_ms": dom_ms}
+        achieved = dom_flops / (dom_ms * 1e-3) / 1e12
+        roofline = {"kernel": dom_name, "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                    "frac": achieved / peak, "traffic": None, "avg_ms": dom_ms, "algorithmic_flops": dom_flops}
 
     out = {
         "metric": "packed train samples x models / s",
@@ -146,7 +153,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == wl.BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: K={w.K} packed models, batch {w.B}, input {list(w.in_shape)}, "
-                               f"{n_params} parameters", "K": w.K, "batch": w.B, "launches_per_step": launches,
+                               f"{n_params} parameters, optimiser {args.optimizer}", "K": w.K, "batch": w.B, "launches_per_step": launches,
                    "device_bytes": dev_bytes},
         "tflops": flops / t_pack / 1e12,
         "tflops_frac_of_mfma_peak": flops / t_pack / 1e12 / MFMA_PEAK_TFLOPS[w.dtype],
@@ -184,12 +191,14 @@ def main():
         except Exception:
             threads = len(os.sched_getaffinity(0))
         mode = "weights" if w.dtype == wl.BF16 else "exact"
+        opts = [{"kind": args.optimizer}] * w.K if args.optimizer != "sgd" else None
         blobs = [b.astype(np.float64) for b in w.weights]
         x64 = w.x.astype(np.float64)
         n_steps, t_cpu = 0, 0.0
         while t_cpu < 12.0 and n_steps < 50:
             t0 = time.perf_counter()
-            po.train_pack(w.models, w.in_shape, blobs, w.batch, lr.astype(np.float64), x64, w.labels, 1, mode=mode)
+            po.train_pack(w.models, w.in_shape, blobs, w.batch, lr.astype(np.float64), x64, w.labels, 1, mode=mode,
+                          optimizers=opts)
             t_cpu += time.perf_counter() - t0
             n_steps += 1
         out["cpu_baseline"] = {"value": samples_models * n_steps / t_cpu, "unit": "samples*models/s", "cores": int(threads),

@@ -198,6 +198,10 @@ pack_status pack_profile_start(pack_t* p, int32_t which, int32_t every);
 pack_status pack_profile_stop(pack_t* p, float* ms_sum, int32_t* count);
 pack_status pack_launch_name(const pack_t* p, int32_t i, char* buf, size_t n);
 
+/* Multiply-add work of launch i: 2 * rows * columns * reduction summed over the matrix products
+ * the launch executes (0 for launches that are not matrix products).  flops: host. */
+pack_status pack_launch_flops(const pack_t* p, int32_t i, double* flops);
+
 /* Thread-local text describing the last failing call on this thread ("" if none). */
 const char* pack_last_error(void);
 

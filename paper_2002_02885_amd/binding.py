@@ -21,7 +21,7 @@ STATUS_NAMES = ["PACK_OK", "PACK_EINVAL", "PACK_ENOMEM", "PACK_EDEVICE", "PACK_E
 EXPORTS = ["pack_create", "pack_write_weights", "pack_step", "pack_read_loss", "pack_read_weights",
            "pack_read_pred", "pack_read_grads", "pack_read_logits", "pack_num_params",
            "pack_num_classes", "pack_num_launches", "pack_device_bytes", "pack_last_error", "pack_destroy",
-           "pack_profile_start", "pack_profile_stop", "pack_launch_name",
+           "pack_profile_start", "pack_profile_stop", "pack_launch_name", "pack_launch_flops",
            "pack_set_optimizer", "pack_read_opt_state", "pack_write_opt_state"]
 
 
@@ -85,13 +85,14 @@ def lib() -> C.CDLL:
         l.pack_profile_start.argtypes = [vp, i32, i32]
         l.pack_profile_stop.argtypes = [vp, fp, C.POINTER(C.c_int32)]
         l.pack_launch_name.argtypes = [vp, i32, C.c_char_p, sz]
+        l.pack_launch_flops.argtypes = [vp, i32, C.POINTER(C.c_double)]
         l.pack_set_optimizer.argtypes = [vp, i32, C.POINTER(pack_opt_spec)]
         l.pack_read_opt_state.argtypes = [vp, i32, i32, fp, sz, C.POINTER(C.c_int64)]
         l.pack_write_opt_state.argtypes = [vp, i32, i32, fp, sz, C.c_int64]
         for name in ("pack_create", "pack_write_weights", "pack_step", "pack_read_loss",
                      "pack_read_weights", "pack_read_pred", "pack_read_grads", "pack_read_logits",
                      "pack_profile_start", "pack_profile_stop", "pack_launch_name",
-                     "pack_set_optimizer", "pack_read_opt_state", "pack_write_opt_state"):
+                     "pack_launch_flops", "pack_set_optimizer", "pack_read_opt_state", "pack_write_opt_state"):
             getattr(l, name).restype = C.c_int
         _lib = l
     return _lib
@@ -217,6 +218,11 @@ class Pack:
         buf = C.create_string_buffer(64)
         _check(lib().pack_launch_name(self._h, i, buf, 64))
         return buf.value.decode()
+
+    def launch_flops(self, i: int) -> float:
+        out = C.c_double(0.0)
+        _check(lib().pack_launch_flops(self._h, i, C.byref(out)))
+        return float(out.value)
 
     def destroy(self):
         if self._h:

@@ -88,6 +88,7 @@ struct Launch {
     size_t desc_off = 0;    // byte offset of the problem array in the descriptor buffer
     size_t map_off = 0;     // byte offset of the tile / block map
     int n = 0;              // grid size
+    double flops = 0.0;     // GEMM launches: 2 * rows * columns * reduction, summed over the launch's problems
 };
 
 }  // namespace
@@ -401,6 +402,7 @@ void emit_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, int cfg, const std
     L.desc_off = db.add(probs.data(), probs.size() * sizeof(GemmProb));
     L.map_off = db.add(tiles.data(), tiles.size() * sizeof(TileRef));
     L.n = (int)tiles.size();
+    for (const GemmProb& g : probs) L.flops += 2.0 * g.R * g.Q * g.Kd;
     p->plan.push_back(L);
 }
 
@@ -1112,7 +1114,15 @@ pack_status pack_launch_name(const pack_t* p, int32_t i, char* buf, size_t n) {
     static const char* names[] = {"", "reduce_partials", "softmax_xent", "gap_fwd", "gap_bwd", "shortcut_bwd", "sgd_update", "im2col_shared_input", "transpose_conv_weights"};
     const Launch& L = p->plan[i];
     const char* nm = (L.kind == L_GEMM) ? gemm_names[L.mode] : names[L.kind];
+    if (L.kind == L_SGD && p->any_opt) nm = "optimizer_update";
     std::snprintf(buf, n, "%s", nm);
+    return PACK_OK;
+}
+
+pack_status pack_launch_flops(const pack_t* p, int32_t i, double* flops) {
+    if (!p || !flops) return fail(PACK_EINVAL, "null argument");
+    if (i < 0 || i >= (int32_t)p->plan.size()) return fail(PACK_EINVAL, "launch index out of range");
+    *flops = p->plan[i].flops;
     return PACK_OK;
 }
 

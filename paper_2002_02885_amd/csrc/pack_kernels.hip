@@ -1407,51 +1407,62 @@ __global__ __launch_bounds__(256) void opt_kernel(float* __restrict__ w, const f
     }
     int mdl = lo;
     constexpr int IT = SGD_PER_BLOCK / 1024;
+    // all loads of the block's vectors are requested before any arithmetic
+    long long idx[IT];
+    int mem[IT];
+    f32x4_t wv[IT], gv[IT], av[IT], bv[IT];
 #pragma unroll
     for (int i = 0; i < IT; ++i) {
-        const long long idx = base + i * 1024 + threadIdx.x * 4;
-        if (idx >= n) break;
-        while (mdl < K - 1 && idx >= s_end[mdl]) ++mdl;
-        const OptStatic o = s_par[mdl];
-        const float lr = s_lr[mdl];
-        f32x4_t wv = *reinterpret_cast<const f32x4_t*>(w + idx);
-        const f32x4_t gv = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(g + idx));
+        idx[i] = base + i * 1024 + threadIdx.x * 4;
+        if (idx[i] < n) {
+            while (mdl < K - 1 && idx[i] >= s_end[mdl]) ++mdl;
+            mem[i] = mdl;
+            const int kind = s_par[mdl].kind;
+            wv[i] = *reinterpret_cast<const f32x4_t*>(w + idx[i]);
+            gv[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(g + idx[i]));
+            if (kind != OPT_SGD) av[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(ms + idx[i]));
+            if (kind == OPT_ADAM) bv[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(vs + idx[i]));
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < IT; ++i) {
+        if (idx[i] >= n) continue;
+        const OptStatic o = s_par[mem[i]];
+        const float lr = s_lr[mem[i]];
+        f32x4_t wo = wv[i], a = av[i], b = bv[i];
+        const f32x4_t gg = gv[i];
         if (o.kind == OPT_SGD) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) wv[e] = wv[e] - lr * gv[e];
+            for (int e = 0; e < 4; ++e) wo[e] = wo[e] - lr * gg[e];
         } else if (o.kind == OPT_MOMENTUM) {
-            f32x4_t a = *reinterpret_cast<const f32x4_t*>(ms + idx);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                a[e] = o.mu * a[e] + gv[e];
-                wv[e] = wv[e] - lr * a[e];
+                a[e] = o.mu * a[e] + gg[e];
+                wo[e] = wo[e] - lr * a[e];
             }
-            __builtin_nontemporal_store(a, reinterpret_cast<f32x4_t*>(ms + idx));
+            __builtin_nontemporal_store(a, reinterpret_cast<f32x4_t*>(ms + idx[i]));
         } else if (o.kind == OPT_ADAGRAD) {
-            f32x4_t a = *reinterpret_cast<const f32x4_t*>(ms + idx);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                a[e] = a[e] + gv[e] * gv[e];
-                wv[e] = wv[e] - lr * (gv[e] / sqrtf(a[e]));
+                a[e] = a[e] + gg[e] * gg[e];
+                wo[e] = wo[e] - lr * (gg[e] / sqrtf(a[e]));
             }
-            __builtin_nontemporal_store(a, reinterpret_cast<f32x4_t*>(ms + idx));
+            __builtin_nontemporal_store(a, reinterpret_cast<f32x4_t*>(ms + idx[i]));
         } else {
-            f32x4_t a = *reinterpret_cast<const f32x4_t*>(ms + idx);
-            f32x4_t b = *reinterpret_cast<const f32x4_t*>(vs + idx);
-            const float c1 = s_c1[mdl], c2 = s_c2[mdl];
+            const float c1 = s_c1[mem[i]], c2 = s_c2[mem[i]];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                a[e] = o.beta1 * a[e] + (1.f - o.beta1) * gv[e];
-                b[e] = o.beta2 * b[e] + (1.f - o.beta2) * (gv[e] * gv[e]);
-                wv[e] = wv[e] - lr * ((a[e] * c1) / (sqrtf(b[e] * c2) + o.eps));
+                a[e] = o.beta1 * a[e] + (1.f - o.beta1) * gg[e];
+                b[e] = o.beta2 * b[e] + (1.f - o.beta2) * (gg[e] * gg[e]);
+                wo[e] = wo[e] - lr * ((a[e] * c1) / (sqrtf(b[e] * c2) + o.eps));
             }
-            __builtin_nontemporal_store(a, reinterpret_cast<f32x4_t*>(ms + idx));
-            __builtin_nontemporal_store(b, reinterpret_cast<f32x4_t*>(vs + idx));
+            __builtin_nontemporal_store(a, reinterpret_cast<f32x4_t*>(ms + idx[i]));
+            __builtin_nontemporal_store(b, reinterpret_cast<f32x4_t*>(vs + idx[i]));
         }
-        __builtin_nontemporal_store(wv, reinterpret_cast<f32x4_t*>(w + idx));
+        __builtin_nontemporal_store(wo, reinterpret_cast<f32x4_t*>(w + idx[i]));
         if constexpr (SHADOW) {
             typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
-            __builtin_nontemporal_store(u32x2_t{pack2bf(wv.x, wv.y), pack2bf(wv.z, wv.w)}, reinterpret_cast<u32x2_t*>(shadow + idx));
+            __builtin_nontemporal_store(u32x2_t{pack2bf(wo.x, wo.y), pack2bf(wo.z, wo.w)}, reinterpret_cast<u32x2_t*>(shadow + idx[i]));
         }
     }
 }
