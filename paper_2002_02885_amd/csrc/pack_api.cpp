@@ -409,8 +409,41 @@ void emit_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, int cfg, const std
 void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<GemmProb>& all_probs) {
     // problems whose operands are not aligned for 16-byte loads go to the scalar-gather kernel
     std::vector<GemmProb> probs, scalar;
-    for (const GemmProb& g : all_probs)
-        ((g.flags & F_VEC_A) && (g.flags & F_VEC_B) ? probs : scalar).push_back(g);
+    for (const GemmProb& g : all_probs) {
+        bool vec = (g.flags & F_VEC_A) && (g.flags & F_VEC_B);
+        if (vec) {
+            // The aligned kernels address an operand with 32-bit byte offsets inside a 2 GB window:
+            // larger operands (and weight-gradient convolutions over images narrower than the four
+            // pixels a load block covers) take the scalar kernel.
+            const double esz = p->bf16 ? 2.0 : 4.0;
+            double ea = 0, eb = 0;
+            switch (mode) {
+                case LIN_FWD: ea = (double)g.R * g.lda; eb = (double)g.Q * g.ldb; break;
+                case LIN_DX: ea = (double)g.R * g.lda; eb = (double)g.Kd * g.ldb; break;
+                case LIN_DW: ea = (double)g.Kd * g.lda; eb = (double)g.Kd * g.ldb; break;
+                case CONV_FWD: ea = (double)g.R / (g.Ho * g.Wo) * g.H * g.W * g.Cin + (g.W + 1) * g.Cin; eb = (double)g.Q * g.ldb; break;
+                case CONV_DX: {
+                    const double images = (double)g.R / ((g.flags & F_ROWMAP) ? g.cls_h * g.cls_w : g.H * g.W);
+                    ea = images * g.Ho * g.Wo * g.Cout + (g.Wo + 1) * g.Cout;
+                    eb = (double)g.Q * g.ldb;
+                    break;
+                }
+                default:
+                    ea = (double)g.Kd * g.lda;
+                    eb = (double)g.Kd / (g.Ho * g.Wo) * g.H * g.W * g.Cin + (g.W + 1) * g.Cin;
+                    if (g.Wo < 4) vec = false;
+                    break;
+            }
+            if (ea * esz >= 2.0e9 || eb * esz >= 2.0e9) vec = false;
+        }
+        if (vec) {
+            probs.push_back(g);
+        } else {
+            GemmProb gs = g;
+            gs.flags &= ~(F_VEC_A | F_VEC_B);
+            scalar.push_back(gs);
+        }
+    }
     if (!scalar.empty()) emit_gemm_launch(p, db, mode, GEMM_CFG_SCALAR, scalar);
     if (probs.empty()) return;
     if (std::getenv("PACK_GEMM_ONE_PER_LAUNCH")) {
@@ -680,7 +713,11 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 // long reductions (many pixels) are split over workgroups; the split length
                 // depends on the layer shape only, partial results are summed in split order
                 const int out_tiles = ((nd.out + 127) / 128) * ((q_dim + 127) / 128);
-                const int chunk = (out_tiles == 1) ? 1024 : 8192;   // a one-tile output gets its parallelism from splits
+                int chunk = (out_tiles == 1) ? 1024 : 8192;   // a one-tile output gets its parallelism from splits
+                if (const char* v = std::getenv("PACK_DW_SPLIT_ROWS")) {   // measuring aid: split length of multi-tile outputs
+                    const int c = std::atoi(v);
+                    if (c >= 64 && out_tiles > 1) chunk = c;
+                }
                 int S = std::min(128, std::max(1, (rows + chunk - 1) / chunk));
                 g.ksplit = (int)align_up((size_t)(rows + S - 1) / S, 64);
                 S = (rows + g.ksplit - 1) / g.ksplit;

@@ -446,34 +446,80 @@ __device__ __forceinline__ u32x4_t asm_load16(const void* ptr) {
     return v;
 }
 
-// Per-thread operand fetcher of one tile.  The generic form recomputes addresses from (row, k)
-// for every load.  The gathered convolution operands get a form that decodes each thread's rows
-// (pixel coordinates, border validity of the nine taps) ONCE per tile and then needs only an
-// add and a bit test per load; it relies on the alignment the planner checks before it marks a
-// convolution problem as vectorisable: a chunk of BK reduction indices never straddles a tap
-// (forward: Cin % BK == 0, input gradient: Cout % BK == 0) or an image (weight gradient:
-// Ho*Wo % BK == 0 with Wo a power of two), and tensors have fewer than 2^31 elements.
+// ------------------------------------------------------------------------------------------------
+// Operand fetch of the aligned kernels: raw buffer loads.  Each operand gets a buffer descriptor
+// (base address, 2 GB of records); a thread keeps one 32-bit byte offset per load that is fixed
+// for the whole tile, the part that changes per chunk is wave-uniform and travels in the scalar
+// offset of the instruction, and an element that does not exist is addressed beyond the records,
+// which the hardware answers with zeros without touching memory.  So a load costs no vector
+// arithmetic at all unless its validity changes from chunk to chunk (border taps of the gathered
+// convolution operands, a reduction that ends inside a chunk).  The planner only marks a problem
+// as aligned when every operand spans less than 2 GB, so that offset + scalar offset never wraps.
+// The loads are assembly statements for the same reason as before: their completion is awaited
+// by hand (wait_stage), not by the compiler.
+// ------------------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(4))) int i32x4_t;
+constexpr unsigned BUF_RECORDS = 0x80000000u;   // bytes a descriptor covers
+constexpr unsigned BUF_POISON = 0x80000000u;    // offset of an element that does not exist
+
+__device__ __forceinline__ i32x4_t make_rsrc(const void* base, long long margin_bytes) {
+    const unsigned long long a = (unsigned long long)base - (unsigned long long)margin_bytes;
+    i32x4_t r;
+    r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
+    r.y = __builtin_amdgcn_readfirstlane((int)(unsigned)(a >> 32));   // stride 0: raw buffer
+    r.z = (int)BUF_RECORDS;
+    r.w = 0x00020000;                                                 // 32-bit data format
+    return r;
+}
+
+__device__ __forceinline__ u32x4_t buf_load16(const i32x4_t rsrc, unsigned voff, unsigned soff) {
+    u32x4_t v;
+    // the scalar operands are wave-uniform by construction; say so, since values that went through
+    // vector arithmetic (an integer division) would otherwise be handed over in vector registers
+    const unsigned so = __builtin_amdgcn_readfirstlane(soff);
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(v) : "v"(voff), "s"(rsrc), "s"(so) : "memory");
+    return v;
+}
+
+// Per-thread operand fetcher of one tile.  VEC kernels use the buffer form above: everything that
+// depends on the thread's rows (pixel coordinates, border validity of the nine taps) is decoded
+// ONCE per tile into the per-load offsets; it relies on the alignment the planner checks before
+// it marks a convolution problem as vectorisable: a chunk of BK reduction indices never straddles
+// a tap (forward: Cin % BK == 0, input gradient: Cout % BK == 0) or an image (weight gradient:
+// Ho*Wo % BK == 0 with Wo a power of two).  The scalar kernels recompute addresses from (row, k)
+// for every element (fetch_tile).
 template <int MODE, typename T, bool IS_A, int BR, int BK, bool VEC>
 struct Fetcher {
     typedef TileGeom<T, BR, BK> G;
     static constexpr bool KC = IS_A ? OperandLayout<MODE>::A_KC : OperandLayout<MODE>::B_KC;
-    static constexpr bool ASM = ((PACK_ASM_MODES >> MODE) & 1) != 0;
-    static constexpr bool GATHER_KC = VEC && ASM && IS_A && (MODE == CONV_FWD || MODE == CONV_DX);
-    static constexpr bool WEIGHT_KC = VEC && ASM && !IS_A && MODE == CONV_DX;
-    static constexpr bool GATHER_RC = VEC && ASM && !IS_A && MODE == CONV_DW;
-    static constexpr int NS = (GATHER_KC || WEIGHT_KC) ? G::KC_SLOTS : (GATHER_RC ? G::RC_PER_THREAD : 1);
+    static constexpr bool BUF = VEC && (((PACK_ASM_MODES >> MODE) & 1) != 0);
+    static constexpr bool GATHER_KC = BUF && IS_A && (MODE == CONV_FWD || MODE == CONV_DX);
+    static constexpr bool WEIGHT_KC = BUF && !IS_A && (MODE == CONV_DX || MODE == CONV_FWD);
+    static constexpr bool GATHER_RC = BUF && !IS_A && MODE == CONV_DW;
+    static constexpr bool PLAIN_KC = BUF && KC && !GATHER_KC && !WEIGHT_KC;
+    static constexpr bool PLAIN_RC = BUF && !KC && !GATHER_RC;
+    static constexpr int NL = KC ? G::KC_SLOTS : 4 * G::RC_PER_THREAD;   // loads per thread and chunk
+    static constexpr int NB = KC ? G::KC_SLOTS : G::RC_PER_THREAD;       // rows (KC) or blocks (RC) per thread
+    static constexpr int ESZ = (int)sizeof(T);
 
     int row0;
-    int base[NS];        // element offset of the thread's row / block, without the per-chunk part
-    unsigned mask[NS];   // GATHER_KC: bit t = tap t reads inside the image; others: bit 0 = live
-    int aux0[NS], aux1[NS], aux2[NS];   // GATHER_RC: u - 1, v - 1, first reduction index of the block
+    i32x4_t rsrc;
+    unsigned voff[BUF ? NL : 1];    // byte offset of each load, BUF_POISON when the row does not exist
+    unsigned mask[BUF ? NB : 1];    // GATHER_KC: bit t = tap t reads inside the image
+    int kpos[BUF ? NB : 1];         // PLAIN_KC: first reduction index of the slot; RC forms: 4 * kq
+    int du[GATHER_RC ? NB : 1], dv[GATHER_RC ? NB : 1];   // GATHER_RC: tap offsets u - 1, v - 1
 
     __device__ __forceinline__ void init(const GemmProb& p, int row0_) {
         row0 = row0_;
         const int tid = threadIdx.x;
+        const void* src = IS_A ? p.A : p.B;
         if constexpr (GATHER_KC) {
+            // margin: the first tap of a border pixel lies one row and one pixel before the tensor
+            const int pw = (MODE == CONV_FWD) ? p.W : p.Wo, pc = (MODE == CONV_FWD) ? p.Cin : p.Cout;
+            const int margin = (pw + 1) * pc;
+            rsrc = make_rsrc(src, (long long)margin * ESZ);
 #pragma unroll
-            for (int s = 0; s < NS; ++s) {
+            for (int s = 0; s < NB; ++s) {
                 const int vid = tid + 256 * s;
                 const int r = row0 + vid / G::VPR;
                 const int kv = (vid % G::VPR) * G::V;
@@ -482,23 +528,28 @@ struct Fetcher {
                 // tap (u, v) is inside the image iff row condition u and column condition v hold:
                 // three bits each, combined into the nine-bit mask
                 unsigned rb = 0, cb = 0;
+                int base;
                 if constexpr (MODE == CONV_FWD) {
                     int b, i, j;
                     decode_row(p, r, b, i, j);
                     const int y0 = p.stride * i - 1, x0 = p.stride * j - 1;
-                    base[s] = ((b * p.H + y0) * p.W + x0) * p.Cin + kv;
+                    base = ((b * p.H + y0) * p.W + x0) * p.Cin + kv;
 #pragma unroll
                     for (int t = 0; t < 3; ++t) {
                         if ((unsigned)(y0 + t) < (unsigned)p.H) rb |= 1u << t;
                         if ((unsigned)(x0 + t) < (unsigned)p.W) cb |= 1u << t;
                     }
-                } else {   // CONV_DX: rows are input pixels, the gather reads dz
+                } else {   // CONV_DX: rows are input pixels, the gather reads dz; the thread's
+                           // offset is that of the LAST tap (2, 2) (or the class's last), so that
+                           // the per-chunk part is never negative
                     int b, y, x;
                     if (p.flags & F_ROWMAP) class_pixel(p, r, b, y, x);
                     else decode_row(p, r, b, y, x);
                     const int yy = y + 1, xx = x + 1;
                     const int sh = (p.stride == 2) ? 1 : 0;
-                    base[s] = ((b * p.Ho + (yy >> sh)) * p.Wo + (xx >> sh)) * p.Cout + kv;
+                    const int um = (p.flags & F_ROWMAP) ? (p.cls_py ? 1 : 2) : 2;
+                    const int vm = (p.flags & F_ROWMAP) ? (p.cls_px ? 1 : 2) : 2;
+                    base = ((b * p.Ho + ((yy - um) >> sh)) * p.Wo + ((xx - vm) >> sh)) * p.Cout + kv;
 #pragma unroll
                     for (int t = 0; t < 3; ++t) {
                         const int ty = yy - t, tx = xx - t;
@@ -508,83 +559,140 @@ struct Fetcher {
                 }
                 m = ((rb & 1u) ? cb : 0u) | ((rb & 2u) ? cb << 3 : 0u) | ((rb & 4u) ? cb << 6 : 0u);
                 mask[s] = live ? m : 0u;
+                voff[s] = (unsigned)(base + margin) * ESZ;
             }
-        } else if constexpr (WEIGHT_KC) {
+        } else if constexpr (WEIGHT_KC || PLAIN_KC) {
+            rsrc = make_rsrc(src, 0);
+            const int ld = IS_A ? p.lda : p.ldb;
+            const int rows = IS_A ? p.R : p.Q;
 #pragma unroll
-            for (int s = 0; s < NS; ++s) {
+            for (int s = 0; s < NB; ++s) {
                 const int vid = tid + 256 * s;
-                const int q = row0 + vid / G::VPR;
-                base[s] = q * p.ldb + (vid % G::VPR) * G::V;
-                mask[s] = ((vid < G::NVEC) && (q < p.Q)) ? 1u : 0u;
+                const int r = row0 + vid / G::VPR;
+                kpos[s] = (vid % G::VPR) * G::V;
+                const bool live = (vid < G::NVEC) && (r < rows);
+                voff[s] = live ? (unsigned)(r * ld + kpos[s]) * ESZ : BUF_POISON;
+            }
+        } else if constexpr (PLAIN_RC) {
+            rsrc = make_rsrc(src, 0);
+            const int ld = IS_A ? p.lda : p.ldb;
+            const int rows = IS_A ? p.R : p.Q;
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                const int b = tid + 256 * j;
+                int kq, rv;
+                rc_block_coords<G>(b, kq, rv);
+                const int r = row0 + rv * G::V;
+                kpos[j] = kq * 4;
+                const bool live = (b < G::RC_BLOCKS) && (r < rows);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    voff[4 * j + e] = live ? (unsigned)((kq * 4 + e) * ld + r) * ESZ : BUF_POISON;
             }
         } else if constexpr (GATHER_RC) {
+            const int margin = (p.W + 1) * p.Cin;
+            rsrc = make_rsrc(src, (long long)margin * ESZ);
 #pragma unroll
-            for (int j = 0; j < NS; ++j) {
+            for (int j = 0; j < NB; ++j) {
                 const int b = tid + 256 * j;
                 int kq, rv;
                 rc_block_coords<G>(b, kq, rv);
                 const int q = row0 + rv * G::V;
                 const int tap = q / p.Cin, c = q - tap * p.Cin;
-                aux0[j] = tap / 3 - 1;
-                aux1[j] = tap % 3 - 1;
-                aux2[j] = kq * 4;
-                base[j] = (aux0[j] * p.W + aux1[j]) * p.Cin + c;
-                mask[j] = ((b < G::RC_BLOCKS) && (q < p.Q)) ? 1u : 0u;
+                du[j] = tap / 3 - 1;
+                dv[j] = tap % 3 - 1;
+                kpos[j] = kq * 4;
+                const bool live = (b < G::RC_BLOCKS) && (q < p.Q);
+                // fixed part: channel and tap displacement; the pixel part is added per chunk
+                voff[4 * j] = live ? (unsigned)((du[j] * p.W + dv[j]) * p.Cin + c + margin) * ESZ : BUF_POISON;
             }
         }
     }
 
     __device__ __forceinline__ void fetch(const GemmProb& p, int k0, int kend, u32x4_t (&regs)[G::NREG]) const {
-        const T* src = (const T*)(IS_A ? p.A : p.B);
         if constexpr (GATHER_KC) {
             // the whole chunk lies in one tap: its offset is the same for every thread
             const int span = (MODE == CONV_FWD) ? p.Cin : p.Cout;
             const int tc = k0 / span, c0 = k0 - tc * span;
-            const int tap = (MODE == CONV_DX && (p.flags & F_ROWMAP)) ? class_tap(p, tc) : tc;
-            const int u = tap / 3, v = tap - 3 * u;
-            int toff;
+            int tap, toff;
             if constexpr (MODE == CONV_FWD) {
+                tap = tc;
+                const int u = tap / 3, v = tap - 3 * u;
                 toff = (u * p.W + v) * p.Cin + c0;
             } else {
+                const bool cls = (p.flags & F_ROWMAP) != 0;
+                tap = cls ? class_tap(p, tc) : tc;
+                const int u = tap / 3, v = tap - 3 * u;
                 const int sh = (p.stride == 2) ? 1 : 0;
-                toff = c0 - ((u >> sh) * p.Wo + (v >> sh)) * p.Cout;
+                const int um = cls ? (p.cls_py ? 1 : 2) : 2, vm = cls ? (p.cls_px ? 1 : 2) : 2;
+                toff = (((um - u) >> sh) * p.Wo + ((vm - v) >> sh)) * p.Cout + c0;
             }
-            const bool in_range = k0 < kend;
+            i32x4_t r = rsrc;
+            r.z = __builtin_amdgcn_readfirstlane((k0 < kend) ? (int)BUF_RECORDS : 0);   // a chunk beyond the reduction reads zeros
+            const unsigned soff = (unsigned)toff * ESZ;
 #pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                const bool ok = in_range && ((mask[s] >> tap) & 1u);
-                const void* ptr = ok ? (const void*)(src + (base[s] + toff)) : p.zeros;
-                regs[s] = asm_load16(ptr);
+            for (int s = 0; s < NB; ++s) {
+                const unsigned o = ((mask[s] >> tap) & 1u) ? voff[s] : BUF_POISON;
+                regs[s] = buf_load16(r, o, soff);
             }
         } else if constexpr (WEIGHT_KC) {
-            // transposed weights [Cin][9][Cout]: the chunk lies in one tap
-            const int tc = k0 / p.Cout, o0 = k0 - tc * p.Cout;
-            const int tap = (p.flags & F_ROWMAP) ? class_tap(p, tc) : tc;
-            const int toff = tap * p.Cout + o0;
-            const bool in_range = k0 < kend;
+            // forward: W[Cout][9*Cin], the chunk starts at k0; input gradient: transposed weights
+            // [Cin][9][Cout], the chunk lies in one tap (class problems skip taps)
+            int koff = k0;
+            if constexpr (MODE == CONV_DX) {
+                if (p.flags & F_ROWMAP) {
+                    const int tc = k0 / p.Cout;
+                    koff = class_tap(p, tc) * p.Cout + (k0 - tc * p.Cout);
+                }
+            }
+            i32x4_t r = rsrc;
+            r.z = __builtin_amdgcn_readfirstlane((k0 < kend) ? (int)BUF_RECORDS : 0);
+            const unsigned soff = (unsigned)koff * ESZ;
 #pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                const bool ok = in_range && mask[s];
-                const void* ptr = ok ? (const void*)(src + (base[s] + toff)) : p.zeros;
-                regs[s] = asm_load16(ptr);
+            for (int s = 0; s < NB; ++s) regs[s] = buf_load16(r, voff[s], soff);
+        } else if constexpr (PLAIN_KC) {
+            const int rem = kend - k0;   // reduction indices left; the last chunk may end inside
+            const unsigned soff = (unsigned)max(k0, 0) * ESZ;
+#pragma unroll
+            for (int s = 0; s < NB; ++s) {
+                const unsigned o = (kpos[s] < rem) ? voff[s] : BUF_POISON;
+                regs[s] = buf_load16(rsrc, o, soff);
+            }
+        } else if constexpr (PLAIN_RC) {
+            const int ld = IS_A ? p.lda : p.ldb;
+            const int rem = kend - k0;
+            i32x4_t r = rsrc;
+            r.z = __builtin_amdgcn_readfirstlane((rem > 0) ? (int)BUF_RECORDS : 0);
+            const unsigned soff = (rem > 0) ? (unsigned)k0 * (unsigned)ld * ESZ : 0u;
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const unsigned o = (kpos[j] + e < rem) ? voff[4 * j + e] : BUF_POISON;
+                    regs[4 * j + e] = buf_load16(r, o, soff);
+                }
             }
         } else if constexpr (GATHER_RC) {
-            // reduction index = output pixel; the chunk lies inside one image
+            // reduction index = output pixel; the chunk lies inside one image, and the four
+            // pixels of a block lie in one image row (Wo is a power of two >= 4)
             const int hw = p.Ho * p.Wo;
             const int img = k0 / hw, p0 = k0 - img * hw;
             const int lw = 31 - __builtin_clz(p.Wo);
-            const int ibase = img * p.H * p.W * p.Cin;
+            i32x4_t r = rsrc;
+            r.z = __builtin_amdgcn_readfirstlane((k0 < kend) ? (int)BUF_RECORDS : 0);
+            const unsigned soff = (k0 < kend) ? (unsigned)(img * p.H * p.W * p.Cin) * ESZ : 0u;
+            const int xstep = p.stride * p.Cin * ESZ;
 #pragma unroll
-            for (int j = 0; j < NS; ++j) {
+            for (int j = 0; j < NB; ++j) {
+                const int pidx = p0 + kpos[j];
+                const int i = pidx >> lw, jx = pidx & (p.Wo - 1);
+                const int yb = p.stride * i, xb = p.stride * jx;
+                const bool rowok = (voff[4 * j] != BUF_POISON) && ((unsigned)(yb + du[j]) < (unsigned)p.H);
+                const unsigned pix = voff[4 * j] + (unsigned)((yb * p.W + xb) * p.Cin) * ESZ;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const int pidx = p0 + aux2[j] + e;
-                    const int i = pidx >> lw, jx = pidx & (p.Wo - 1);
-                    const int yb = p.stride * i, xb = p.stride * jx;
-                    const bool ok = mask[j] && (k0 + aux2[j] + e < kend) &&
-                                    ((unsigned)(yb + aux0[j]) < (unsigned)p.H) && ((unsigned)(xb + aux1[j]) < (unsigned)p.W);
-                    const void* ptr = ok ? (const void*)(src + (ibase + (yb * p.W + xb) * p.Cin + base[j])) : p.zeros;
-                    regs[4 * j + e] = asm_load16(ptr);
+                    const bool ok = rowok && ((unsigned)(xb + e * p.stride + dv[j]) < (unsigned)p.W);
+                    regs[4 * j + e] = buf_load16(r, ok ? pix + e * xstep : BUF_POISON, soff);
                 }
             }
         } else {
