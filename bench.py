@@ -28,7 +28,7 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # HBM bytes per launch of the update kernel on workload c2 from hardware counters (FETCH_SIZE and
 # WRITE_SIZE, each scaled by a copy kernel of known size; profiles/c2_sgd_update_hbm_counters.txt),
 # valid only for the kernel source it was measured on (hash of the kernel's text).
-SGD_TRAFFIC = {"workload": "c2", "bytes": 471.2e6, "kernel_sha": "ea5903734b85f3fa"}
+SGD_TRAFFIC = {"workload": "c2", "bytes": 471.2e6, "kernel_sha": "ec085e8cf50b69f2"}
 
 
 def _sgd_kernel_sha():
