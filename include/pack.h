@@ -12,8 +12,13 @@
  * back-propagation are exactly those of the member trained alone on a dedicated device.
  *
  * One `pack_t` is one packed model resident on one GPU: the paper's `pack` + `load`.
- * `pack_read_weights` + `pack_destroy` are the paper's `free` (retrieve the checkpoint, release
- * the memory).  Plain SGD has no optimiser state, so the checkpoint is the weights.
+ * `pack_read_weights` (+ `pack_read_opt_state`) followed by `pack_free` or `pack_destroy` is the
+ * paper's `free` (retrieve the checkpoint, release the memory).  Members can leave and join a live
+ * pack (`pack_free`, `pack_load`; Section 3.3), and an epoch over members with different batch
+ * sizes is driven by `pack_schedule_*`, `pack_gather_batch` and `pack_set_batch` (Section 3.2).
+ * A pack has K slots; a slot holds a member or is vacant.  Calls that name a vacant slot fail with
+ * PACK_EINVAL; arrays indexed by member (lr, loss, batch) have one entry per slot and the entries
+ * of vacant slots are ignored (read as 0).
  *
  * Conventions
  *   - All functions return a pack_status; nothing is thrown across the ABI.  A failing call
@@ -53,7 +58,8 @@ typedef enum {
     PACK_ENOMEM = 2,   /* device or host allocation failed (the out-of-memory case of Section 4.2) */
     PACK_EDEVICE = 3,  /* a HIP runtime call failed */
     PACK_ESHAPE = 4,   /* layer list is not a classifier this library can run (see pack_create) */
-    PACK_ELABEL = 5    /* a label outside [0, C_k) was seen since the last pack_read_loss */
+    PACK_ELABEL = 5,   /* a label outside [0, C_k) was seen since the last pack_read_loss */
+    PACK_EINDEX = 6    /* pack_gather_batch met a sample index outside the dataset since the last pack_read_loss */
 } pack_status;
 
 typedef enum {
@@ -126,6 +132,71 @@ typedef struct {
 pack_status pack_create(const pack_input_spec* input, const pack_model_spec* models, int32_t K,
                         uint64_t seed, void* hip_stream, pack_t** out);
 
+/* free of ONE member of a live pack (Section 2.2 `free`; Section 3.3, Figure 3: the member that has
+ * taken all its steps is freed while the others keep training).  The caller retrieves the
+ * checkpoint first (pack_read_weights, pack_read_opt_state).  Slot k becomes vacant and the member's
+ * device memory is released.  Weights, optimiser state and step counters of every other member are
+ * carried over on the device bit for bit, so their training continues exactly as if nothing had
+ * happened.  Waits for the stream.  While the call runs the pack holds its old and new buffers at
+ * once.  Per-launch timing is switched off and launch indices change.
+ * Errors: PACK_EINVAL (k out of range or vacant), PACK_ENOMEM, PACK_EDEVICE; the pack is unchanged then. */
+pack_status pack_free(pack_t* p, int32_t k);
+
+/* load of one more member into a live pack (Section 2.2 `load`; Section 3.3: "a new model can be
+ * loaded and packed with the incomplete models").  The member takes the lowest vacant slot, or a new
+ * slot at the end (the number of slots grows by one); *k_out receives the slot.  Its weights are
+ * seeded as in pack_create from (seed, slot) (use pack_write_weights / pack_write_opt_state to load a
+ * checkpoint), its optimiser is PACK_OPT_SGD.  Other members as in pack_free.
+ * Errors: PACK_EINVAL (null, batch outside [1, B], PACK_MAX_MODELS slots in use), PACK_ESHAPE,
+ * PACK_ENOMEM, PACK_EDEVICE; the pack is unchanged then. */
+pack_status pack_load(pack_t* p, const pack_model_spec* model, uint64_t seed, int32_t* k_out);
+
+/* Re-slice the shared batch (Section 3.2): from now on the shared batch has B rows and member k
+ * trains on rows [0, batch[k]).  batch: host int32 [pack_num_slots(p)].  Used when the member with
+ * the largest batch has left (the next largest batch becomes the shared batch) and for the short
+ * last batch of a phase.  Member state is carried over as in pack_free; a call that changes nothing
+ * returns at once.  Errors: PACK_EINVAL (null, B < 1, batch[k] outside [1, B]), PACK_ENOMEM, PACK_EDEVICE. */
+pack_status pack_set_batch(pack_t* p, int32_t B, const int32_t* batch);
+
+/* Number of slots K (members + vacant slots); 0 if p is null. */
+int32_t pack_num_slots(const pack_t* p);
+
+/* b_k of member k; 0 if the slot is vacant or out of range. */
+int32_t pack_member_batch(const pack_t* p, int32_t k);
+
+/* Epoch schedule for members with different batch sizes (Section 3.2, "we track the progress of each
+ * model individually"; step counts as in Section 3.3).  Host logic, no GPU involved.  The shared
+ * batch of a step has the size of the largest batch among the members that have not yet used the
+ * whole dataset and is cut, in dataset order, from the samples THAT member has not used; every other
+ * unfinished member trains on the leading rows.  When the member with the largest batch has used
+ * everything it leaves and the next largest batch leads.  Every member sees every sample exactly
+ * once.  A phase whose samples do not divide by the batch size ends with one short shared batch.
+ * pack_schedule_create: n_samples >= 1; batch: host int32 [K], each >= 1.
+ * pack_schedule_next: writes the sample indices of the next shared batch into idx_host (host int64,
+ *   room for max(batch) entries), their number into *rows, the number of leading rows each member
+ *   trains on into rows_k (host int32 [K]; 0 = the member has finished) and, if lead is not null, the
+ *   member whose batch size rules the phase.  After the last step of the epoch it returns PACK_OK
+ *   with *rows = 0.
+ * pack_schedule_used: samples each member has trained on so far (host int64 [K]).
+ * Errors: PACK_EINVAL, PACK_ENOMEM. */
+typedef struct pack_schedule pack_schedule_t;
+pack_status pack_schedule_create(int64_t n_samples, const int32_t* batch, int32_t K, pack_schedule_t** out);
+pack_status pack_schedule_next(pack_schedule_t* s, int64_t* idx_host, int32_t* rows, int32_t* rows_k, int32_t* lead);
+pack_status pack_schedule_used(const pack_schedule_t* s, int64_t* used_host);
+void pack_schedule_destroy(pack_schedule_t* s);
+
+/* Assemble a shared batch from a dataset resident on the device (Section 3.2: the shared batches of
+ * later phases are cut from the samples not yet used, which are not contiguous):
+ * x_out[r] = data[idx[r]] and labels_out[r] = labels_all[idx[r]] for r < rows.  All pointers are
+ * device memory; data: [n_samples, H, W, C] of the pack's dtype; labels_all: int32 [n_samples];
+ * idx: int64 [rows]; x_out: room for B rows (16-byte aligned, as pack_step requires); labels_out:
+ * int32 [B].  rows in [0, B]; rows beyond `rows` are left as they are.  Enqueues one kernel on the
+ * pack's stream.  An index outside [0, n_samples) gives a row of zeros with label -1 (ignored by the
+ * loss) and makes the next pack_read_loss return PACK_EINDEX.
+ * Errors: PACK_EINVAL (null, rows outside [0, B], misaligned pointer), PACK_EDEVICE. */
+pack_status pack_gather_batch(pack_t* p, const void* data_dev, const int32_t* labels_all_dev, int64_t n_samples,
+                              const int64_t* idx_dev, int32_t rows, void* x_out_dev, int32_t* labels_out_dev);
+
 /* load a member's weights (Section 2.2 `load`): host_src holds pack_num_params(p, k) floats in
  * the blob layout above.  For PACK_BF16 the bf16 operand copy is refreshed too.
  * Errors: PACK_EINVAL (k out of range, n_floats mismatch), PACK_EDEVICE. */
@@ -157,7 +228,8 @@ pack_status pack_write_opt_state(pack_t* p, int32_t k, int32_t slot, const float
 /* Loss of each member at the last step, evaluated at that step's pre-update weights.
  * host_dst: float [K].  Waits for the stream.  Returns PACK_ELABEL (and still fills host_dst)
  * if any step since the previous pack_read_loss met a label outside [0, C_k); such rows
- * contribute nothing to loss or gradients and index no memory. */
+ * contribute nothing to loss or gradients and index no memory.  Returns PACK_EINDEX (likewise)
+ * if pack_gather_batch met a sample index outside the dataset. */
 pack_status pack_read_loss(pack_t* p, float* host_dst);
 
 /* free's checkpoint (Section 2.2): the member's current fp32 weights in the blob layout. */

@@ -11,18 +11,21 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("PACK_LIB", os.path.join(_HERE, "libpack.so"))
 
-PACK_OK, PACK_EINVAL, PACK_ENOMEM, PACK_EDEVICE, PACK_ESHAPE, PACK_ELABEL = range(6)
+PACK_OK, PACK_EINVAL, PACK_ENOMEM, PACK_EDEVICE, PACK_ESHAPE, PACK_ELABEL, PACK_EINDEX = range(7)
 PACK_F32, PACK_BF16 = 0, 1
 OPS = {"linear": 0, "conv3x3": 1, "relu": 2, "gap": 3, "res_begin": 4, "res_end": 5,
        "sigmoid": 6, "tanh": 7, "leaky_relu": 8}
 OPT_KINDS = {"sgd": 0, "momentum": 1, "adagrad": 2, "adam": 3}
-STATUS_NAMES = ["PACK_OK", "PACK_EINVAL", "PACK_ENOMEM", "PACK_EDEVICE", "PACK_ESHAPE", "PACK_ELABEL"]
+STATUS_NAMES = ["PACK_OK", "PACK_EINVAL", "PACK_ENOMEM", "PACK_EDEVICE", "PACK_ESHAPE", "PACK_ELABEL", "PACK_EINDEX"]
 
 EXPORTS = ["pack_create", "pack_write_weights", "pack_step", "pack_read_loss", "pack_read_weights",
            "pack_read_pred", "pack_read_grads", "pack_read_logits", "pack_num_params",
            "pack_num_classes", "pack_num_launches", "pack_device_bytes", "pack_last_error", "pack_destroy",
            "pack_profile_start", "pack_profile_stop", "pack_launch_name", "pack_launch_flops",
-           "pack_set_optimizer", "pack_read_opt_state", "pack_write_opt_state"]
+           "pack_set_optimizer", "pack_read_opt_state", "pack_write_opt_state",
+           "pack_free", "pack_load", "pack_set_batch", "pack_num_slots", "pack_member_batch",
+           "pack_schedule_create", "pack_schedule_next", "pack_schedule_used", "pack_schedule_destroy",
+           "pack_gather_batch"]
 
 
 class pack_opt_spec(C.Structure):
@@ -45,7 +48,7 @@ class pack_input_spec(C.Structure):
 
 class PackError(RuntimeError):
     def __init__(self, status: int, text: str):
-        super().__init__(f"{STATUS_NAMES[status] if 0 <= status < 6 else status}: {text}")
+        super().__init__(f"{STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else status}: {text}")
         self.status = status
 
 
@@ -89,6 +92,23 @@ def lib() -> C.CDLL:
         l.pack_set_optimizer.argtypes = [vp, i32, C.POINTER(pack_opt_spec)]
         l.pack_read_opt_state.argtypes = [vp, i32, i32, fp, sz, C.POINTER(C.c_int64)]
         l.pack_write_opt_state.argtypes = [vp, i32, i32, fp, sz, C.c_int64]
+        i64 = C.c_int64
+        l.pack_free.argtypes = [vp, i32]
+        l.pack_load.argtypes = [vp, C.POINTER(pack_model_spec), u64, C.POINTER(i32)]
+        l.pack_set_batch.argtypes = [vp, i32, C.POINTER(i32)]
+        l.pack_num_slots.argtypes = [vp]
+        l.pack_num_slots.restype = i32
+        l.pack_member_batch.argtypes = [vp, i32]
+        l.pack_member_batch.restype = i32
+        l.pack_schedule_create.argtypes = [i64, C.POINTER(i32), i32, C.POINTER(vp)]
+        l.pack_schedule_next.argtypes = [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
+        l.pack_schedule_used.argtypes = [vp, C.POINTER(i64)]
+        l.pack_schedule_destroy.argtypes = [vp]
+        l.pack_schedule_destroy.restype = None
+        l.pack_gather_batch.argtypes = [vp, vp, vp, i64, vp, i32, vp, vp]
+        for name in ("pack_free", "pack_load", "pack_set_batch", "pack_schedule_create", "pack_schedule_next",
+                     "pack_schedule_used", "pack_gather_batch"):
+            getattr(l, name).restype = C.c_int
         for name in ("pack_create", "pack_write_weights", "pack_step", "pack_read_loss",
                      "pack_read_weights", "pack_read_pred", "pack_read_grads", "pack_read_logits",
                      "pack_profile_start", "pack_profile_stop", "pack_launch_name",
@@ -108,6 +128,15 @@ def _fptr(a: np.ndarray):
     return a.ctypes.data_as(C.POINTER(C.c_float))
 
 
+def _layer_array(layers):
+    arr = (pack_layer * max(len(layers), 1))()
+    for i, op in enumerate(layers):
+        arr[i].op = OPS[op[0]] if op[0] in OPS else int(op[0])
+        arr[i].out = int(op[1]) if len(op) > 1 else 0
+        arr[i].stride = int(op[2]) if len(op) > 2 else 1
+    return arr
+
+
 class Pack:
     """One packed model on the current GPU.  `models` is a list of layer lists of tuples
     ("linear", out) / ("conv3x3", out, stride) / ("relu",) / ("sigmoid",) / ("tanh",) /
@@ -123,11 +152,7 @@ class Pack:
         keep = []
         specs = (pack_model_spec * max(self.K, 1))()
         for k, layers in enumerate(models):
-            arr = (pack_layer * max(len(layers), 1))()
-            for i, op in enumerate(layers):
-                arr[i].op = OPS[op[0]] if op[0] in OPS else int(op[0])
-                arr[i].out = int(op[1]) if len(op) > 1 else 0
-                arr[i].stride = int(op[2]) if len(op) > 2 else 1
+            arr = _layer_array(layers)
             keep.append(arr)
             specs[k].layers = arr
             specs[k].n_layers = len(layers)
@@ -146,6 +171,38 @@ class Pack:
         lr = np.ascontiguousarray(lr, dtype=np.float32)
         assert lr.size == self.K
         _check(lib().pack_step(self._h, C.c_void_p(x_ptr), C.c_void_p(labels_ptr), _fptr(lr)))
+
+    def _refresh_slots(self):
+        self.K = int(lib().pack_num_slots(self._h))
+        self.batch = [int(lib().pack_member_batch(self._h, k)) for k in range(self.K)]
+
+    def free(self, k: int):
+        """Member k leaves the pack (read its checkpoint first); its slot becomes vacant."""
+        _check(lib().pack_free(self._h, k))
+        self._refresh_slots()
+
+    def load(self, layers: list, batch: int, seed: int = 0) -> int:
+        """A new member joins the pack; returns its slot."""
+        arr = _layer_array(layers)
+        spec = pack_model_spec(arr, len(layers), int(batch))
+        k = C.c_int32(-1)
+        _check(lib().pack_load(self._h, C.byref(spec), seed, C.byref(k)))
+        self._refresh_slots()
+        return int(k.value)
+
+    def set_batch(self, B: int, batch: Sequence[int]):
+        """The shared batch has B rows from now on; batch[k] per slot (entries of vacant slots ignored)."""
+        arr = (C.c_int32 * max(self.K, 1))(*[int(b) for b in batch])
+        assert len(batch) == self.K
+        _check(lib().pack_set_batch(self._h, int(B), arr))
+        self.B = int(B)
+        self._refresh_slots()
+
+    def gather_batch(self, data_ptr: int, labels_all_ptr: int, n_samples: int, idx_ptr: int, rows: int,
+                     x_out_ptr: int, labels_out_ptr: int):
+        """All pointers are raw device addresses; idx is int64 [rows]."""
+        _check(lib().pack_gather_batch(self._h, C.c_void_p(data_ptr), C.c_void_p(labels_all_ptr), int(n_samples),
+                                       C.c_void_p(idx_ptr), int(rows), C.c_void_p(x_out_ptr), C.c_void_p(labels_out_ptr)))
 
     def set_optimizer(self, k: int, opt: dict):
         """`opt` as in the oracle: {"kind": "sgd" | "momentum" | "adagrad" | "adam", and optionally
@@ -167,7 +224,7 @@ class Pack:
 
     def read_loss(self, allow_label_error: bool = False) -> np.ndarray:
         out = np.empty(self.K, dtype=np.float32)
-        st = _check(lib().pack_read_loss(self._h, _fptr(out)), allow=(PACK_ELABEL,) if allow_label_error else ())
+        st = _check(lib().pack_read_loss(self._h, _fptr(out)), allow=(PACK_ELABEL, PACK_EINDEX) if allow_label_error else ())
         self.last_status = st
         return out
 
@@ -227,6 +284,44 @@ class Pack:
     def destroy(self):
         if self._h:
             lib().pack_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+class Schedule:
+    """Epoch schedule for members with different batch sizes (host logic of the library)."""
+
+    def __init__(self, n_samples: int, batch: Sequence[int]):
+        self._h = C.c_void_p()
+        self.K = len(batch)
+        self.max_batch = max(batch) if len(batch) else 0
+        arr = (C.c_int32 * max(self.K, 1))(*[int(b) for b in batch])
+        _check(lib().pack_schedule_create(int(n_samples), arr, self.K, C.byref(self._h)))
+
+    def next(self):
+        """Returns (idx int64 [rows], rows_k int32 [K], lead) or None after the last step."""
+        idx = np.empty(max(self.max_batch, 1), dtype=np.int64)
+        rows_k = np.zeros(self.K, dtype=np.int32)
+        rows, lead = C.c_int32(0), C.c_int32(-1)
+        _check(lib().pack_schedule_next(self._h, idx.ctypes.data_as(C.POINTER(C.c_int64)), C.byref(rows),
+                                        rows_k.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(lead)))
+        if rows.value == 0:
+            return None
+        return idx[:rows.value].copy(), rows_k, int(lead.value)
+
+    def used(self) -> np.ndarray:
+        out = np.zeros(self.K, dtype=np.int64)
+        _check(lib().pack_schedule_used(self._h, out.ctypes.data_as(C.POINTER(C.c_int64))))
+        return out
+
+    def destroy(self):
+        if self._h:
+            lib().pack_schedule_destroy(self._h)
             self._h = C.c_void_p()
 
     def __del__(self):

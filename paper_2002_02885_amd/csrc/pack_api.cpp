@@ -71,6 +71,8 @@ struct NodeInfo {
 };
 
 struct ModelInfo {
+    bool vacant = false;             // slot without a member (freed, not yet loaded again)
+    std::vector<pack_layer> layers;  // the member as given, kept to plan it again when the pack changes
     std::vector<TensorInfo> tensors;
     std::vector<NodeInfo> nodes;
     int batch = 0, C = 0;
@@ -92,6 +94,11 @@ struct Launch {
 };
 
 }  // namespace
+
+namespace packk {
+// for the library's other source files: records the text pack_last_error returns
+pack_status set_error(pack_status s, const std::string& msg) { return fail(s, msg); }
+}  // namespace packk
 
 struct pack_ctx {
     int device = 0;
@@ -207,6 +214,7 @@ pack_status parse_model(const pack_input_spec& in, const pack_model_spec& spec, 
     if (!spec.layers || spec.n_layers < 1) return fail(PACK_EINVAL, who + "empty layer list");
     if (spec.batch < 1 || spec.batch > in.B) return fail(PACK_EINVAL, who + "batch outside [1, B]");
     m.batch = spec.batch;
+    m.layers.assign(spec.layers, spec.layers + spec.n_layers);
     TensorInfo t0;
     t0.n = spec.batch; t0.h = in.in_h; t0.w = in.in_w; t0.c = in.in_c; t0.is_input = true;
     m.tensors.push_back(t0);
@@ -620,17 +628,20 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
     {
         std::vector<CeProb> ce;
         for (ModelInfo& m : p->models) {
+            if (m.vacant) continue;
             const TensorInfo& lg = m.tensors[m.nodes.back().out_t];
             CeProb c{};
             c.logits = (const float*)lg.act; c.dlogits = lg.dz; c.pred = m.pred; c.loss = m.loss;
             c.rows = m.batch; c.C = m.C; c.ld = m.C; c.ldd = lg.ld_dz;
             ce.push_back(c);
         }
-        Launch L;
-        L.kind = L_CE;
-        L.desc_off = db.add(ce.data(), ce.size() * sizeof(CeProb));
-        L.n = (int)ce.size();
-        p->plan.push_back(L);
+        if (!ce.empty()) {
+            Launch L;
+            L.kind = L_CE;
+            L.desc_off = db.add(ce.data(), ce.size() * sizeof(CeProb));
+            L.n = (int)ce.size();
+            p->plan.push_back(L);
+        }
     }
 
     // ---------------- backward ----------------
@@ -825,26 +836,31 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
     add_mapped_launch(p, db, L_REDUCE, dw_red, dw_red_blocks);
 
     // ---------------- update ----------------
-    Launch L;
-    L.kind = L_SGD;
-    L.n = 1;
-    p->plan.push_back(L);
+    if (p->arena_elems) {
+        Launch L;
+        L.kind = L_SGD;
+        L.n = 1;
+        p->plan.push_back(L);
+    }
+}
+
+// frees every device buffer and event the pack holds; the host-side description stays
+void free_device(pack_ctx* p) {
+    void** bufs[] = {(void**)&p->master, (void**)&p->grad, &p->shadow, &p->wt, (void**)&p->opt_m, (void**)&p->opt_v,
+                     (void**)&p->opt_params, (void**)&p->seg_end, (void**)&p->slab, (void**)&p->workspace, (void**)&p->desc};
+    for (void** b : bufs) {
+        if (*b) (void)hipFree(*b);
+        *b = nullptr;
+    }
+    for (auto& s : p->stamps) { (void)hipEventDestroy(s.t0); (void)hipEventDestroy(s.t1); }
+    p->stamps.clear();
+    p->profiling = false;
+    p->device_bytes = 0;
 }
 
 void release(pack_ctx* p) {
     if (!p) return;
-    if (p->master) (void)hipFree(p->master);
-    if (p->grad) (void)hipFree(p->grad);
-    if (p->shadow) (void)hipFree(p->shadow);
-    if (p->wt) (void)hipFree(p->wt);
-    if (p->opt_m) (void)hipFree(p->opt_m);
-    if (p->opt_v) (void)hipFree(p->opt_v);
-    if (p->opt_params) (void)hipFree(p->opt_params);
-    if (p->seg_end) (void)hipFree(p->seg_end);
-    if (p->slab) (void)hipFree(p->slab);
-    if (p->workspace) (void)hipFree(p->workspace);
-    if (p->desc) (void)hipFree(p->desc);
-    for (auto& s : p->stamps) { (void)hipEventDestroy(s.t0); (void)hipEventDestroy(s.t1); }
+    free_device(p);
     delete p;
 }
 
@@ -860,6 +876,8 @@ pack_status dev_alloc(void** ptr, size_t bytes, pack_ctx* p) {
     p->device_bytes += bytes;
     return PACK_OK;
 }
+
+pack_status live_member(const pack_ctx* p, int32_t k);
 
 pack_status upload_weights(pack_ctx* p, int k, const float* blob) {
     ModelInfo& m = p->models[k];
@@ -877,7 +895,8 @@ pack_status upload_weights(pack_ctx* p, int k, const float* blob) {
 
 pack_status download(pack_ctx* p, int k, const float* dev_arena, float* host_dst, size_t n_floats) {
     if (!p || !host_dst) return fail(PACK_EINVAL, "null argument");
-    if (k < 0 || k >= p->K) return fail(PACK_EINVAL, "member index out of range");
+    pack_status st = live_member(p, k);
+    if (st != PACK_OK) return st;
     ModelInfo& m = p->models[k];
     if (n_floats != m.n_params) return fail(PACK_EINVAL, "n_floats does not match pack_num_params");
     std::vector<float> arena(m.arena_end - m.arena_begin);
@@ -887,39 +906,14 @@ pack_status download(pack_ctx* p, int k, const float* dev_arena, float* host_dst
     return PACK_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-const char* pack_last_error(void) { return g_err.c_str(); }
-
-pack_status pack_create(const pack_input_spec* input, const pack_model_spec* models, int32_t K,
-                        uint64_t seed, void* hip_stream, pack_t** out) {
-    if (out) *out = nullptr;
-    if (!input || !models || !out) return fail(PACK_EINVAL, "null argument");
-    if (K < 1 || K > PACK_MAX_MODELS) return fail(PACK_EINVAL, "K must be in [1, PACK_MAX_MODELS]");
-    if (input->B < 1 || input->in_h < 1 || input->in_w < 1 || input->in_c < 1) return fail(PACK_EINVAL, "bad input shape");
-    if (input->dtype != PACK_F32 && input->dtype != PACK_BF16) return fail(PACK_EINVAL, "unknown dtype");
-
-    pack_ctx* p = new (std::nothrow) pack_ctx();
-    if (!p) return fail(PACK_ENOMEM, "host allocation failed");
-    p->stream = (hipStream_t)hip_stream;
-    p->bf16 = (input->dtype == PACK_BF16);
-    p->K = K;
-    p->in = *input;
-    p->models.resize(K);
-    p->opt.assign(K, pack_opt_spec{PACK_OPT_SGD, 0.f, 0.f, 0.f, 0.f, 0.f});
-    p->opt_t.assign(K, 0);
-    for (int k = 0; k < K; ++k) {
-        pack_status s = parse_model(*input, models[k], k, p->models[k]);
-        if (s != PACK_OK) { release(p); return s; }
-    }
-    if (hipGetDevice(&p->device) != hipSuccess) {
-        (void)hipGetLastError();
-        release(p);
-        return fail(PACK_EDEVICE, "no HIP device is current");
-    }
-
+// Lays the members of p->models out in the parameter arena, allocates every device buffer, builds the
+// launch plan and uploads it.  Expects a pack without device buffers; on failure it has none again.
+// Weights and optimiser state are zero afterwards (Adagrad accumulators excepted): the caller writes them.
+pack_status build_device(pack_ctx* p) {
+    const int K = p->K;
+    const pack_input_spec* input = &p->in;
+    p->im2col.clear();
+    p->plan.clear();
     // parameter arena: members back to back, every tensor starting on a 64-element boundary
     size_t off = 0;
     for (ModelInfo& m : p->models) {
@@ -939,13 +933,24 @@ pack_status pack_create(const pack_input_spec* input, const pack_model_spec* mod
     pack_status s;
 #define TRY_ALLOC(ptr, bytes)                                         \
     if ((s = dev_alloc((void**)&(ptr), (bytes), p)) != PACK_OK) {     \
-        release(p);                                                   \
+        free_device(p);                                               \
         return s;                                                     \
     }
     TRY_ALLOC(p->master, p->arena_elems * 4);
     TRY_ALLOC(p->grad, p->arena_elems * 4);
     if (p->bf16) TRY_ALLOC(p->shadow, p->arena_elems * 2);
     TRY_ALLOC(p->seg_end, (size_t)K * sizeof(long long));
+    bool need_m = false, need_v = false;
+    for (const pack_opt_spec& o : p->opt) {
+        if (o.kind != PACK_OPT_SGD) need_m = true;
+        if (o.kind == PACK_OPT_ADAM) need_v = true;
+    }
+    p->any_opt = need_m;
+    if (need_m) {
+        TRY_ALLOC(p->opt_m, p->arena_elems * 4);
+        TRY_ALLOC(p->opt_params, (size_t)K * sizeof(OptStatic));
+    }
+    if (need_v) TRY_ALLOC(p->opt_v, p->arena_elems * 4);
     {
         size_t wt_elems = 0;
         for (ModelInfo& m : p->models)
@@ -964,8 +969,10 @@ pack_status pack_create(const pack_input_spec* input, const pack_model_spec* mod
     std::vector<std::pair<void**, size_t>> fix;
     // shared im2col buffers: one per stride used by a first-layer convolution over few channels
     for (ModelInfo& m : p->models) {
+        if (m.vacant) continue;
         NodeInfo& nd = m.nodes[0];
         if (!nd.kp) continue;
+        nd.im2col_idx = -1;
         for (size_t i = 0; i < p->im2col.size(); ++i)
             if (p->im2col[i].stride == nd.stride) nd.im2col_idx = (int)i;
         if (nd.im2col_idx < 0) {
@@ -977,10 +984,10 @@ pack_status pack_create(const pack_input_spec* input, const pack_model_spec* mod
             nd.im2col_idx = (int)p->im2col.size() - 1;
         }
     }
-    p->im2col.reserve(p->im2col.size());
     for (Im2colProb& ip : p->im2col)
         fix.push_back({&ip.out, reserve((size_t)ip.B * ip.Ho * ip.Wo * ip.Kp * esz)});
     for (ModelInfo& m : p->models) {
+        if (m.vacant) continue;
         for (TensorInfo& t : m.tensors) {
             if (t.is_input) continue;
             fix.push_back({&t.act, reserve(t.elems() * (t.f32 ? 4 : esz))});
@@ -1020,37 +1027,225 @@ pack_status pack_create(const pack_input_spec* input, const pack_model_spec* mod
     if (e == hipSuccess) e = hipMemset(p->grad, 0, p->arena_elems * 4);
     if (e == hipSuccess) e = hipMemset(p->master, 0, p->arena_elems * 4);
     if (e == hipSuccess && p->shadow) e = hipMemset(p->shadow, 0, p->arena_elems * 2);
+    if (e == hipSuccess && p->opt_m) e = hipMemset(p->opt_m, 0, p->arena_elems * 4);
+    if (e == hipSuccess && p->opt_v) e = hipMemset(p->opt_v, 0, p->arena_elems * 4);
     std::vector<long long> ends(K);
     for (int k = 0; k < K; ++k) ends[k] = (long long)p->models[k].arena_end;
     if (e == hipSuccess) e = hipMemcpy(p->seg_end, ends.data(), (size_t)K * sizeof(long long), hipMemcpyHostToDevice);
+    if (e == hipSuccess && p->opt_params) {
+        std::vector<OptStatic> par(K);
+        for (int i = 0; i < K; ++i)
+            par[i] = OptStatic{p->opt[i].kind, p->opt[i].mu, p->opt[i].beta1, p->opt[i].beta2, p->opt[i].eps};
+        e = hipMemcpy(p->opt_params, par.data(), par.size() * sizeof(OptStatic), hipMemcpyHostToDevice);
+    }
     if (e != hipSuccess) {
-        release(p);
+        free_device(p);
         return fail(PACK_EDEVICE, std::string("initial upload: ") + hipGetErrorString(e));
     }
+    return PACK_OK;
+}
 
-    // seeded initial weights
-    for (int k = 0; k < K; ++k) {
-        ModelInfo& m = p->models[k];
-        std::vector<float> blob(m.n_params);
-        int tensor = 0;
-        for (const NodeInfo& nd : m.nodes) {
-            if (nd.kind == NODE_GAP) continue;
-            const float bw = std::sqrt(6.0f / (float)nd.fan_in), bb = 1.0f / std::sqrt((float)nd.fan_in);
-            for (size_t i = 0; i < nd.w_elems; ++i) blob[nd.blob_off + i] = uniform_pm(seed, k, tensor, i, bw);
-            for (int i = 0; i < nd.out; ++i) blob[nd.blob_off + nd.w_elems + i] = uniform_pm(seed, k, tensor + 1, i, bb);
-            tensor += 2;
+// seeded initial weights of member k: uniform in +-sqrt(6/fan_in), biases in +-1/sqrt(fan_in)
+pack_status seed_weights(pack_ctx* p, int k, uint64_t seed) {
+    ModelInfo& m = p->models[k];
+    std::vector<float> blob(m.n_params);
+    int tensor = 0;
+    for (const NodeInfo& nd : m.nodes) {
+        if (nd.kind == NODE_GAP) continue;
+        const float bw = std::sqrt(6.0f / (float)nd.fan_in), bb = 1.0f / std::sqrt((float)nd.fan_in);
+        for (size_t i = 0; i < nd.w_elems; ++i) blob[nd.blob_off + i] = uniform_pm(seed, k, tensor, i, bw);
+        for (int i = 0; i < nd.out; ++i) blob[nd.blob_off + nd.w_elems + i] = uniform_pm(seed, k, tensor + 1, i, bb);
+        tensor += 2;
+    }
+    if (p->bf16) for (float& v : blob) v = round_to_bf16(v);
+    return upload_weights(p, k, blob.data());
+}
+
+// What a slot of the pack shall hold after a change of membership or batch sizes.
+struct SlotPlan {
+    bool vacant = true;
+    std::vector<pack_layer> layers;
+    int batch = 0;
+    int from = -1;   // slot of the current pack whose weights and optimiser state move in; -1: a new member
+};
+
+// Rebuilds the pack for `slots` and a shared batch of B rows.  A second pack is built beside the
+// current one (so that a failure leaves the current one untouched), the state of every member that
+// stays is copied over on the device, bit for bit, and the two change places.
+pack_status rebuild(pack_ctx* p, int B, const std::vector<SlotPlan>& slots, uint64_t seed) {
+    HIP_TRY(hipStreamSynchronize(p->stream), PACK_EDEVICE);
+    pack_ctx* q = new (std::nothrow) pack_ctx();
+    if (!q) return fail(PACK_ENOMEM, "host allocation failed");
+    q->device = p->device;
+    q->stream = p->stream;
+    q->bf16 = p->bf16;
+    q->in = p->in;
+    q->in.B = B;
+    q->K = (int)slots.size();
+    q->models.resize(q->K);
+    q->opt.assign(q->K, pack_opt_spec{PACK_OPT_SGD, 0.f, 0.f, 0.f, 0.f, 0.f});
+    q->opt_t.assign(q->K, 0);
+    for (int k = 0; k < q->K; ++k) {
+        const SlotPlan& sp = slots[k];
+        if (sp.vacant) {
+            q->models[k].vacant = true;
+            continue;
         }
-        if (p->bf16) for (float& v : blob) v = round_to_bf16(v);
-        s = upload_weights(p, k, blob.data());
+        pack_model_spec spec{sp.layers.data(), (int32_t)sp.layers.size(), sp.batch};
+        pack_status s = parse_model(q->in, spec, k, q->models[k]);
+        if (s != PACK_OK) { release(q); return s; }
+        if (sp.from >= 0) {
+            q->opt[k] = p->opt[sp.from];
+            q->opt_t[k] = p->opt_t[sp.from];
+        }
+    }
+    pack_status s = build_device(q);
+    if (s != PACK_OK) { release(q); return s; }
+    hipError_t e = hipSuccess;
+    for (int k = 0; k < q->K && e == hipSuccess; ++k) {
+        const int f = slots[k].vacant ? -1 : slots[k].from;
+        if (f < 0) continue;
+        const ModelInfo& a = p->models[f];
+        const ModelInfo& b = q->models[k];
+        const size_t n = a.arena_end - a.arena_begin;
+        if (n != b.arena_end - b.arena_begin) { release(q); return fail(PACK_EINVAL, "internal: member layout changed"); }
+        e = hipMemcpyAsync(q->master + b.arena_begin, p->master + a.arena_begin, n * 4, hipMemcpyDeviceToDevice, p->stream);
+        if (e == hipSuccess && p->shadow)
+            e = hipMemcpyAsync((char*)q->shadow + b.arena_begin * 2, (const char*)p->shadow + a.arena_begin * 2, n * 2,
+                               hipMemcpyDeviceToDevice, p->stream);
+        if (e == hipSuccess && p->opt_m && q->opt_m)
+            e = hipMemcpyAsync(q->opt_m + b.arena_begin, p->opt_m + a.arena_begin, n * 4, hipMemcpyDeviceToDevice, p->stream);
+        if (e == hipSuccess && p->opt_v && q->opt_v)
+            e = hipMemcpyAsync(q->opt_v + b.arena_begin, p->opt_v + a.arena_begin, n * 4, hipMemcpyDeviceToDevice, p->stream);
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(p->stream);
+    if (e != hipSuccess) { release(q); return fail(PACK_EDEVICE, std::string("moving member state: ") + hipGetErrorString(e)); }
+    for (int k = 0; k < q->K; ++k) {
+        if (slots[k].vacant || slots[k].from >= 0) continue;
+        s = seed_weights(q, k, seed);
+        if (s != PACK_OK) { release(q); return s; }
+    }
+    std::swap(*p, *q);
+    release(q);   // the previous buffers
+    return PACK_OK;
+}
+
+// the current pack as a list of slots that all stay where they are
+std::vector<SlotPlan> current_slots(const pack_ctx* p) {
+    std::vector<SlotPlan> slots(p->K);
+    for (int k = 0; k < p->K; ++k) {
+        const ModelInfo& m = p->models[k];
+        slots[k].vacant = m.vacant;
+        if (m.vacant) continue;
+        slots[k].layers = m.layers;
+        slots[k].batch = m.batch;
+        slots[k].from = k;
+    }
+    return slots;
+}
+
+pack_status live_member(const pack_ctx* p, int32_t k) {
+    if (!p) return fail(PACK_EINVAL, "null argument");
+    if (k < 0 || k >= p->K) return fail(PACK_EINVAL, "member index out of range");
+    if (p->models[k].vacant) return fail(PACK_EINVAL, "slot " + std::to_string(k) + " holds no member");
+    return PACK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* pack_last_error(void) { return g_err.c_str(); }
+
+pack_status pack_create(const pack_input_spec* input, const pack_model_spec* models, int32_t K,
+                        uint64_t seed, void* hip_stream, pack_t** out) {
+    if (out) *out = nullptr;
+    if (!input || !models || !out) return fail(PACK_EINVAL, "null argument");
+    if (K < 1 || K > PACK_MAX_MODELS) return fail(PACK_EINVAL, "K must be in [1, PACK_MAX_MODELS]");
+    if (input->B < 1 || input->in_h < 1 || input->in_w < 1 || input->in_c < 1) return fail(PACK_EINVAL, "bad input shape");
+    if (input->dtype != PACK_F32 && input->dtype != PACK_BF16) return fail(PACK_EINVAL, "unknown dtype");
+
+    pack_ctx* p = new (std::nothrow) pack_ctx();
+    if (!p) return fail(PACK_ENOMEM, "host allocation failed");
+    p->stream = (hipStream_t)hip_stream;
+    p->bf16 = (input->dtype == PACK_BF16);
+    p->K = K;
+    p->in = *input;
+    p->models.resize(K);
+    p->opt.assign(K, pack_opt_spec{PACK_OPT_SGD, 0.f, 0.f, 0.f, 0.f, 0.f});
+    p->opt_t.assign(K, 0);
+    for (int k = 0; k < K; ++k) {
+        pack_status s = parse_model(*input, models[k], k, p->models[k]);
+        if (s != PACK_OK) { release(p); return s; }
+    }
+    if (hipGetDevice(&p->device) != hipSuccess) {
+        (void)hipGetLastError();
+        release(p);
+        return fail(PACK_EDEVICE, "no HIP device is current");
+    }
+    pack_status s = build_device(p);
+    if (s != PACK_OK) { release(p); return s; }
+    for (int k = 0; k < K; ++k) {
+        s = seed_weights(p, k, seed);
         if (s != PACK_OK) { release(p); return s; }
     }
     *out = p;
     return PACK_OK;
 }
 
+pack_status pack_free(pack_t* p, int32_t k) {
+    pack_status s = live_member(p, k);
+    if (s != PACK_OK) return s;
+    std::vector<SlotPlan> slots = current_slots(p);
+    slots[k] = SlotPlan{};
+    return rebuild(p, p->in.B, slots, 0);
+}
+
+pack_status pack_load(pack_t* p, const pack_model_spec* model, uint64_t seed, int32_t* k_out) {
+    if (!p || !model || !k_out) return fail(PACK_EINVAL, "null argument");
+    if (!model->layers || model->n_layers < 1) return fail(PACK_EINVAL, "empty layer list");
+    std::vector<SlotPlan> slots = current_slots(p);
+    int k = 0;
+    while (k < (int)slots.size() && !slots[k].vacant) ++k;
+    if (k == (int)slots.size()) {
+        if (k >= PACK_MAX_MODELS) return fail(PACK_EINVAL, "the pack already has PACK_MAX_MODELS members");
+        slots.push_back(SlotPlan{});
+    }
+    slots[k].vacant = false;
+    slots[k].layers.assign(model->layers, model->layers + model->n_layers);
+    slots[k].batch = model->batch;
+    slots[k].from = -1;
+    pack_status s = rebuild(p, p->in.B, slots, seed);
+    if (s == PACK_OK) *k_out = k;
+    return s;
+}
+
+pack_status pack_set_batch(pack_t* p, int32_t B, const int32_t* batch) {
+    if (!p || !batch) return fail(PACK_EINVAL, "null argument");
+    if (B < 1) return fail(PACK_EINVAL, "B < 1");
+    std::vector<SlotPlan> slots = current_slots(p);
+    bool same = (B == p->in.B);
+    for (int k = 0; k < p->K; ++k) {
+        if (slots[k].vacant) continue;
+        if (batch[k] < 1 || batch[k] > B) return fail(PACK_EINVAL, "member " + std::to_string(k) + ": batch outside [1, B]");
+        if (batch[k] != slots[k].batch) same = false;
+        slots[k].batch = batch[k];
+    }
+    if (same) return PACK_OK;
+    return rebuild(p, B, slots, 0);
+}
+
+int32_t pack_num_slots(const pack_t* p) { return p ? p->K : 0; }
+
+int32_t pack_member_batch(const pack_t* p, int32_t k) {
+    if (!p || k < 0 || k >= p->K || p->models[k].vacant) return 0;
+    return p->models[k].batch;
+}
+
 pack_status pack_write_weights(pack_t* p, int32_t k, const float* host_src, size_t n_floats) {
     if (!p || !host_src) return fail(PACK_EINVAL, "null argument");
-    if (k < 0 || k >= p->K) return fail(PACK_EINVAL, "member index out of range");
+    pack_status st = live_member(p, k);
+    if (st != PACK_OK) return st;
     if (n_floats != p->models[k].n_params) return fail(PACK_EINVAL, "n_floats does not match pack_num_params");
     return upload_weights(p, k, host_src);
 }
@@ -1165,7 +1360,10 @@ pack_status pack_launch_flops(const pack_t* p, int32_t i, double* flops) {
 
 pack_status pack_set_optimizer(pack_t* p, int32_t k, const pack_opt_spec* spec) {
     if (!p || !spec) return fail(PACK_EINVAL, "null argument");
-    if (k < 0 || k >= p->K) return fail(PACK_EINVAL, "member index out of range");
+    {
+        pack_status lm = live_member(p, k);
+        if (lm != PACK_OK) return lm;
+    }
     const pack_opt_spec o = *spec;
     auto unit = [](float v) { return v >= 0.f && v < 1.f; };
     switch (o.kind) {
@@ -1212,8 +1410,8 @@ pack_status pack_set_optimizer(pack_t* p, int32_t k, const pack_opt_spec* spec) 
 }
 
 static pack_status opt_slot(pack_t* p, int32_t k, int32_t slot, float** arena) {
-    if (!p) return fail(PACK_EINVAL, "null argument");
-    if (k < 0 || k >= p->K) return fail(PACK_EINVAL, "member index out of range");
+    pack_status lm = live_member(p, k);
+    if (lm != PACK_OK) return lm;
     const int kind = p->opt[k].kind;
     const bool has = (slot == 0 && kind != PACK_OPT_SGD) || (slot == 1 && kind == PACK_OPT_ADAM);
     if (!has) return fail(PACK_EINVAL, "the member's optimiser has no such state array");
@@ -1252,6 +1450,20 @@ pack_status pack_write_opt_state(pack_t* p, int32_t k, int32_t slot, const float
     return PACK_OK;
 }
 
+pack_status pack_gather_batch(pack_t* p, const void* data_dev, const int32_t* labels_all_dev, int64_t n_samples,
+                              const int64_t* idx_dev, int32_t rows, void* x_out_dev, int32_t* labels_out_dev) {
+    if (!p || !data_dev || !labels_all_dev || !idx_dev || !x_out_dev || !labels_out_dev) return fail(PACK_EINVAL, "null argument");
+    if (n_samples < 1) return fail(PACK_EINVAL, "n_samples < 1");
+    if (rows < 0 || rows > p->in.B) return fail(PACK_EINVAL, "rows outside [0, B]");
+    if (((uintptr_t)labels_all_dev & 3) || ((uintptr_t)labels_out_dev & 3) || ((uintptr_t)idx_dev & 7))
+        return fail(PACK_EINVAL, "labels must be 4-byte aligned and indices 8-byte aligned");
+    const long long row_bytes = (long long)p->in.in_h * p->in.in_w * p->in.in_c * (p->bf16 ? 2 : 4);
+    if (((uintptr_t)data_dev | (uintptr_t)x_out_dev) & (p->bf16 ? 1 : 3)) return fail(PACK_EINVAL, "data pointers must be aligned to the element type");
+    HIP_TRY(launch_gather_rows(data_dev, labels_all_dev, (const long long*)idx_dev, (long long)n_samples, rows, row_bytes,
+                               x_out_dev, labels_out_dev, p->err_flag, p->stream), PACK_EDEVICE);
+    return PACK_OK;
+}
+
 pack_status pack_read_loss(pack_t* p, float* host_dst) {
     if (!p || !host_dst) return fail(PACK_EINVAL, "null argument");
     HIP_TRY(hipStreamSynchronize(p->stream), PACK_EDEVICE);
@@ -1260,6 +1472,7 @@ pack_status pack_read_loss(pack_t* p, float* host_dst) {
     HIP_TRY(hipMemcpy(&flag, p->err_flag, 4, hipMemcpyDeviceToHost), PACK_EDEVICE);
     if (flag) {
         HIP_TRY(hipMemset(p->err_flag, 0, 4), PACK_EDEVICE);
+        if (flag & 2) return fail(PACK_EINDEX, "pack_gather_batch met a sample index outside the dataset since the last pack_read_loss");
         return fail(PACK_ELABEL, "a label outside [0, C_k) was seen since the last pack_read_loss");
     }
     return PACK_OK;
@@ -1275,7 +1488,8 @@ pack_status pack_read_grads(pack_t* p, int32_t k, float* host_dst, size_t n_floa
 
 pack_status pack_read_pred(pack_t* p, int32_t k, int32_t* host_dst) {
     if (!p || !host_dst) return fail(PACK_EINVAL, "null argument");
-    if (k < 0 || k >= p->K) return fail(PACK_EINVAL, "member index out of range");
+    pack_status lm = live_member(p, k);
+    if (lm != PACK_OK) return lm;
     HIP_TRY(hipStreamSynchronize(p->stream), PACK_EDEVICE);
     HIP_TRY(hipMemcpy(host_dst, p->models[k].pred, (size_t)p->models[k].batch * 4, hipMemcpyDeviceToHost), PACK_EDEVICE);
     return PACK_OK;
@@ -1283,7 +1497,8 @@ pack_status pack_read_pred(pack_t* p, int32_t k, int32_t* host_dst) {
 
 pack_status pack_read_logits(pack_t* p, int32_t k, float* host_dst, size_t n_floats) {
     if (!p || !host_dst) return fail(PACK_EINVAL, "null argument");
-    if (k < 0 || k >= p->K) return fail(PACK_EINVAL, "member index out of range");
+    pack_status lm = live_member(p, k);
+    if (lm != PACK_OK) return lm;
     const ModelInfo& m = p->models[k];
     if (n_floats != (size_t)m.batch * m.C) return fail(PACK_EINVAL, "n_floats must be b_k * C_k");
     HIP_TRY(hipStreamSynchronize(p->stream), PACK_EDEVICE);

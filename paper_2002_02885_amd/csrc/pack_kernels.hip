@@ -1682,6 +1682,46 @@ hipError_t launch_cast_bf16(const float* src, void* dst, long long n, hipStream_
     return hipGetLastError();
 }
 
+// Batch assembly for epochs in which the shared batch is cut from an index list (Section 3.2: the
+// samples a member has not used yet): row r of the shared batch is sample idx[r] of a dataset
+// resident on the device.  One block copies V * 256 bytes of one row.  An index outside the dataset
+// yields a row of zeros with label -1 (which the loss kernel ignores) and sets bit 1 of the flag.
+template <int V>
+__global__ __launch_bounds__(256) void gather_rows_kernel(const char* __restrict__ data, const int32_t* __restrict__ labels_all,
+                                                         const long long* __restrict__ idx, long long n_samples,
+                                                         long long row_bytes, char* __restrict__ x_out,
+                                                         int32_t* __restrict__ labels_out, int* __restrict__ err_flag) {
+    typedef typename std::conditional<V == 16, u32x4_t, typename std::conditional<V == 4, unsigned, unsigned short>::type>::type vec_t;
+    const long long r = blockIdx.x;
+    const long long i = idx[r];
+    const bool ok = i >= 0 && i < n_samples;
+    const long long off = ((long long)blockIdx.y * 256 + threadIdx.x) * V;
+    if (off < row_bytes) {
+        vec_t v = vec_t{};
+        if (ok) v = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(data + i * row_bytes + off));
+        *reinterpret_cast<vec_t*>(x_out + r * row_bytes + off) = v;
+    }
+    if (blockIdx.y == 0 && threadIdx.x == 0) {
+        labels_out[r] = ok ? labels_all[i] : -1;
+        if (!ok) atomicOr(err_flag, 2);
+    }
+}
+
+hipError_t launch_gather_rows(const void* data, const int32_t* labels_all, const long long* idx, long long n_samples,
+                              int rows, long long row_bytes, void* x_out, int32_t* labels_out, int* err_flag, hipStream_t st) {
+    if (rows <= 0) return hipSuccess;
+    const uintptr_t align = (uintptr_t)data | (uintptr_t)x_out | (uintptr_t)row_bytes;
+    const int V = (align % 16 == 0) ? 16 : (align % 4 == 0) ? 4 : 2;
+    const dim3 grid((unsigned)rows, (unsigned)((row_bytes + (long long)V * 256 - 1) / ((long long)V * 256)));
+    if (V == 16)
+        hipLaunchKernelGGL(gather_rows_kernel<16>, grid, dim3(256), 0, st, (const char*)data, labels_all, idx, n_samples, row_bytes, (char*)x_out, labels_out, err_flag);
+    else if (V == 4)
+        hipLaunchKernelGGL(gather_rows_kernel<4>, grid, dim3(256), 0, st, (const char*)data, labels_all, idx, n_samples, row_bytes, (char*)x_out, labels_out, err_flag);
+    else
+        hipLaunchKernelGGL(gather_rows_kernel<2>, grid, dim3(256), 0, st, (const char*)data, labels_all, idx, n_samples, row_bytes, (char*)x_out, labels_out, err_flag);
+    return hipGetLastError();
+}
+
 __global__ __launch_bounds__(256) void fill_zero_kernel(u32x4_t* __restrict__ dst, long long n16) {
     const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
     if (i < n16) dst[i] = u32x4_t{0u, 0u, 0u, 0u};
