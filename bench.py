@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--optimizer", default="sgd", choices=["sgd", "momentum", "adagrad", "adam"],
                     help="optimiser of every member (the headline workload uses plain SGD)")
+    ap.add_argument("--swap-cost", action="store_true",
+                    help="also time a member leaving a live pack (checkpoint read + pack_free) and a member joining "
+                         "(pack_load + checkpoint write): the switching overhead of Section 3.3, outside the timed steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unpacked", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -169,6 +172,27 @@ def main():
             torch.add(a, 0.0, out=b)
         torch.cuda.synchronize()
         del a, b
+
+    if args.swap_cost:
+        pk2 = make(w.models, w.batch, w.weights)
+        pk2.step(x.data_ptr(), y.data_ptr(), lr)
+        torch.cuda.synchronize()
+        k = w.K - 1
+        t0 = time.perf_counter()
+        blob = pk2.read_weights(k)
+        t1 = time.perf_counter()
+        pk2.free(k)
+        t2 = time.perf_counter()
+        kk = pk2.load(w.models[k], w.batch[k], seed=1)
+        t3 = time.perf_counter()
+        pk2.write_weights(kk, blob)
+        t4 = time.perf_counter()
+        pk2.step(x.data_ptr(), y.data_ptr(), lr)
+        assert kk == k and np.all(np.isfinite(pk2.read_loss()))
+        pk2.destroy()
+        out["swap_ms"] = {"checkpoint_read": (t1 - t0) * 1e3, "free": (t2 - t1) * 1e3, "load": (t3 - t2) * 1e3,
+                          "checkpoint_write": (t4 - t3) * 1e3, "member_params": int(blob.size),
+                          "in_steps": (t4 - t0) / t_pack}
 
     if not args.no_unpacked:
         t_seq = 0.0
