@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--optimizer", default="sgd", choices=["sgd", "momentum", "adagrad", "adam"],
                     help="optimiser of every member (the headline workload uses plain SGD)")
+    ap.add_argument("--different-inputs", action="store_true",
+                    help="every member trains on its own batch (the 'Training Data: Different' rows of the paper's "
+                         "Table 2) instead of the shared one")
     ap.add_argument("--swap-cost", action="store_true",
                     help="also time a member leaving a live pack (checkpoint read + pack_free) and a member joining "
                          "(pack_load + checkpoint write): the switching overhead of Section 3.3, outside the timed steps")
@@ -82,8 +85,17 @@ def main():
     x = (x.to(torch.bfloat16) if w.dtype == wl.BF16 else x).cuda().contiguous()
     y = torch.from_numpy(w.labels).cuda().contiguous()
 
+    if args.different_inputs:
+        # K independent seeded batches, stacked [K][B, ...]; single-member packs read block 0
+        g = torch.Generator().manual_seed(1234)
+        xs = torch.rand((w.K,) + tuple(w.x.shape), generator=g, dtype=torch.float32)
+        x = (xs.to(torch.bfloat16) if w.dtype == wl.BF16 else xs).cuda().contiguous()
+        y = torch.randint(0, w.n_classes, (w.K, w.B), generator=g, dtype=torch.int32).cuda().contiguous()
+
     def make(models, batch, weights):
         pk = binding.Pack(w.B, w.in_shape, w.dtype, models, batch, stream=stream)
+        if args.different_inputs and len(models) > 1:
+            pk.set_input_mode(True)
         for k, blob in enumerate(weights):
             pk.write_weights(k, blob)
             if args.optimizer != "sgd":
@@ -156,7 +168,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == wl.BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: K={w.K} packed models, batch {w.B}, input {list(w.in_shape)}, "
-                               f"{n_params} parameters, optimiser {args.optimizer}", "K": w.K, "batch": w.B, "launches_per_step": launches,
+                               f"{n_params} parameters, optimiser {args.optimizer}"
+                               + (", every member on its own batch" if args.different_inputs else ""), "K": w.K, "batch": w.B, "launches_per_step": launches,
                    "device_bytes": dev_bytes},
         "tflops": flops / t_pack / 1e12,
         "tflops_frac_of_mfma_peak": flops / t_pack / 1e12 / MFMA_PEAK_TFLOPS[w.dtype],

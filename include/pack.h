@@ -158,6 +158,17 @@ pack_status pack_load(pack_t* p, const pack_model_spec* model, uint64_t seed, in
  * returns at once.  Errors: PACK_EINVAL (null, B < 1, batch[k] outside [1, B]), PACK_ENOMEM, PACK_EDEVICE. */
 pack_status pack_set_batch(pack_t* p, int32_t B, const int32_t* batch);
 
+/* Which data the members train on.  PACK_INPUT_SHARED (the default; Section 3.4): one batch and one
+ * label vector for all members.  PACK_INPUT_PER_MEMBER (the "Training Data: Different" rows of the
+ * paper's ablation, Section 4.3 / Table 2): every slot has its own batch; pack_step then takes x_dev as
+ * [pack_num_slots][B, H, W, C] and labels_dev as [pack_num_slots][B], and member k trains on rows
+ * [0, b_k) of block k.  Nothing is shared between members any more: each first layer (and, for
+ * convolutions over few channels, each im2col copy) reads its own block.  Changing the mode plans the
+ * pack again; member state is carried over as in pack_free.
+ * Errors: PACK_EINVAL (null, unknown mode), PACK_ENOMEM, PACK_EDEVICE. */
+typedef enum { PACK_INPUT_SHARED = 0, PACK_INPUT_PER_MEMBER = 1 } pack_input_mode;
+pack_status pack_set_input_mode(pack_t* p, int32_t mode);
+
 /* Number of slots K (members + vacant slots); 0 if p is null. */
 int32_t pack_num_slots(const pack_t* p);
 
@@ -206,7 +217,8 @@ pack_status pack_write_weights(pack_t* p, int32_t k, const float* host_src, size
  * slices Section 3.2): forward, mean softmax cross-entropy over each member's own rows, backward,
  * and W <- W - lr[k] * dW for every parameter of member k, with gradients taken at the
  * pre-update weights.  x_dev: device, 16-byte aligned, [B, H, W, C] of the pack's dtype; labels_dev: device int32
- * [B]; lr_host: host float [K], copied during the call.  Enqueues only.
+ * [B] (K blocks of that shape each after pack_set_input_mode(PACK_INPUT_PER_MEMBER)); lr_host: host
+ * float [K], copied during the call.  Enqueues only.
  * Errors: PACK_EINVAL (null argument), PACK_EDEVICE (launch failure). */
 pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, const float* lr_host);
 

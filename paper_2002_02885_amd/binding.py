@@ -25,7 +25,7 @@ EXPORTS = ["pack_create", "pack_write_weights", "pack_step", "pack_read_loss", "
            "pack_set_optimizer", "pack_read_opt_state", "pack_write_opt_state",
            "pack_free", "pack_load", "pack_set_batch", "pack_num_slots", "pack_member_batch",
            "pack_schedule_create", "pack_schedule_next", "pack_schedule_used", "pack_schedule_destroy",
-           "pack_gather_batch"]
+           "pack_gather_batch", "pack_set_input_mode"]
 
 
 class pack_opt_spec(C.Structure):
@@ -106,6 +106,8 @@ def lib() -> C.CDLL:
         l.pack_schedule_destroy.argtypes = [vp]
         l.pack_schedule_destroy.restype = None
         l.pack_gather_batch.argtypes = [vp, vp, vp, i64, vp, i32, vp, vp]
+        l.pack_set_input_mode.argtypes = [vp, i32]
+        l.pack_set_input_mode.restype = C.c_int
         for name in ("pack_free", "pack_load", "pack_set_batch", "pack_schedule_create", "pack_schedule_next",
                      "pack_schedule_used", "pack_gather_batch"):
             getattr(l, name).restype = C.c_int
@@ -197,6 +199,10 @@ class Pack:
         _check(lib().pack_set_batch(self._h, int(B), arr))
         self.B = int(B)
         self._refresh_slots()
+
+    def set_input_mode(self, per_member: bool):
+        """per_member: step() then takes K stacked batches [K][B, ...] and K stacked label vectors."""
+        _check(lib().pack_set_input_mode(self._h, 1 if per_member else 0))
 
     def gather_batch(self, data_ptr: int, labels_all_ptr: int, n_samples: int, idx_ptr: int, rows: int,
                      x_out_ptr: int, labels_out_ptr: int):

@@ -130,6 +130,8 @@ struct pack_ctx {
     float* loss_all = nullptr;   // [K]
     void* zeros = nullptr;       // 256 bytes of zeros inside the slab (never written)
     std::vector<Im2colProb> im2col;   // shared-input loaders, one per first-layer stride in use
+    bool own_input = false;           // members read their own block of the step's input instead of one shared batch
+    std::vector<long long> im2col_xoff;   // byte offset of each loader's source in the step's input
     std::vector<Launch> plan;
     size_t device_bytes = 0;
     // per-launch timing (off unless pack_profile_start was called)
@@ -443,6 +445,7 @@ void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<G
                     break;
             }
             if (ea * esz >= 2.0e9 || eb * esz >= 2.0e9) vec = false;
+            if ((g.flags & (F_A_INPUT | F_B_INPUT | F_AUX_INPUT)) && (g.x_off & 15)) vec = false;
         }
         if (vec) {
             probs.push_back(g);
@@ -539,6 +542,10 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
     ws_need = 0;
     char* const ws = p->workspace;   // null during the sizing pass; offsets are added to it later
 
+    const long long block_bytes = (long long)p->in.B * p->in.in_h * p->in.in_w * p->in.in_c * (long long)esz;
+    auto x_off = [&](const ModelInfo& m) -> long long {
+        return p->own_input ? (long long)(&m - p->models.data()) * block_bytes : 0;
+    };
     auto weight_ptr = [&](const NodeInfo& nd) -> const void* {
         return bf ? (const void*)((const char*)p->shadow + nd.w_off * 2) : (const void*)(p->master + nd.w_off);
     };
@@ -570,7 +577,8 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 continue;
             }
             GemmProb g{};
-                g.zeros = p->zeros;
+            g.zeros = p->zeros;
+            g.x_off = x_off(m);
             g.A = ti.is_input ? nullptr : ti.act;
             g.B = weight_ptr(nd);
             g.C = to.act;
@@ -633,6 +641,7 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
             CeProb c{};
             c.logits = (const float*)lg.act; c.dlogits = lg.dz; c.pred = m.pred; c.loss = m.loss;
             c.rows = m.batch; c.C = m.C; c.ld = m.C; c.ldd = lg.ld_dz;
+            c.label_off = p->own_input ? (int)(&m - p->models.data()) * p->in.B : 0;
             ce.push_back(c);
         }
         if (!ce.empty()) {
@@ -696,6 +705,7 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
             {
                 GemmProb g{};
                 g.zeros = p->zeros;
+                g.x_off = x_off(m);
                 g.A = to.dz;
                 g.B = ti.is_input ? nullptr : ti.act;
                 g.flags = ti.is_input ? F_B_INPUT : 0;
@@ -968,19 +978,24 @@ pack_status build_device(pack_ctx* p) {
     auto reserve = [&](size_t bytes) { const size_t o = slab; slab += align_up(std::max<size_t>(bytes, 16), 256); return o; };
     std::vector<std::pair<void**, size_t>> fix;
     // shared im2col buffers: one per stride used by a first-layer convolution over few channels
+    p->im2col_xoff.clear();
     for (ModelInfo& m : p->models) {
         if (m.vacant) continue;
         NodeInfo& nd = m.nodes[0];
         if (!nd.kp) continue;
         nd.im2col_idx = -1;
-        for (size_t i = 0; i < p->im2col.size(); ++i)
-            if (p->im2col[i].stride == nd.stride) nd.im2col_idx = (int)i;
+        if (!p->own_input)   // one shared input: members with the same first-layer stride share one loader
+            for (size_t i = 0; i < p->im2col.size(); ++i)
+                if (p->im2col[i].stride == nd.stride) nd.im2col_idx = (int)i;
         if (nd.im2col_idx < 0) {
             Im2colProb ip{};
-            ip.B = input->B; ip.H = input->in_h; ip.W = input->in_w; ip.C = input->in_c;
+            ip.B = p->own_input ? m.batch : input->B;
+            ip.H = input->in_h; ip.W = input->in_w; ip.C = input->in_c;
             ip.stride = nd.stride; ip.Kp = nd.kp;
             ip.Ho = (ip.H - 1) / nd.stride + 1; ip.Wo = (ip.W - 1) / nd.stride + 1;
             p->im2col.push_back(ip);
+            p->im2col_xoff.push_back(p->own_input ? (long long)(&m - p->models.data()) * input->B * input->in_h *
+                                                        input->in_w * input->in_c * (long long)esz : 0);
             nd.im2col_idx = (int)p->im2col.size() - 1;
         }
     }
@@ -1072,7 +1087,7 @@ struct SlotPlan {
 // Rebuilds the pack for `slots` and a shared batch of B rows.  A second pack is built beside the
 // current one (so that a failure leaves the current one untouched), the state of every member that
 // stays is copied over on the device, bit for bit, and the two change places.
-pack_status rebuild(pack_ctx* p, int B, const std::vector<SlotPlan>& slots, uint64_t seed) {
+pack_status rebuild(pack_ctx* p, int B, const std::vector<SlotPlan>& slots, uint64_t seed, int own_input = -1) {
     HIP_TRY(hipStreamSynchronize(p->stream), PACK_EDEVICE);
     pack_ctx* q = new (std::nothrow) pack_ctx();
     if (!q) return fail(PACK_ENOMEM, "host allocation failed");
@@ -1081,6 +1096,7 @@ pack_status rebuild(pack_ctx* p, int B, const std::vector<SlotPlan>& slots, uint
     q->bf16 = p->bf16;
     q->in = p->in;
     q->in.B = B;
+    q->own_input = own_input < 0 ? p->own_input : own_input != 0;
     q->K = (int)slots.size();
     q->models.resize(q->K);
     q->opt.assign(q->K, pack_opt_spec{PACK_OPT_SGD, 0.f, 0.f, 0.f, 0.f, 0.f});
@@ -1235,6 +1251,13 @@ pack_status pack_set_batch(pack_t* p, int32_t B, const int32_t* batch) {
     return rebuild(p, B, slots, 0);
 }
 
+pack_status pack_set_input_mode(pack_t* p, int32_t mode) {
+    if (!p) return fail(PACK_EINVAL, "null argument");
+    if (mode != PACK_INPUT_SHARED && mode != PACK_INPUT_PER_MEMBER) return fail(PACK_EINVAL, "unknown input mode");
+    if ((mode == PACK_INPUT_PER_MEMBER) == p->own_input) return PACK_OK;
+    return rebuild(p, p->in.B, current_slots(p), 0, mode == PACK_INPUT_PER_MEMBER ? 1 : 0);
+}
+
 int32_t pack_num_slots(const pack_t* p) { return p ? p->K : 0; }
 
 int32_t pack_member_batch(const pack_t* p, int32_t k) {
@@ -1278,7 +1301,7 @@ pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, c
             case L_GAP_FWD: e = launch_gap(bf, false, (const GapProb*)d, (const int2*)mp, L.n, p->stream); break;
             case L_GAP_BWD: e = launch_gap(bf, true, (const GapProb*)d, (const int2*)mp, L.n, p->stream); break;
             case L_SHORTCUT: e = launch_shortcut_bwd(bf, (const ShortcutProb*)d, (const int2*)mp, L.n, p->stream); break;
-            case L_IM2COL: e = launch_im2col(bf, p->im2col[L.mode], x_dev, p->stream); break;
+            case L_IM2COL: e = launch_im2col(bf, p->im2col[L.mode], (const char*)x_dev + p->im2col_xoff[L.mode], p->stream); break;
             case L_WTRANS: e = launch_wtranspose(bf, (const TransposeProb*)d, (const int2*)mp, L.n, p->stream); break;
             case L_SGD:
                 if (!p->any_opt) {

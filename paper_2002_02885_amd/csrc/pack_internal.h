@@ -27,7 +27,7 @@ enum GemmFlags : int {
     F_RES_DOWN = 32,   // forward: add aux[b, 2i, 2j, col] for col < resC (subsampling shortcut)
     F_VEC_A = 64,      // operand A may be fetched as aligned 16-byte vectors
     F_VEC_B = 128,     // operand B likewise
-    F_A_INPUT = 256,   // operand A is the shared input batch handed to this step
+    F_A_INPUT = 256,   // operand A is the input batch handed to this step (+ x_off)
     F_B_INPUT = 512,   // operand B is the shared input batch
     F_AUX_INPUT = 1024,// the shortcut source is the shared input batch
     F_ROWMAP = 2048    // stride-2 input gradient, one parity class of input pixels: output row r is
@@ -59,6 +59,7 @@ struct GemmProb {
     int flags;
     int ksplit;                            // reduction indices per split (>= Kd when not split)
     long long split_stride;                // elements between the partial outputs of two splits
+    long long x_off;                       // bytes added to the step's input pointer (packs whose members read their own batch)
 };
 
 struct TileRef {      // one workgroup's job; prob < 0 marks a filler slot
@@ -79,6 +80,7 @@ struct CeProb {       // softmax cross-entropy of one member
     int* pred;             // [rows]
     float* loss;           // scalar
     int rows, C, ld, ldd;
+    int label_off;         // first label of the member in the step's label vector
 };
 
 struct GapProb {      // global average pool: in [n, hw, c] -> out [n, c]

@@ -1092,9 +1092,11 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
     if (tr.prob < 0) return;
     GemmProb p = probs[tr.prob];
     // the shared input batch (Section 3.4) arrives per step; every member's first layer reads it
-    if (p.flags & F_A_INPUT) p.A = x;
-    if (p.flags & F_B_INPUT) p.B = x;
-    if (p.flags & F_AUX_INPUT) p.aux = x;
+    // (x_off is 0 then; it is the member's own block when the members train on different data)
+    const void* const xin = (const char*)x + p.x_off;
+    if (p.flags & F_A_INPUT) p.A = xin;
+    if (p.flags & F_B_INPUT) p.B = xin;
+    if (p.flags & F_AUX_INPUT) p.aux = xin;
     // one block: operand tiles A (two buffers) then B (two buffers); the epilogue reuses it
     __shared__ __attribute__((aligned(16))) T lds[2 * BM * TileGeom<T, BM, BK>::LDS_LD + 2 * BN * TileGeom<T, BN, BK>::LDS_LD];
     T* const As = lds;
@@ -1190,7 +1192,7 @@ __global__ __launch_bounds__(64 * CE_WAVES) void ce_kernel(const CeProb* __restr
         const int row = row0 + wave * rpw + sub;
         const bool active = row < p.rows;
         const float* z = p.logits + (size_t)(active ? row : 0) * p.ld;
-        const int y = active ? labels[row] : 0;
+        const int y = active ? labels[p.label_off + row] : 0;
         float zv[CE_PER_LANE];
         float mx = -INFINITY;
         int arg = 0x7fffffff;
