@@ -208,6 +208,49 @@ void pack_schedule_destroy(pack_schedule_t* s);
 pack_status pack_gather_batch(pack_t* p, const void* data_dev, const int32_t* labels_all_dev, int64_t n_samples,
                               const int64_t* idx_dev, int32_t rows, void* x_out_dev, int32_t* labels_out_dev);
 
+/* ---- pack-aware hyper-parameter search (Section 5): host logic, no GPU involved -------------------
+ * A configuration is a row of D table indices (for the paper's Table 3: batch size, optimiser, learning
+ * rate, activation); categorical[j] != 0 marks a dimension without an order.  Every random choice is an
+ * argument, so a search can be replayed.  Groups are returned as one group number per configuration,
+ * numbered in the order the groups were formed.
+ *
+ * pack_config_distance: Section 5.2: numeric dimensions contribute |index difference|, categorical ones
+ *   0 if equal else 1; the contributions are added (the text's worked example: batch size 20 -> 40 is
+ *   four index steps, plus a different optimiser: 5).  Returns -1 on a null argument.
+ * pack_opt_knn: Section 5.2, the nearest-neighbour heuristic.  feats: host int32 [T][D]; need: host
+ *   uint64 [T], the device memory each configuration takes as a member (pack_estimate_bytes);
+ *   capacity: the memory available; threshold: the similarity threshold (largest distance to the
+ *   centroid at which a configuration may still join); draws: host double [T] in [0, 1), draw j picks
+ *   the centroid of group j as element floor(u * remaining) of the configurations not yet grouped, in
+ *   list order.  Candidates join nearest first (list order on ties) while they fit; one that does not
+ *   fit is passed over.  A configuration larger than the capacity forms a group of its own.
+ * pack_opt_random: Section 5.3 "Random Pack": the configurations in the order of perm (host int32 [T],
+ *   a permutation), m per group.
+ * pack_opt_batchsize: Section 5.3 "Batch-size Pack": batch: host int32 [T]; only equal values share a
+ *   group; groups are filled in list order until the next configuration does not fit.
+ * pack_hyperband_plan: the brackets of Hyperband (Section 5.1, Algorithm 1, with the bracket sizes of the
+ *   Hyperband paper it cites): bracket j has rungs_out[j] rungs; the rungs of all brackets follow each
+ *   other in n_out / r_out (configurations alive in the rung, resource units each has been trained for
+ *   when the rung ends).  capacity: entries available in n_out and r_out.
+ * pack_halving_keep: the `keep` smallest of n losses, the earlier on ties, as increasing indices.
+ * Errors: PACK_EINVAL. */
+int32_t pack_config_distance(const int32_t* a, const int32_t* b, const uint8_t* categorical, int32_t n_dims);
+pack_status pack_opt_knn(const int32_t* feats, const uint8_t* categorical, int32_t T, int32_t D, const uint64_t* need,
+                         uint64_t capacity, int32_t threshold, const double* draws, int32_t* group_out, int32_t* n_groups);
+pack_status pack_opt_random(int32_t T, int32_t m, const int32_t* perm, int32_t* group_out, int32_t* n_groups);
+pack_status pack_opt_batchsize(const int32_t* batch, int32_t T, const uint64_t* need, uint64_t capacity,
+                               int32_t* group_out, int32_t* n_groups);
+pack_status pack_hyperband_plan(int32_t R, int32_t eta, int32_t* n_out, int32_t* r_out, int32_t* rungs_out,
+                                int32_t capacity, int32_t* n_brackets);
+pack_status pack_halving_keep(const float* loss, int32_t n, int32_t keep, int32_t* idx_out);
+
+/* The memory model of pack_opt (the paper finds the limit by running out of memory, Section 5.2; here
+ * it is computed): bytes of device memory a member with this layer list, batch size and optimiser adds
+ * to a pack - parameters (master, gradient, operand copy, optimiser state), activations and their
+ * gradients - not counting what members share (im2col copy of the input, workspace of split
+ * reductions, problem tables).  0 if the specification is invalid. */
+size_t pack_estimate_bytes(const pack_input_spec* input, const pack_model_spec* model, int32_t opt_kind);
+
 /* load a member's weights (Section 2.2 `load`): host_src holds pack_num_params(p, k) floats in
  * the blob layout above.  For PACK_BF16 the bf16 operand copy is refreshed too.
  * Errors: PACK_EINVAL (k out of range, n_floats mismatch), PACK_EDEVICE. */

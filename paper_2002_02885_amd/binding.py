@@ -25,7 +25,8 @@ EXPORTS = ["pack_create", "pack_write_weights", "pack_step", "pack_read_loss", "
            "pack_set_optimizer", "pack_read_opt_state", "pack_write_opt_state",
            "pack_free", "pack_load", "pack_set_batch", "pack_num_slots", "pack_member_batch",
            "pack_schedule_create", "pack_schedule_next", "pack_schedule_used", "pack_schedule_destroy",
-           "pack_gather_batch", "pack_set_input_mode"]
+           "pack_gather_batch", "pack_set_input_mode", "pack_config_distance", "pack_opt_knn", "pack_opt_random",
+           "pack_opt_batchsize", "pack_hyperband_plan", "pack_halving_keep", "pack_estimate_bytes"]
 
 
 class pack_opt_spec(C.Structure):
@@ -106,6 +107,18 @@ def lib() -> C.CDLL:
         l.pack_schedule_destroy.argtypes = [vp]
         l.pack_schedule_destroy.restype = None
         l.pack_gather_batch.argtypes = [vp, vp, vp, i64, vp, i32, vp, vp]
+        ip, u8p, u64p, dp = C.POINTER(i32), C.POINTER(C.c_uint8), C.POINTER(u64), C.POINTER(C.c_double)
+        l.pack_config_distance.argtypes = [ip, ip, u8p, i32]
+        l.pack_config_distance.restype = i32
+        l.pack_opt_knn.argtypes = [ip, u8p, i32, i32, u64p, u64, i32, dp, ip, ip]
+        l.pack_opt_random.argtypes = [i32, i32, ip, ip, ip]
+        l.pack_opt_batchsize.argtypes = [ip, i32, u64p, u64, ip, ip]
+        l.pack_hyperband_plan.argtypes = [i32, i32, ip, ip, ip, i32, ip]
+        l.pack_halving_keep.argtypes = [fp, i32, i32, ip]
+        for name in ("pack_opt_knn", "pack_opt_random", "pack_opt_batchsize", "pack_hyperband_plan", "pack_halving_keep"):
+            getattr(l, name).restype = C.c_int
+        l.pack_estimate_bytes.argtypes = [C.POINTER(pack_input_spec), C.POINTER(pack_model_spec), i32]
+        l.pack_estimate_bytes.restype = sz
         l.pack_set_input_mode.argtypes = [vp, i32]
         l.pack_set_input_mode.restype = C.c_int
         for name in ("pack_free", "pack_load", "pack_set_batch", "pack_schedule_create", "pack_schedule_next",
@@ -335,3 +348,88 @@ class Schedule:
             self.destroy()
         except Exception:
             pass
+
+
+# ---- pack-aware search: host logic of the library -------------------------------------------------
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _groups_from_ids(ids, n_groups):
+    groups = [[] for _ in range(n_groups)]
+    for i, g in enumerate(ids):
+        groups[int(g)].append(i)
+    return groups
+
+
+def config_distance(a, b, categorical) -> int:
+    a, b = _i32(a), _i32(b)
+    cat = np.ascontiguousarray(categorical, dtype=np.uint8)
+    ip, u8p = C.POINTER(C.c_int32), C.POINTER(C.c_uint8)
+    return int(lib().pack_config_distance(a.ctypes.data_as(ip), b.ctypes.data_as(ip), cat.ctypes.data_as(u8p), a.size))
+
+
+def opt_knn(feats, categorical, need, capacity: int, threshold: int, draws):
+    """Groups as lists of indices in list order (the C ABI returns one group number per configuration)."""
+    feats = _i32(feats).reshape(len(need), -1)
+    cat = np.ascontiguousarray(categorical, dtype=np.uint8)
+    need = np.ascontiguousarray(need, dtype=np.uint64)
+    draws = np.ascontiguousarray(draws, dtype=np.float64)
+    T, D = feats.shape
+    assert draws.size >= T
+    ids = np.zeros(T, dtype=np.int32)
+    n = C.c_int32(0)
+    ip = C.POINTER(C.c_int32)
+    _check(lib().pack_opt_knn(feats.ctypes.data_as(ip), cat.ctypes.data_as(C.POINTER(C.c_uint8)), T, D,
+                              need.ctypes.data_as(C.POINTER(C.c_uint64)), int(capacity), int(threshold),
+                              draws.ctypes.data_as(C.POINTER(C.c_double)), ids.ctypes.data_as(ip), C.byref(n)))
+    return _groups_from_ids(ids, n.value)
+
+
+def opt_random(T: int, m: int, perm):
+    perm = _i32(perm)
+    ids = np.zeros(max(T, 1), dtype=np.int32)
+    n = C.c_int32(0)
+    ip = C.POINTER(C.c_int32)
+    _check(lib().pack_opt_random(T, m, perm.ctypes.data_as(ip), ids.ctypes.data_as(ip), C.byref(n)))
+    return _groups_from_ids(ids[:T], n.value)
+
+
+def opt_batchsize(batch, need, capacity: int):
+    batch = _i32(batch)
+    need = np.ascontiguousarray(need, dtype=np.uint64)
+    ids = np.zeros(max(batch.size, 1), dtype=np.int32)
+    n = C.c_int32(0)
+    ip = C.POINTER(C.c_int32)
+    _check(lib().pack_opt_batchsize(batch.ctypes.data_as(ip), batch.size, need.ctypes.data_as(C.POINTER(C.c_uint64)),
+                                    int(capacity), ids.ctypes.data_as(ip), C.byref(n)))
+    return _groups_from_ids(ids[:batch.size], n.value)
+
+
+def hyperband_plan(R: int, eta: int):
+    """List of brackets, each a list of (n_i, r_i)."""
+    cap = 4096
+    n_out, r_out, rungs = np.zeros(cap, np.int32), np.zeros(cap, np.int32), np.zeros(64, np.int32)
+    nb = C.c_int32(0)
+    ip = C.POINTER(C.c_int32)
+    _check(lib().pack_hyperband_plan(R, eta, n_out.ctypes.data_as(ip), r_out.ctypes.data_as(ip), rungs.ctypes.data_as(ip),
+                                     cap, C.byref(nb)))
+    out, at = [], 0
+    for j in range(nb.value):
+        out.append([(int(n_out[at + i]), int(r_out[at + i])) for i in range(rungs[j])])
+        at += int(rungs[j])
+    return out
+
+
+def halving_keep(loss, keep: int):
+    loss = np.ascontiguousarray(loss, dtype=np.float32)
+    idx = np.zeros(max(keep, 1), dtype=np.int32)
+    _check(lib().pack_halving_keep(_fptr(loss), loss.size, keep, idx.ctypes.data_as(C.POINTER(C.c_int32))))
+    return [int(i) for i in idx[:keep]]
+
+
+def estimate_bytes(B: int, in_shape, dtype: str, layers: list, batch: int, opt_kind: str = "sgd") -> int:
+    arr = _layer_array(layers)
+    spec = pack_model_spec(arr, len(layers), int(batch))
+    inp = pack_input_spec(B, in_shape[0], in_shape[1], in_shape[2], PACK_BF16 if dtype == "bf16" else PACK_F32)
+    return int(lib().pack_estimate_bytes(C.byref(inp), C.byref(spec), OPT_KINDS[opt_kind]))

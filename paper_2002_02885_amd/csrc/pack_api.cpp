@@ -1258,6 +1258,31 @@ pack_status pack_set_input_mode(pack_t* p, int32_t mode) {
     return rebuild(p, p->in.B, current_slots(p), 0, mode == PACK_INPUT_PER_MEMBER ? 1 : 0);
 }
 
+size_t pack_estimate_bytes(const pack_input_spec* input, const pack_model_spec* model, int32_t opt_kind) {
+    if (!input || !model || input->B < 1 || input->in_h < 1 || input->in_w < 1 || input->in_c < 1) return 0;
+    if (input->dtype != PACK_F32 && input->dtype != PACK_BF16) return 0;
+    if (opt_kind < PACK_OPT_SGD || opt_kind > PACK_OPT_ADAM) return 0;
+    ModelInfo m;
+    if (parse_model(*input, *model, 0, m) != PACK_OK) return 0;
+    const bool bf = input->dtype == PACK_BF16;
+    const size_t esz = bf ? 2 : 4;
+    size_t arena = 0, wt = 0, slab = 0;
+    for (const NodeInfo& nd : m.nodes) {
+        if (nd.kind == NODE_GAP) continue;
+        arena = align_up(arena + nd.w_arena, 64);
+        arena = align_up(arena + (size_t)nd.out, 64);
+        if (nd.kind == NODE_CONV && !nd.kp && m.tensors[nd.in_t].needs_grad) wt = align_up(wt + nd.w_elems, 64);
+    }
+    for (const TensorInfo& t : m.tensors) {
+        if (t.is_input) continue;
+        slab += align_up(t.elems() * (t.f32 ? 4 : esz), 256);
+        slab += align_up((t.ld_dz ? (size_t)t.n * t.ld_dz : t.elems()) * esz, 256);
+    }
+    slab += align_up((size_t)m.batch * 4, 256);
+    const size_t states = opt_kind == PACK_OPT_SGD ? 0 : opt_kind == PACK_OPT_ADAM ? 2 : 1;
+    return arena * (4 + 4 + (bf ? 2 : 0) + 4 * states) + wt * esz + slab;
+}
+
 int32_t pack_num_slots(const pack_t* p) { return p ? p->K : 0; }
 
 int32_t pack_member_batch(const pack_t* p, int32_t k) {
