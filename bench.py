@@ -47,6 +47,47 @@ def _time_steps(pk, x, y, lr, steps, torch):
     return (time.perf_counter() - t0) / steps
 
 
+def _search(args, np, torch, wl):
+    """Hyperband and its pack-aware variants (paper Section 5.3, Table 4) with the library's tuner."""
+    from paper_2002_02885_amd import tuner
+    in_shape, n, dtype = (1, 1, 3072), 50000, wl.BF16          # CIFAR-10's training set shape, flattened
+    X, Y = wl.labelled_dataset(5, n, in_shape, dtype)
+    data = torch.from_numpy(X).to(torch.bfloat16).cuda().contiguous()
+    labels = torch.from_numpy(Y).cuda().contiguous()
+    family = tuner.mlp_family([512], 10)
+
+    def init(cfg, layers):
+        seed = 7919 + ((cfg[0] * 4 + cfg[1]) * 6 + cfg[2]) * 4 + cfg[3]
+        return wl.draw_weights(np.random.default_rng(np.random.PCG64(seed)), layers, in_shape, dtype)
+
+    space = tuner.all_configurations()
+    rng = np.random.default_rng(17)
+    from paper_2002_02885_amd import binding
+    sampled = [[space[i] for i in rng.choice(len(space), size=rungs[0][0], replace=False)]
+               for rungs in binding.hyperband_plan(81, 3)]
+    res = {}
+    # the similarity threshold is the user's knob (Section 5.2): 4 packs near neighbours only, 17 (the
+    # diameter of the space) lets memory alone bound a group
+    for name, policy, threshold in (("none", "none", 0), ("knn", "knn", 4), ("knn_threshold_17", "knn", 17),
+                                    ("random", "random", 0), ("batchsize", "batchsize", 0)):
+        t = tuner.Tuner(data.data_ptr(), labels.data_ptr(), n, in_shape, dtype, family, init,
+                        steps_per_unit=args.search_units, policy=policy, capacity_bytes=16 << 30, threshold=threshold,
+                        random_m=8, seed=3, sync=torch.cuda.synchronize)
+        t0 = time.perf_counter()
+        best, loss = t.run(81, 3, sampled)
+        wall = time.perf_counter() - t0
+        res[name] = {"wall_s": wall, "train_s": t.train_seconds, "packs": t.packs_built, "best": list(best), "best_loss": loss,
+                       "largest_group": max(len(g) for e in t.log for g in e["groups"])}
+    assert len(set((tuple(r["best"]), r["best_loss"]) for r in res.values())) == 1, "policies must agree on the winner"
+    out = {"metric": "hyperband training time", "unit": "s", "higher_is_better": False, "n_gpus": 1,
+           "config": {"workload": "Hyperband R=81 eta=3 over the 1056 configurations of Table 3, MLP 3072-512-10 bf16, "
+                                  f"50000 synthetic samples, {args.search_units} steps per resource unit"},
+           "value": res["knn"]["train_s"], "policies": res,
+           "time_saved_vs_plain": {p: 1.0 - res[p]["train_s"] / res["none"]["train_s"] for p in res if p != "none"},
+           "data": "synthetic", "dtype": "bf16"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -58,6 +99,11 @@ def main():
     ap.add_argument("--different-inputs", action="store_true",
                     help="every member trains on its own batch (the 'Training Data: Different' rows of the paper's "
                          "Table 2) instead of the shared one")
+    ap.add_argument("--search", action="store_true",
+                    help="instead of the step benchmark: run Hyperband (R=81, eta=3) over the paper's Table 3 space with "
+                         "every grouping policy (none / kNN pack_opt / Random Pack / Batch-size Pack) on a CIFAR-shaped "
+                         "synthetic dataset and print the training time of each (the paper's Table 4)")
+    ap.add_argument("--search-units", type=int, default=10, help="training steps per Hyperband resource unit")
     ap.add_argument("--swap-cost", action="store_true",
                     help="also time a member leaving a live pack (checkpoint read + pack_free) and a member joining "
                          "(pack_load + checkpoint write): the switching overhead of Section 3.3, outside the timed steps")
@@ -79,6 +125,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.search:
+        return _search(args, np, torch, wl)
     w = wl.CONFIGS[args.workload]()
     stream = torch.cuda.current_stream().cuda_stream
     x = torch.from_numpy(w.x)

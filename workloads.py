@@ -261,3 +261,17 @@ def custom(name: str, seed: int, dtype: str, B: int, in_shape, models, batch=Non
         lr = lambda r: 10.0 ** r.uniform(-3.0, -1.0, size=K)
     return _finish(name, dtype, B, tuple(in_shape), [list(m) for m in models],
                    batch if batch is not None else [B] * K, lr, rng, pixel, n_classes, steps)
+
+
+def labelled_dataset(seed: int, n: int, in_shape, dtype: str = F32, n_classes: int = 10):
+    """n samples whose labels can be learnt: x ~ N(0, 1) and label = argmax of a fixed random linear
+    map of x (a stand-in for the CIFAR-10 training set of the paper's search experiment, Section 5.3,
+    with its 32x32x3 shape and 10 classes when called so).  Returns (x fp32 [n, H, W, C], labels int32 [n])."""
+    rng = np.random.default_rng(np.random.PCG64(seed))
+    h, w, c = in_shape
+    x = rng.standard_normal(size=(n, h, w, c)).astype(np.float32)
+    if dtype == BF16:
+        x = to_bf16_representable(x)
+    teacher = rng.standard_normal(size=(h * w * c, n_classes)).astype(np.float32)
+    labels = np.argmax(x.reshape(n, -1) @ teacher, axis=1).astype(np.int32)
+    return x, labels
