@@ -294,8 +294,13 @@ pack_status pack_read_weights(pack_t* p, int32_t k, float* host_dst, size_t n_fl
  * host_dst: int32 [b_k]. */
 pack_status pack_read_pred(pack_t* p, int32_t k, int32_t* host_dst);
 
-/* Test hook: the gradients the last step applied to member k, in the blob layout. */
+/* Test hook: the gradients the last step applied to member k, in the blob layout.  A pack whose
+ * members all use PACK_OPT_SGD applies W <- W - lr dW inside the kernels that produce dW and does not
+ * store the gradient at all (that saves a write and a read of every parameter per step); such a pack
+ * returns PACK_EINVAL here unless pack_keep_grads(p, 1) was called, which makes the same kernels store
+ * the gradient as well.  pack_keep_grads plans the pack again (member state is carried over). */
 pack_status pack_read_grads(pack_t* p, int32_t k, float* host_dst, size_t n_floats);
+pack_status pack_keep_grads(pack_t* p, int32_t on);
 
 /* Test hook: the last step's logits of member k, row-major float [b_k, C_k]. */
 pack_status pack_read_logits(pack_t* p, int32_t k, float* host_dst, size_t n_floats);
@@ -328,6 +333,11 @@ pack_status pack_launch_name(const pack_t* p, int32_t i, char* buf, size_t n);
 /* Multiply-add work of launch i: 2 * rows * columns * reduction summed over the matrix products
  * the launch executes (0 for launches that are not matrix products).  flops: host. */
 pack_status pack_launch_flops(const pack_t* p, int32_t i, double* flops);
+
+/* Algorithmic bytes of launch i if it is a matrix-product launch: every operand read once, every
+ * result written once, plus, where the update is applied in the same kernel, the weights read and
+ * written and their bf16 copy written (0 for other launches).  bytes: host. */
+pack_status pack_launch_bytes(const pack_t* p, int32_t i, double* bytes);
 
 /* Thread-local text describing the last failing call on this thread ("" if none). */
 const char* pack_last_error(void);

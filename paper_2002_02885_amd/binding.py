@@ -26,7 +26,8 @@ EXPORTS = ["pack_create", "pack_write_weights", "pack_step", "pack_read_loss", "
            "pack_free", "pack_load", "pack_set_batch", "pack_num_slots", "pack_member_batch",
            "pack_schedule_create", "pack_schedule_next", "pack_schedule_used", "pack_schedule_destroy",
            "pack_gather_batch", "pack_set_input_mode", "pack_config_distance", "pack_opt_knn", "pack_opt_random",
-           "pack_opt_batchsize", "pack_hyperband_plan", "pack_halving_keep", "pack_estimate_bytes"]
+           "pack_opt_batchsize", "pack_hyperband_plan", "pack_halving_keep", "pack_estimate_bytes",
+           "pack_keep_grads", "pack_launch_bytes"]
 
 
 class pack_opt_spec(C.Structure):
@@ -121,6 +122,10 @@ def lib() -> C.CDLL:
         l.pack_estimate_bytes.restype = sz
         l.pack_set_input_mode.argtypes = [vp, i32]
         l.pack_set_input_mode.restype = C.c_int
+        l.pack_keep_grads.argtypes = [vp, i32]
+        l.pack_keep_grads.restype = C.c_int
+        l.pack_launch_bytes.argtypes = [vp, i32, C.POINTER(C.c_double)]
+        l.pack_launch_bytes.restype = C.c_int
         for name in ("pack_free", "pack_load", "pack_set_batch", "pack_schedule_create", "pack_schedule_next",
                      "pack_schedule_used", "pack_gather_batch"):
             getattr(l, name).restype = C.c_int
@@ -294,6 +299,15 @@ class Pack:
         buf = C.create_string_buffer(64)
         _check(lib().pack_launch_name(self._h, i, buf, 64))
         return buf.value.decode()
+
+    def keep_grads(self, on: bool = True):
+        """Plain-SGD packs do not store gradients unless asked to (read_grads needs it)."""
+        _check(lib().pack_keep_grads(self._h, 1 if on else 0))
+
+    def launch_bytes(self, i: int) -> float:
+        out = C.c_double(0.0)
+        _check(lib().pack_launch_bytes(self._h, i, C.byref(out)))
+        return float(out.value)
 
     def launch_flops(self, i: int) -> float:
         out = C.c_double(0.0)

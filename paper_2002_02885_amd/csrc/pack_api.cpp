@@ -91,6 +91,7 @@ struct Launch {
     size_t map_off = 0;     // byte offset of the tile / block map
     int n = 0;              // grid size
     double flops = 0.0;     // GEMM launches: 2 * rows * columns * reduction, summed over the launch's problems
+    double bytes = 0.0;     // GEMM launches: operands once + results once (+ the fused update's weight traffic)
 };
 
 }  // namespace
@@ -131,6 +132,8 @@ struct pack_ctx {
     void* zeros = nullptr;       // 256 bytes of zeros inside the slab (never written)
     std::vector<Im2colProb> im2col;   // shared-input loaders, one per first-layer stride in use
     bool own_input = false;           // members read their own block of the step's input instead of one shared batch
+    bool fused = false;               // all members use plain SGD: the update is applied in the weight-gradient kernels
+    bool keep_grads = false;          // fused packs: store the gradients as well (pack_read_grads)
     std::vector<long long> im2col_xoff;   // byte offset of each loader's source in the step's input
     std::vector<Launch> plan;
     size_t device_bytes = 0;
@@ -412,7 +415,27 @@ void emit_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, int cfg, const std
     L.desc_off = db.add(probs.data(), probs.size() * sizeof(GemmProb));
     L.map_off = db.add(tiles.data(), tiles.size() * sizeof(TileRef));
     L.n = (int)tiles.size();
-    for (const GemmProb& g : probs) L.flops += 2.0 * g.R * g.Q * g.Kd;
+    const double esz = p->bf16 ? 2.0 : 4.0;
+    for (const GemmProb& g : probs) {
+        L.flops += 2.0 * g.R * g.Q * g.Kd;
+        const double out = (double)g.R * g.Q;
+        double a = 0, b = 0, c = 0;
+        switch (mode) {
+            case LIN_FWD: a = (double)g.R * g.Kd; b = (double)g.Q * g.Kd; c = out * ((g.flags & F_OUT_F32) ? 4.0 : esz) / esz; break;
+            case LIN_DX: a = (double)g.R * g.Kd; b = (double)g.Q * g.Kd; c = out * (1.0 + ((g.flags & F_MASK) ? 1.0 : 0.0) + ((g.flags & F_ACCUM) ? 1.0 : 0.0)); break;
+            case LIN_DW: a = (double)g.R * g.Kd; b = (double)g.Q * g.Kd; break;
+            case CONV_FWD: a = (double)g.R / (g.Ho * g.Wo) * g.H * g.W * g.Cin; b = (double)g.Q * g.Kd; c = out; break;
+            case CONV_DX: a = (double)g.R * g.Cout / ((g.flags & F_ROWMAP) ? 1.0 : (double)(g.stride * g.stride)); b = (double)g.Q * g.Kd;
+                          c = out * (1.0 + ((g.flags & F_MASK) ? 1.0 : 0.0) + ((g.flags & F_ACCUM) ? 1.0 : 0.0)); break;
+            default: a = (double)g.R * g.Kd; b = (double)g.Kd / (g.Ho * g.Wo) * g.H * g.W * g.Cin; break;
+        }
+        L.bytes += (a + b + c) * esz;
+        if (mode == LIN_DW || mode == CONV_DW) {
+            const double splits = std::max(1, (g.Kd + g.ksplit - 1) / g.ksplit);
+            if (!(g.flags & F_UPDATE) || (g.flags & F_KEEP_G)) L.bytes += out * 4.0 * splits;      // gradient (or partials) written
+            if (g.flags & F_UPDATE) L.bytes += out * (8.0 + (g.upd_shadow ? 2.0 : 0.0));            // W read + written, bf16 copy written
+        }
+    }
     p->plan.push_back(L);
 }
 
@@ -742,17 +765,21 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 int S = std::min(128, std::max(1, (rows + chunk - 1) / chunk));
                 g.ksplit = (int)align_up((size_t)(rows + S - 1) / S, 64);
                 S = (rows + g.ksplit - 1) / g.ksplit;
+                const int member = (int)(&m - p->models.data());
+                void* const shadow_w = bf ? (void*)((char*)p->shadow + nd.w_off * 2) : nullptr;
                 if (S > 1) {
                     g.C = ws + ws_off;
                     g.split_stride = (long long)nd.w_arena;
                     ReduceProb r{};
                     r.in = (const float*)g.C; r.out = dst; r.stride = (long long)nd.w_arena; r.n = (int)nd.w_arena; r.S = S;
+                    if (p->fused) { r.upd_w = p->master + nd.w_off; r.upd_shadow = shadow_w; r.member = member; r.keep_g = p->keep_grads; }
                     dw_red.push_back(r);
                     dw_red_blocks.push_back((int)((nd.w_arena + 1023) / 1024));
                     ws_off += align_up((size_t)S * nd.w_arena * 4, 256);
                     g.dbias = (float*)(ws + ws_off);
                     ReduceProb rb{};
                     rb.in = g.dbias; rb.out = p->grad + nd.b_off; rb.stride = nd.out; rb.n = nd.out; rb.S = S;
+                    if (p->fused) { rb.upd_w = p->master + nd.b_off; rb.member = member; rb.keep_g = p->keep_grads; }
                     dw_red.push_back(rb);
                     dw_red_blocks.push_back((nd.out + 1023) / 1024);
                     ws_off += align_up((size_t)S * nd.out * 4, 256);
@@ -760,6 +787,10 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                     g.ksplit = std::max(g.Kd, 1);
                     g.C = dst;
                     g.dbias = p->grad + nd.b_off;
+                    if (p->fused) {
+                        g.flags |= F_UPDATE | (p->keep_grads ? F_KEEP_G : 0);
+                        g.upd_w = p->master + nd.w_off; g.upd_shadow = shadow_w; g.upd_b = p->master + nd.b_off; g.member = member;
+                    }
                 }
                 if (dense) lin_dw.push_back(g);
                 else conv_dw.push_back(g);
@@ -846,7 +877,8 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
     add_mapped_launch(p, db, L_REDUCE, dw_red, dw_red_blocks);
 
     // ---------------- update ----------------
-    if (p->arena_elems) {
+    // (plain-SGD packs have applied it in the weight-gradient launches above)
+    if (p->arena_elems && !p->fused) {
         Launch L;
         L.kind = L_SGD;
         L.n = 1;
@@ -956,6 +988,7 @@ pack_status build_device(pack_ctx* p) {
         if (o.kind == PACK_OPT_ADAM) need_v = true;
     }
     p->any_opt = need_m;
+    p->fused = !need_m && !std::getenv("PACK_NO_FUSED_UPDATE");   // the variable is a measuring aid
     if (need_m) {
         TRY_ALLOC(p->opt_m, p->arena_elems * 4);
         TRY_ALLOC(p->opt_params, (size_t)K * sizeof(OptStatic));
@@ -1097,6 +1130,7 @@ pack_status rebuild(pack_ctx* p, int B, const std::vector<SlotPlan>& slots, uint
     q->in = p->in;
     q->in.B = B;
     q->own_input = own_input < 0 ? p->own_input : own_input != 0;
+    q->keep_grads = p->keep_grads;
     q->K = (int)slots.size();
     q->models.resize(q->K);
     q->opt.assign(q->K, pack_opt_spec{PACK_OPT_SGD, 0.f, 0.f, 0.f, 0.f, 0.f});
@@ -1319,9 +1353,9 @@ pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, c
         const char* mp = p->desc + L.map_off;
         switch (L.kind) {
             case L_GEMM:
-                e = launch_gemm(L.mode, bf, L.tile_cfg, (const GemmProb*)d, (const TileRef*)mp, L.n, x_dev, p->stream);
+                e = launch_gemm(L.mode, bf, L.tile_cfg, (const GemmProb*)d, (const TileRef*)mp, L.n, x_dev, lr, p->stream);
                 break;
-            case L_REDUCE: e = launch_reduce((const ReduceProb*)d, (const int2*)mp, L.n, p->stream); break;
+            case L_REDUCE: e = launch_reduce((const ReduceProb*)d, (const int2*)mp, L.n, lr, p->stream); break;
             case L_CE: e = launch_ce(bf, (const CeProb*)d, L.n, labels_dev, p->err_flag, p->stream); break;
             case L_GAP_FWD: e = launch_gap(bf, false, (const GapProb*)d, (const int2*)mp, L.n, p->stream); break;
             case L_GAP_BWD: e = launch_gap(bf, true, (const GapProb*)d, (const int2*)mp, L.n, p->stream); break;
@@ -1395,7 +1429,8 @@ pack_status pack_launch_name(const pack_t* p, int32_t i, char* buf, size_t n) {
     const Launch& L = p->plan[i];
     const char* nm = (L.kind == L_GEMM) ? gemm_names[L.mode] : names[L.kind];
     if (L.kind == L_SGD && p->any_opt) nm = "optimizer_update";
-    std::snprintf(buf, n, "%s", nm);
+    const bool with_update = p->fused && (L.kind == L_REDUCE || (L.kind == L_GEMM && (L.mode == LIN_DW || L.mode == CONV_DW)));
+    std::snprintf(buf, n, "%s%s", nm, with_update ? "+sgd" : "");
     return PACK_OK;
 }
 
@@ -1404,6 +1439,22 @@ pack_status pack_launch_flops(const pack_t* p, int32_t i, double* flops) {
     if (i < 0 || i >= (int32_t)p->plan.size()) return fail(PACK_EINVAL, "launch index out of range");
     *flops = p->plan[i].flops;
     return PACK_OK;
+}
+
+pack_status pack_launch_bytes(const pack_t* p, int32_t i, double* bytes) {
+    if (!p || !bytes) return fail(PACK_EINVAL, "null argument");
+    if (i < 0 || i >= (int32_t)p->plan.size()) return fail(PACK_EINVAL, "launch index out of range");
+    *bytes = p->plan[i].bytes;
+    return PACK_OK;
+}
+
+pack_status pack_keep_grads(pack_t* p, int32_t on) {
+    if (!p) return fail(PACK_EINVAL, "null argument");
+    if ((on != 0) == p->keep_grads) return PACK_OK;
+    p->keep_grads = (on != 0);
+    pack_status st = rebuild(p, p->in.B, current_slots(p), 0);
+    if (st != PACK_OK) p->keep_grads = !p->keep_grads;
+    return st;
 }
 
 pack_status pack_set_optimizer(pack_t* p, int32_t k, const pack_opt_spec* spec) {
@@ -1424,20 +1475,30 @@ pack_status pack_set_optimizer(pack_t* p, int32_t k, const pack_opt_spec* spec) 
         default: return fail(PACK_EINVAL, "unknown optimiser kind");
     }
     HIP_TRY(hipStreamSynchronize(p->stream), PACK_EDEVICE);
-    pack_status st;
-    if (o.kind != PACK_OPT_SGD && !p->opt_m) {
-        if ((st = dev_alloc((void**)&p->opt_m, p->arena_elems * 4, p)) != PACK_OK) return st;
-        HIP_TRY(hipMemset(p->opt_m, 0, p->arena_elems * 4), PACK_EDEVICE);
-    }
-    if (o.kind == PACK_OPT_ADAM && !p->opt_v) {
-        if ((st = dev_alloc((void**)&p->opt_v, p->arena_elems * 4, p)) != PACK_OK) return st;
-        HIP_TRY(hipMemset(p->opt_v, 0, p->arena_elems * 4), PACK_EDEVICE);
-    }
-    if (!p->opt_params) {
-        if ((st = dev_alloc((void**)&p->opt_params, (size_t)p->K * sizeof(OptStatic), p)) != PACK_OK) return st;
-    }
+    const pack_opt_spec old_spec = p->opt[k];
+    const long long old_t = p->opt_t[k];
     p->opt[k] = o;
     p->opt_t[k] = 0;
+    bool need_m = false, need_v = false;
+    for (const pack_opt_spec& q : p->opt) {
+        if (q.kind != PACK_OPT_SGD) need_m = true;
+        if (q.kind == PACK_OPT_ADAM) need_v = true;
+    }
+    if (need_m != (p->opt_m != nullptr) || need_v != (p->opt_v != nullptr) || need_m != p->any_opt) {
+        // the set of state arrays, or whether the update is fused into the weight-gradient kernels,
+        // changes: plan the pack again (members keep their weights and state)
+        pack_status st = rebuild(p, p->in.B, current_slots(p), 0);
+        if (st != PACK_OK) {
+            p->opt[k] = old_spec;
+            p->opt_t[k] = old_t;
+            return st;
+        }
+    } else if (p->opt_params) {
+        std::vector<OptStatic> par(p->K);
+        for (int i = 0; i < p->K; ++i)
+            par[i] = OptStatic{p->opt[i].kind, p->opt[i].mu, p->opt[i].beta1, p->opt[i].beta2, p->opt[i].eps};
+        HIP_TRY(hipMemcpy(p->opt_params, par.data(), par.size() * sizeof(OptStatic), hipMemcpyHostToDevice), PACK_EDEVICE);
+    }
     // starting state over the member's whole arena segment (alignment gaps included: their gradient
     // is always zero, and a positive Adagrad accumulator there keeps 0 / sqrt(acc) well defined)
     const ModelInfo& m = p->models[k];
@@ -1447,13 +1508,6 @@ pack_status pack_set_optimizer(pack_t* p, int32_t k, const pack_opt_spec* spec) 
         HIP_TRY(hipMemcpy(p->opt_m + m.arena_begin, init.data(), seg * 4, hipMemcpyHostToDevice), PACK_EDEVICE);
     }
     if (p->opt_v) HIP_TRY(hipMemset(p->opt_v + m.arena_begin, 0, seg * 4), PACK_EDEVICE);
-    p->any_opt = false;
-    std::vector<OptStatic> par(p->K);
-    for (int i = 0; i < p->K; ++i) {
-        par[i] = OptStatic{p->opt[i].kind, p->opt[i].mu, p->opt[i].beta1, p->opt[i].beta2, p->opt[i].eps};
-        if (p->opt[i].kind != PACK_OPT_SGD) p->any_opt = true;
-    }
-    HIP_TRY(hipMemcpy(p->opt_params, par.data(), par.size() * sizeof(OptStatic), hipMemcpyHostToDevice), PACK_EDEVICE);
     return PACK_OK;
 }
 
@@ -1531,6 +1585,9 @@ pack_status pack_read_weights(pack_t* p, int32_t k, float* host_dst, size_t n_fl
 }
 
 pack_status pack_read_grads(pack_t* p, int32_t k, float* host_dst, size_t n_floats) {
+    if (p && p->fused && !p->keep_grads)
+        return fail(PACK_EINVAL, "plain-SGD packs apply the update where the gradient is produced and do not store it: "
+                                 "call pack_keep_grads(p, 1) first");
     return download(p, k, p ? p->grad : nullptr, host_dst, n_floats);
 }
 

@@ -18,6 +18,11 @@ enum GemmMode : int {
     CONV_DW = 5    // dW[o,(tap,c)] = sum_(b,i,j) dZ[(b,i,j),o] In[b,s*i+u-1,s*j+v-1,c]   (split over the sum)
 };
 
+#ifndef PACK_LR_N
+#define PACK_LR_N 256
+#endif
+struct LrTable { float lr[PACK_LR_N]; };
+
 enum GemmFlags : int {
     F_RELU = 1,        // forward: max(v, 0)
     F_OUT_F32 = 2,     // forward: store float regardless of the pack dtype (logits)
@@ -30,9 +35,12 @@ enum GemmFlags : int {
     F_A_INPUT = 256,   // operand A is the input batch handed to this step (+ x_off)
     F_B_INPUT = 512,   // operand B is the shared input batch
     F_AUX_INPUT = 1024,// the shortcut source is the shared input batch
-    F_ROWMAP = 2048    // stride-2 input gradient, one parity class of input pixels: output row r is
+    F_ROWMAP = 2048,   // stride-2 input gradient, one parity class of input pixels: output row r is
                        // pixel (b, 2*yc + 1 - cls_py, 2*xc + 1 - cls_px) and the reduction runs over the
                        // taps of that class only (u = 1 or u in {0, 2}, likewise v)
+    F_UPDATE = 4096,   // weight gradient, not split: apply W <- W - lr[member] * dW (and b likewise) in the
+                       // epilogue instead of storing the gradient for a separate update launch
+    F_KEEP_G = 8192    // with F_UPDATE: store the gradient as well
 };
 
 // activation kinds (paper Table 3); the value is also what GemmProb::act / mask_act hold
@@ -60,6 +68,10 @@ struct GemmProb {
     int ksplit;                            // reduction indices per split (>= Kd when not split)
     long long split_stride;                // elements between the partial outputs of two splits
     long long x_off;                       // bytes added to the step's input pointer (packs whose members read their own batch)
+    float* upd_w;                          // F_UPDATE: master weights, same layout as C
+    void* upd_shadow;                      // F_UPDATE: bf16 operand copy of the weights (null for fp32 packs)
+    float* upd_b;                          // F_UPDATE: master bias [R]
+    int member;                            // F_UPDATE: index into the step's learning-rate table
 };
 
 struct TileRef {      // one workgroup's job; prob < 0 marks a filler slot
@@ -72,6 +84,9 @@ struct ReduceProb {   // out[e] = sum_{s < S} in[s * stride + e], fixed order
     float* out;
     long long stride;
     int n, S;
+    float* upd_w;         // not null: apply w[e] <- w[e] - lr[member] * sum instead of (keep_g: as well as) storing it
+    void* upd_shadow;     // bf16 copy of w to refresh, or null
+    int member, keep_g;
 };
 
 struct CeProb {       // softmax cross-entropy of one member
@@ -114,16 +129,14 @@ struct TransposeProb {   // convolution weights [Cout][9][Cin] -> [Cin][9][Cout]
     int Cin, Cout, tiles_ci, tiles_co;   // 64 x 64 tiles per tap
 };
 
-#ifndef PACK_LR_N
-#define PACK_LR_N 256
-#endif
-struct LrTable { float lr[PACK_LR_N]; };
+
 
 // launch wrappers; all enqueue on `st` and return the launch status -----------------------------
 // tile_cfg indexes GEMM_TILE_M / GEMM_TILE_N
+// lr: the step's learning rates (used by weight-gradient launches whose problems carry F_UPDATE)
 hipError_t launch_gemm(int mode, bool bf16, int tile_cfg, const GemmProb* probs_dev, const TileRef* tiles_dev,
-                       int n_tiles, const void* x_dev, hipStream_t st);
-hipError_t launch_reduce(const ReduceProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);
+                       int n_tiles, const void* x_dev, const LrTable& lr, hipStream_t st);
+hipError_t launch_reduce(const ReduceProb* probs_dev, const int2* map_dev, int n_blocks, const LrTable& lr, hipStream_t st);
 hipError_t launch_ce(bool bf16, const CeProb* probs_dev, int K, const int32_t* labels, int* err_flag, hipStream_t st);
 hipError_t launch_gap(bool bf16, bool backward, const GapProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);
 hipError_t launch_shortcut_bwd(bool bf16, const ShortcutProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);

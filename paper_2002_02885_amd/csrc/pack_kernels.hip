@@ -721,8 +721,18 @@ struct StageCount {   // register stages of prefetch per tile shape (bounded by 
     static constexpr int value = (BKM > 1 || !VEC) ? 2 : ((BM * BN >= 128 * 128) ? PACK_ST_128x128 : ((BM * BN >= 128 * 64) ? PACK_ST_128x64 : PACK_ST_64x64));
 };
 
+// the SGD update of one parameter; every path that applies it (update kernels, fused epilogues)
+// uses this one expression so that a member's bits do not depend on which path its pack takes
+__device__ __forceinline__ float sgd_apply(float w, float g, float lr) { return __builtin_fmaf(-lr, g, w); }
+
+__device__ __forceinline__ void update_one(const GemmProb& p, size_t off, float g, float lr) {
+    const float w = sgd_apply(p.upd_w[off], g, lr);
+    p.upd_w[off] = w;
+    if (p.upd_shadow) ((bf16_t*)p.upd_shadow)[off] = ET<bf16_t>::from_f(w);
+}
+
 template <int MODE, typename T, int BM, int BN, int BKM, bool VEC>
-__device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, T* __restrict__ As_, T* __restrict__ Bs_) {
+__device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, T* __restrict__ As_, T* __restrict__ Bs_, float lrk) {
     constexpr int V = ET<T>::V, BK = ET<T>::BK * BKM;
     typedef TileGeom<T, BM, BK> GA;
     typedef TileGeom<T, BN, BK> GB;
@@ -887,9 +897,16 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
         }
     }
 
+    // fused update (F_UPDATE): W <- W - lr dW is applied where the gradient is produced, so the
+    // gradient is neither written nor read back by a separate update launch
+    const bool upd = IS_DW && (p.flags & F_UPDATE);
+    const bool keep_g = !upd || (p.flags & F_KEEP_G);
     if constexpr (IS_DW) {
-        if (do_bias_grad && threadIdx.x < BM && row0 + (int)threadIdx.x < p.R)
-            p.dbias[(size_t)tr.ks * p.R + row0 + threadIdx.x] = bias_grad;
+        if (do_bias_grad && threadIdx.x < BM && row0 + (int)threadIdx.x < p.R) {
+            const int r = row0 + threadIdx.x;
+            if (keep_g) p.dbias[(size_t)tr.ks * p.R + r] = bias_grad;
+            if (upd) p.upd_b[r] = sgd_apply(p.upd_b[r], bias_grad, lrk);
+        }
     }
 
     // ---- epilogue ----
@@ -957,6 +974,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                 size_t off[BATCH];
                 bool live[BATCH];
                 ev_t auxv[BATCH][EV], oldv[BATCH][EV];
+                f32x4_t wv[IS_DW ? BATCH : 1][2];
 #pragma unroll
                 for (int n = 0; n < BATCH; ++n) {
                     const int row = row0 + lr0 + (n0 + n) * RSTEP;
@@ -992,6 +1010,12 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                         else oz = f32x4_t{0.f, 0.f, 0.f, 0.f};
                         oldv[n][h] = op ? *reinterpret_cast<const ev_t*>(op + h * 4) : oz;
                     }
+                    if constexpr (IS_DW) {
+                        if (upd && live[n] && full) {
+                            wv[n][0] = *reinterpret_cast<const f32x4_t*>(p.upd_w + off[n]);
+                            wv[n][1] = *reinterpret_cast<const f32x4_t*>(p.upd_w + off[n] + 4);
+                        }
+                    }
                 }
 #pragma unroll
                 for (int n = 0; n < BATCH; ++n) {
@@ -1008,8 +1032,13 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                     if (!full) {   // ragged right edge: element by element
                         for (int e = 0; e < 8 && col + e < p.Q; ++e) {
                             const float r = finish(v[e], row, col + e, off[n] + e);
-                            if (out_f32) cf[off[n] + e] = r;
-                            else ((T*)p.C)[off[n] + e] = ET<T>::from_f(r);
+                            if constexpr (IS_DW) {
+                                if (upd) update_one(p, off[n] + e, r, lrk);
+                                if (keep_g) cf[off[n] + e] = r;
+                            } else {
+                                if (out_f32) cf[off[n] + e] = r;
+                                else ((T*)p.C)[off[n] + e] = ET<T>::from_f(r);
+                            }
                         }
                         continue;
                     }
@@ -1051,7 +1080,28 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                         for (int e = 0; e < 8; ++e)
                             if (accum) v[e] += old[e];
                     }
-                    if (out_f32) {
+                    if constexpr (IS_DW) {
+                        if (upd) {
+                            float w[8];
+#pragma unroll
+                            for (int d = 0; d < 4; ++d) {
+                                w[d] = sgd_apply(wv[n][0][d], v[d], lrk);
+                                w[4 + d] = sgd_apply(wv[n][1][d], v[4 + d], lrk);
+                            }
+                            *reinterpret_cast<f32x4_t*>(p.upd_w + off[n]) = f32x4_t{w[0], w[1], w[2], w[3]};
+                            *reinterpret_cast<f32x4_t*>(p.upd_w + off[n] + 4) = f32x4_t{w[4], w[5], w[6], w[7]};
+                            if (p.upd_shadow) {
+                                u32x4_t o;
+#pragma unroll
+                                for (int d = 0; d < 4; ++d) o[d] = pack2bf(w[2 * d], w[2 * d + 1]);
+                                *reinterpret_cast<u32x4_t*>((bf16_t*)p.upd_shadow + off[n]) = o;
+                            }
+                        }
+                        if (keep_g) {
+                            *reinterpret_cast<f32x4_t*>(cf + off[n]) = f32x4_t{v[0], v[1], v[2], v[3]};
+                            *reinterpret_cast<f32x4_t*>(cf + off[n] + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
+                        }
+                    } else if (out_f32) {
                         *reinterpret_cast<f32x4_t*>(cf + off[n]) = f32x4_t{v[0], v[1], v[2], v[3]};
                         *reinterpret_cast<f32x4_t*>(cf + off[n] + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
                     } else if constexpr (sizeof(T) == 2) {
@@ -1073,11 +1123,21 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
             if (row >= p.R || col >= p.Q) continue;
             const size_t off = out_row_base(p, row) + col;
             const float r = finish(stage[lr][lc], row, col, off);
-            if (out_f32) cf[off] = r;
-            else ((T*)p.C)[off] = ET<T>::from_f(r);
+            if constexpr (IS_DW) {
+                if (upd) update_one(p, off, r, lrk);
+                if (keep_g) cf[off] = r;
+            } else {
+                if (out_f32) cf[off] = r;
+                else ((T*)p.C)[off] = ET<T>::from_f(r);
+            }
         }
     }
 }
+
+// weight-gradient kernels also take the step's learning rates (by value), the others nothing
+struct NoLr {};
+template <int MODE>
+using LrArg = typename std::conditional<MODE == LIN_DW || MODE == CONV_DW, LrTable, NoLr>::type;
 
 // VEC = true: every problem of the launch has both operands aligned for 16-byte loads (the planner
 // sorts problems into launches by that); VEC = false: the element-by-element gather for any shape.
@@ -1086,7 +1146,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
 template <int MODE, typename T, int BM, int BN, int BKM, bool VEC>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ probs,
                                                    const TileRef* __restrict__ tiles,
-                                                   const void* __restrict__ x) {
+                                                   const void* __restrict__ x, LrArg<MODE> lr) {
     constexpr int BK = ET<T>::BK * BKM;
     const TileRef tr = tiles[blockIdx.x];
     if (tr.prob < 0) return;
@@ -1101,43 +1161,48 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
     __shared__ __attribute__((aligned(16))) T lds[2 * BM * TileGeom<T, BM, BK>::LDS_LD + 2 * BN * TileGeom<T, BN, BK>::LDS_LD];
     T* const As = lds;
     T* const Bs = lds + 2 * BM * TileGeom<T, BM, BK>::LDS_LD;
-    gemm_body<MODE, T, BM, BN, BKM, VEC>(p, tr, As, Bs);
+    float lrk = 0.f;
+    if constexpr (MODE == LIN_DW || MODE == CONV_DW) lrk = lr.lr[p.member];
+    gemm_body<MODE, T, BM, BN, BKM, VEC>(p, tr, As, Bs, lrk);
 }
 
 template <int MODE, typename T>
-static void launch_gemm_tile(int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, hipStream_t st) {
+static void launch_gemm_tile(int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, const LrTable& lr, hipStream_t st) {
+    LrArg<MODE> la;
+    if constexpr (MODE == LIN_DW || MODE == CONV_DW) la = lr;
     switch (tile_cfg) {
-        case 0: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 128, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
-        case 1: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 64, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
-        case 2: hipLaunchKernelGGL((gemm_kernel<MODE, T, 64, 64, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
-        default: hipLaunchKernelGGL((gemm_kernel<MODE, T, 64, 64, 1, false>), dim3(n), dim3(256), 0, st, probs, tiles, x); break;
+        case 0: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 128, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, la); break;
+        case 1: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 64, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, la); break;
+        case 2: hipLaunchKernelGGL((gemm_kernel<MODE, T, 64, 64, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, la); break;
+        default: hipLaunchKernelGGL((gemm_kernel<MODE, T, 64, 64, 1, false>), dim3(n), dim3(256), 0, st, probs, tiles, x, la); break;
     }
 }
 
 template <int MODE>
-static hipError_t launch_gemm_mode(bool bf16, int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, hipStream_t st) {
-    if (bf16) launch_gemm_tile<MODE, bf16_t>(tile_cfg, probs, tiles, n, x, st);
-    else launch_gemm_tile<MODE, float>(tile_cfg, probs, tiles, n, x, st);
+static hipError_t launch_gemm_mode(bool bf16, int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, const LrTable& lr, hipStream_t st) {
+    if (bf16) launch_gemm_tile<MODE, bf16_t>(tile_cfg, probs, tiles, n, x, lr, st);
+    else launch_gemm_tile<MODE, float>(tile_cfg, probs, tiles, n, x, lr, st);
     return hipGetLastError();
 }
 
-hipError_t launch_gemm(int mode, bool bf16, int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, hipStream_t st) {
+hipError_t launch_gemm(int mode, bool bf16, int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, const LrTable& lr, hipStream_t st) {
     if (n <= 0) return hipSuccess;
     switch (mode) {
-        case LIN_FWD: return launch_gemm_mode<LIN_FWD>(bf16, tile_cfg, probs, tiles, n, x, st);
-        case LIN_DX: return launch_gemm_mode<LIN_DX>(bf16, tile_cfg, probs, tiles, n, x, st);
-        case LIN_DW: return launch_gemm_mode<LIN_DW>(bf16, tile_cfg, probs, tiles, n, x, st);
-        case CONV_FWD: return launch_gemm_mode<CONV_FWD>(bf16, tile_cfg, probs, tiles, n, x, st);
-        case CONV_DX: return launch_gemm_mode<CONV_DX>(bf16, tile_cfg, probs, tiles, n, x, st);
-        case CONV_DW: return launch_gemm_mode<CONV_DW>(bf16, tile_cfg, probs, tiles, n, x, st);
+        case LIN_FWD: return launch_gemm_mode<LIN_FWD>(bf16, tile_cfg, probs, tiles, n, x, lr, st);
+        case LIN_DX: return launch_gemm_mode<LIN_DX>(bf16, tile_cfg, probs, tiles, n, x, lr, st);
+        case LIN_DW: return launch_gemm_mode<LIN_DW>(bf16, tile_cfg, probs, tiles, n, x, lr, st);
+        case CONV_FWD: return launch_gemm_mode<CONV_FWD>(bf16, tile_cfg, probs, tiles, n, x, lr, st);
+        case CONV_DX: return launch_gemm_mode<CONV_DX>(bf16, tile_cfg, probs, tiles, n, x, lr, st);
+        case CONV_DW: return launch_gemm_mode<CONV_DW>(bf16, tile_cfg, probs, tiles, n, x, lr, st);
         default: return hipErrorInvalidValue;
     }
 }
 
 // out[e] = sum over S partials, in order
-__global__ __launch_bounds__(256) void reduce_kernel(const ReduceProb* __restrict__ probs, const int2* __restrict__ map) {
+__global__ __launch_bounds__(256) void reduce_kernel(const ReduceProb* __restrict__ probs, const int2* __restrict__ map, LrTable lr) {
     const int2 m = map[blockIdx.x];
     const ReduceProb p = probs[m.x];
+    const float lrk = p.upd_w ? lr.lr[p.member] : 0.f;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int e = m.y * 1024 + i * 256 + threadIdx.x;
@@ -1152,14 +1217,19 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceProb* __restric
 #pragma unroll
                 for (int j = 0; j < 8; ++j) s += v[j];
             }
-            p.out[e] = s;
+            if (p.upd_w) {   // fused update: the summed gradient goes straight into the weights
+                const float w = sgd_apply(p.upd_w[e], s, lrk);
+                p.upd_w[e] = w;
+                if (p.upd_shadow) ((bf16_t*)p.upd_shadow)[e] = ET<bf16_t>::from_f(w);
+            }
+            if (!p.upd_w || p.keep_g) p.out[e] = s;
         }
     }
 }
 
-hipError_t launch_reduce(const ReduceProb* probs, const int2* map, int n, hipStream_t st) {
+hipError_t launch_reduce(const ReduceProb* probs, const int2* map, int n, const LrTable& lr, hipStream_t st) {
     if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(reduce_kernel, dim3(n), dim3(256), 0, st, probs, map);
+    hipLaunchKernelGGL(reduce_kernel, dim3(n), dim3(256), 0, st, probs, map, lr);
     return hipGetLastError();
 }
 
@@ -1456,10 +1526,10 @@ __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ w, const f
             while (mdl < K - 1 && idx[i] >= s_end[mdl]) ++mdl;
             const float r = s_lr[mdl];
             f32x4_t o;
-            o.x = wv[i].x - r * gv[i].x;
-            o.y = wv[i].y - r * gv[i].y;
-            o.z = wv[i].z - r * gv[i].z;
-            o.w = wv[i].w - r * gv[i].w;
+            o.x = sgd_apply(wv[i].x, gv[i].x, r);
+            o.y = sgd_apply(wv[i].y, gv[i].y, r);
+            o.z = sgd_apply(wv[i].z, gv[i].z, r);
+            o.w = sgd_apply(wv[i].w, gv[i].w, r);
             // streaming stores: nothing re-reads these lines before they leave the caches
             __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t*>(w + idx[i]));
             if constexpr (SHADOW) {
@@ -1543,7 +1613,7 @@ __global__ __launch_bounds__(256) void opt_kernel(float* __restrict__ w, const f
         const f32x4_t gg = gv[i];
         if (o.kind == OPT_SGD) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) wo[e] = wo[e] - lr * gg[e];
+            for (int e = 0; e < 4; ++e) wo[e] = sgd_apply(wo[e], gg[e], lr);
         } else if (o.kind == OPT_MOMENTUM) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {

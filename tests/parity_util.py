@@ -33,6 +33,8 @@ def run_gpu(w: wl.PackWorkload, steps=None, lr=None, x_dev=None, y_dev=None, kee
         if opts:
             for k in range(w.K):
                 pk.set_optimizer(k, opts[k])
+        if keep_first_grads:
+            pk.keep_grads(True)
         if x_dev is None:
             x_dev, y_dev = device_inputs(w)
         loss = np.zeros((steps, w.K), dtype=np.float64)
