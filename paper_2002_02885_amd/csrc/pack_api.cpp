@@ -80,9 +80,11 @@ struct ModelInfo {
     size_t arena_begin = 0, arena_end = 0;
     int* pred = nullptr;
     float* loss = nullptr;
+    bool fused_head = false;         // classifier head (last linear layer, loss, its input gradient) runs in one kernel
+    float* head_partial = nullptr;   // per-block loss sums of that kernel
 };
 
-enum LaunchKind { L_GEMM, L_REDUCE, L_CE, L_GAP_FWD, L_GAP_BWD, L_SHORTCUT, L_SGD, L_IM2COL, L_WTRANS };
+enum LaunchKind { L_GEMM, L_REDUCE, L_CE, L_GAP_FWD, L_GAP_BWD, L_SHORTCUT, L_SGD, L_IM2COL, L_WTRANS, L_HEAD };
 
 struct Launch {
     int kind = 0, mode = 0;
@@ -134,6 +136,8 @@ struct pack_ctx {
     bool own_input = false;           // members read their own block of the step's input instead of one shared batch
     bool fused = false;               // all members use plain SGD: the update is applied in the weight-gradient kernels
     bool keep_grads = false;          // fused packs: store the gradients as well (pack_read_grads)
+    size_t head_desc_off = 0;         // problem table of the classifier-head launch
+    int n_heads = 0;
     std::vector<long long> im2col_xoff;   // byte offset of each loader's source in the step's input
     std::vector<Launch> plan;
     size_t device_bytes = 0;
@@ -393,12 +397,13 @@ double padded_work(const GemmProb& g, int c) {
 void emit_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, int cfg, const std::vector<GemmProb>& probs) {
     const int BMc = GEMM_TILE_M[cfg], BNc = GEMM_TILE_N[cfg];
     std::vector<TileOrder> logical;
+    const bool dw_cols_fastest = std::getenv("PACK_DW_COLS_FASTEST") != nullptr;
     for (size_t i = 0; i < probs.size(); ++i) {
         const GemmProb& g = probs[i];
         const int tms = (g.R + BMc - 1) / BMc, tns = (g.Q + BNc - 1) / BNc;
         const int S = (g.Kd + g.ksplit - 1) / g.ksplit;
         for (int ks = 0; ks < std::max(S, 1); ++ks) {
-            if (mode == CONV_FWD || mode == CONV_DX) {
+            if (mode == CONV_FWD || mode == CONV_DX || ((mode == LIN_DW || mode == CONV_DW) && dw_cols_fastest)) {
                 for (int tm = 0; tm < tms; ++tm)
                     for (int tn = 0; tn < tns; ++tn) logical.push_back({(int)i, tm, tn, ks});
             } else {
@@ -496,8 +501,10 @@ void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<G
     // half of a 128-wide tile); the launch as a whole needs enough workgroups to fill the 256
     // compute units about twice.  Problems whose preferred shape carries little of the work
     // ride along in the main launch rather than paying for a launch of their own.
+    size_t min_tiles = 512;
+    if (const char* v = std::getenv("PACK_MIN_TILES")) min_tiles = (size_t)std::max(1, std::atoi(v));   // tuning knob
     int floor_cfg = 0;
-    while (floor_cfg < 2 && count_tiles(probs, floor_cfg) < 512) ++floor_cfg;
+    while (floor_cfg < 2 && count_tiles(probs, floor_cfg) < min_tiles) ++floor_cfg;
     std::vector<int> want(probs.size());
     double work[3] = {0, 0, 0}, total = 0;
     for (size_t i = 0; i < probs.size(); ++i) {
@@ -599,6 +606,7 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 gap_blocks.push_back((ti.n * ti.c + 255) / 256);
                 continue;
             }
+            if (m.fused_head && s + 1 == m.nodes.size()) continue;   // part of the head kernel
             GemmProb g{};
             g.zeros = p->zeros;
             g.x_off = x_off(m);
@@ -658,9 +666,26 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
     // ---------------- loss ----------------
     {
         std::vector<CeProb> ce;
+        std::vector<HeadProb> heads;
+        std::vector<int> head_blocks;
         for (ModelInfo& m : p->models) {
             if (m.vacant) continue;
             const TensorInfo& lg = m.tensors[m.nodes.back().out_t];
+            if (m.fused_head) {
+                const NodeInfo& nd = m.nodes.back();
+                const TensorInfo& ti = m.tensors[nd.in_t];
+                HeadProb h{};
+                h.h = ti.act; h.W = weight_ptr(nd); h.bias = p->master + nd.b_off;
+                h.logits = (float*)lg.act; h.dlogits = lg.dz; h.dh = ti.needs_grad ? ti.dz : nullptr;
+                h.pred = m.pred; h.loss = m.loss; h.partial = m.head_partial;
+                h.rows = m.batch; h.C = m.C; h.Kd = nd.fan_in; h.ldd = lg.ld_dz;
+                h.label_off = p->own_input ? (int)(&m - p->models.data()) * p->in.B : 0;
+                h.mask_act = ti.act_out;
+                h.nblk = (m.batch + HEAD_ROWS - 1) / HEAD_ROWS;
+                heads.push_back(h);
+                head_blocks.push_back(h.nblk);
+                continue;
+            }
             CeProb c{};
             c.logits = (const float*)lg.act; c.dlogits = lg.dz; c.pred = m.pred; c.loss = m.loss;
             c.rows = m.batch; c.C = m.C; c.ld = m.C; c.ldd = lg.ld_dz;
@@ -674,6 +699,9 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
             L.n = (int)ce.size();
             p->plan.push_back(L);
         }
+        add_mapped_launch(p, db, L_HEAD, heads, head_blocks);
+        p->n_heads = (int)heads.size();
+        if (!heads.empty()) p->head_desc_off = p->plan.back().desc_off;
     }
 
     // ---------------- backward ----------------
@@ -795,8 +823,10 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 if (dense) lin_dw.push_back(g);
                 else conv_dw.push_back(g);
             }
-            // input gradient
-            if (ti.needs_grad) {
+            // input gradient (the head kernel has already written it for a fused classifier head)
+            if (m.fused_head && s + 1 == m.nodes.size()) {
+                if (ti.needs_grad) ti.grad_written = true;
+            } else if (ti.needs_grad) {
                 GemmProb g{};
                 g.zeros = p->zeros;
                 g.A = to.dz;
@@ -1036,6 +1066,16 @@ pack_status build_device(pack_ctx* p) {
         fix.push_back({&ip.out, reserve((size_t)ip.B * ip.Ho * ip.Wo * ip.Kp * esz)});
     for (ModelInfo& m : p->models) {
         if (m.vacant) continue;
+        {   // few classes: logits, loss and the input gradient of the last layer in one kernel
+            const NodeInfo& last = m.nodes.back();
+            const TensorInfo& hin = m.tensors[last.in_t];
+            m.fused_head = !std::getenv("PACK_NO_FUSED_HEAD") && m.C <= HEAD_MAX_C && !hin.is_input &&
+                           last.fan_in % (p->bf16 ? 8 : 4) == 0;
+            if (m.fused_head) {
+                const int nblk = (m.batch + HEAD_ROWS - 1) / HEAD_ROWS;
+                fix.push_back({(void**)&m.head_partial, reserve((size_t)nblk * 4)});
+            }
+        }
         for (TensorInfo& t : m.tensors) {
             if (t.is_input) continue;
             fix.push_back({&t.act, reserve(t.elems() * (t.f32 ? 4 : esz))});
@@ -1357,6 +1397,7 @@ pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, c
                 break;
             case L_REDUCE: e = launch_reduce((const ReduceProb*)d, (const int2*)mp, L.n, lr, p->stream); break;
             case L_CE: e = launch_ce(bf, (const CeProb*)d, L.n, labels_dev, p->err_flag, p->stream); break;
+            case L_HEAD: e = launch_head(bf, (const HeadProb*)d, (const int2*)mp, L.n, labels_dev, p->err_flag, p->stream); break;
             case L_GAP_FWD: e = launch_gap(bf, false, (const GapProb*)d, (const int2*)mp, L.n, p->stream); break;
             case L_GAP_BWD: e = launch_gap(bf, true, (const GapProb*)d, (const int2*)mp, L.n, p->stream); break;
             case L_SHORTCUT: e = launch_shortcut_bwd(bf, (const ShortcutProb*)d, (const int2*)mp, L.n, p->stream); break;
@@ -1425,7 +1466,7 @@ pack_status pack_launch_name(const pack_t* p, int32_t i, char* buf, size_t n) {
     if (!p || !buf || n == 0) return fail(PACK_EINVAL, "null argument");
     if (i < 0 || i >= (int32_t)p->plan.size()) return fail(PACK_EINVAL, "launch index out of range");
     static const char* gemm_names[] = {"gemm_lin_fwd", "gemm_lin_dx", "gemm_lin_dw", "gemm_conv_fwd", "gemm_conv_dx", "gemm_conv_dw"};
-    static const char* names[] = {"", "reduce_partials", "softmax_xent", "gap_fwd", "gap_bwd", "shortcut_bwd", "sgd_update", "im2col_shared_input", "transpose_conv_weights"};
+    static const char* names[] = {"", "reduce_partials", "softmax_xent", "gap_fwd", "gap_bwd", "shortcut_bwd", "sgd_update", "im2col_shared_input", "transpose_conv_weights", "classifier_head"};
     const Launch& L = p->plan[i];
     const char* nm = (L.kind == L_GEMM) ? gemm_names[L.mode] : names[L.kind];
     if (L.kind == L_SGD && p->any_opt) nm = "optimizer_update";
@@ -1568,6 +1609,8 @@ pack_status pack_gather_batch(pack_t* p, const void* data_dev, const int32_t* la
 
 pack_status pack_read_loss(pack_t* p, float* host_dst) {
     if (!p || !host_dst) return fail(PACK_EINVAL, "null argument");
+    // members with a fused classifier head leave per-block sums; add them up now, in block order
+    if (p->n_heads) HIP_TRY(launch_head_loss((const HeadProb*)(p->desc + p->head_desc_off), p->n_heads, p->stream), PACK_EDEVICE);
     HIP_TRY(hipStreamSynchronize(p->stream), PACK_EDEVICE);
     HIP_TRY(hipMemcpy(host_dst, p->loss_all, (size_t)p->K * 4, hipMemcpyDeviceToHost), PACK_EDEVICE);
     int flag = 0;

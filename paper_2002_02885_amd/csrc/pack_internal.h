@@ -98,6 +98,21 @@ struct CeProb {       // softmax cross-entropy of one member
     int label_off;         // first label of the member in the step's label vector
 };
 
+struct HeadProb {     // classifier head of one member in one kernel: logits, softmax cross-entropy, dlogits, input gradient
+    const void* h;         // [rows, Kd] pack dtype: the activations the last linear layer reads
+    const void* W;         // [C, Kd] pack dtype (operand copy of the weights)
+    const float* bias;     // [C]
+    float* logits;         // [rows, C]
+    void* dlogits;         // [rows, ldd] pack dtype
+    void* dh;              // [rows, Kd] pack dtype: gradient wrt h, or null when nothing upstream needs it
+    int* pred;             // [rows]
+    float* loss;           // scalar
+    float* partial;        // [nblk] per-block loss sums
+    int rows, C, Kd, ldd, label_off, mask_act, nblk;
+};
+constexpr int HEAD_ROWS = 16;      // rows one block of the head kernel handles
+constexpr int HEAD_MAX_C = 16;     // classes the head kernel keeps in registers
+
 struct GapProb {      // global average pool: in [n, hw, c] -> out [n, c]
     const void* in;
     void* out;
@@ -138,6 +153,9 @@ hipError_t launch_gemm(int mode, bool bf16, int tile_cfg, const GemmProb* probs_
                        int n_tiles, const void* x_dev, const LrTable& lr, hipStream_t st);
 hipError_t launch_reduce(const ReduceProb* probs_dev, const int2* map_dev, int n_blocks, const LrTable& lr, hipStream_t st);
 hipError_t launch_ce(bool bf16, const CeProb* probs_dev, int K, const int32_t* labels, int* err_flag, hipStream_t st);
+hipError_t launch_head(bool bf16, const HeadProb* probs_dev, const int2* map_dev, int n_blocks, const int32_t* labels,
+                       int* err_flag, hipStream_t st);
+hipError_t launch_head_loss(const HeadProb* probs_dev, int n_members, hipStream_t st);
 hipError_t launch_gap(bool bf16, bool backward, const GapProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);
 hipError_t launch_shortcut_bwd(bool bf16, const ShortcutProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);
 hipError_t launch_sgd(float* master, const float* grad, void* shadow_bf16, long long n,

@@ -917,6 +917,22 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
     constexpr int SLD = BN + 8;   // 4 rows apart = 32 banks apart: the two half-waves do not collide
     static_assert((size_t)BM * SLD * 4 <= (size_t)2 * (BM * GA::LDS_LD + BN * GB::LDS_LD) * sizeof(T), "staging tile must fit");
     float(*stage)[SLD] = reinterpret_cast<float(*)[SLD]>(As_);
+    // Weight-gradient tiles with the fused update: a thread owns four consecutive columns (one
+    // 16-byte vector of fp32 weights) in DW_NIT rows, and requests all its weights now, so that
+    // their round trip runs under the staging of the accumulators instead of after it.
+    constexpr int DW_G = BN / 4, DW_NIT = BM * DW_G / 256, DW_RSTEP = 256 / DW_G;
+    const int dw_lc = (threadIdx.x % DW_G) * 4, dw_lr0 = threadIdx.x / DW_G;
+    const bool dw_full = vec_out && (col0 + dw_lc + 4 <= p.Q);
+    f32x4_t dw_w[IS_DW ? DW_NIT : 1];
+    if constexpr (IS_DW) {
+        if (upd && dw_full) {
+#pragma unroll
+            for (int n = 0; n < DW_NIT; ++n) {
+                const int row = row0 + dw_lr0 + n * DW_RSTEP;
+                if (row < p.R) dw_w[n] = *reinterpret_cast<const f32x4_t*>(p.upd_w + (size_t)row * p.ldc + col0 + dw_lc);
+            }
+        }
+    }
     __syncthreads();   // every wave is done with the operand tiles
 #pragma unroll
     for (int a = 0; a < TM; ++a)
@@ -927,8 +943,53 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                 stage[wm * (BM / 2) + a * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)][wn * (BN / 2) + b * 32 + (lane & 31)] = acc[a][b][e];
     __syncthreads();
 
+    if constexpr (IS_DW) {
+        float* const gf = (float*)p.C + (size_t)tr.ks * p.split_stride;
+        if (vec_out) {
+            const int col = col0 + dw_lc;
+            if (col < p.Q) {
+#pragma unroll
+                for (int n = 0; n < DW_NIT; ++n) {
+                    const int lr = dw_lr0 + n * DW_RSTEP, row = row0 + lr;
+                    if (row >= p.R) continue;
+                    const size_t off = (size_t)row * p.ldc + col;
+                    const f32x4_t g = *reinterpret_cast<const f32x4_t*>(&stage[lr][dw_lc]);
+                    if (!dw_full) {   // ragged right edge: element by element
+                        for (int e = 0; e < 4 && col + e < p.Q; ++e) {
+                            if (upd) update_one(p, off + e, g[e], lrk);
+                            if (keep_g) gf[off + e] = g[e];
+                        }
+                        continue;
+                    }
+                    if (upd) {
+                        f32x4_t w;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) w[e] = sgd_apply(dw_w[n][e], g[e], lrk);
+                        __builtin_nontemporal_store(w, reinterpret_cast<f32x4_t*>(p.upd_w + off));
+                        if (p.upd_shadow) {
+                            typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
+                            __builtin_nontemporal_store(u32x2_t{pack2bf(w[0], w[1]), pack2bf(w[2], w[3])},
+                                                        reinterpret_cast<u32x2_t*>((bf16_t*)p.upd_shadow + off));
+                        }
+                    }
+                    if (keep_g) *reinterpret_cast<f32x4_t*>(gf + off) = g;
+                }
+            }
+        } else {
+            for (int idx = threadIdx.x; idx < BM * BN; idx += 256) {
+                const int lr = idx / BN, lc = idx % BN;
+                const int row = row0 + lr, col = col0 + lc;
+                if (row >= p.R || col >= p.Q) continue;
+                const size_t off = (size_t)row * p.ldc + col;
+                if (upd) update_one(p, off, stage[lr][lc], lrk);
+                if (keep_g) gf[off] = stage[lr][lc];
+            }
+        }
+        return;
+    }
+
     constexpr bool IS_FWD = (MODE == LIN_FWD || MODE == CONV_FWD);
-    const bool out_f32 = IS_DW || (IS_FWD && (p.flags & F_OUT_F32));
+    const bool out_f32 = IS_FWD && (p.flags & F_OUT_F32);
     // element-wise tail of one output element; `v` comes from the staging tile
     auto finish = [&](float v, int row, int col, size_t off) -> float {
         if constexpr (IS_FWD) {
@@ -953,7 +1014,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
         }
         return v;
     };
-    float* const cf = (float*)p.C + (IS_DW ? (size_t)tr.ks * p.split_stride : (size_t)0);
+    float* const cf = (float*)p.C;
 
     // vector form: 8 consecutive columns per thread (two 16-byte LDS reads); needs aligned rows.
     // A thread keeps its column group for all its rows.  What the tail reads from global memory
@@ -974,7 +1035,6 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                 size_t off[BATCH];
                 bool live[BATCH];
                 ev_t auxv[BATCH][EV], oldv[BATCH][EV];
-                f32x4_t wv[IS_DW ? BATCH : 1][2];
 #pragma unroll
                 for (int n = 0; n < BATCH; ++n) {
                     const int row = row0 + lr0 + (n0 + n) * RSTEP;
@@ -1010,12 +1070,6 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                         else oz = f32x4_t{0.f, 0.f, 0.f, 0.f};
                         oldv[n][h] = op ? *reinterpret_cast<const ev_t*>(op + h * 4) : oz;
                     }
-                    if constexpr (IS_DW) {
-                        if (upd && live[n] && full) {
-                            wv[n][0] = *reinterpret_cast<const f32x4_t*>(p.upd_w + off[n]);
-                            wv[n][1] = *reinterpret_cast<const f32x4_t*>(p.upd_w + off[n] + 4);
-                        }
-                    }
                 }
 #pragma unroll
                 for (int n = 0; n < BATCH; ++n) {
@@ -1032,13 +1086,8 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                     if (!full) {   // ragged right edge: element by element
                         for (int e = 0; e < 8 && col + e < p.Q; ++e) {
                             const float r = finish(v[e], row, col + e, off[n] + e);
-                            if constexpr (IS_DW) {
-                                if (upd) update_one(p, off[n] + e, r, lrk);
-                                if (keep_g) cf[off[n] + e] = r;
-                            } else {
-                                if (out_f32) cf[off[n] + e] = r;
-                                else ((T*)p.C)[off[n] + e] = ET<T>::from_f(r);
-                            }
+                            if (out_f32) cf[off[n] + e] = r;
+                            else ((T*)p.C)[off[n] + e] = ET<T>::from_f(r);
                         }
                         continue;
                     }
@@ -1080,28 +1129,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                         for (int e = 0; e < 8; ++e)
                             if (accum) v[e] += old[e];
                     }
-                    if constexpr (IS_DW) {
-                        if (upd) {
-                            float w[8];
-#pragma unroll
-                            for (int d = 0; d < 4; ++d) {
-                                w[d] = sgd_apply(wv[n][0][d], v[d], lrk);
-                                w[4 + d] = sgd_apply(wv[n][1][d], v[4 + d], lrk);
-                            }
-                            *reinterpret_cast<f32x4_t*>(p.upd_w + off[n]) = f32x4_t{w[0], w[1], w[2], w[3]};
-                            *reinterpret_cast<f32x4_t*>(p.upd_w + off[n] + 4) = f32x4_t{w[4], w[5], w[6], w[7]};
-                            if (p.upd_shadow) {
-                                u32x4_t o;
-#pragma unroll
-                                for (int d = 0; d < 4; ++d) o[d] = pack2bf(w[2 * d], w[2 * d + 1]);
-                                *reinterpret_cast<u32x4_t*>((bf16_t*)p.upd_shadow + off[n]) = o;
-                            }
-                        }
-                        if (keep_g) {
-                            *reinterpret_cast<f32x4_t*>(cf + off[n]) = f32x4_t{v[0], v[1], v[2], v[3]};
-                            *reinterpret_cast<f32x4_t*>(cf + off[n] + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
-                        }
-                    } else if (out_f32) {
+                    if (out_f32) {
                         *reinterpret_cast<f32x4_t*>(cf + off[n]) = f32x4_t{v[0], v[1], v[2], v[3]};
                         *reinterpret_cast<f32x4_t*>(cf + off[n] + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
                     } else if constexpr (sizeof(T) == 2) {
@@ -1123,13 +1151,8 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
             if (row >= p.R || col >= p.Q) continue;
             const size_t off = out_row_base(p, row) + col;
             const float r = finish(stage[lr][lc], row, col, off);
-            if constexpr (IS_DW) {
-                if (upd) update_one(p, off, r, lrk);
-                if (keep_g) cf[off] = r;
-            } else {
-                if (out_f32) cf[off] = r;
-                else ((T*)p.C)[off] = ET<T>::from_f(r);
-            }
+            if (out_f32) cf[off] = r;
+            else ((T*)p.C)[off] = ET<T>::from_f(r);
         }
     }
 }
@@ -1350,6 +1373,236 @@ __global__ __launch_bounds__(64 * CE_WAVES) void ce_kernel(const CeProb* __restr
 hipError_t launch_ce(bool bf16, const CeProb* probs, int K, const int32_t* labels, int* err_flag, hipStream_t st) {
     if (bf16) hipLaunchKernelGGL(ce_kernel<bf16_t>, dim3(K), dim3(64 * CE_WAVES), 0, st, probs, labels, err_flag);
     else hipLaunchKernelGGL(ce_kernel<float>, dim3(K), dim3(64 * CE_WAVES), 0, st, probs, labels, err_flag);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Classifier head in one kernel (few classes): logits = h W^T + b, softmax cross-entropy with its
+// gradient and the argmax, and the gradient wrt h.  With ten classes the three matrix products
+// around the loss are a few MFLOP each and cost a launch apiece at the dispatch floor; here a
+// block takes HEAD_ROWS rows of one member, eight lanes share a row (each a 16-byte slice of every
+// 128 bytes of it) and keep the C partial sums in registers.  Every sum has a fixed order: a
+// lane's slices in ascending k, the eight lanes by a butterfly, rows of a block in row order,
+// blocks of a member in block order (by a small kernel when the loss is read), classes ascending
+// in the input gradient.  Rounding points are those of the separate kernels: dlogits is rounded
+// to the pack dtype before it is multiplied with the weights.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void head_kernel(const HeadProb* __restrict__ probs, const int2* __restrict__ map,
+                                                   const int32_t* __restrict__ labels, int* __restrict__ err_flag) {
+    constexpr int V = ET<T>::V;
+    constexpr int LPR = 256 / HEAD_ROWS;   // lanes that share a row
+    constexpr int KCH = 128 * V;           // reduction indices per pass (the weights of a pass sit in LDS)
+    constexpr int NV = KCH / (LPR * V);    // 16-byte vectors of a row a lane handles per pass
+    typedef typename std::conditional<sizeof(T) == 2, u32x4_t, f32x4_t>::type vec_t;
+    __shared__ __attribute__((aligned(16))) T Ws[HEAD_MAX_C][KCH];
+    __shared__ float row_losses[HEAD_ROWS];
+    const int2 mb = map[blockIdx.x];
+    const HeadProb p = probs[mb.x];
+    const int kl = threadIdx.x % LPR, lr = threadIdx.x / LPR;
+    const int row = mb.y * HEAD_ROWS + lr;
+    const bool active = row < p.rows;
+    const T* hrow = (const T*)p.h + (size_t)(active ? row : 0) * p.Kd;
+    const int nch = (p.Kd + KCH - 1) / KCH;
+    auto unpack = [](const vec_t& v, float (&f)[V]) {
+        if constexpr (sizeof(T) == 2) {
+#pragma unroll
+            for (int d = 0; d < 4; ++d) { f[2 * d] = __uint_as_float(v[d] << 16); f[2 * d + 1] = __uint_as_float(v[d] & 0xffff0000u); }
+        } else {
+#pragma unroll
+            for (int d = 0; d < 4; ++d) f[d] = v[d];
+        }
+    };
+    vec_t zero_v;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) zero_v[d] = 0;
+    vec_t hv[NV];
+    // all of a pass's loads are requested before any is used: the lane's slices of its row ...
+    auto load_h = [&](int ch) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int k = ch * KCH + (j * LPR + kl) * V;
+            hv[j] = (active && k < p.Kd) ? *reinterpret_cast<const vec_t*>(hrow + k) : zero_v;
+        }
+    };
+    // ... and the block's share of the weights of the pass, which go to LDS
+    auto stage_w = [&](int ch) {
+        constexpr int VPR = KCH / V;   // vectors per class row of the pass
+        for (int i0 = 0; i0 < HEAD_MAX_C * VPR; i0 += 4 * 256) {
+            vec_t wv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int idx = i0 + u * 256 + threadIdx.x;
+                const int c = idx / VPR, k = ch * KCH + (idx % VPR) * V;
+                wv[u] = (c < p.C && k < p.Kd) ? *reinterpret_cast<const vec_t*>((const T*)p.W + (size_t)c * p.Kd + k) : zero_v;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int idx = i0 + u * 256 + threadIdx.x;
+                if (idx < HEAD_MAX_C * VPR) *reinterpret_cast<vec_t*>(&Ws[idx / VPR][(idx % VPR) * V]) = wv[u];
+            }
+        }
+    };
+
+    // ---- logits ----
+    float acc[HEAD_MAX_C];
+#pragma unroll
+    for (int c = 0; c < HEAD_MAX_C; ++c) acc[c] = 0.f;
+    for (int ch = 0; ch < nch; ++ch) {
+        if (ch > 0) __syncthreads();   // the previous pass's weights are no longer read
+        load_h(ch);
+        stage_w(ch);
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            float hf[V];
+            unpack(hv[j], hf);
+            // all HEAD_MAX_C rows, without a branch on the class count (rows beyond it hold zeros), so
+            // that the LDS reads of a slice are requested together
+            vec_t wv[HEAD_MAX_C];
+#pragma unroll
+            for (int c = 0; c < HEAD_MAX_C; ++c) wv[c] = *reinterpret_cast<const vec_t*>(&Ws[c][(j * LPR + kl) * V]);
+            __builtin_amdgcn_sched_barrier(0);   // keep the sixteen LDS reads together, ahead of their use
+#pragma unroll
+            for (int c = 0; c < HEAD_MAX_C; ++c) {
+                float wf[V];
+                unpack(wv[c], wf);
+#pragma unroll
+                for (int e = 0; e < V; ++e) acc[c] = __builtin_fmaf(hf[e], wf[e], acc[c]);
+            }
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < HEAD_MAX_C; ++c)
+#pragma unroll
+        for (int m = 1; m < LPR; m <<= 1) acc[c] += __shfl_xor(acc[c], m, 64);
+
+    // ---- softmax cross-entropy of the row (every lane of the row's group computes the same) ----
+    const int y = active ? labels[p.label_off + row] : 0;
+    const bool ok = (y >= 0 && y < p.C);
+    if (active && !ok && kl == 0) atomicOr(err_flag, 1);
+    float mx = -INFINITY, zy = 0.f;
+    int arg = 0;
+    float bias[HEAD_MAX_C];
+#pragma unroll
+    for (int c = 0; c < HEAD_MAX_C; ++c) bias[c] = p.bias[c < p.C ? c : 0];
+#pragma unroll
+    for (int c = 0; c < HEAD_MAX_C; ++c) {
+        acc[c] = (c < p.C) ? acc[c] + bias[c] : -INFINITY;
+        if (acc[c] > mx) { mx = acc[c]; arg = c; }   // ascending class index: lowest among equals
+        if (c == y) zy = acc[c];
+    }
+    float ssum = 0.f;
+    float dz[HEAD_MAX_C];
+#pragma unroll
+    for (int c = 0; c < HEAD_MAX_C; ++c) {
+        dz[c] = expf(acc[c] - mx);   // exp(-inf) = 0 beyond the class count
+        ssum += dz[c];
+    }
+    const float inv_rows = 1.f / (float)p.rows, inv_s = 1.f / ssum;
+    const float row_loss = (active && ok) ? (mx + logf(ssum)) - zy : 0.f;
+#pragma unroll
+    for (int c = 0; c < HEAD_MAX_C; ++c) {
+        const float g = (ok && c < p.C) ? (dz[c] * inv_s - (c == y ? 1.f : 0.f)) * inv_rows : 0.f;
+        dz[c] = ET<T>::to_f(ET<T>::from_f(g));   // as stored: the input gradient multiplies the rounded value
+    }
+    if (active && kl == 0) {
+        float* zr = p.logits + (size_t)row * p.C;
+        T* dr = (T*)p.dlogits + (size_t)row * p.ldd;
+#pragma unroll
+        for (int c = 0; c < HEAD_MAX_C; ++c) {
+            if (c < p.C) {
+                zr[c] = acc[c];
+                dr[c] = ET<T>::from_f(dz[c]);
+            }
+        }
+        p.pred[row] = arg;
+    }
+    if (kl == 0) row_losses[lr] = row_loss;
+
+    // ---- gradient wrt h: dh[r, k] = act'(h[r, k]) * sum_c dz[r, c] W[c, k] ----
+    T* drow = (T*)p.dh + (size_t)(active ? row : 0) * p.Kd;
+    for (int ch = 0; ch < (p.dh ? nch : 0); ++ch) {
+        if (nch > 1) {   // a single pass still has its weights in LDS and its slices of h in registers
+            __syncthreads();
+            load_h(ch);
+            stage_w(ch);
+            __syncthreads();
+        }
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int k = ch * KCH + (j * LPR + kl) * V;
+            float o[V];
+#pragma unroll
+            for (int e = 0; e < V; ++e) o[e] = 0.f;
+            vec_t wv[HEAD_MAX_C];
+#pragma unroll
+            for (int c = 0; c < HEAD_MAX_C; ++c) wv[c] = *reinterpret_cast<const vec_t*>(&Ws[c][(j * LPR + kl) * V]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int c = 0; c < HEAD_MAX_C; ++c) {   // dz is zero beyond the class count
+                float wf[V];
+                unpack(wv[c], wf);
+#pragma unroll
+                for (int e = 0; e < V; ++e) o[e] = __builtin_fmaf(dz[c], wf[e], o[e]);
+            }
+            if (p.mask_act != ACT_NONE) {
+                float hf[V];
+                unpack(hv[j], hf);
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    if (p.mask_act == ACT_RELU) { if (!(hf[e] > 0.f)) o[e] = 0.f; }
+                    else o[e] *= act_deriv(p.mask_act, hf[e]);
+                }
+            }
+            vec_t out;
+            if constexpr (sizeof(T) == 2) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) out[d] = pack2bf(o[2 * d], o[2 * d + 1]);
+            } else {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) out[d] = o[d];
+            }
+            if (active && k < p.Kd) *reinterpret_cast<vec_t*>(drow + k) = out;
+        }
+    }
+
+    // ---- the block's share of the member's loss: its rows in row order ----
+    // (the blocks' sums are added in block order by head_loss_kernel when the loss is read)
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.f;
+        for (int r = 0; r < HEAD_ROWS; ++r) t += row_losses[r];
+        p.partial[mb.y] = t;
+    }
+}
+
+// loss of each member with a fused head = (sum of its blocks' sums, in block order) / rows
+__global__ __launch_bounds__(256) void head_loss_kernel(const HeadProb* __restrict__ probs) {
+    const HeadProb p = probs[blockIdx.x];
+    __shared__ float block_sums[256];
+    float total = 0.f;
+    for (int b0 = 0; b0 < p.nblk; b0 += 256) {
+        const int b = b0 + threadIdx.x;
+        block_sums[threadIdx.x] = (b < p.nblk) ? p.partial[b] : 0.f;
+        __syncthreads();
+        if (threadIdx.x == 0)
+            for (int i = 0; i < 256 && b0 + i < p.nblk; ++i) total += block_sums[i];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *p.loss = total * (1.f / (float)p.rows);
+}
+
+hipError_t launch_head_loss(const HeadProb* probs, int n_members, hipStream_t st) {
+    if (n_members <= 0) return hipSuccess;
+    hipLaunchKernelGGL(head_loss_kernel, dim3(n_members), dim3(256), 0, st, probs);
+    return hipGetLastError();
+}
+
+hipError_t launch_head(bool bf16, const HeadProb* probs, const int2* map, int n, const int32_t* labels, int* err_flag, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    if (bf16) hipLaunchKernelGGL(head_kernel<bf16_t>, dim3(n), dim3(256), 0, st, probs, map, labels, err_flag);
+    else hipLaunchKernelGGL(head_kernel<float>, dim3(n), dim3(256), 0, st, probs, map, labels, err_flag);
     return hipGetLastError();
 }
 
