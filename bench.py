@@ -25,16 +25,17 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
-# HBM bytes per launch of the update kernel on workload c2 from hardware counters (FETCH_SIZE and
-# WRITE_SIZE, each scaled by a copy kernel of known size; profiles/c2_sgd_update_hbm_counters.txt),
-# valid only for the kernel source it was measured on (hash of the kernel's text).
-SGD_TRAFFIC = {"workload": "c2", "bytes": 471.2e6, "kernel_sha": "ec085e8cf50b69f2"}
+# HBM bytes per launch of the dominant kernel of workload c2 (weight gradients with the SGD update in
+# the epilogue) from hardware counters (FETCH_SIZE and WRITE_SIZE, each scaled by a copy kernel of known
+# size; profiles/c2_weight_gradient_update_hbm_counters.txt), valid only for the kernel source it was
+# measured on (hash of the GEMM kernel's text).
+DW_TRAFFIC = {"workload": "c2", "kernel": "gemm_lin_dw+sgd", "bytes": 421.6e6, "kernel_sha": "feb4044e7603981c"}
 
 
-def _sgd_kernel_sha():
+def _gemm_kernel_sha():
     import hashlib
     src = open(os.path.join(ROOT, "paper_2002_02885_amd", "csrc", "pack_kernels.hip")).read()
-    a, b = src.index("template <bool SHADOW>"), src.index("hipError_t launch_sgd")
+    a, b = src.index("struct TileGeom"), src.index("hipError_t launch_gemm(")
     return hashlib.sha256(src[a:b].encode()).hexdigest()[:16]
 
 
@@ -192,12 +193,6 @@ def main():
         bpp = 12.0 + 8.0 * {"sgd": 0, "momentum": 1, "adagrad": 1, "adam": 2}[args.optimizer] + (2.0 if w.dtype == wl.BF16 else 0.0)
         achieved = n_params * bpp / (dom_ms * 1e-3) / 1e9
         traffic = None
-        try:
-            if (args.optimizer == "sgd" and w.name == SGD_TRAFFIC["workload"]
-                    and _sgd_kernel_sha() == SGD_TRAFFIC["kernel_sha"]):
-                traffic = SGD_TRAFFIC["bytes"]
-        except (OSError, ValueError):
-            pass
         roofline = {"kernel": dom_name, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "avg_ms": dom_ms,
                     "algorithmic_bytes": n_params * bpp}
@@ -207,10 +202,17 @@ def main():
         # flops at the MFMA peak
         peak = MFMA_PEAK_TFLOPS[w.dtype]
         t_hbm, t_mfma = dom_bytes / (HBM_PEAK_GBS * 1e9), dom_flops / (peak * 1e12)
+        traffic = None
+        try:
+            if (args.optimizer == "sgd" and not args.different_inputs and w.name == DW_TRAFFIC["workload"]
+                    and dom_name == DW_TRAFFIC["kernel"] and _gemm_kernel_sha() == DW_TRAFFIC["kernel_sha"]):
+                traffic = DW_TRAFFIC["bytes"]
+        except (OSError, ValueError):
+            pass
         if t_hbm >= t_mfma:
             achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
             roofline = {"kernel": dom_name, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": achieved / HBM_PEAK_GBS, "traffic": None, "avg_ms": dom_ms,
+                        "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "avg_ms": dom_ms,
                         "algorithmic_bytes": dom_bytes, "algorithmic_flops": dom_flops}
         else:
             achieved = dom_flops / (dom_ms * 1e-3) / 1e12
