@@ -397,13 +397,12 @@ double padded_work(const GemmProb& g, int c) {
 void emit_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, int cfg, const std::vector<GemmProb>& probs) {
     const int BMc = GEMM_TILE_M[cfg], BNc = GEMM_TILE_N[cfg];
     std::vector<TileOrder> logical;
-    const bool dw_cols_fastest = std::getenv("PACK_DW_COLS_FASTEST") != nullptr;
     for (size_t i = 0; i < probs.size(); ++i) {
         const GemmProb& g = probs[i];
         const int tms = (g.R + BMc - 1) / BMc, tns = (g.Q + BNc - 1) / BNc;
         const int S = (g.Kd + g.ksplit - 1) / g.ksplit;
         for (int ks = 0; ks < std::max(S, 1); ++ks) {
-            if (mode == CONV_FWD || mode == CONV_DX || ((mode == LIN_DW || mode == CONV_DW) && dw_cols_fastest)) {
+            if (mode == CONV_FWD || mode == CONV_DX) {
                 for (int tm = 0; tm < tms; ++tm)
                     for (int tn = 0; tn < tns; ++tn) logical.push_back({(int)i, tm, tn, ks});
             } else {

@@ -374,3 +374,54 @@ def test_optimiser_argument_errors():
         assert pk.read_opt_state(0, 0)[1] == 0
     finally:
         pk.destroy()
+
+
+def test_update_in_the_gradient_kernels_equals_the_separate_update_bit_for_bit(monkeypatch):
+    """Plain-SGD packs apply W <- W - lr dW where dW is produced; the separate update launch (kept as a
+    measuring aid behind an environment variable) must give the same bits, for unsplit weight
+    gradients (MLP), split ones (CNN: the update then happens in the reduction kernel), fp32 and bf16."""
+    cases = [wl.config2(B=48, D=200, hidden=(72, 40), K=3, steps=3),
+             wl.config3(K=2, B=8, size=16, widths=(16, 32, 32), steps=2),
+             wl.config5(K=2, B=4, size=16, widths=(16, 32, 32, 64), n_classes=100, steps=2)]
+    for w in cases:
+        fused = pu.run_gpu(w, keep_first_grads=False)
+        fused_keep = pu.run_gpu(w)                       # same kernels, gradients stored as well
+        monkeypatch.setenv("PACK_NO_FUSED_UPDATE", "1")
+        separate = pu.run_gpu(w)
+        monkeypatch.delenv("PACK_NO_FUSED_UPDATE")
+        assert separate["launches"] == fused["launches"] + 1
+        for k in range(w.K):
+            assert np.array_equal(fused["blobs"][k], separate["blobs"][k]), (w.name, k)
+            assert np.array_equal(fused_keep["blobs"][k], separate["blobs"][k]), (w.name, k)
+            assert np.array_equal(fused_keep["grads"][k], separate["grads"][k]), (w.name, k)
+        assert np.array_equal(fused["loss"], separate["loss"])
+
+
+def test_gradients_of_a_plain_sgd_pack_are_only_kept_on_request():
+    from paper_2002_02885_amd import binding
+    w = wl.config2(B=16, D=64, hidden=(32,), K=2, steps=1)
+    x_dev, y_dev = pu.device_inputs(w)
+    pk = binding.Pack(w.B, w.in_shape, w.dtype, w.models, w.batch)
+    try:
+        pk.step(x_dev.data_ptr(), y_dev.data_ptr(), w.lr)
+        with pytest.raises(binding.PackError) as e:
+            pk.read_grads(0)
+        assert e.value.status == binding.PACK_EINVAL
+        pk.keep_grads(True)
+        pk.step(x_dev.data_ptr(), y_dev.data_ptr(), w.lr)
+        assert np.any(pk.read_grads(0) != 0)
+        pk.set_optimizer(1, {"kind": "adam"})            # a member with state: the separate update stores them anyway
+        pk.keep_grads(False)
+        pk.step(x_dev.data_ptr(), y_dev.data_ptr(), w.lr)
+        assert np.any(pk.read_grads(0) != 0)
+    finally:
+        pk.destroy()
+
+
+def test_the_separate_head_kernels_match_the_oracle_too(monkeypatch):
+    """Members with few classes take the one-kernel classifier head; the three separate kernels it
+    replaces (last linear forward, loss, its input gradient) stay in use for many classes and behind an
+    environment variable, and must pass the same parity check on the same workloads."""
+    monkeypatch.setenv("PACK_NO_FUSED_HEAD", "1")
+    _check_bf16(wl.config2(B=64, D=256, hidden=(128, 64), K=3, steps=4))
+    _check_f32(wl.config3(K=2, B=8, size=16, widths=(16, 32, 32), steps=2))
