@@ -500,7 +500,9 @@ void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<G
     // half of a 128-wide tile); the launch as a whole needs enough workgroups to fill the 256
     // compute units about twice.  Problems whose preferred shape carries little of the work
     // ride along in the main launch rather than paying for a launch of their own.
-    size_t min_tiles = 512;
+    // (measured: dense products are better off with one larger tile per compute unit than with two
+    // smaller ones, convolutions the other way round)
+    size_t min_tiles = (mode == LIN_FWD || mode == LIN_DX || mode == LIN_DW) ? 256 : 512;
     if (const char* v = std::getenv("PACK_MIN_TILES")) min_tiles = (size_t)std::max(1, std::atoi(v));   // tuning knob
     int floor_cfg = 0;
     while (floor_cfg < 2 && count_tiles(probs, floor_cfg) < min_tiles) ++floor_cfg;
@@ -700,7 +702,10 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
         }
         add_mapped_launch(p, db, L_HEAD, heads, head_blocks);
         p->n_heads = (int)heads.size();
-        if (!heads.empty()) p->head_desc_off = p->plan.back().desc_off;
+        if (!heads.empty()) {
+            p->head_desc_off = p->plan.back().desc_off;
+            for (const HeadProb& h : heads) p->plan.back().mode = std::max(p->plan.back().mode, h.C);   // largest class count
+        }
     }
 
     // ---------------- backward ----------------
@@ -1396,7 +1401,7 @@ pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, c
                 break;
             case L_REDUCE: e = launch_reduce((const ReduceProb*)d, (const int2*)mp, L.n, lr, p->stream); break;
             case L_CE: e = launch_ce(bf, (const CeProb*)d, L.n, labels_dev, p->err_flag, p->stream); break;
-            case L_HEAD: e = launch_head(bf, (const HeadProb*)d, (const int2*)mp, L.n, labels_dev, p->err_flag, p->stream); break;
+            case L_HEAD: e = launch_head(bf, L.mode, (const HeadProb*)d, (const int2*)mp, L.n, labels_dev, p->err_flag, p->stream); break;
             case L_GAP_FWD: e = launch_gap(bf, false, (const GapProb*)d, (const int2*)mp, L.n, p->stream); break;
             case L_GAP_BWD: e = launch_gap(bf, true, (const GapProb*)d, (const int2*)mp, L.n, p->stream); break;
             case L_SHORTCUT: e = launch_shortcut_bwd(bf, (const ShortcutProb*)d, (const int2*)mp, L.n, p->stream); break;

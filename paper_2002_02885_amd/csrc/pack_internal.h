@@ -110,7 +110,7 @@ struct HeadProb {     // classifier head of one member in one kernel: logits, so
     float* partial;        // [nblk] per-block loss sums
     int rows, C, Kd, ldd, label_off, mask_act, nblk;
 };
-constexpr int HEAD_ROWS = 16;      // rows one block of the head kernel handles
+constexpr int HEAD_ROWS = 8;       // rows one block of the head kernel handles
 constexpr int HEAD_MAX_C = 16;     // classes the head kernel keeps in registers
 
 struct GapProb {      // global average pool: in [n, hw, c] -> out [n, c]
@@ -153,7 +153,8 @@ hipError_t launch_gemm(int mode, bool bf16, int tile_cfg, const GemmProb* probs_
                        int n_tiles, const void* x_dev, const LrTable& lr, hipStream_t st);
 hipError_t launch_reduce(const ReduceProb* probs_dev, const int2* map_dev, int n_blocks, const LrTable& lr, hipStream_t st);
 hipError_t launch_ce(bool bf16, const CeProb* probs_dev, int K, const int32_t* labels, int* err_flag, hipStream_t st);
-hipError_t launch_head(bool bf16, const HeadProb* probs_dev, const int2* map_dev, int n_blocks, const int32_t* labels,
+// max_c: the largest class count among the launch's members (<= HEAD_MAX_C)
+hipError_t launch_head(bool bf16, int max_c, const HeadProb* probs_dev, const int2* map_dev, int n_blocks, const int32_t* labels,
                        int* err_flag, hipStream_t st);
 hipError_t launch_head_loss(const HeadProb* probs_dev, int n_members, hipStream_t st);
 hipError_t launch_gap(bool bf16, bool backward, const GapProb* probs_dev, const int2* map_dev, int n_blocks, hipStream_t st);

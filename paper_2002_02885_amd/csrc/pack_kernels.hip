@@ -1387,7 +1387,7 @@ hipError_t launch_ce(bool bf16, const CeProb* probs, int K, const int32_t* label
 // in the input gradient.  Rounding points are those of the separate kernels: dlogits is rounded
 // to the pack dtype before it is multiplied with the weights.
 // ------------------------------------------------------------------------------------------------
-template <typename T>
+template <typename T, int MAXC>
 __global__ __launch_bounds__(256) void head_kernel(const HeadProb* __restrict__ probs, const int2* __restrict__ map,
                                                    const int32_t* __restrict__ labels, int* __restrict__ err_flag) {
     constexpr int V = ET<T>::V;
@@ -1395,7 +1395,7 @@ __global__ __launch_bounds__(256) void head_kernel(const HeadProb* __restrict__ 
     constexpr int KCH = 128 * V;           // reduction indices per pass (the weights of a pass sit in LDS)
     constexpr int NV = KCH / (LPR * V);    // 16-byte vectors of a row a lane handles per pass
     typedef typename std::conditional<sizeof(T) == 2, u32x4_t, f32x4_t>::type vec_t;
-    __shared__ __attribute__((aligned(16))) T Ws[HEAD_MAX_C][KCH];
+    __shared__ __attribute__((aligned(16))) T Ws[MAXC][KCH];
     __shared__ float row_losses[HEAD_ROWS];
     const int2 mb = map[blockIdx.x];
     const HeadProb p = probs[mb.x];
@@ -1428,7 +1428,7 @@ __global__ __launch_bounds__(256) void head_kernel(const HeadProb* __restrict__ 
     // ... and the block's share of the weights of the pass, which go to LDS
     auto stage_w = [&](int ch) {
         constexpr int VPR = KCH / V;   // vectors per class row of the pass
-        for (int i0 = 0; i0 < HEAD_MAX_C * VPR; i0 += 4 * 256) {
+        for (int i0 = 0; i0 < MAXC * VPR; i0 += 4 * 256) {
             vec_t wv[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -1439,15 +1439,15 @@ __global__ __launch_bounds__(256) void head_kernel(const HeadProb* __restrict__ 
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int idx = i0 + u * 256 + threadIdx.x;
-                if (idx < HEAD_MAX_C * VPR) *reinterpret_cast<vec_t*>(&Ws[idx / VPR][(idx % VPR) * V]) = wv[u];
+                if (idx < MAXC * VPR) *reinterpret_cast<vec_t*>(&Ws[idx / VPR][(idx % VPR) * V]) = wv[u];
             }
         }
     };
 
     // ---- logits ----
-    float acc[HEAD_MAX_C];
+    float acc[MAXC];
 #pragma unroll
-    for (int c = 0; c < HEAD_MAX_C; ++c) acc[c] = 0.f;
+    for (int c = 0; c < MAXC; ++c) acc[c] = 0.f;
     for (int ch = 0; ch < nch; ++ch) {
         if (ch > 0) __syncthreads();   // the previous pass's weights are no longer read
         load_h(ch);
@@ -1457,14 +1457,14 @@ __global__ __launch_bounds__(256) void head_kernel(const HeadProb* __restrict__ 
         for (int j = 0; j < NV; ++j) {
             float hf[V];
             unpack(hv[j], hf);
-            // all HEAD_MAX_C rows, without a branch on the class count (rows beyond it hold zeros), so
+            // all MAXC rows, without a branch on the class count (rows beyond it hold zeros), so
             // that the LDS reads of a slice are requested together
-            vec_t wv[HEAD_MAX_C];
+            vec_t wv[MAXC];
 #pragma unroll
-            for (int c = 0; c < HEAD_MAX_C; ++c) wv[c] = *reinterpret_cast<const vec_t*>(&Ws[c][(j * LPR + kl) * V]);
+            for (int c = 0; c < MAXC; ++c) wv[c] = *reinterpret_cast<const vec_t*>(&Ws[c][(j * LPR + kl) * V]);
             __builtin_amdgcn_sched_barrier(0);   // keep the sixteen LDS reads together, ahead of their use
 #pragma unroll
-            for (int c = 0; c < HEAD_MAX_C; ++c) {
+            for (int c = 0; c < MAXC; ++c) {
                 float wf[V];
                 unpack(wv[c], wf);
 #pragma unroll
@@ -1473,7 +1473,7 @@ __global__ __launch_bounds__(256) void head_kernel(const HeadProb* __restrict__ 
         }
     }
 #pragma unroll
-    for (int c = 0; c < HEAD_MAX_C; ++c)
+    for (int c = 0; c < MAXC; ++c)
 #pragma unroll
         for (int m = 1; m < LPR; m <<= 1) acc[c] += __shfl_xor(acc[c], m, 64);
 
@@ -1483,26 +1483,26 @@ __global__ __launch_bounds__(256) void head_kernel(const HeadProb* __restrict__ 
     if (active && !ok && kl == 0) atomicOr(err_flag, 1);
     float mx = -INFINITY, zy = 0.f;
     int arg = 0;
-    float bias[HEAD_MAX_C];
+    float bias[MAXC];
 #pragma unroll
-    for (int c = 0; c < HEAD_MAX_C; ++c) bias[c] = p.bias[c < p.C ? c : 0];
+    for (int c = 0; c < MAXC; ++c) bias[c] = p.bias[c < p.C ? c : 0];
 #pragma unroll
-    for (int c = 0; c < HEAD_MAX_C; ++c) {
+    for (int c = 0; c < MAXC; ++c) {
         acc[c] = (c < p.C) ? acc[c] + bias[c] : -INFINITY;
         if (acc[c] > mx) { mx = acc[c]; arg = c; }   // ascending class index: lowest among equals
         if (c == y) zy = acc[c];
     }
     float ssum = 0.f;
-    float dz[HEAD_MAX_C];
+    float dz[MAXC];
 #pragma unroll
-    for (int c = 0; c < HEAD_MAX_C; ++c) {
+    for (int c = 0; c < MAXC; ++c) {
         dz[c] = expf(acc[c] - mx);   // exp(-inf) = 0 beyond the class count
         ssum += dz[c];
     }
     const float inv_rows = 1.f / (float)p.rows, inv_s = 1.f / ssum;
     const float row_loss = (active && ok) ? (mx + logf(ssum)) - zy : 0.f;
 #pragma unroll
-    for (int c = 0; c < HEAD_MAX_C; ++c) {
+    for (int c = 0; c < MAXC; ++c) {
         const float g = (ok && c < p.C) ? (dz[c] * inv_s - (c == y ? 1.f : 0.f)) * inv_rows : 0.f;
         dz[c] = ET<T>::to_f(ET<T>::from_f(g));   // as stored: the input gradient multiplies the rounded value
     }
@@ -1510,7 +1510,7 @@ __global__ __launch_bounds__(256) void head_kernel(const HeadProb* __restrict__ 
         float* zr = p.logits + (size_t)row * p.C;
         T* dr = (T*)p.dlogits + (size_t)row * p.ldd;
 #pragma unroll
-        for (int c = 0; c < HEAD_MAX_C; ++c) {
+        for (int c = 0; c < MAXC; ++c) {
             if (c < p.C) {
                 zr[c] = acc[c];
                 dr[c] = ET<T>::from_f(dz[c]);
@@ -1535,12 +1535,12 @@ __global__ __launch_bounds__(256) void head_kernel(const HeadProb* __restrict__ 
             float o[V];
 #pragma unroll
             for (int e = 0; e < V; ++e) o[e] = 0.f;
-            vec_t wv[HEAD_MAX_C];
+            vec_t wv[MAXC];
 #pragma unroll
-            for (int c = 0; c < HEAD_MAX_C; ++c) wv[c] = *reinterpret_cast<const vec_t*>(&Ws[c][(j * LPR + kl) * V]);
+            for (int c = 0; c < MAXC; ++c) wv[c] = *reinterpret_cast<const vec_t*>(&Ws[c][(j * LPR + kl) * V]);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int c = 0; c < HEAD_MAX_C; ++c) {   // dz is zero beyond the class count
+            for (int c = 0; c < MAXC; ++c) {   // dz is zero beyond the class count
                 float wf[V];
                 unpack(wv[c], wf);
 #pragma unroll
@@ -1599,10 +1599,19 @@ hipError_t launch_head_loss(const HeadProb* probs, int n_members, hipStream_t st
     return hipGetLastError();
 }
 
-hipError_t launch_head(bool bf16, const HeadProb* probs, const int2* map, int n, const int32_t* labels, int* err_flag, hipStream_t st) {
+template <typename T>
+static void launch_head_t(int max_c, const HeadProb* probs, const int2* map, int n, const int32_t* labels, int* err_flag, hipStream_t st) {
+    // instantiated for a few class counts: the kernel's arithmetic grows with the count it is built for
+    if (max_c <= 4) hipLaunchKernelGGL((head_kernel<T, 4>), dim3(n), dim3(256), 0, st, probs, map, labels, err_flag);
+    else if (max_c <= 10) hipLaunchKernelGGL((head_kernel<T, 10>), dim3(n), dim3(256), 0, st, probs, map, labels, err_flag);
+    else hipLaunchKernelGGL((head_kernel<T, HEAD_MAX_C>), dim3(n), dim3(256), 0, st, probs, map, labels, err_flag);
+}
+
+hipError_t launch_head(bool bf16, int max_c, const HeadProb* probs, const int2* map, int n, const int32_t* labels, int* err_flag, hipStream_t st) {
     if (n <= 0) return hipSuccess;
-    if (bf16) hipLaunchKernelGGL(head_kernel<bf16_t>, dim3(n), dim3(256), 0, st, probs, map, labels, err_flag);
-    else hipLaunchKernelGGL(head_kernel<float>, dim3(n), dim3(256), 0, st, probs, map, labels, err_flag);
+    if (max_c > HEAD_MAX_C) return hipErrorInvalidValue;
+    if (bf16) launch_head_t<bf16_t>(max_c, probs, map, n, labels, err_flag, st);
+    else launch_head_t<float>(max_c, probs, map, n, labels, err_flag, st);
     return hipGetLastError();
 }
 
