@@ -110,7 +110,7 @@ struct HeadProb {     // classifier head of one member in one kernel: logits, so
     float* partial;        // [nblk] per-block loss sums
     int rows, C, Kd, ldd, label_off, mask_act, nblk;
 };
-constexpr int HEAD_ROWS = 8;       // rows one block of the head kernel handles
+constexpr int HEAD_ROWS = 4;       // rows one block of the head kernel handles
 constexpr int HEAD_MAX_C = 16;     // classes the head kernel keeps in registers
 
 struct GapProb {      // global average pool: in [n, hw, c] -> out [n, c]
