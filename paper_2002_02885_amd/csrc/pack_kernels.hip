@@ -715,6 +715,9 @@ __device__ __forceinline__ void for_each_stage(std::integer_sequence<int, Is...>
 #ifndef PACK_ST_128x128
 #define PACK_ST_128x128 2
 #endif
+#ifndef PACK_DW_EARLY
+#define PACK_DW_EARLY 0   // 16-byte weight vectors per thread requested ahead of the main loop (fused update)
+#endif
 
 template <int BM, int BN, int BKM, bool VEC>
 struct StageCount {   // register stages of prefetch per tile shape (bounded by the register file)
@@ -779,6 +782,27 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
             const f32x4_t b1 = *reinterpret_cast<const f32x4_t*>(p.bias + bcol + 4);
             bias_v[0] = b0.x; bias_v[1] = b0.y; bias_v[2] = b0.z; bias_v[3] = b0.w;
             bias_v[4] = b1.x; bias_v[5] = b1.y; bias_v[6] = b1.z; bias_v[7] = b1.w;
+        }
+    }
+    // Weight-gradient tiles with the fused update: a thread owns four consecutive columns (one
+    // 16-byte vector of fp32 weights) in DW_NIT rows.  DW_EARLY of them can be requested here,
+    // ahead of the operands, the rest when the main loop ends.  Measured: requesting any early is
+    // slower (83 -> 86 us on the headline workload), because loads return in order and the
+    // operands, which come from L2, then queue behind weights that come from HBM; so it is 0.
+    constexpr int DW_G = BN / 4, DW_NIT = BM * DW_G / 256, DW_RSTEP = 256 / DW_G;
+    constexpr int DW_EARLY = (DW_NIT < PACK_DW_EARLY) ? DW_NIT : PACK_DW_EARLY;
+    const int dw_lc = (threadIdx.x % DW_G) * 4, dw_lr0 = threadIdx.x / DW_G;
+    const bool dw_full = vec_out && (col0 + dw_lc + 4 <= p.Q);
+    const bool upd = IS_DW && (p.flags & F_UPDATE);
+    const bool keep_g = !upd || (p.flags & F_KEEP_G);
+    f32x4_t dw_w[IS_DW ? DW_NIT : 1];
+    if constexpr (IS_DW) {
+        if (upd && dw_full) {
+#pragma unroll
+            for (int n = 0; n < DW_EARLY; ++n) {
+                const int row = row0 + dw_lr0 + n * DW_RSTEP;
+                if (row < p.R) dw_w[n] = *reinterpret_cast<const f32x4_t*>(p.upd_w + (size_t)row * p.ldc + col0 + dw_lc);
+            }
         }
     }
     constexpr int LOADS = LoadsPerChunk<MODE, T, true, BM, BK>::value + LoadsPerChunk<MODE, T, false, BN, BK>::value;
@@ -899,8 +923,6 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
 
     // fused update (F_UPDATE): W <- W - lr dW is applied where the gradient is produced, so the
     // gradient is neither written nor read back by a separate update launch
-    const bool upd = IS_DW && (p.flags & F_UPDATE);
-    const bool keep_g = !upd || (p.flags & F_KEEP_G);
     if constexpr (IS_DW) {
         if (do_bias_grad && threadIdx.x < BM && row0 + (int)threadIdx.x < p.R) {
             const int r = row0 + threadIdx.x;
@@ -917,17 +939,11 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
     constexpr int SLD = BN + 8;   // 4 rows apart = 32 banks apart: the two half-waves do not collide
     static_assert((size_t)BM * SLD * 4 <= (size_t)2 * (BM * GA::LDS_LD + BN * GB::LDS_LD) * sizeof(T), "staging tile must fit");
     float(*stage)[SLD] = reinterpret_cast<float(*)[SLD]>(As_);
-    // Weight-gradient tiles with the fused update: a thread owns four consecutive columns (one
-    // 16-byte vector of fp32 weights) in DW_NIT rows, and requests all its weights now, so that
-    // their round trip runs under the staging of the accumulators instead of after it.
-    constexpr int DW_G = BN / 4, DW_NIT = BM * DW_G / 256, DW_RSTEP = 256 / DW_G;
-    const int dw_lc = (threadIdx.x % DW_G) * 4, dw_lr0 = threadIdx.x / DW_G;
-    const bool dw_full = vec_out && (col0 + dw_lc + 4 <= p.Q);
-    f32x4_t dw_w[IS_DW ? DW_NIT : 1];
+    // the remaining weights of the tile: their round trip runs under the staging of the accumulators
     if constexpr (IS_DW) {
         if (upd && dw_full) {
 #pragma unroll
-            for (int n = 0; n < DW_NIT; ++n) {
+            for (int n = DW_EARLY; n < DW_NIT; ++n) {
                 const int row = row0 + dw_lr0 + n * DW_RSTEP;
                 if (row < p.R) dw_w[n] = *reinterpret_cast<const f32x4_t*>(p.upd_w + (size_t)row * p.ldc + col0 + dw_lc);
             }
