@@ -529,12 +529,20 @@ void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<G
             return;
         }
     }
+    // weight gradients whose reduction is at most a few chunks long take the lean form of the
+    // 128 x 128 kernel (more tiles resident per compute unit; PACK_NO_LEAN_DW is a measuring aid)
+    const bool lean_ok = (mode == LIN_DW || mode == CONV_DW) && !std::getenv("PACK_NO_LEAN_DW");
+    const int chunk_k = p->bf16 ? 64 : 32;
     for (int c = 0; c < 3; ++c) {
-        std::vector<GemmProb> group;
+        std::vector<GemmProb> group, lean;
         for (size_t i = 0; i < probs.size(); ++i) {
             const int eff = (work[want[i]] < 0.15 * total) ? main_cfg : want[i];
-            if (eff == c) group.push_back(probs[i]);
+            if (eff != c) continue;
+            const int chunks = (std::min(probs[i].Kd, probs[i].ksplit) + chunk_k - 1) / chunk_k;
+            if (c == 0 && lean_ok && chunks <= 8) lean.push_back(probs[i]);
+            else group.push_back(probs[i]);
         }
+        if (!lean.empty()) emit_gemm_launch(p, db, mode, GEMM_CFG_LEAN, lean);
         if (!group.empty()) emit_gemm_launch(p, db, mode, c, group);
     }
 }

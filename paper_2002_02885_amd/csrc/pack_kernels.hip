@@ -734,7 +734,11 @@ __device__ __forceinline__ void update_one(const GemmProb& p, size_t off, float 
     if (p.upd_shadow) ((bf16_t*)p.upd_shadow)[off] = ET<bf16_t>::from_f(w);
 }
 
-template <int MODE, typename T, int BM, int BN, int BKM, bool VEC>
+// LEAN (weight gradients whose reduction is only a few chunks long, aligned operands): one register
+// stage and one LDS buffer instead of several, and the epilogue stages the accumulators in two
+// halves.  A tile of such a product spends most of its life in its prologue and epilogue, so what
+// counts is how many tiles a compute unit can hold at once, not the depth of one tile's pipeline.
+template <int MODE, typename T, int BM, int BN, int BKM, bool VEC, bool LEAN = false>
 __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, T* __restrict__ As_, T* __restrict__ Bs_, float lrk) {
     constexpr int V = ET<T>::V, BK = ET<T>::BK * BKM;
     typedef TileGeom<T, BM, BK> GA;
@@ -745,7 +749,8 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
     // i + ST are issued when chunk i starts to be multiplied, so ST - 1 round trips to memory are
     // in flight per workgroup; a skinny layer has too few workgroups per compute unit to hide that
     // latency by occupancy alone.
-    constexpr int ST = StageCount<BM, BN, BKM, VEC>::value;
+    constexpr int ST = LEAN ? 1 : StageCount<BM, BN, BKM, VEC>::value;
+    static_assert(!LEAN || (VEC && (MODE == LIN_DW || MODE == CONV_DW) && BM == 128), "lean form: aligned weight gradients");
     T(*As)[BM][GA::LDS_LD] = reinterpret_cast<T(*)[BM][GA::LDS_LD]>(As_);
     T(*Bs)[BN][GB::LDS_LD] = reinterpret_cast<T(*)[BN][GB::LDS_LD]>(Bs_);
 
@@ -807,6 +812,70 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
     }
     constexpr int LOADS = LoadsPerChunk<MODE, T, true, BM, BK>::value + LoadsPerChunk<MODE, T, false, BN, BK>::value;
     constexpr bool ASM_WAITS = VEC && ((PACK_ASM_MODES >> MODE) & 1);
+    if constexpr (LEAN) {
+        // chunk it: wait for its operands, store them to the one LDS buffer (after everybody has
+        // finished reading the previous chunk from it), request chunk it + 1 into the same
+        // registers, multiply
+        fa.fetch(p, kbeg, kend, ra[0]);
+        fb.fetch(p, kbeg, kend, rb[0]);
+        for (int it = 0; it < nk; ++it) {
+            wait_stage<0>(ra[0]);
+            wait_stage<0>(rb[0]);
+            __syncthreads();
+            stash_tile<MODE, T, true, BM, BK, VEC>(&As[0][0][0], ra[0]);
+            stash_tile<MODE, T, false, BN, BK, VEC>(&Bs[0][0][0], rb[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            fa.fetch(p, kbeg + (it + 1) * BK, kend, ra[0]);   // beyond the reduction: zeros, no memory access
+            fb.fetch(p, kbeg + (it + 1) * BK, kend, rb[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            T(*Ab)[GA::LDS_LD] = As[0];
+            T(*Bb)[GB::LDS_LD] = Bs[0];
+            if (do_bias_grad && threadIdx.x < BM) {
+#pragma unroll
+                for (int kk = 0; kk < BK; kk += V) {
+                    const u32x4_t v = *reinterpret_cast<const u32x4_t*>(&Ab[threadIdx.x][kk]);
+                    if constexpr (sizeof(T) == 4) {
+                        bias_grad += __uint_as_float(v.x); bias_grad += __uint_as_float(v.y);
+                        bias_grad += __uint_as_float(v.z); bias_grad += __uint_as_float(v.w);
+                    } else {
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            bias_grad += __uint_as_float(v[d] << 16);
+                            bias_grad += __uint_as_float(v[d] & 0xffff0000u);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int kk = 0; kk < BK; kk += 2 * V) {
+                u32x4_t fra[TM], frb[TN];
+#pragma unroll
+                for (int a = 0; a < TM; ++a)
+                    fra[a] = *reinterpret_cast<const u32x4_t*>(&Ab[wm * (BM / 2) + a * 32 + (lane & 31)][kk + (lane >> 5) * V]);
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+                    frb[b] = *reinterpret_cast<const u32x4_t*>(&Bb[wn * (BN / 2) + b * 32 + (lane & 31)][kk + (lane >> 5) * V]);
+#pragma unroll
+                for (int a = 0; a < TM; ++a)
+#pragma unroll
+                    for (int b = 0; b < TN; ++b) {
+                        if constexpr (sizeof(T) == 2) {
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                __builtin_bit_cast(bf16x8_t, fra[a]), __builtin_bit_cast(bf16x8_t, frb[b]), acc[a][b], 0, 0, 0);
+                        } else {
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fra[a].x), __uint_as_float(frb[b].x), acc[a][b], 0, 0, 0);
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fra[a].y), __uint_as_float(frb[b].y), acc[a][b], 0, 0, 0);
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fra[a].z), __uint_as_float(frb[b].z), acc[a][b], 0, 0, 0);
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fra[a].w), __uint_as_float(frb[b].w), acc[a][b], 0, 0, 0);
+                        }
+                    }
+            }
+        }
+        // the request beyond the last chunk still targets the stage registers
+        wait_stage<0>(ra[0]);
+        wait_stage<0>(rb[0]);
+    } else {
 #pragma unroll
     for (int s = 0; s < ST; ++s) {
         // always issued: a chunk beyond the reduction reads the block of zeros.  Keeping the
@@ -920,6 +989,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
             wait_stage<0>(rb[s]);
         }
     }
+    }   // !LEAN
 
     // fused update (F_UPDATE): W <- W - lr dW is applied where the gradient is produced, so the
     // gradient is neither written nor read back by a separate update launch
@@ -937,7 +1007,8 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
     // and the result is written as full vectors instead of one element per lane.
     // Accumulator register e of a 32x32 block holds row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
     constexpr int SLD = BN + 8;   // 4 rows apart = 32 banks apart: the two half-waves do not collide
-    static_assert((size_t)BM * SLD * 4 <= (size_t)2 * (BM * GA::LDS_LD + BN * GB::LDS_LD) * sizeof(T), "staging tile must fit");
+    constexpr int HALVES = LEAN ? 2 : 1;   // the lean form has one operand buffer: room for half the tile at a time
+    static_assert((size_t)(BM / HALVES) * SLD * 4 <= (size_t)(LEAN ? 1 : 2) * (BM * GA::LDS_LD + BN * GB::LDS_LD) * sizeof(T), "staging tile must fit");
     float(*stage)[SLD] = reinterpret_cast<float(*)[SLD]>(As_);
     // the remaining weights of the tile: their round trip runs under the staging of the accumulators
     if constexpr (IS_DW) {
@@ -948,6 +1019,66 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                 if (row < p.R) dw_w[n] = *reinterpret_cast<const f32x4_t*>(p.upd_w + (size_t)row * p.ldc + col0 + dw_lc);
             }
         }
+    }
+    if constexpr (LEAN) {
+        // two passes: the waves that own the upper (then the lower) half of the rows stage their
+        // accumulators, then all threads apply that half
+        float* const gf = (float*)p.C + (size_t)tr.ks * p.split_stride;
+        const int col = col0 + dw_lc;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            __syncthreads();   // operand tiles (half 0) or the previous half's staging no longer read
+            if (wm == half) {
+#pragma unroll
+                for (int a = 0; a < TM; ++a)
+#pragma unroll
+                    for (int b = 0; b < TN; ++b)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e)
+                            stage[a * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)][wn * (BN / 2) + b * 32 + (lane & 31)] = acc[a][b][e];
+            }
+            __syncthreads();
+            if (vec_out) {
+                if (col < p.Q) {
+#pragma unroll
+                    for (int n = half * (DW_NIT / 2); n < (half + 1) * (DW_NIT / 2); ++n) {
+                        const int lr = dw_lr0 + n * DW_RSTEP, row = row0 + lr;   // lr in [half * BM/2, (half + 1) * BM/2)
+                        if (row >= p.R) continue;
+                        const size_t off = (size_t)row * p.ldc + col;
+                        const f32x4_t g = *reinterpret_cast<const f32x4_t*>(&stage[lr - half * (BM / 2)][dw_lc]);
+                        if (!dw_full) {
+                            for (int e = 0; e < 4 && col + e < p.Q; ++e) {
+                                if (upd) update_one(p, off + e, g[e], lrk);
+                                if (keep_g) gf[off + e] = g[e];
+                            }
+                            continue;
+                        }
+                        if (upd) {
+                            f32x4_t w;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) w[e] = sgd_apply(dw_w[n][e], g[e], lrk);
+                            __builtin_nontemporal_store(w, reinterpret_cast<f32x4_t*>(p.upd_w + off));
+                            if (p.upd_shadow) {
+                                typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
+                                __builtin_nontemporal_store(u32x2_t{pack2bf(w[0], w[1]), pack2bf(w[2], w[3])},
+                                                            reinterpret_cast<u32x2_t*>((bf16_t*)p.upd_shadow + off));
+                            }
+                        }
+                        if (keep_g) *reinterpret_cast<f32x4_t*>(gf + off) = g;
+                    }
+                }
+            } else {
+                for (int idx = threadIdx.x; idx < (BM / 2) * BN; idx += 256) {
+                    const int lr = idx / BN, lc = idx % BN;
+                    const int row = row0 + half * (BM / 2) + lr, c2 = col0 + lc;
+                    if (row >= p.R || c2 >= p.Q) continue;
+                    const size_t off = (size_t)row * p.ldc + c2;
+                    if (upd) update_one(p, off, stage[lr][lc], lrk);
+                    if (keep_g) gf[off] = stage[lr][lc];
+                }
+            }
+        }
+        return;
     }
     __syncthreads();   // every wave is done with the operand tiles
 #pragma unroll
@@ -1182,7 +1313,7 @@ using LrArg = typename std::conditional<MODE == LIN_DW || MODE == CONV_DW, LrTab
 // sorts problems into launches by that); VEC = false: the element-by-element gather for any shape.
 // They are separate kernels because the gather needs many more registers, which would halve the
 // occupancy of the aligned path if both lived in one kernel.
-template <int MODE, typename T, int BM, int BN, int BKM, bool VEC>
+template <int MODE, typename T, int BM, int BN, int BKM, bool VEC, bool LEAN = false>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ probs,
                                                    const TileRef* __restrict__ tiles,
                                                    const void* __restrict__ x, LrArg<MODE> lr) {
@@ -1197,12 +1328,13 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
     if (p.flags & F_B_INPUT) p.B = xin;
     if (p.flags & F_AUX_INPUT) p.aux = xin;
     // one block: operand tiles A (two buffers) then B (two buffers); the epilogue reuses it
-    __shared__ __attribute__((aligned(16))) T lds[2 * BM * TileGeom<T, BM, BK>::LDS_LD + 2 * BN * TileGeom<T, BN, BK>::LDS_LD];
+    constexpr int NBUF = LEAN ? 1 : 2;
+    __shared__ __attribute__((aligned(16))) T lds[NBUF * BM * TileGeom<T, BM, BK>::LDS_LD + NBUF * BN * TileGeom<T, BN, BK>::LDS_LD];
     T* const As = lds;
-    T* const Bs = lds + 2 * BM * TileGeom<T, BM, BK>::LDS_LD;
+    T* const Bs = lds + NBUF * BM * TileGeom<T, BM, BK>::LDS_LD;
     float lrk = 0.f;
     if constexpr (MODE == LIN_DW || MODE == CONV_DW) lrk = lr.lr[p.member];
-    gemm_body<MODE, T, BM, BN, BKM, VEC>(p, tr, As, Bs, lrk);
+    gemm_body<MODE, T, BM, BN, BKM, VEC, LEAN>(p, tr, As, Bs, lrk);
 }
 
 template <int MODE, typename T>
@@ -1213,6 +1345,10 @@ static void launch_gemm_tile(int tile_cfg, const GemmProb* probs, const TileRef*
         case 0: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 128, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, la); break;
         case 1: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 64, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, la); break;
         case 2: hipLaunchKernelGGL((gemm_kernel<MODE, T, 64, 64, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, la); break;
+        case GEMM_CFG_LEAN:
+            if constexpr (MODE == LIN_DW || MODE == CONV_DW)
+                hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 128, 1, true, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, la);
+            break;
         default: hipLaunchKernelGGL((gemm_kernel<MODE, T, 64, 64, 1, false>), dim3(n), dim3(256), 0, st, probs, tiles, x, la); break;
     }
 }
