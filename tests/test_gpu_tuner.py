@@ -92,3 +92,27 @@ def test_all_policies_find_the_same_winner_with_the_same_losses_and_match_the_or
                         assert l >= cut * (1 - 2 * tol), (j, i, cfg)
     ref_best = min(l for e in plain.log for l in e["losses"])
     assert best_loss == ref_best
+
+
+def test_memory_model_tracks_what_a_pack_really_allocates():
+    """pack_estimate_bytes per member, summed, against pack_device_bytes of the pack that holds them
+    (which adds what members share: workspace, problem tables, small fixed buffers)."""
+    cases = [(wl.config2(B=64, D=512, hidden=(256, 128), K=6, steps=1), ["sgd", "adam", "momentum", "sgd", "adagrad", "adam"]),
+             (wl.config3(K=3, B=8, size=16, widths=(16, 32, 32), steps=1), ["sgd", "sgd", "sgd"]),
+             (wl.config4(K=8, B=64, D=256, width_choices=(32, 96, 200), steps=1), ["sgd"] * 8)]
+    for w, opts in cases:
+        pk = binding.Pack(w.B, w.in_shape, w.dtype, w.models, w.batch)
+        try:
+            for k, o in enumerate(opts):
+                pk.set_optimizer(k, {"kind": o})
+            real = pk.device_bytes()
+        finally:
+            pk.destroy()
+        est = sum(binding.estimate_bytes(w.B, w.in_shape, w.dtype, w.models[k], w.batch[k], opts[k]) for k in range(w.K))
+        # state arrays are arena-shaped: a pack with one Adam member holds both arrays for every member
+        n_state = max({"sgd": 0, "momentum": 1, "adagrad": 1, "adam": 2}[o] for o in opts)
+        est_upper = sum(binding.estimate_bytes(w.B, w.in_shape, w.dtype, w.models[k], w.batch[k],
+                                               ["sgd", "momentum", "adam"][n_state]) for k in range(w.K))
+        assert est <= real, (w.name, est, real)
+        assert real <= 1.25 * est_upper + (2 << 20), (w.name, est_upper, real)
+        print(f"\n{w.name}: estimate {est / 1e6:.2f} MB (arena-shaped state: {est_upper / 1e6:.2f} MB), allocated {real / 1e6:.2f} MB")
