@@ -115,7 +115,7 @@ def main():
                          "so that a hardware-counter run has a kernel of known traffic to scale by")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the packed step has no cross-GPU part); "
+        print("bench.py: the library runs on ONE GPU (the packed step has no cross-GPU part); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 

@@ -8,8 +8,10 @@
 //
 // Matrix products run on the matrix cores (MFMA 32x32 tiles, 64-lane wavefronts), operands staged
 // through LDS with rows laid out reduction-contiguous so that every fragment read is one
-// 16-byte access.  Everything else (softmax cross-entropy, pooling, bias gradients, the SGD
-// update) is bandwidth work written as coalesced streaming kernels.  All reductions have a
+// 16-byte access.  The SGD update of plain-SGD packs is applied in the epilogue of the
+// weight-gradient products; a classifier head with few classes (last layer, loss, its input
+// gradient) is one kernel.  Everything else (pooling, shortcuts, optimisers with state, batch
+// assembly) is bandwidth work written as coalesced streaming kernels.  All reductions have a
 // fixed order: results are bit-reproducible and a member's result does not depend on which
 // other members share the pack (the isolation guarantee of Section 2.2).
 #include "pack_internal.h"
