@@ -6,6 +6,7 @@ import pytest
 import torch
 
 import workloads as wl
+from oracle import pack_oracle as po
 from tests import parity_util as pu
 
 pytestmark = pytest.mark.gpu
@@ -425,3 +426,29 @@ def test_the_separate_head_kernels_match_the_oracle_too(monkeypatch):
     monkeypatch.setenv("PACK_NO_FUSED_HEAD", "1")
     _check_bf16(wl.config2(B=64, D=256, hidden=(128, 64), K=3, steps=4))
     _check_f32(wl.config3(K=2, B=8, size=16, widths=(16, 32, 32), steps=2))
+
+
+def test_the_largest_pack_256_members_with_their_own_learning_rates_and_optimisers():
+    """PACK_MAX_MODELS members (the per-step tables hold exactly that many entries): a sample of
+    members against the oracle, fp32, with every fourth member on Adam (so the separate update runs)
+    and, in a second pack, all on plain SGD (so the update in the weight-gradient kernel runs)."""
+    K = 256
+    rng = np.random.default_rng(123)
+    models = [wl.mlp([int(rng.integers(8, 40))], 10) for _ in range(K)]
+    batch = [int(b) for b in rng.integers(1, 17, size=K)]
+    w = wl.custom("k256", 9, wl.F32, 16, (1, 1, 48), models, batch=batch, steps=2)
+    for with_adam in (False, True):
+        if with_adam:
+            w.meta["optimizers"] = [{"kind": "adam"} if k % 4 == 0 else {"kind": "sgd"} for k in range(K)]
+        gpu = pu.run_gpu(w)
+        sample = [0, 1, 4, 100, 129, 254, 255]
+        for k in sample:
+            net = po.Model(models[k], w.in_shape, w.weights[k].astype(np.float64), "exact",
+                           opt=(w.meta["optimizers"][k] if with_adam else None))
+            for t in range(w.steps):
+                l, _, _ = net.sgd_step(w.x[:batch[k]].astype(np.float64), w.labels[:batch[k]], float(w.lr[k]))
+                assert abs(gpu["loss"][t, k] - l) <= F32_TOL * abs(l), (with_adam, k, t)
+            ref = net.blob()
+            scale = np.maximum(np.abs(ref), np.sqrt(np.mean(ref * ref)))
+            assert np.max(np.abs(gpu["blobs"][k] - ref) / scale) <= F32_TOL, (with_adam, k)
+        assert np.all(np.isfinite(gpu["loss"]))
