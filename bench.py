@@ -247,6 +247,27 @@ def main():
         torch.cuda.synchronize()
         del a, b
 
+    if args.optimizer == "sgd" and not args.no_unpacked:
+        # the same step with the update as a launch of its own (the library's measuring aid): how the
+        # stand-alone update kernel fares against its own HBM roofline, and what fusing it buys
+        os.environ["PACK_NO_FUSED_UPDATE"] = "1"
+        try:
+            ref = make(w.models, w.batch, w.weights)
+        finally:
+            del os.environ["PACK_NO_FUSED_UPDATE"]
+        for _ in range(10):
+            ref.step(x.data_ptr(), y.data_ptr(), lr)
+        i_sgd = [ref.launch_name(i) for i in range(ref.num_launches())].index("sgd_update")
+        ref.profile_start(i_sgd, every=4)
+        t_ref = _time_steps(ref, x, y, lr, max(args.steps // 4, 8), torch)
+        ms_r, cnt_r = ref.profile_stop()
+        ref.destroy()
+        sgd_ms = float(ms_r[i_sgd] / max(cnt_r[i_sgd], 1))
+        bpp = 12.0 + (2.0 if w.dtype == wl.BF16 else 0.0)
+        out["separate_update"] = {"ms_per_step": t_ref * 1e3, "sgd_kernel_avg_ms": sgd_ms,
+                                  "sgd_kernel_algorithmic_bytes": n_params * bpp,
+                                  "sgd_kernel_frac_of_hbm_peak": n_params * bpp / (sgd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
     if args.swap_cost:
         pk2 = make(w.models, w.batch, w.weights)
         pk2.step(x.data_ptr(), y.data_ptr(), lr)
