@@ -1059,11 +1059,10 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                             f32x4_t w;
 #pragma unroll
                             for (int e = 0; e < 4; ++e) w[e] = sgd_apply(dw_w[n][e], g[e], lrk);
-                            __builtin_nontemporal_store(w, reinterpret_cast<f32x4_t*>(p.upd_w + off));
+                            *reinterpret_cast<f32x4_t*>(p.upd_w + off) = w;
                             if (p.upd_shadow) {
                                 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
-                                __builtin_nontemporal_store(u32x2_t{pack2bf(w[0], w[1]), pack2bf(w[2], w[3])},
-                                                            reinterpret_cast<u32x2_t*>((bf16_t*)p.upd_shadow + off));
+                                *reinterpret_cast<u32x2_t*>((bf16_t*)p.upd_shadow + off) = u32x2_t{pack2bf(w[0], w[1]), pack2bf(w[2], w[3])};
                             }
                         }
                         if (keep_g) *reinterpret_cast<f32x4_t*>(gf + off) = g;
@@ -1114,11 +1113,10 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                         f32x4_t w;
 #pragma unroll
                         for (int e = 0; e < 4; ++e) w[e] = sgd_apply(dw_w[n][e], g[e], lrk);
-                        __builtin_nontemporal_store(w, reinterpret_cast<f32x4_t*>(p.upd_w + off));
+                        *reinterpret_cast<f32x4_t*>(p.upd_w + off) = w;
                         if (p.upd_shadow) {
                             typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
-                            __builtin_nontemporal_store(u32x2_t{pack2bf(w[0], w[1]), pack2bf(w[2], w[3])},
-                                                        reinterpret_cast<u32x2_t*>((bf16_t*)p.upd_shadow + off));
+                            *reinterpret_cast<u32x2_t*>((bf16_t*)p.upd_shadow + off) = u32x2_t{pack2bf(w[0], w[1]), pack2bf(w[2], w[3])};
                         }
                     }
                     if (keep_g) *reinterpret_cast<f32x4_t*>(gf + off) = g;
