@@ -47,6 +47,11 @@ struct TensorInfo {
     bool needs_grad = false;
     bool grad_written = false;
     int ld_dz = 0;           // leading dimension of dz when padded (logits), 0 = c
+    // planning state: the gradient that reaches this tensor through a residual shortcut and is added
+    // by the input-gradient product of the block's first convolution instead of a kernel of its own
+    const void* sc_dz = nullptr;
+    int sc_h = 0, sc_w = 0, sc_c = 0;
+    bool sc_down = false;
     void* act = nullptr;
     void* dz = nullptr;
     size_t elems() const { return (size_t)n * h * w * c; }
@@ -718,7 +723,10 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
 
     // ---------------- backward ----------------
     for (ModelInfo& m : p->models)
-        for (TensorInfo& t : m.tensors) t.grad_written = false;
+        for (TensorInfo& t : m.tensors) {
+            t.grad_written = false;
+            t.sc_dz = nullptr;
+        }
     // Weight gradients need only dz and the stored activations, not each other, so all of them
     // run in ONE launch (per kernel kind) after the chain of input gradients: the small layers
     // fill the gaps the big ones leave instead of each paying a launch of its own.
@@ -863,6 +871,12 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                     g.lda = to.c; g.ldb = 9 * to.c; g.ldc = ti.c;
                     if (to.c % BKc == 0 && ti.c % V == 0 && small_tensors(ti, to)) g.flags |= F_VEC_A | F_VEC_B;
                     g.ksplit = g.Kd;
+                    const bool with_sc = ti.sc_dz != nullptr;
+                    if (with_sc) {
+                        g.sc = ti.sc_dz; g.scH = ti.sc_h; g.scW = ti.sc_w; g.scC = ti.sc_c;
+                        ti.sc_dz = nullptr;
+                    }
+                    const int sc_flag = !with_sc ? 0 : (ti.sc_down ? F_SC_DOWN : F_SC_ID);
                     if (nd.stride == 2 && (g.flags & F_VEC_A)) {
                         // An input pixel of a stride-2 convolution receives gradient through the
                         // taps whose parity matches its own only (1, 2, 2 or 4 of the 9): one
@@ -879,9 +893,11 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                                 set_row_space(c, c.cls_w, c.cls_h * c.cls_w);
                                 c.Kd = (py ? 1 : 2) * (px ? 1 : 2) * to.c;
                                 c.ksplit = c.Kd;
+                                if (py && px) c.flags |= sc_flag;   // pixels with even coordinates: the subsampling shortcut's
                                 if (c.R > 0) conv_dx.push_back(c);
                             }
                     } else {
+                        g.flags |= sc_flag;
                         conv_dx.push_back(g);
                     }
                 }
@@ -889,6 +905,18 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
             // gradient through the shortcut into the block input
             if (nd.res_src >= 0 && m.tensors[nd.res_src].needs_grad) {
                 TensorInfo& rs = m.tensors[nd.res_src];
+                // The block's first layer, if it is a convolution with an input gradient of its own,
+                // adds the shortcut's share in its epilogue (it is planned after this node and is
+                // then the first writer of the tensor); PACK_NO_FUSED_SHORTCUT is a measuring aid.
+                int first = -1, readers = 0;
+                for (size_t j = 0; j < m.nodes.size(); ++j)
+                    if (m.nodes[j].in_t == nd.res_src) { first = (int)j; ++readers; }
+                const bool fuse = readers == 1 && first >= 0 && first < (int)s && m.nodes[first].kind == NODE_CONV && !m.nodes[first].kp && !rs.grad_written &&
+                                  !rs.is_input && !(nd.res_down && m.nodes[first].stride != 2) && !std::getenv("PACK_NO_FUSED_SHORTCUT");
+                if (fuse) {
+                    rs.sc_dz = to.dz; rs.sc_h = to.h; rs.sc_w = to.w; rs.sc_c = to.c; rs.sc_down = nd.res_down;
+                    continue;
+                }
                 ShortcutProb sp{};
                 sp.dz_out = to.dz; sp.src = rs.act; sp.dz_src = rs.dz;
                 sp.n = rs.n; sp.H = rs.h; sp.W = rs.w; sp.C = rs.c; sp.Ho = to.h; sp.Wo = to.w; sp.Co = to.c;

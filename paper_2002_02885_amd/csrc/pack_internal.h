@@ -40,7 +40,10 @@ enum GemmFlags : int {
                        // taps of that class only (u = 1 or u in {0, 2}, likewise v)
     F_UPDATE = 4096,   // weight gradient, not split: apply W <- W - lr[member] * dW (and b likewise) in the
                        // epilogue instead of storing the gradient for a separate update launch
-    F_KEEP_G = 8192    // with F_UPDATE: store the gradient as well
+    F_KEEP_G = 8192,   // with F_UPDATE: store the gradient as well
+    F_SC_ID = 16384,   // dX of the first layer of a residual block: add the gradient that arrives through the
+                       // identity shortcut, sc[row, col] (same shape as the output), before the mask
+    F_SC_DOWN = 32768  // likewise for the subsampling shortcut: pixel (2i, 2j) receives sc[b, i, j, col]
 };
 
 // activation kinds (paper Table 3); the value is also what GemmProb::act / mask_act hold
@@ -72,6 +75,8 @@ struct GemmProb {
     void* upd_shadow;                      // F_UPDATE: bf16 operand copy of the weights (null for fp32 packs)
     float* upd_b;                          // F_UPDATE: master bias [R]
     int member;                            // F_UPDATE: index into the step's learning-rate table
+    const void* sc;                        // F_SC_ID / F_SC_DOWN: gradient wrt the block output [n, scH, scW, scC]
+    int scH, scW, scC;
 };
 
 struct TileRef {      // one workgroup's job; prob < 0 marks a filler slot

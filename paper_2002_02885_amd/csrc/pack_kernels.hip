@@ -740,6 +740,23 @@ __device__ __forceinline__ void update_one(const GemmProb& p, size_t off, float 
 // stage and one LDS buffer instead of several, and the epilogue stages the accumulators in two
 // halves.  A tile of such a product spends most of its life in its prologue and epilogue, so what
 // counts is how many tiles a compute unit can hold at once, not the depth of one tile's pipeline.
+// Gradient that reaches output row `row` of an input-gradient problem through the block's shortcut
+// (element offset into p.sc of column 0), or -1 if none does.  Identity: same pixel.  Subsampling
+// shortcut: only pixels with even coordinates, from the pixel at half the coordinates; a problem
+// that covers one parity class of pixels (F_ROWMAP) carries the flag only for the even-even class,
+// whose rows are already numbered by the halved coordinates.
+__device__ __forceinline__ long long shortcut_row(const GemmProb& p, int row) {
+    if (p.flags & F_SC_ID) return (long long)out_row_base(p, row);
+    int b, i, j;
+    decode_row(p, row, b, i, j);
+    if (!(p.flags & F_ROWMAP)) {
+        if ((i | j) & 1) return -1;
+        i >>= 1;
+        j >>= 1;
+    }
+    return ((long long)(b * p.scH + i) * p.scW + j) * p.scC;
+}
+
 template <int MODE, typename T, int BM, int BN, int BKM, bool VEC, bool LEAN = false>
 __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, T* __restrict__ As_, T* __restrict__ Bs_, float lrk) {
     constexpr int V = ET<T>::V, BK = ET<T>::BK * BKM;
@@ -1152,6 +1169,10 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
             if (p.flags & F_RELU) v = fmaxf(v, 0.f);
             else if (p.act > ACT_RELU) v = act_apply(p.act, v);
         } else if constexpr (!IS_DW) {
+            if (p.flags & (F_SC_ID | F_SC_DOWN)) {
+                const long long so = shortcut_row(p, row);
+                if (so >= 0) v += ET<T>::to_f(((const T*)p.sc)[so + col]);
+            }
             if (p.flags & F_MASK) {
                 const float a = ET<T>::to_f(((const T*)p.aux)[off]);
                 if (p.mask_act == ACT_RELU) { if (!(a > 0.f)) v = 0.f; }
@@ -1201,6 +1222,10 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                         } else if constexpr (!IS_DW) {
                             if (p.flags & F_MASK) ap = (const T*)p.aux + off[n];
                             if (p.flags & F_ACCUM) op = (const T*)p.C + off[n];
+                            if (p.flags & (F_SC_ID | F_SC_DOWN)) {   // never together with F_ACCUM
+                                const long long so = shortcut_row(p, row);
+                                if (so >= 0) op = (const T*)p.sc + so + col;
+                            }
                         }
                     }
 #pragma unroll
@@ -1264,6 +1289,10 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                         }
                     } else if constexpr (!IS_DW) {
                         const bool accum = (p.flags & F_ACCUM) != 0;
+                        if (p.flags & (F_SC_ID | F_SC_DOWN)) {   // the shortcut's share joins before the mask
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[e] += old[e];
+                        }
                         if (!(p.flags & F_MASK) || p.mask_act == ACT_RELU) {   // absent mask source reads as ones
 #pragma unroll
                             for (int e = 0; e < 8; ++e)

@@ -452,3 +452,22 @@ def test_the_largest_pack_256_members_with_their_own_learning_rates_and_optimise
             scale = np.maximum(np.abs(ref), np.sqrt(np.mean(ref * ref)))
             assert np.max(np.abs(gpu["blobs"][k] - ref) / scale) <= F32_TOL, (with_adam, k)
         assert np.all(np.isfinite(gpu["loss"]))
+
+
+def test_shortcut_gradient_in_the_first_convolutions_epilogue_equals_the_separate_kernel(monkeypatch):
+    """The gradient through a residual shortcut is added by the input-gradient product of the block's
+    first convolution (identity: same pixel; subsampling: even pixels of the stride-2 classes or of the
+    scalar kernel's rows).  The separate shortcut kernel, kept behind an environment variable, must give
+    the same bits: the shortcut's share is exact in the pack dtype and joins the same fp32 sum."""
+    cases = [wl.config5(K=2, B=4, size=16, widths=(64, 64, 128), n_classes=10, steps=2),             # aligned: class problems
+             wl.config5(K=2, B=3, size=12, widths=(16, 24, 40), n_classes=10, steps=2),              # scalar kernels
+             wl.config5(K=2, B=4, size=16, widths=(32, 64), n_classes=10, steps=2, dtype=wl.F32)]
+    for w in cases:
+        fused = pu.run_gpu(w)
+        monkeypatch.setenv("PACK_NO_FUSED_SHORTCUT", "1")
+        separate = pu.run_gpu(w)
+        monkeypatch.delenv("PACK_NO_FUSED_SHORTCUT")
+        assert separate["launches"] > fused["launches"]
+        for k in range(w.K):
+            assert np.array_equal(fused["grads"][k], separate["grads"][k]), (w.name, w.dtype, k)
+            assert np.array_equal(fused["blobs"][k], separate["blobs"][k]), (w.name, w.dtype, k)
