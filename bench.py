@@ -29,7 +29,7 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # the epilogue) from hardware counters (FETCH_SIZE and WRITE_SIZE, each scaled by a copy kernel of known
 # size; profiles/c2_weight_gradient_update_hbm_counters.txt), valid only for the kernel source it was
 # measured on (hash of the GEMM kernel's text).
-DW_TRAFFIC = {"workload": "c2", "kernel": "gemm_lin_dw+sgd", "bytes": 420.5e6, "kernel_sha": "29e5adc2e7ab7b9b"}
+DW_TRAFFIC = {"workload": "c2", "kernel": "gemm_lin_dw+sgd", "bytes": 420.2e6, "kernel_sha": "d28042634a8728c2"}
 
 
 def _gemm_kernel_sha():

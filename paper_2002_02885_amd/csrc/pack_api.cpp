@@ -15,6 +15,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <string>
+#include <thread>
 #include <vector>
 
 using namespace packk;
@@ -1177,15 +1178,31 @@ pack_status build_device(pack_ctx* p) {
 pack_status seed_weights(pack_ctx* p, int k, uint64_t seed) {
     ModelInfo& m = p->models[k];
     std::vector<float> blob(m.n_params);
+    const bool bf16 = p->bf16;
+    // every value is a hash of (seed, member, tensor, index): the ranges can be filled by several threads
+    auto fill = [&](float* dst, size_t n, int tensor, float bound) {
+        const size_t per = 1u << 18;
+        const unsigned workers = (unsigned)std::min<size_t>(std::max(1u, std::min(16u, std::thread::hardware_concurrency())), (n + per - 1) / per);
+        auto work = [=](size_t lo, size_t hi) {
+            for (size_t i = lo; i < hi; ++i) {
+                const float v = uniform_pm(seed, k, tensor, i, bound);
+                dst[i] = bf16 ? round_to_bf16(v) : v;
+            }
+        };
+        if (workers <= 1) { work(0, n); return; }
+        std::vector<std::thread> pool;
+        const size_t step = (n + workers - 1) / workers;
+        for (unsigned t = 0; t < workers; ++t) pool.emplace_back(work, std::min(n, t * step), std::min(n, (t + 1) * step));
+        for (std::thread& t : pool) t.join();
+    };
     int tensor = 0;
     for (const NodeInfo& nd : m.nodes) {
         if (nd.kind == NODE_GAP) continue;
         const float bw = std::sqrt(6.0f / (float)nd.fan_in), bb = 1.0f / std::sqrt((float)nd.fan_in);
-        for (size_t i = 0; i < nd.w_elems; ++i) blob[nd.blob_off + i] = uniform_pm(seed, k, tensor, i, bw);
-        for (int i = 0; i < nd.out; ++i) blob[nd.blob_off + nd.w_elems + i] = uniform_pm(seed, k, tensor + 1, i, bb);
+        fill(blob.data() + nd.blob_off, nd.w_elems, tensor, bw);
+        fill(blob.data() + nd.blob_off + nd.w_elems, (size_t)nd.out, tensor + 1, bb);
         tensor += 2;
     }
-    if (p->bf16) for (float& v : blob) v = round_to_bf16(v);
     return upload_weights(p, k, blob.data());
 }
 
