@@ -110,6 +110,8 @@ def main():
                          "(pack_load + checkpoint write): the switching overhead of Section 3.3, outside the timed steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unpacked", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip measuring what this GPU sustains on a plain copy and on a register-resident MFMA loop")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise copy of 256 MiB (reads 256 MiB, writes 256 MiB) five times, "
                          "so that a hardware-counter run has a kernel of known traffic to scale by")
@@ -238,6 +240,16 @@ def main():
         "launch_us": [[nm, round(float(t) * 1e3, 2)] for nm, t in zip(names, per_launch)],
         "roofline": roofline,
     }
+
+    if not args.no_ceilings:
+        # what this GPU delivers on the simplest code of each kind, beside the published peaks used above
+        ceil = {"hbm_copy_GBps": binding.measure_ceiling("hbm_copy", stream),
+                "mfma_bf16_TFLOPs": binding.measure_ceiling("mfma_bf16", stream),
+                "mfma_fp32_TFLOPs": binding.measure_ceiling("mfma_fp32", stream)}
+        out["measured_ceilings"] = {k: round(v, 1) for k, v in ceil.items()}
+        if roofline is not None:
+            own = ceil["hbm_copy_GBps"] if roofline["bound"] == "hbm" else ceil["mfma_bf16_TFLOPs" if w.dtype == wl.BF16 else "mfma_fp32_TFLOPs"]
+            roofline["frac_of_measured_ceiling"] = roofline["achieved"] / own
 
     if args.calibrate_copy:
         a = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")

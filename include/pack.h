@@ -251,6 +251,18 @@ pack_status pack_halving_keep(const float* loss, int32_t n, int32_t keep, int32_
  * reductions, problem tables).  0 if the specification is invalid. */
 size_t pack_estimate_bytes(const pack_input_spec* input, const pack_model_spec* model, int32_t opt_kind);
 
+/* Measuring aid (Section 4.1 reports every figure on one named device; a rate is only meaningful
+ * beside what that device delivers): what this GPU sustains on the simplest code of each kind, timed
+ * with events on `stream` (host handle of a HIP stream, or null for the default stream).
+ *   PACK_CEILING_HBM_COPY: a streaming copy of 1 GiB, bytes read + bytes written, in GB/s;
+ *   PACK_CEILING_MFMA_BF16 / _FP32: a loop of 32x32 matrix instructions on register operands, the shape
+ *     the GEMM kernels use, fp32 accumulation, in TFLOP/s.
+ * Allocates its own buffers (2 GiB for the copy) and frees them before it returns; takes a few
+ * milliseconds.  value_out: host double.  PACK_EINVAL on an unknown `what` or a null pointer,
+ * PACK_EDEVICE if a HIP call fails (out of memory included). */
+enum { PACK_CEILING_HBM_COPY = 0, PACK_CEILING_MFMA_BF16 = 1, PACK_CEILING_MFMA_FP32 = 2 };
+pack_status pack_measure_ceiling(int32_t what, void* stream, double* value_out);
+
 /* load a member's weights (Section 2.2 `load`): host_src holds pack_num_params(p, k) floats in
  * the blob layout above.  For PACK_BF16 the bf16 operand copy is refreshed too.
  * Errors: PACK_EINVAL (k out of range, n_floats mismatch), PACK_EDEVICE. */

@@ -27,7 +27,7 @@ EXPORTS = ["pack_create", "pack_write_weights", "pack_step", "pack_read_loss", "
            "pack_schedule_create", "pack_schedule_next", "pack_schedule_used", "pack_schedule_destroy",
            "pack_gather_batch", "pack_set_input_mode", "pack_config_distance", "pack_opt_knn", "pack_opt_random",
            "pack_opt_batchsize", "pack_hyperband_plan", "pack_halving_keep", "pack_estimate_bytes",
-           "pack_keep_grads", "pack_launch_bytes"]
+           "pack_keep_grads", "pack_launch_bytes", "pack_measure_ceiling"]
 
 
 class pack_opt_spec(C.Structure):
@@ -95,6 +95,7 @@ def lib() -> C.CDLL:
         l.pack_read_opt_state.argtypes = [vp, i32, i32, fp, sz, C.POINTER(C.c_int64)]
         l.pack_write_opt_state.argtypes = [vp, i32, i32, fp, sz, C.c_int64]
         i64 = C.c_int64
+        l.pack_measure_ceiling.argtypes = [i32, vp, C.POINTER(C.c_double)]
         l.pack_free.argtypes = [vp, i32]
         l.pack_load.argtypes = [vp, C.POINTER(pack_model_spec), u64, C.POINTER(i32)]
         l.pack_set_batch.argtypes = [vp, i32, C.POINTER(i32)]
@@ -447,3 +448,14 @@ def estimate_bytes(B: int, in_shape, dtype: str, layers: list, batch: int, opt_k
     spec = pack_model_spec(arr, len(layers), int(batch))
     inp = pack_input_spec(B, in_shape[0], in_shape[1], in_shape[2], PACK_BF16 if dtype == "bf16" else PACK_F32)
     return int(lib().pack_estimate_bytes(C.byref(inp), C.byref(spec), OPT_KINDS[opt_kind]))
+
+
+CEILINGS = {"hbm_copy": 0, "mfma_bf16": 1, "mfma_fp32": 2}
+
+
+def measure_ceiling(what: str, stream: int = 0) -> float:
+    """GB/s of a streaming copy ("hbm_copy") or TFLOP/s of a register-resident matrix-instruction
+    loop ("mfma_bf16", "mfma_fp32") on the current device."""
+    out = C.c_double(0.0)
+    _check(lib().pack_measure_ceiling(CEILINGS[what], C.c_void_p(stream), C.byref(out)))
+    return out.value

@@ -1664,6 +1664,44 @@ pack_status pack_gather_batch(pack_t* p, const void* data_dev, const int32_t* la
     return PACK_OK;
 }
 
+pack_status pack_measure_ceiling(int32_t what, void* stream, double* value_out) {
+    if (!value_out) return fail(PACK_EINVAL, "null argument");
+    if (what < PACK_CEILING_HBM_COPY || what > PACK_CEILING_MFMA_FP32) return fail(PACK_EINVAL, "unknown ceiling");
+    hipStream_t st = (hipStream_t)stream;
+    const long long copy_bytes = 1ll << 30;                  // far beyond every cache on the chip
+    const int blocks = 256 * 8, iters = 20000, reps = 5;
+    char* buf = nullptr;
+    hipEvent_t t0 = nullptr, t1 = nullptr;
+    const size_t need = what == PACK_CEILING_HBM_COPY ? (size_t)copy_bytes * 2 : (size_t)blocks * 256 * 4;
+    auto cleanup = [&]() {
+        if (t0) (void)hipEventDestroy(t0);
+        if (t1) (void)hipEventDestroy(t1);
+        if (buf) (void)hipFree(buf);
+    };
+    hipError_t e = hipMalloc((void**)&buf, need);
+    if (e == hipSuccess) e = hipEventCreate(&t0);
+    if (e == hipSuccess) e = hipEventCreate(&t1);
+    double work = 0.0;                                       // bytes or flops of one launch
+    auto once = [&]() -> hipError_t {
+        if (what == PACK_CEILING_HBM_COPY) { work = 2.0 * (double)copy_bytes; return launch_ceiling_copy(buf, buf + copy_bytes, copy_bytes, st); }
+        return launch_ceiling_mfma(what == PACK_CEILING_MFMA_BF16, (float*)buf, blocks, iters, &work, st);
+    };
+    if (e == hipSuccess && what == PACK_CEILING_HBM_COPY) e = launch_fill_zero(buf, copy_bytes, st);
+    for (int i = 0; i < 2 && e == hipSuccess; ++i) e = once();          // warm-up
+    if (e == hipSuccess) e = hipEventRecord(t0, st);
+    for (int i = 0; i < reps && e == hipSuccess; ++i) e = once();
+    if (e == hipSuccess) e = hipEventRecord(t1, st);
+    if (e == hipSuccess) e = hipEventSynchronize(t1);
+    float ms = 0.0f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
+    cleanup();
+    if (e != hipSuccess) return fail(PACK_EDEVICE, std::string("pack_measure_ceiling: ") + hipGetErrorString(e));
+    if (!(ms > 0.0f)) return fail(PACK_EDEVICE, "pack_measure_ceiling: no time elapsed");
+    const double per_s = work * reps / ((double)ms * 1e-3);
+    *value_out = what == PACK_CEILING_HBM_COPY ? per_s / 1e9 : per_s / 1e12;
+    return PACK_OK;
+}
+
 pack_status pack_read_loss(pack_t* p, float* host_dst) {
     if (!p || !host_dst) return fail(PACK_EINVAL, "null argument");
     // members with a fused classifier head leave per-block sums; add them up now, in block order

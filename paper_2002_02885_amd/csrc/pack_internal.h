@@ -176,6 +176,8 @@ hipError_t launch_wtranspose(bool bf16, const TransposeProb* probs_dev, const in
 hipError_t launch_cast_bf16(const float* src, void* dst_bf16, long long n, hipStream_t st);
 hipError_t launch_fill_zero(void* dst, long long bytes, hipStream_t st);
 // x_out[r] = data[idx[r]], labels_out[r] = labels_all[idx[r]] for r < rows; rows of row_bytes bytes (a multiple of 2)
+hipError_t launch_ceiling_copy(const void* src, void* dst, long long bytes, hipStream_t st);
+hipError_t launch_ceiling_mfma(bool bf16, float* out, int blocks, int iters, double* flops, hipStream_t st);
 hipError_t launch_gather_rows(const void* data, const int32_t* labels_all, const long long* idx, long long n_samples,
                               int rows, long long row_bytes, void* x_out, int32_t* labels_out, int* err_flag, hipStream_t st);
 

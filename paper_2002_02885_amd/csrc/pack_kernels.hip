@@ -2250,4 +2250,66 @@ hipError_t launch_fill_zero(void* dst, long long bytes, hipStream_t st) {
     return hipGetLastError();
 }
 
+// ---- measured ceilings --------------------------------------------------------------------------
+// Two measuring aids, so that a kernel's rate can be set beside what this chip delivers on the
+// simplest possible code as well as beside the published peak: a streaming copy (every byte read
+// once and written once, 64 bytes in flight per thread) and a loop of matrix instructions on
+// operands that never leave the registers (four independent accumulator tiles per wave, so that
+// no instruction waits for the one before it).
+__global__ __launch_bounds__(256) void ceiling_copy_kernel(const u32x4_t* __restrict__ src, u32x4_t* __restrict__ dst, long long n16) {
+    const long long base = (long long)blockIdx.x * 1024 + threadIdx.x;
+    u32x4_t v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (base + j * 256 < n16) v[j] = __builtin_nontemporal_load(src + base + j * 256);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (base + j * 256 < n16) __builtin_nontemporal_store(v[j], dst + base + j * 256);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void ceiling_mfma_kernel(float* __restrict__ out, int iters) {
+    f32x16_t acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[j][e] = 0.0f;
+    // operands near 1.0 that depend on the lane, so that nothing can be folded at compile time
+    const unsigned lane_bit = threadIdx.x & 1u;
+    const u32x4_t a = u32x4_t{0x3f803f80u + lane_bit, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+    const u32x4_t b = u32x4_t{0x3f803f80u, 0x3f803f80u + lane_bit, 0x3f803f80u, 0x3f803f80u};
+    const float af = 1.0f + 0.5f * (float)lane_bit, bf = 1.0f - 0.25f * (float)lane_bit;
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if constexpr (BF16)
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), acc[j], 0, 0, 0);
+            else
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af, bf, acc[j], 0, 0, 0);
+        }
+    }
+    float sum = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sum += acc[j][e];
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = sum;
+}
+
+hipError_t launch_ceiling_copy(const void* src, void* dst, long long bytes, hipStream_t st) {
+    const long long n16 = bytes / 16;
+    if (n16 <= 0) return hipSuccess;
+    hipLaunchKernelGGL(ceiling_copy_kernel, dim3((unsigned)((n16 + 1023) / 1024)), dim3(256), 0, st, (const u32x4_t*)src, (u32x4_t*)dst, n16);
+    return hipGetLastError();
+}
+
+// `out` holds blocks * 256 floats; returns the flops of the launch in *flops
+hipError_t launch_ceiling_mfma(bool bf16, float* out, int blocks, int iters, double* flops, hipStream_t st) {
+    if (bf16) hipLaunchKernelGGL(ceiling_mfma_kernel<true>, dim3(blocks), dim3(256), 0, st, out, iters);
+    else hipLaunchKernelGGL(ceiling_mfma_kernel<false>, dim3(blocks), dim3(256), 0, st, out, iters);
+    const double per = bf16 ? 2.0 * 32 * 32 * 16 : 2.0 * 32 * 32 * 2;
+    *flops = (double)blocks * 4.0 * (double)iters * 4.0 * per;
+    return hipGetLastError();
+}
+
 }  // namespace packk
