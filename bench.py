@@ -29,14 +29,18 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # the epilogue) from hardware counters (FETCH_SIZE and WRITE_SIZE, each scaled by a copy kernel of known
 # size; profiles/c2_weight_gradient_update_hbm_counters.txt), valid only for the kernel source it was
 # measured on (hash of the GEMM kernel's text).
-DW_TRAFFIC = {"workload": "c2", "kernel": "gemm_lin_dw+sgd", "bytes": 420.2e6, "kernel_sha": "d28042634a8728c2"}
+DW_TRAFFIC = {"workload": "c2", "kernel": "gemm_lin_dw+sgd", "bytes": 373.3e6, "kernel_sha": "3603bb6b3bfcfcc9"}
 
 
 def _gemm_kernel_sha():
     import hashlib
     src = open(os.path.join(ROOT, "paper_2002_02885_amd", "csrc", "pack_kernels.hip")).read()
     a, b = src.index("struct TileGeom"), src.index("hipError_t launch_gemm(")
-    return hashlib.sha256(src[a:b].encode()).hexdigest()[:16]
+    # the order in which tiles are dealt to the XCDs decides how often an operand is fetched
+    api = open(os.path.join(ROOT, "paper_2002_02885_amd", "csrc", "pack_api.cpp")).read()
+    c, d = api.index("struct TileOrder"), api.index("void set_row_space(")
+    e, f = api.index("void emit_gemm_launch("), api.index("    Launch L;\n    L.kind = L_GEMM;")
+    return hashlib.sha256((src[a:b] + api[c:d] + api[e:f]).encode()).hexdigest()[:16]
 
 
 def _time_steps(pk, x, y, lr, steps, torch):
