@@ -92,6 +92,19 @@ def test_c2_reduced_bf16():
     _check_bf16(wl.config2(B=64, D=256, hidden=(128, 136), K=3, steps=3))
 
 
+@pytest.mark.parametrize("K", [1, 3, 4, 16])
+def test_identical_members_whose_weight_gradient_tiles_are_dealt_to_the_xcds_by_member(K, monkeypatch):
+    # K = 4: each member cut into two parts (column strips 3 and 2 wide); K = 16: two members per XCD;
+    # K = 3: falls back to the rotating deal.  Both deals must give the same bits.
+    w = wl.config2(B=160, D=384, hidden=(640, 272), K=K, steps=2)
+    _check_bf16(w, trials=1)
+    by_member = pu.run_gpu(w, steps=2, keep_first_grads=False)
+    monkeypatch.setenv("PACK_XCD_ROTATE", "1")
+    rotating = pu.run_gpu(w, steps=2, keep_first_grads=False)
+    for a, b in zip(by_member["blobs"], rotating["blobs"]):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
 def test_c2_eight_mlps_bf16_full_size():
     _check_bf16(wl.config2(), trials=1)
 
