@@ -378,9 +378,9 @@ std::vector<TileRef> xcd_order(const std::vector<TileOrder>& logical) {
 // one XCD, so the member's activations and output gradients are fetched into one L2 instead of all
 // eight; members are spread over the XCDs so that the XCDs' totals match (largest first, each to the
 // least loaded XCD).  With fewer than 8 members each one is cut into 8 / K parts that take every
-// P-th column strip of each of its problems.  Workgroups are dispatched in index order, so an XCD
-// whose next tile is slow holds back the others: every XCD walks its tiles in the launch's
-// slow-first problem order, which keeps tiles of like cost at like positions on all eight.
+// P-th column strip of each of its problems.  Every XCD walks its tiles in the launch's slow-first
+// problem order, which keeps tiles of like cost at like positions on all eight (workgroups are
+// handed out in index order, so an XCD whose next tile is slow may hold back the others).
 // Used for the weight gradients of dense layers.  cost[t]: tile t's estimate in arbitrary units.
 std::vector<TileRef> xcd_by_member(const std::vector<TileOrder>& logical, const std::vector<double>& cost,
                                    const std::vector<GemmProb>& probs) {
@@ -461,8 +461,8 @@ void emit_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, int cfg, const std
     std::vector<TileRef> tiles;
     // by member only where every XCD then walks the same sequence of tiles: members with identical
     // problem lists, no split reductions, and a member count that divides or is divided by 8
-    // (measured: 4 % faster on 8 equal MLPs; slower on mixed members and on split reductions, where
-    // tiles of unlike cost meet at the same position of different XCDs).  PACK_XCD_ROTATE: measuring aid.
+    // (measured: 4 % faster on 8 equal MLPs, 5 % slower on 32 mixed MLPs and several times slower on
+    // split reductions, so those keep the rotating deal).  PACK_XCD_ROTATE: measuring aid.
     bool by_member = mode == LIN_DW && !std::getenv("PACK_XCD_ROTATE");
     if (by_member) {
         std::vector<int> ids;
