@@ -1407,26 +1407,33 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceProb* __restric
     const int2 m = map[blockIdx.x];
     const ReduceProb p = probs[m.x];
     const float lrk = p.upd_w ? lr.lr[p.member] : 0.f;
+    // A thread owns four elements.  Partials are added in split order; the loads of eight splits of
+    // all four elements (32 loads) are issued before their adds, so that the strided reads overlap
+    // instead of paying one round trip each.
+    const int e0 = m.y * 1024 + threadIdx.x;
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < p.S; k0 += 8) {
+        float v[4][8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                v[i][j] = (k0 + j < p.S && e0 + i * 256 < p.n) ? p.in[(size_t)(k0 + j) * p.stride + e0 + i * 256] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) s[i] += v[i][j];
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int e = m.y * 1024 + i * 256 + threadIdx.x;
+        const int e = e0 + i * 256;
         if (e < p.n) {
-            // partials are added in split order; eight loads are issued before their adds so
-            // that the (strided) reads overlap instead of paying one round trip each
-            float s = 0.f;
-            for (int k0 = 0; k0 < p.S; k0 += 8) {
-                float v[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) v[j] = (k0 + j < p.S) ? p.in[(size_t)(k0 + j) * p.stride + e] : 0.f;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) s += v[j];
-            }
             if (p.upd_w) {   // fused update: the summed gradient goes straight into the weights
-                const float w = sgd_apply(p.upd_w[e], s, lrk);
+                const float w = sgd_apply(p.upd_w[e], s[i], lrk);
                 p.upd_w[e] = w;
                 if (p.upd_shadow) ((bf16_t*)p.upd_shadow)[e] = ET<bf16_t>::from_f(w);
             }
-            if (!p.upd_w || p.keep_g) p.out[e] = s;
+            if (!p.upd_w || p.keep_g) p.out[e] = s[i];
         }
     }
 }
