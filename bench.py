@@ -29,7 +29,7 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # the epilogue) from hardware counters (FETCH_SIZE and WRITE_SIZE, each scaled by a copy kernel of known
 # size; profiles/c2_weight_gradient_update_hbm_counters.txt), valid only for the kernel source it was
 # measured on (hash of the GEMM kernel's text).
-DW_TRAFFIC = {"workload": "c2", "kernel": "gemm_lin_dw+sgd", "bytes": 373.3e6, "kernel_sha": "8c172c9884a8828f"}
+DW_TRAFFIC = {"workload": "c2", "kernel": "gemm_lin_dw+sgd", "bytes": 373.4e6, "kernel_sha": "91660fd69127babe"}
 
 
 def _gemm_kernel_sha():

@@ -351,6 +351,12 @@ pack_status pack_launch_flops(const pack_t* p, int32_t i, double* flops);
  * written and their bf16 copy written (0 for other launches).  bytes: host. */
 pack_status pack_launch_bytes(const pack_t* p, int32_t i, double* bytes);
 
+/* Tile shape of launch i, for tests and measurements that need to know which kernel form the planner
+ * chose: rows and columns of an output tile, and lean != 0 for the forms that keep one operand buffer and
+ * one register stage (more workgroups per compute unit).  All three are 0 for launches that are not
+ * matrix products.  The choice never changes results.  Outputs: host int32. */
+pack_status pack_launch_tile(const pack_t* p, int32_t i, int32_t* tile_rows, int32_t* tile_cols, int32_t* lean);
+
 /* Thread-local text describing the last failing call on this thread ("" if none). */
 const char* pack_last_error(void);
 

@@ -27,7 +27,7 @@ EXPORTS = ["pack_create", "pack_write_weights", "pack_step", "pack_read_loss", "
            "pack_schedule_create", "pack_schedule_next", "pack_schedule_used", "pack_schedule_destroy",
            "pack_gather_batch", "pack_set_input_mode", "pack_config_distance", "pack_opt_knn", "pack_opt_random",
            "pack_opt_batchsize", "pack_hyperband_plan", "pack_halving_keep", "pack_estimate_bytes",
-           "pack_keep_grads", "pack_launch_bytes", "pack_measure_ceiling"]
+           "pack_keep_grads", "pack_launch_bytes", "pack_measure_ceiling", "pack_launch_tile"]
 
 
 class pack_opt_spec(C.Structure):
@@ -127,6 +127,7 @@ def lib() -> C.CDLL:
         l.pack_keep_grads.restype = C.c_int
         l.pack_launch_bytes.argtypes = [vp, i32, C.POINTER(C.c_double)]
         l.pack_launch_bytes.restype = C.c_int
+        l.pack_launch_tile.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
         for name in ("pack_free", "pack_load", "pack_set_batch", "pack_schedule_create", "pack_schedule_next",
                      "pack_schedule_used", "pack_gather_batch"):
             getattr(l, name).restype = C.c_int
@@ -309,6 +310,11 @@ class Pack:
         out = C.c_double(0.0)
         _check(lib().pack_launch_bytes(self._h, i, C.byref(out)))
         return float(out.value)
+
+    def launch_tile(self, i: int):
+        r, c, lean = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+        _check(lib().pack_launch_tile(self._h, i, C.byref(r), C.byref(c), C.byref(lean)))
+        return r.value, c.value, bool(lean.value)
 
     def launch_flops(self, i: int) -> float:
         out = C.c_double(0.0)

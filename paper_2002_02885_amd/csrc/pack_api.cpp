@@ -361,6 +361,13 @@ struct TileOrder { int prob, tm, tn, ks; };
 // one XCD; runs are dealt over the XCDs in rotation so that problems of different cost in one
 // launch spread evenly instead of landing on one XCD each.
 constexpr size_t XCD_RUN = 8;
+// The lean 128 x 64 form (forward, input gradients) hides memory latency by occupancy (four workgroups
+// per compute unit) instead of by prefetch depth, so it needs a launch with enough tiles to reach that
+// occupancy and a reduction short enough that the prologue and epilogue weigh more than the main loop
+// (measured: configs 3 and 5 gain 5 % and 8 % of their step with reductions up to 18 chunks; the
+// 256-tile launches of config 2 lose 15 %).
+constexpr int LEAN64_MAX_CHUNKS = 18;
+constexpr size_t LEAN64_MIN_TILES = 1024;
 std::vector<TileRef> xcd_order(const std::vector<TileOrder>& logical) {
     const size_t n = align_up(std::max<size_t>(logical.size(), 1), 8 * XCD_RUN);
     std::vector<TileRef> out(n, TileRef{-1, 0, 0, 0});
@@ -609,6 +616,12 @@ void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<G
     // weight gradients whose reduction is at most a few chunks long take the lean form of the
     // 128 x 128 kernel (more tiles resident per compute unit; PACK_NO_LEAN_DW is a measuring aid)
     const bool lean_ok = (mode == LIN_DW || mode == CONV_DW) && !std::getenv("PACK_NO_LEAN_DW");
+    // forward products and input gradients on 128 x 64 tiles have a lean form too (one register stage,
+    // one operand buffer, four workgroups per compute unit); PACK_LEAN64_CHUNKS sets the longest
+    // reduction, in chunks, that takes it (0: never; a measuring aid)
+    int lean64_chunks = LEAN64_MAX_CHUNKS;
+    if (const char* v = std::getenv("PACK_LEAN64_CHUNKS")) lean64_chunks = std::atoi(v);
+    const bool is_dw = mode == LIN_DW || mode == CONV_DW;
     const int chunk_k = p->bf16 ? 64 : 32;
     for (int c = 0; c < 3; ++c) {
         std::vector<GemmProb> group, lean;
@@ -617,9 +630,14 @@ void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<G
             if (eff != c) continue;
             const int chunks = (std::min(probs[i].Kd, probs[i].ksplit) + chunk_k - 1) / chunk_k;
             if (c == 0 && lean_ok && chunks <= 8) lean.push_back(probs[i]);
+            else if (c == 1 && !is_dw && chunks <= lean64_chunks) lean.push_back(probs[i]);
             else group.push_back(probs[i]);
         }
-        if (!lean.empty()) emit_gemm_launch(p, db, mode, GEMM_CFG_LEAN, lean);
+        if (!is_dw && !lean.empty() && count_tiles(lean, GEMM_CFG_LEAN64) < LEAN64_MIN_TILES && !std::getenv("PACK_LEAN64_CHUNKS")) {
+            group.insert(group.end(), lean.begin(), lean.end());   // too few tiles to fill the occupancy
+            lean.clear();
+        }
+        if (!lean.empty()) emit_gemm_launch(p, db, mode, is_dw ? GEMM_CFG_LEAN : GEMM_CFG_LEAN64, lean);
         if (!group.empty()) emit_gemm_launch(p, db, mode, c, group);
     }
 }
@@ -1614,6 +1632,17 @@ pack_status pack_launch_bytes(const pack_t* p, int32_t i, double* bytes) {
     if (!p || !bytes) return fail(PACK_EINVAL, "null argument");
     if (i < 0 || i >= (int32_t)p->plan.size()) return fail(PACK_EINVAL, "launch index out of range");
     *bytes = p->plan[i].bytes;
+    return PACK_OK;
+}
+
+pack_status pack_launch_tile(const pack_t* p, int32_t i, int32_t* tile_rows, int32_t* tile_cols, int32_t* lean) {
+    if (!p || !tile_rows || !tile_cols || !lean) return fail(PACK_EINVAL, "null argument");
+    if (i < 0 || i >= (int32_t)p->plan.size()) return fail(PACK_EINVAL, "launch index out of range");
+    const Launch& L = p->plan[i];
+    const bool gemm = L.kind == L_GEMM;
+    *tile_rows = gemm ? GEMM_TILE_M[L.tile_cfg] : 0;
+    *tile_cols = gemm ? GEMM_TILE_N[L.tile_cfg] : 0;
+    *lean = gemm && (L.tile_cfg == GEMM_CFG_LEAN || L.tile_cfg == GEMM_CFG_LEAN64);
     return PACK_OK;
 }
 

@@ -184,10 +184,11 @@ hipError_t launch_gather_rows(const void* data, const int32_t* labels_all, const
 // tile geometry the planner needs
 // configurations 0..2: aligned problems (16-byte operand loads); 3: the scalar gather for any shape
 // 4: the lean 128 x 128 form of the weight-gradient kernels (short reductions)
-constexpr int GEMM_TILE_M[5] = {128, 128, 64, 64, 128};
-constexpr int GEMM_TILE_N[5] = {128, 64, 64, 64, 128};
+constexpr int GEMM_TILE_M[6] = {128, 128, 64, 64, 128, 128};
+constexpr int GEMM_TILE_N[6] = {128, 64, 64, 64, 128, 64};
 constexpr int GEMM_CFG_SCALAR = 3;
-constexpr int GEMM_CFG_LEAN = 4;
+constexpr int GEMM_CFG_LEAN = 4;     // weight gradients, 128 x 128, short reductions
+constexpr int GEMM_CFG_LEAN64 = 5;   // forward / input gradients, 128 x 64, short reductions
 constexpr int ELEMWISE_PER_BLOCK = 2048;   // elements one block of the elementwise kernels covers
 constexpr int SGD_PER_BLOCK = 2048;        // parameters one block of the update kernel covers (measured best of 1024..8192)
 

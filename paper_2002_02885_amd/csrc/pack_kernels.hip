@@ -757,6 +757,16 @@ __device__ __forceinline__ long long shortcut_row(const GemmProb& p, int row) {
     return ((long long)(b * p.scH + i) * p.scW + j) * p.scC;
 }
 
+// Bytes of the workgroup's LDS block: the operand buffers (two of each, one in the lean forms); the
+// lean forward / input-gradient form, whose epilogue stages the whole fp32 tile, takes the larger of
+// that and the staging tile.
+template <typename T, int BM, int BN, int BK, bool LEAN, bool IS_DW>
+struct LdsBytes {
+    static constexpr size_t operands = (size_t)(LEAN ? 1 : 2) * (BM * TileGeom<T, BM, BK>::LDS_LD + BN * TileGeom<T, BN, BK>::LDS_LD) * sizeof(T);
+    static constexpr size_t staging = (size_t)BM * (BN + 8) * 4;
+    static constexpr size_t value = (LEAN && !IS_DW && staging > operands) ? staging : operands;
+};
+
 template <int MODE, typename T, int BM, int BN, int BKM, bool VEC, bool LEAN = false>
 __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, T* __restrict__ As_, T* __restrict__ Bs_, float lrk) {
     constexpr int V = ET<T>::V, BK = ET<T>::BK * BKM;
@@ -769,7 +779,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
     // in flight per workgroup; a skinny layer has too few workgroups per compute unit to hide that
     // latency by occupancy alone.
     constexpr int ST = LEAN ? 1 : StageCount<BM, BN, BKM, VEC>::value;
-    static_assert(!LEAN || (VEC && (MODE == LIN_DW || MODE == CONV_DW) && BM == 128), "lean form: aligned weight gradients");
+    static_assert(!LEAN || (VEC && BM == 128 && (IS_DW ? BN == 128 : BN == 64)), "lean form: aligned operands, 128x128 weight gradients or 128x64 forward / input gradients");
     T(*As)[BM][GA::LDS_LD] = reinterpret_cast<T(*)[BM][GA::LDS_LD]>(As_);
     T(*Bs)[BN][GB::LDS_LD] = reinterpret_cast<T(*)[BN][GB::LDS_LD]>(Bs_);
 
@@ -1026,8 +1036,10 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
     // and the result is written as full vectors instead of one element per lane.
     // Accumulator register e of a 32x32 block holds row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
     constexpr int SLD = BN + 8;   // 4 rows apart = 32 banks apart: the two half-waves do not collide
-    constexpr int HALVES = LEAN ? 2 : 1;   // the lean form has one operand buffer: room for half the tile at a time
-    static_assert((size_t)(BM / HALVES) * SLD * 4 <= (size_t)(LEAN ? 1 : 2) * (BM * GA::LDS_LD + BN * GB::LDS_LD) * sizeof(T), "staging tile must fit");
+    // the lean weight-gradient form has one operand buffer: room for half the tile at a time; the lean
+    // forward / input-gradient form sizes its LDS block for the whole staging tile (LeanLds below)
+    constexpr int HALVES = (LEAN && IS_DW) ? 2 : 1;
+    static_assert((size_t)(BM / HALVES) * SLD * 4 <= LdsBytes<T, BM, BN, BK, LEAN, IS_DW>::value, "staging tile must fit");
     float(*stage)[SLD] = reinterpret_cast<float(*)[SLD]>(As_);
     // the remaining weights of the tile: their round trip runs under the staging of the accumulators
     if constexpr (IS_DW) {
@@ -1039,7 +1051,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
             }
         }
     }
-    if constexpr (LEAN) {
+    if constexpr (LEAN && IS_DW) {
         // two passes: the waves that own the upper (then the lower) half of the rows stage their
         // accumulators, then all threads apply that half
         float* const gf = (float*)p.C + (size_t)tr.ks * p.split_stride;
@@ -1358,7 +1370,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
     if (p.flags & F_AUX_INPUT) p.aux = xin;
     // one block: operand tiles A (two buffers) then B (two buffers); the epilogue reuses it
     constexpr int NBUF = LEAN ? 1 : 2;
-    __shared__ __attribute__((aligned(16))) T lds[NBUF * BM * TileGeom<T, BM, BK>::LDS_LD + NBUF * BN * TileGeom<T, BN, BK>::LDS_LD];
+    __shared__ __attribute__((aligned(16))) T lds[LdsBytes<T, BM, BN, BK, LEAN, (MODE == LIN_DW || MODE == CONV_DW)>::value / sizeof(T)];
     T* const As = lds;
     T* const Bs = lds + NBUF * BM * TileGeom<T, BM, BK>::LDS_LD;
     float lrk = 0.f;
@@ -1377,6 +1389,10 @@ static void launch_gemm_tile(int tile_cfg, const GemmProb* probs, const TileRef*
         case GEMM_CFG_LEAN:
             if constexpr (MODE == LIN_DW || MODE == CONV_DW)
                 hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 128, 1, true, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, la);
+            break;
+        case GEMM_CFG_LEAN64:
+            if constexpr (!(MODE == LIN_DW || MODE == CONV_DW))
+                hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 64, 1, true, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, la);
             break;
         default: hipLaunchKernelGGL((gemm_kernel<MODE, T, 64, 64, 1, false>), dim3(n), dim3(256), 0, st, probs, tiles, x, la); break;
     }

@@ -49,7 +49,8 @@ def run_gpu(w: wl.PackWorkload, steps=None, lr=None, x_dev=None, y_dev=None, kee
         out = {"loss": loss, "grads": grads, "logits": logits, "pred_first": pred_first,
                "pred": [pk.read_pred(k) for k in range(w.K)],
                "blobs": [pk.read_weights(k) for k in range(w.K)],
-               "launches": pk.num_launches(), "device_bytes": pk.device_bytes()}
+               "launches": pk.num_launches(), "device_bytes": pk.device_bytes(),
+               "tiles": [pk.launch_tile(i) for i in range(pk.num_launches())]}
         if opts:
             out["opt_state"] = [[pk.read_opt_state(k, s) for s in range({"sgd": 0, "momentum": 1, "adagrad": 1, "adam": 2}[opts[k]["kind"]])]
                                 for k in range(w.K)]

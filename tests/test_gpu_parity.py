@@ -136,6 +136,30 @@ def test_c5_reduced_fp32_and_bf16():
     _check_bf16(wl.config5(K=2, B=4, size=16, widths=(8, 16, 32, 64), n_classes=10, steps=2))
 
 
+@pytest.mark.parametrize("make", [
+    lambda: wl.config5(K=2, B=8, size=16, steps=2),                                   # bf16, 128 x 64 and 128 x 128 tiles
+    lambda: wl.config3(K=2, B=16, size=16, widths=(32, 64, 128), steps=2),            # fp32
+    lambda: wl.config2(B=256, D=384, hidden=(64, 192), K=3, steps=2),                 # dense layers, bf16
+])
+def test_lean_form_of_forward_and_input_gradient_tiles_gives_the_same_bits(make, monkeypatch):
+    # the occupancy-bound form of the 128 x 64 kernels multiplies the same chunks in the same order:
+    # forced on for every reduction length and tile count, it must reproduce the regular form exactly
+    w = make()
+    monkeypatch.setenv("PACK_MIN_TILES", "1")       # small layers keep the 128-row tiles they would get in a large pack
+    monkeypatch.setenv("PACK_LEAN64_CHUNKS", "0")
+    regular = pu.run_gpu(w, steps=2)
+    monkeypatch.setenv("PACK_LEAN64_CHUNKS", "100000")
+    lean = pu.run_gpu(w, steps=2)
+    assert not any(t == (128, 64, True) for t in regular["tiles"])
+    assert any(t == (128, 64, True) for t in lean["tiles"])
+    for a, b in zip(regular["blobs"], lean["blobs"]):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    for a, b in zip(regular["logits"], lean["logits"]):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    for a, b in zip(regular["grads"], lean["grads"]):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
 def test_c5_resnet_style_bf16_full_width_reduced_images():
     _check_bf16(wl.config5(K=2, B=8, size=16, steps=2))
 
