@@ -15,6 +15,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <string>
+#include <system_error>
 #include <thread>
 #include <vector>
 
@@ -1281,7 +1282,16 @@ pack_status seed_weights(pack_ctx* p, int k, uint64_t seed) {
         if (workers <= 1) { work(0, n); return; }
         std::vector<std::thread> pool;
         const size_t step = (n + workers - 1) / workers;
-        for (unsigned t = 0; t < workers; ++t) pool.emplace_back(work, std::min(n, t * step), std::min(n, (t + 1) * step));
+        size_t started = 0;   // elements handed to threads so far
+        try {
+            for (unsigned t = 0; t < workers; ++t) {
+                pool.emplace_back(work, std::min(n, t * step), std::min(n, (t + 1) * step));
+                started = std::min(n, (t + 1) * step);
+            }
+        } catch (const std::system_error&) {
+            // no more threads to be had: this thread fills the rest
+        }
+        work(started, n);
         for (std::thread& t : pool) t.join();
     };
     int tensor = 0;
