@@ -736,10 +736,6 @@ __device__ __forceinline__ void update_one(const GemmProb& p, size_t off, float 
     if (p.upd_shadow) ((bf16_t*)p.upd_shadow)[off] = ET<bf16_t>::from_f(w);
 }
 
-// LEAN (weight gradients whose reduction is only a few chunks long, aligned operands): one register
-// stage and one LDS buffer instead of several, and the epilogue stages the accumulators in two
-// halves.  A tile of such a product spends most of its life in its prologue and epilogue, so what
-// counts is how many tiles a compute unit can hold at once, not the depth of one tile's pipeline.
 // Gradient that reaches output row `row` of an input-gradient problem through the block's shortcut
 // (element offset into p.sc of column 0), or -1 if none does.  Identity: same pixel.  Subsampling
 // shortcut: only pixels with even coordinates, from the pixel at half the coordinates; a problem
@@ -757,6 +753,14 @@ __device__ __forceinline__ long long shortcut_row(const GemmProb& p, int row) {
     return ((long long)(b * p.scH + i) * p.scW + j) * p.scC;
 }
 
+// LEAN (aligned operands, reductions only a few chunks long): one register stage and one LDS buffer
+// instead of several.  A tile of such a product spends most of its life in its prologue and
+// epilogue, so what counts is how many tiles a compute unit can hold at once, not the depth of one
+// tile's pipeline.  Two forms: 128 x 128 weight gradients, whose epilogue stages the accumulators in
+// two halves (three workgroups per compute unit), and 128 x 64 forward products / input gradients,
+// whose LDS block is sized for the epilogue's staging tile (four workgroups per compute unit).
+// Both multiply the same chunks in the same order as the regular kernels: the bits are the same.
+//
 // Bytes of the workgroup's LDS block: the operand buffers (two of each, one in the lean forms); the
 // lean forward / input-gradient form, whose epilogue stages the whole fp32 tile, takes the larger of
 // that and the staging tile.
