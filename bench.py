@@ -116,6 +116,8 @@ def main():
     ap.add_argument("--swap-cost", action="store_true",
                     help="also time a member leaving a live pack (checkpoint read + pack_free) and a member joining "
                          "(pack_load + checkpoint write): the switching overhead of Section 3.3, outside the timed steps")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="also time the same members as two packs of K/2 on two streams (pack against device concurrency)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unpacked", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true",
@@ -151,8 +153,8 @@ def main():
         x = (xs.to(torch.bfloat16) if w.dtype == wl.BF16 else xs).cuda().contiguous()
         y = torch.randint(0, w.n_classes, (w.K, w.B), generator=g, dtype=torch.int32).cuda().contiguous()
 
-    def make(models, batch, weights):
-        pk = binding.Pack(w.B, w.in_shape, w.dtype, models, batch, stream=stream)
+    def make(models, batch, weights, on_stream=None):
+        pk = binding.Pack(w.B, w.in_shape, w.dtype, models, batch, stream=stream if on_stream is None else on_stream)
         if args.different_inputs and len(models) > 1:
             pk.set_input_mode(True)
         for k, blob in enumerate(weights):
@@ -321,6 +323,29 @@ def main():
         out["unpacked_ms_per_step"] = t_seq * 1e3
         out["speedup_vs_unpacked"] = t_seq / t_pack
         out["impv"] = (t_seq - t_pack) / t_seq
+
+    if args.two_streams and w.K >= 2 and not args.different_inputs:
+        # packing against concurrency on the device (Section 4.6 compares pack with running the models side
+        # by side): the same members as two packs of K/2 on two streams of default priority, their steps
+        # enqueued alternately and left to the hardware to overlap
+        h = w.K // 2
+        sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+        pa = make(w.models[:h], w.batch[:h], w.weights[:h], sa.cuda_stream)
+        pb = make(w.models[h:], w.batch[h:], w.weights[h:], sb.cuda_stream)
+        torch.cuda.synchronize()
+
+        def both(n):
+            for _ in range(n):
+                pa.step(x.data_ptr(), y.data_ptr(), lr[:h])
+                pb.step(x.data_ptr(), y.data_ptr(), lr[h:])
+        both(max(args.warmup, 2))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        both(args.steps)
+        torch.cuda.synchronize()
+        out["two_half_packs_on_two_streams_ms_per_step"] = (time.perf_counter() - t0) / args.steps * 1e3
+        pa.destroy()
+        pb.destroy()
 
     if not args.no_cpu_baseline:
         from oracle import pack_oracle as po
