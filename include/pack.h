@@ -71,7 +71,7 @@ typedef enum {
     PACK_RES_END = 5,   /* y = relu(current + shortcut(source)); must directly follow PACK_CONV3X3.
                            shortcut = identity when shapes agree; otherwise source[b,2i,2j,c] for
                            c < Cin and 0 for the remaining channels (parameter-free) */
-    /* the other activations of the paper's search space (Section 6, Table 3); like PACK_RELU each
+    /* the other activations of the paper's search space (Section 5.3, Table 3); like PACK_RELU each
        must directly follow PACK_LINEAR or PACK_CONV3X3 */
     PACK_SIGMOID = 6,   /* 1 / (1 + exp(-z)) */
     PACK_TANH = 7,      /* tanh(z) */
@@ -81,7 +81,7 @@ typedef enum {
 
 typedef enum { PACK_F32 = 0, PACK_BF16 = 1 } pack_dtype;
 
-/* Optimisers of the paper's search space (Section 6, Table 3).  A member's optimiser is one of its
+/* Optimisers of the paper's search space (Section 5.3, Table 3).  A member's optimiser is one of its
  * hyper-parameters (Section 2.2, task trait (a)); members of one pack may differ (Table 2,
  * "Optimizer: Different").  The paper prints no update formula; the library follows the published
  * definitions of the methods it names, always with gradients taken at the pre-update weights:
@@ -142,8 +142,8 @@ pack_status pack_create(const pack_input_spec* input, const pack_model_spec* mod
  * Errors: PACK_EINVAL (k out of range or vacant), PACK_ENOMEM, PACK_EDEVICE; the pack is unchanged then. */
 pack_status pack_free(pack_t* p, int32_t k);
 
-/* load of one more member into a live pack (Section 2.2 `load`; Section 3.3: "a new model can be
- * loaded and packed with the incomplete models").  The member takes the lowest vacant slot, or a new
+/* load of one more member into a live pack (Section 2.2 `load`; Section 3.3: a fresh model may join
+ * the members that have not finished yet).  The member takes the lowest vacant slot, or a new
  * slot at the end (the number of slots grows by one); *k_out receives the slot.  Its weights are
  * seeded as in pack_create from (seed, slot) (use pack_write_weights / pack_write_opt_state to load a
  * checkpoint), its optimiser is PACK_OPT_SGD.  Other members as in pack_free.
@@ -160,7 +160,7 @@ pack_status pack_set_batch(pack_t* p, int32_t B, const int32_t* batch);
 
 /* Which data the members train on.  PACK_INPUT_SHARED (the default; Section 3.4): one batch and one
  * label vector for all members.  PACK_INPUT_PER_MEMBER (the "Training Data: Different" rows of the
- * paper's ablation, Section 4.3 / Table 2): every slot has its own batch; pack_step then takes x_dev as
+ * paper's ablation, Section 4.7 / Table 2): every slot has its own batch; pack_step then takes x_dev as
  * [pack_num_slots][B, H, W, C] and labels_dev as [pack_num_slots][B], and member k trains on rows
  * [0, b_k) of block k.  Nothing is shared between members any more: each first layer (and, for
  * convolutions over few channels, each im2col copy) reads its own block.  Changing the mode plans the
@@ -175,8 +175,8 @@ int32_t pack_num_slots(const pack_t* p);
 /* b_k of member k; 0 if the slot is vacant or out of range. */
 int32_t pack_member_batch(const pack_t* p, int32_t k);
 
-/* Epoch schedule for members with different batch sizes (Section 3.2, "we track the progress of each
- * model individually"; step counts as in Section 3.3).  Host logic, no GPU involved.  The shared
+/* Epoch schedule for members with different batch sizes (Section 3.2: every member's progress
+ * through the dataset is followed separately; step counts as in Section 3.3).  Host logic, no GPU involved.  The shared
  * batch of a step has the size of the largest batch among the members that have not yet used the
  * whole dataset and is cut, in dataset order, from the samples THAT member has not used; every other
  * unfinished member trains on the leading rows.  When the member with the largest batch has used
@@ -232,7 +232,8 @@ pack_status pack_gather_batch(pack_t* p, const void* data_dev, const int32_t* la
  *   Hyperband paper it cites): bracket j has rungs_out[j] rungs; the rungs of all brackets follow each
  *   other in n_out / r_out (configurations alive in the rung, resource units each has been trained for
  *   when the rung ends).  capacity: entries available in n_out and r_out.
- * pack_halving_keep: the `keep` smallest of n losses, the earlier on ties, as increasing indices.
+ * pack_halving_keep: the `keep` smallest of n losses, the earlier on ties, as increasing indices.  A NaN loss
+ *   (a diverged configuration) ranks after every number, +inf included, so it never displaces a finite one.
  * Errors: PACK_EINVAL. */
 int32_t pack_config_distance(const int32_t* a, const int32_t* b, const uint8_t* categorical, int32_t n_dims);
 pack_status pack_opt_knn(const int32_t* feats, const uint8_t* categorical, int32_t T, int32_t D, const uint64_t* need,
@@ -284,7 +285,7 @@ pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, c
  * Errors: PACK_EINVAL (null, k out of range, unknown kind, parameter outside its range), PACK_ENOMEM. */
 pack_status pack_set_optimizer(pack_t* p, int32_t k, const pack_opt_spec* spec);
 
-/* The optimiser part of free's checkpoint (Section 2.2: the state is stored with the model): state
+/* The optimiser part of free's checkpoint (Section 2.2 keeps an optimiser's state with its model): state
  * array `slot` of member k in the blob layout of the weights (slot 0: momentum / Adagrad accumulator
  * or Adam's first moment; slot 1: Adam's second moment) and, if `steps` is not null, the number of
  * steps the optimiser has taken.  pack_write_opt_state restores both (the load of a checkpoint).
@@ -346,9 +347,10 @@ pack_status pack_launch_name(const pack_t* p, int32_t i, char* buf, size_t n);
  * the launch executes (0 for launches that are not matrix products).  flops: host. */
 pack_status pack_launch_flops(const pack_t* p, int32_t i, double* flops);
 
-/* Algorithmic bytes of launch i if it is a matrix-product launch: every operand read once, every
- * result written once, plus, where the update is applied in the same kernel, the weights read and
- * written and their bf16 copy written (0 for other launches).  bytes: host. */
+/* Algorithmic bytes of launch i if it is a matrix-product launch: every operand read once (an operand
+ * that several members share, the input batch of Section 3.4 or its im2col copy, once for the whole
+ * launch), every result written once, plus, where the update is applied in the same kernel, the
+ * weights read and written and their bf16 copy written (0 for other launches).  bytes: host. */
 pack_status pack_launch_bytes(const pack_t* p, int32_t i, double* bytes);
 
 /* Tile shape of launch i, for tests and measurements that need to know which kernel form the planner

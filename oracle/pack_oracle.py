@@ -23,7 +23,7 @@ The paper fixes none of the layer numerics; the readings used here are:
   * the other activations of the paper's search space (Table 3): sigmoid 1/(1+e^-z), tanh, and
     leaky ReLU max(z, a*z) with a = 0.2 (the default slope of the framework the paper ran on;
     the paper names no slope); derivative of leaky ReLU at 0 is a;
-  * the other optimisers of Table 3, each with state "stored with the model" (Section 2.2), all
+  * the other optimisers of Table 3, each with its state kept beside the model (Section 2.2), all
     applied to gradients taken at the pre-update weights:
       momentum  acc <- mu*acc + g;  W <- W - lr*acc                       (acc starts at 0)
       adagrad   acc <- acc + g*g;   W <- W - lr*g/sqrt(acc)               (acc starts at acc0 > 0)
@@ -336,6 +336,7 @@ class Model:
         """loss (mean over rows), argmax predictions, and [dW, db] per parameterised layer."""
         q = self.q
         logits, tape = self.forward(X)
+        self.last_logits = logits                  # kept for tests that compare the argmax margin
         loss, dlogits, pred = softmax_xent(logits, np.asarray(y))
         g = dlogits.reshape(dlogits.shape[0], 1, 1, -1)
         grads = [None] * len(self.params)
@@ -396,6 +397,7 @@ def train_pack(models, in_shape, blobs, batch, lr, x, labels, steps, mode="exact
     and `labels` at every step (the same batch each step).  Returns a dict with
       loss  [steps, K]   pre-update losses,
       pred  list over steps of list over models of int32 [b_k],
+      logits list over steps of list over models of float64 [b_k, C_k] (what `pred` is the argmax of),
       blobs list of K flat float64 weight vectors after the last step,
       grads (when keep_grads) list over steps of list over models of flat float64 gradients,
       nets  the K trained Model objects (optimiser state included).
@@ -404,18 +406,20 @@ def train_pack(models, in_shape, blobs, batch, lr, x, labels, steps, mode="exact
     nets = [Model(models[k], in_shape, blobs[k], mode, acc_noise, opt=(optimizers[k] if optimizers else None))
             for k in range(K)]
     loss = np.zeros((steps, K))
-    preds, grads = [], []
+    preds, grads, logits = [], [], []
     for t in range(steps):
         preds.append([])
         grads.append([])
+        logits.append([])
         for k, net in enumerate(nets):
             b = int(batch[k])
             l, p, g = net.sgd_step(x[:b], labels[:b], float(lr[k]))
             loss[t, k] = l
             preds[-1].append(p)
+            logits[-1].append(net.last_logits)
             if keep_grads:
                 grads[-1].append(Model.flatten_grads(g))
-    out = {"loss": loss, "pred": preds, "blobs": [n.blob() for n in nets], "nets": nets}
+    out = {"loss": loss, "pred": preds, "logits": logits, "blobs": [n.blob() for n in nets], "nets": nets}
     if keep_grads:
         out["grads"] = grads
     return out

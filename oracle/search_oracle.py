@@ -135,8 +135,10 @@ def hyperband_brackets(R, eta):
 
 
 def keep_best(losses, keep):
-    """Indices of the `keep` smallest losses, the earlier one on ties, in increasing index order."""
-    order = sorted(range(len(losses)), key=lambda i: (losses[i], i))
+    """Indices of the `keep` smallest losses, the earlier one on ties, in increasing index order.
+    A loss that is not a number (a diverged run) ranks after every number, +inf included: Section 5.1
+    keeps the best fraction, and a run without a loss cannot be among the best."""
+    order = sorted(range(len(losses)), key=lambda i: (1, 0.0, i) if math.isnan(losses[i]) else (0, losses[i], i))
     return sorted(order[:keep])
 
 

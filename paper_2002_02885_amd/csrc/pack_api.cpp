@@ -14,6 +14,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <map>
 #include <string>
 #include <system_error>
 #include <thread>
@@ -505,6 +506,12 @@ void emit_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, int cfg, const std
     L.map_off = db.add(tiles.data(), tiles.size() * sizeof(TileRef));
     L.n = (int)tiles.size();
     const double esz = p->bf16 ? 2.0 : 4.0;
+    // An operand that several problems of the launch read (the shared input batch or its im2col copy,
+    // Section 3.4) counts once, at the size of its largest reader (smaller batches are prefixes of it).
+    std::map<std::pair<int, long long>, double> shared_a, shared_b;
+    auto operand_key = [](const void* ptr, bool is_input, long long x_off) {
+        return is_input ? std::make_pair(1, x_off) : std::make_pair(0, (long long)(uintptr_t)ptr);
+    };
     for (const GemmProb& g : probs) {
         L.flops += 2.0 * g.R * g.Q * g.Kd;
         const double out = (double)g.R * g.Q;
@@ -518,13 +525,19 @@ void emit_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, int cfg, const std
                           c = out * (1.0 + ((g.flags & F_MASK) ? 1.0 : 0.0) + ((g.flags & F_ACCUM) ? 1.0 : 0.0)); break;
             default: a = (double)g.R * g.Kd; b = (double)g.Kd / (g.Ho * g.Wo) * g.H * g.W * g.Cin; break;
         }
-        L.bytes += (a + b + c) * esz;
+        double& sa = shared_a[operand_key(g.A, (g.flags & F_A_INPUT) != 0, g.x_off)];
+        double& sb = shared_b[operand_key(g.B, (g.flags & F_B_INPUT) != 0, g.x_off)];
+        sa = std::max(sa, a);
+        sb = std::max(sb, b);
+        L.bytes += c * esz;
         if (mode == LIN_DW || mode == CONV_DW) {
             const double splits = std::max(1, (g.Kd + g.ksplit - 1) / g.ksplit);
             if (!(g.flags & F_UPDATE) || (g.flags & F_KEEP_G)) L.bytes += out * 4.0 * splits;      // gradient (or partials) written
             if (g.flags & F_UPDATE) L.bytes += out * (8.0 + (g.upd_shadow ? 2.0 : 0.0));            // W read + written, bf16 copy written
         }
     }
+    for (const auto& kv : shared_a) L.bytes += kv.second * esz;
+    for (const auto& kv : shared_b) L.bytes += kv.second * esz;
     p->plan.push_back(L);
 }
 
@@ -569,16 +582,6 @@ void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<G
     }
     if (!scalar.empty()) emit_gemm_launch(p, db, mode, GEMM_CFG_SCALAR, scalar);
     if (probs.empty()) return;
-    if (std::getenv("PACK_GEMM_ONE_PER_LAUNCH")) {
-        // measuring aid: every problem in a launch of its own, so that per-launch timing shows
-        // each layer separately (results do not depend on it)
-        for (const GemmProb& g : probs) {
-            int c = 0;
-            while (c < 2 && padded_work(g, c + 1) < 0.8 * padded_work(g, c)) ++c;
-            emit_gemm_launch(p, db, mode, c, std::vector<GemmProb>(1, g));
-        }
-        return;
-    }
     // The tile shape only partitions the output; the summation order of an element does not
     // depend on it, so a member's bits do not depend on who else is in the launch.  Each problem
     // prefers the shape that multiplies the fewest padding elements (a 64-channel layer wastes
@@ -588,7 +591,7 @@ void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<G
     // (measured: dense products are better off with one larger tile per compute unit than with two
     // smaller ones, convolutions the other way round)
     size_t min_tiles = (mode == LIN_FWD || mode == LIN_DX || mode == LIN_DW) ? 256 : 512;
-    if (const char* v = std::getenv("PACK_MIN_TILES")) min_tiles = (size_t)std::max(1, std::atoi(v));   // tuning knob
+    if (const char* v = std::getenv("PACK_MIN_TILES")) min_tiles = (size_t)std::max(1, std::atoi(v));   // tests: large-pack tile shapes on small cases
     int floor_cfg = 0;
     while (floor_cfg < 2 && count_tiles(probs, floor_cfg) < min_tiles) ++floor_cfg;
     std::vector<int> want(probs.size());
@@ -603,20 +606,9 @@ void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<G
     int main_cfg = 0;
     for (int c = 1; c < 3; ++c)
         if (work[c] > work[main_cfg]) main_cfg = c;
-    {   // tuning knob: PACK_GEMM_CFG_FWD / _DX / _DW (linear layers) and PACK_GEMM_CFG_CONV_FWD /
-        // _CONV_DX / _CONV_DW = 0..2 force the tile configuration of the launches of that kind
-        // (results do not depend on it)
-        const char* names[6] = {"PACK_GEMM_CFG_FWD", "PACK_GEMM_CFG_DX", "PACK_GEMM_CFG_DW",
-                                "PACK_GEMM_CFG_CONV_FWD", "PACK_GEMM_CFG_CONV_DX", "PACK_GEMM_CFG_CONV_DW"};
-        const char* v = std::getenv(names[mode]);
-        if (v && v[0] >= '0' && v[0] <= '2' && v[1] == 0) {
-            emit_gemm_launch(p, db, mode, v[0] - '0', probs);
-            return;
-        }
-    }
     // weight gradients whose reduction is at most a few chunks long take the lean form of the
-    // 128 x 128 kernel (more tiles resident per compute unit; PACK_NO_LEAN_DW is a measuring aid)
-    const bool lean_ok = (mode == LIN_DW || mode == CONV_DW) && !std::getenv("PACK_NO_LEAN_DW");
+    // 128 x 128 kernel (more tiles resident per compute unit)
+    const bool lean_ok = (mode == LIN_DW || mode == CONV_DW);
     // forward products and input gradients on 128 x 64 tiles have a lean form too (one register stage,
     // one operand buffer, four workgroups per compute unit); PACK_LEAN64_CHUNKS sets the longest
     // reduction, in chunks, that takes it (0: never; a measuring aid)
@@ -896,11 +888,7 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 // long reductions (many pixels) are split over workgroups; the split length
                 // depends on the layer shape only, partial results are summed in split order
                 const int out_tiles = ((nd.out + 127) / 128) * ((q_dim + 127) / 128);
-                int chunk = (out_tiles == 1) ? 1024 : 8192;   // a one-tile output gets its parallelism from splits
-                if (const char* v = std::getenv("PACK_DW_SPLIT_ROWS")) {   // measuring aid: split length of multi-tile outputs
-                    const int c = std::atoi(v);
-                    if (c >= 64 && out_tiles > 1) chunk = c;
-                }
+                const int chunk = (out_tiles == 1) ? 1024 : 8192;   // a one-tile output gets its parallelism from splits
                 int S = std::min(128, std::max(1, (rows + chunk - 1) / chunk));
                 g.ksplit = (int)align_up((size_t)(rows + S - 1) / S, 64);
                 S = (rows + g.ksplit - 1) / g.ksplit;

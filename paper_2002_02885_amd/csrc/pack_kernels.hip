@@ -218,12 +218,6 @@ struct TileGeom {
     static_assert(BK % (16 * 4) == 0 || BK % 32 == 0, "reduction extent");
 };
 
-// bit m set: GEMM mode m issues its operand loads as assembly statements with hand-placed
-// waits (see load_vec); clear: ordinary loads, waits left to the compiler
-#ifndef PACK_ASM_MODES
-#define PACK_ASM_MODES 63
-#endif
-
 typedef const __attribute__((address_space(1))) u32x4_t* gvec_ptr;
 typedef const __attribute__((address_space(1))) unsigned short* gu16_ptr;
 typedef const __attribute__((address_space(1))) float* gf32_ptr;
@@ -246,13 +240,9 @@ __device__ __forceinline__ u32x4_t load_vec(const GemmProb& p, int r, int k, int
     ok = ok && (k < kend) && live;
     const T* base = (const T*)(IS_A ? p.A : p.B);
     const void* ptr = ok ? (const void*)(base + off) : p.zeros;
-    if constexpr ((PACK_ASM_MODES >> MODE) & 1) {
-        u32x4_t v;
-        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(ptr) : "memory");
-        return v;
-    } else {
-        return *(gvec_ptr)ptr;
-    }
+    u32x4_t v;
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(ptr) : "memory");
+    return v;
 }
 
 // number of load_vec() calls fetch_tile<..., VEC = true> makes per thread and chunk
@@ -494,7 +484,7 @@ template <int MODE, typename T, bool IS_A, int BR, int BK, bool VEC>
 struct Fetcher {
     typedef TileGeom<T, BR, BK> G;
     static constexpr bool KC = IS_A ? OperandLayout<MODE>::A_KC : OperandLayout<MODE>::B_KC;
-    static constexpr bool BUF = VEC && (((PACK_ASM_MODES >> MODE) & 1) != 0);
+    static constexpr bool BUF = VEC;
     static constexpr bool GATHER_KC = BUF && IS_A && (MODE == CONV_FWD || MODE == CONV_DX);
     static constexpr bool WEIGHT_KC = BUF && !IS_A && (MODE == CONV_DX || MODE == CONV_FWD);
     static constexpr bool GATHER_RC = BUF && !IS_A && MODE == CONV_DW;
@@ -708,22 +698,9 @@ __device__ __forceinline__ void for_each_stage(std::integer_sequence<int, Is...>
     (f(std::integral_constant<int, Is>{}), ...);
 }
 
-#ifndef PACK_ST_64x64
-#define PACK_ST_64x64 4
-#endif
-#ifndef PACK_ST_128x64
-#define PACK_ST_128x64 3
-#endif
-#ifndef PACK_ST_128x128
-#define PACK_ST_128x128 2
-#endif
-#ifndef PACK_DW_EARLY
-#define PACK_DW_EARLY 0   // 16-byte weight vectors per thread requested ahead of the main loop (fused update)
-#endif
-
 template <int BM, int BN, int BKM, bool VEC>
-struct StageCount {   // register stages of prefetch per tile shape (bounded by the register file)
-    static constexpr int value = (BKM > 1 || !VEC) ? 2 : ((BM * BN >= 128 * 128) ? PACK_ST_128x128 : ((BM * BN >= 128 * 64) ? PACK_ST_128x64 : PACK_ST_64x64));
+struct StageCount {   // register stages of prefetch per tile shape (bounded by the register file): 2, 3, 4 from the largest tile down
+    static constexpr int value = (BKM > 1 || !VEC) ? 2 : ((BM * BN >= 128 * 128) ? 2 : ((BM * BN >= 128 * 64) ? 3 : 4));
 };
 
 // the SGD update of one parameter; every path that applies it (update kernels, fused epilogues)
@@ -823,28 +800,17 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
         }
     }
     // Weight-gradient tiles with the fused update: a thread owns four consecutive columns (one
-    // 16-byte vector of fp32 weights) in DW_NIT rows.  DW_EARLY of them can be requested here,
-    // ahead of the operands, the rest when the main loop ends.  Measured: requesting any early is
-    // slower (83 -> 86 us on the headline workload), because loads return in order and the
-    // operands, which come from L2, then queue behind weights that come from HBM; so it is 0.
+    // 16-byte vector of fp32 weights) in DW_NIT rows, requested when the main loop ends.  (Requesting
+    // some ahead of the operands measured slower: loads return in order, and the operands, which
+    // come from L2, then queue behind weights that come from HBM.)
     constexpr int DW_G = BN / 4, DW_NIT = BM * DW_G / 256, DW_RSTEP = 256 / DW_G;
-    constexpr int DW_EARLY = (DW_NIT < PACK_DW_EARLY) ? DW_NIT : PACK_DW_EARLY;
     const int dw_lc = (threadIdx.x % DW_G) * 4, dw_lr0 = threadIdx.x / DW_G;
     const bool dw_full = vec_out && (col0 + dw_lc + 4 <= p.Q);
     const bool upd = IS_DW && (p.flags & F_UPDATE);
     const bool keep_g = !upd || (p.flags & F_KEEP_G);
     f32x4_t dw_w[IS_DW ? DW_NIT : 1];
-    if constexpr (IS_DW) {
-        if (upd && dw_full) {
-#pragma unroll
-            for (int n = 0; n < DW_EARLY; ++n) {
-                const int row = row0 + dw_lr0 + n * DW_RSTEP;
-                if (row < p.R) dw_w[n] = *reinterpret_cast<const f32x4_t*>(p.upd_w + (size_t)row * p.ldc + col0 + dw_lc);
-            }
-        }
-    }
     constexpr int LOADS = LoadsPerChunk<MODE, T, true, BM, BK>::value + LoadsPerChunk<MODE, T, false, BN, BK>::value;
-    constexpr bool ASM_WAITS = VEC && ((PACK_ASM_MODES >> MODE) & 1);
+    constexpr bool ASM_WAITS = VEC;
     if constexpr (LEAN) {
         // chunk it: wait for its operands, store them to the one LDS buffer (after everybody has
         // finished reading the previous chunk from it), request chunk it + 1 into the same
@@ -1011,7 +977,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
         constexpr int j = decltype(J)::value;
         if (it0 + j < nk) chunk(integral_constant<int, j % ST>{}, integral_constant<int, j & 1>{}, it0 + j);
     });
-    if constexpr (VEC && ((PACK_ASM_MODES >> MODE) & 1)) {
+    if constexpr (VEC) {
         // The last chunks prefetched beyond the reduction (reads of the zeros block).
         // Those loads are invisible to the compiler and still target the stage registers, which
         // it would otherwise reuse for the epilogue at once: drain them, with every stage
@@ -1045,11 +1011,11 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
     constexpr int HALVES = (LEAN && IS_DW) ? 2 : 1;
     static_assert((size_t)(BM / HALVES) * SLD * 4 <= LdsBytes<T, BM, BN, BK, LEAN, IS_DW>::value, "staging tile must fit");
     float(*stage)[SLD] = reinterpret_cast<float(*)[SLD]>(As_);
-    // the remaining weights of the tile: their round trip runs under the staging of the accumulators
+    // the weights of the tile: their round trip runs under the staging of the accumulators
     if constexpr (IS_DW) {
         if (upd && dw_full) {
 #pragma unroll
-            for (int n = DW_EARLY; n < DW_NIT; ++n) {
+            for (int n = 0; n < DW_NIT; ++n) {
                 const int row = row0 + dw_lr0 + n * DW_RSTEP;
                 if (row < p.R) dw_w[n] = *reinterpret_cast<const f32x4_t*>(p.upd_w + (size_t)row * p.ldc + col0 + dw_lc);
             }
@@ -2021,7 +1987,7 @@ hipError_t launch_sgd(float* master, const float* grad, void* shadow, long long 
 
 // ------------------------------------------------------------------------------------------------
 // The other optimisers of the paper's search space (Table 3), each member with its own kind,
-// hyper-parameters and state (the state is "stored with the model", Section 2.2):
+// hyper-parameters and state (Section 2.2 keeps the optimiser state with the model it belongs to):
 //   momentum  acc <- mu*acc + g;  W <- W - lr*acc
 //   adagrad   acc <- acc + g*g;   W <- W - lr*g/sqrt(acc)
 //   adam      m <- b1*m + (1-b1)*g;  v <- b2*v + (1-b2)*g*g;  W <- W - lr*(m*c1)/(sqrt(v*c2) + eps),

@@ -159,7 +159,14 @@ pack_status pack_halving_keep(const float* loss, int32_t n, int32_t keep, int32_
     if (n < 1 || keep < 0 || keep > n) return set_error(PACK_EINVAL, "need n >= 1 and keep in [0, n]");
     std::vector<int32_t> order((size_t)n);
     std::iota(order.begin(), order.end(), 0);
-    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return loss[a] < loss[b]; });
+    // A diverged configuration reports NaN (or +inf).  NaN compares false with everything, which is no
+    // ordering at all, so it is ranked explicitly: after every number, +inf included, ties by position.
+    auto before = [&](int32_t a, int32_t b) {
+        const bool na = std::isnan(loss[a]), nb = std::isnan(loss[b]);
+        if (na || nb) return !na && nb;
+        return loss[a] < loss[b];
+    };
+    std::stable_sort(order.begin(), order.end(), before);
     std::sort(order.begin(), order.begin() + keep);
     for (int i = 0; i < keep; ++i) idx_out[i] = order[(size_t)i];
     return PACK_OK;

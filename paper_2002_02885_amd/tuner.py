@@ -34,8 +34,9 @@ POLICIES = ("none", "knn", "random", "batchsize")
 
 def all_configurations():
     """The search space of the paper's evaluation (Table 3) as index tuples."""
-    return [(b, o, l, a) for b in range(len(BATCH_SIZES)) for o in range(len(OPTIMIZERS))
-            for l in range(len(LEARNING_RATES)) for a in range(len(ACTIVATIONS))]
+    import itertools
+    axes = (BATCH_SIZES, OPTIMIZERS, LEARNING_RATES, ACTIVATIONS)
+    return list(itertools.product(*(range(len(axis)) for axis in axes)))
 
 
 def mlp_family(hidden: Sequence[int], n_classes: int) -> Callable[[str], list]:
@@ -159,7 +160,7 @@ class Tuner:
                 self.log.append({"bracket": j, "rung": i, "configs": [t.cfg for t in trials], "groups": groups,
                                  "losses": losses, "r": r_i})
                 for t in trials:
-                    if t.loss < best_loss:
+                    if np.isfinite(t.loss) and t.loss < best_loss:    # a diverged run never becomes the winner
                         best, best_loss = t.cfg, t.loss
                 if i + 1 < len(rungs):
                     keep = binding.halving_keep(losses, max(n_i // eta, 1))

@@ -121,30 +121,58 @@ def measure(w: wl.PackWorkload, a: dict, ref: dict, what=("loss", "grads", "disp
     return out
 
 
-def gate(name: str, errs: dict, tol: float, sens: dict = None):
-    """Asserts every measured error is within `tol` (+ its allowance).  `sens` holds the oracle's
-    own sensitivity for the same items (how far its result moves when its inputs to a rounding
-    move by one part in 10^7, i.e. by fp32 accumulation noise): an item whose sensitivity
-    exceeds tol/4 is ill-conditioned, is listed in the returned report, and is gated at
-    tol + 4 * sensitivity instead of being passed or failed silently."""
-    worst, ill = {}, []
+# Which measured items may take the oracle-sensitivity allowance (see gate): single entries of a
+# tensor (infinity norms) and displacements accumulated over several steps.  A 2-norm taken at step 1
+# and every loss are robust against a flipped ReLU unit or a value on a rounding boundary, and get none.
+ALLOWANCE_KINDS_ALWAYS = ("grad_inf", "disp_inf")
+ALLOWANCE_KINDS_MULTI_STEP = ("disp_l2", "weights")
+MAX_ALLOWANCE_SHARE = 0.25     # of the eligible items of a comparison that may need the allowance
+
+
+def gate(name: str, errs: dict, tol: float, sens=None, steps: int = 1, max_share: float = MAX_ALLOWANCE_SHARE):
+    """Asserts every measured error is within `tol` (+ what fp32 storage of the master weights alone
+    contributes).  Items of the kinds listed above that exceed it are ill-conditioned candidates: a
+    ReLU unit within accumulation noise of zero, or a value within that noise of a bf16 rounding
+    boundary, takes the other branch on the device and moves single gradient entries by whole
+    summands, and over several steps the two trajectories drift apart.  For those, `sens` (a dict, or
+    a function returning one, evaluated only when needed) gives the oracle's own sensitivity: how far
+    ITS result moves under fp32-sized accumulation noise.  An item whose sensitivity exceeds tol/4 is
+    gated at tol + 4 x sensitivity and listed in the report; the share of eligible items that needed
+    this must stay below `max_share`.  Everything else fails outright.
+    Returns (worst error per kind among the items within tol, the items that took the allowance,
+    number of eligible items)."""
+    eligible = set(ALLOWANCE_KINDS_ALWAYS) | (set(ALLOWANCE_KINDS_MULTI_STEP) if steps > 1 else set())
+    worst, over = {}, []
     for key, (e, allow) in errs.items():
-        lim = tol + allow
-        s = sens.get(key, (0.0, 0.0))[0] if sens else 0.0
-        if s > tol / 4:
-            ill.append((key, float(s), float(e)))
-            lim += 4 * s
-        else:
+        if e <= tol + allow:
             worst[key[0]] = max(worst.get(key[0], 0.0), float(e))
-        assert e <= lim, f"{name}: {key}: error {e} > {lim} (oracle sensitivity {s})"
-    return worst, ill
+        else:
+            over.append((key, float(e), float(allow)))
+    n_eligible = sum(1 for key in errs if key[0] in eligible)
+    took = []
+    if over:
+        hard = [(k, e) for k, e, _ in over if k[0] not in eligible]
+        assert not hard, f"{name}: beyond {tol} with no allowance for this kind of item: {hard[:8]}"
+        assert sens is not None, f"{name}: beyond {tol} and no sensitivity given: {[(k, e) for k, e, _ in over[:8]]}"
+        sens = sens() if callable(sens) else sens
+        for key, e, allow in over:
+            s = sens.get(key, (0.0, 0.0))[0]
+            assert s > tol / 4, f"{name}: {key}: error {e} > {tol + allow} on a well-conditioned item (oracle sensitivity {s})"
+            assert e <= tol + allow + 4 * s, f"{name}: {key}: error {e} > {tol + allow + 4 * s} (oracle sensitivity {s})"
+            took.append((key, s, e))
+        share = len(took) / max(n_eligible, 1)
+        assert share <= max_share, (f"{name}: {len(took)} of {n_eligible} eligible items needed the ill-conditioning "
+                                    f"allowance (share {share:.2f} > {max_share}): {took[:8]}")
+    return worst, took, n_eligible
 
 
 def compare(w: wl.PackWorkload, gpu: dict, ref: dict, tol: float, what=("loss", "grads", "disp", "weights"),
-            label="", sens: dict = None):
-    worst, ill = gate(label + w.name, measure(w, gpu, ref, what), tol, sens)
-    if ill:
-        worst["ill_conditioned"] = ill
+            label="", sens=None, max_share: float = MAX_ALLOWANCE_SHARE):
+    steps = min(gpu["loss"].shape[0], ref["loss"].shape[0])
+    worst, took, n_eligible = gate(label + w.name, measure(w, gpu, ref, what), tol, sens, steps, max_share)
+    if took:
+        worst["took_allowance"] = f"{len(took)} of {n_eligible} eligible items"
+        worst["ill_conditioned"] = took
     return worst
 
 
@@ -157,12 +185,12 @@ def accumulation_noise(w: wl.PackWorkload) -> float:
 
 def oracle_sensitivity(w: wl.PackWorkload, steps, base: dict, mode="rounded", trials=2, eps=None):
     """Runs the oracle again with every matrix-product result perturbed by a relative `eps`
-    (default: four times the size of fp32 accumulation-order noise) through the oracle's
+    (default: the size of fp32 accumulation-order noise, see accumulation_noise) through the oracle's
     `acc_noise` probe, and measures how far the results move.  A ReLU unit whose pre-activation
     is that close to zero flips, and a value that close to a bf16 rounding boundary rounds the
     other way; both move single gradient entries by whole summands.  The perturbation is
     planted in the oracle, on the CPU."""
-    eps = 4.0 * accumulation_noise(w) if eps is None else eps
+    eps = accumulation_noise(w) if eps is None else eps
     out = {}
     for trial in range(trials):
         rng = np.random.default_rng(1000 + trial)
@@ -178,17 +206,28 @@ def oracle_sensitivity(w: wl.PackWorkload, steps, base: dict, mode="rounded", tr
     return out
 
 
-def compare_pred(w: wl.PackWorkload, gpu_pred, gpu_logits, ref_pred, tol: float):
-    """argmax must agree exactly on every row whose top-2 logit gap is resolvable at the
-    comparison tolerance; returns (rows compared, rows skipped as unresolvable)."""
+def compare_pred(w: wl.PackWorkload, gpu_pred, gpu_logits, ref_pred, ref_logits, max_skipped_share: float = 0.10):
+    """argmax must agree exactly on every row the comparison can resolve: a row whose two largest
+    oracle logits are closer than four times the largest difference between the device's and the
+    oracle's logits of that member (the measured error, not a tolerance) may legitimately order them
+    either way and is skipped.  Returns (rows compared, rows skipped, largest logit difference);
+    fails if more than `max_skipped_share` of the rows had to be skipped."""
     compared = skipped = 0
+    worst = 0.0
     for k in range(w.K):
-        lg = gpu_logits[k].astype(np.float64)
-        srt = np.sort(lg, axis=1)
-        gap = srt[:, -1] - srt[:, -2] if lg.shape[1] > 1 else np.full(lg.shape[0], np.inf)
-        ok = gap > 4 * tol * np.max(np.abs(lg))
+        lg = np.asarray(gpu_logits[k], dtype=np.float64)
+        rl = np.asarray(ref_logits[k], dtype=np.float64)
+        assert lg.shape == rl.shape
+        err = float(np.max(np.abs(lg - rl)))
+        worst = max(worst, err)
+        srt = np.sort(rl, axis=1)
+        gap = srt[:, -1] - srt[:, -2] if rl.shape[1] > 1 else np.full(rl.shape[0], np.inf)
+        ok = gap > 4 * err
         assert gpu_pred[k].dtype == np.int32
         assert np.array_equal(gpu_pred[k][ok], ref_pred[k][ok]), f"{w.name} member {k}: argmax differs"
+        # the device's own argmax is that of its own logits, lowest index on ties, on every row
+        assert np.array_equal(gpu_pred[k], np.argmax(lg, axis=1).astype(np.int32)), f"{w.name} member {k}: argmax of own logits"
         compared += int(ok.sum())
         skipped += int((~ok).sum())
-    return compared, skipped
+    assert skipped <= max_skipped_share * (compared + skipped), f"{w.name}: {skipped} of {compared + skipped} rows unresolvable"
+    return compared, skipped, worst

@@ -598,3 +598,99 @@ def test_weight_rounding_mode_equals_exact_while_weights_are_representable_then_
     assert ex["loss"][0, 0] == wt["loss"][0, 0] and np.array_equal(ex["grads"][0][0], wt["grads"][0][0])
     assert ex["loss"][1, 0] != wt["loss"][1, 0]
     assert abs(ex["loss"][2, 0] - wt["loss"][2, 0]) < 0.05 * ex["loss"][2, 0]
+
+
+def _bf16_by_hand(v):
+    """Round one Python float to bfloat16 (8 significant bits, halves to even) with integer rounding of
+    the scaled significand; written here so that the pin below does not lean on the oracle's q_bf16."""
+    if v == 0.0:
+        return 0.0
+    m, e = math.frexp(v)                 # v = m * 2**e, 0.5 <= |m| < 1
+    return math.ldexp(round(m * 256.0), e - 8)   # round() rounds halves to even; m * 256 is exact
+
+
+def _residual_fork_by_hand(drop=()):
+    """One training example through   conv - relu - [ conv - relu - conv ] + shortcut - relu - gap - linear(2)
+    on a 1 x 2 image with one channel, every convolution with only its centre tap non-zero, so that each
+    pixel is a chain of scalar operations that can be followed by hand.  `r(i, v)` is rounding point
+    number i of the bf16 configuration: the per-step operand copy of each weight (1-4), every stored
+    activation (5-8: first relu, inner relu, block output, pooled value) and every stored gradient
+    (9: dlogits, 10: gradient wrt the pooled value, 11: after the inner relu's mask, 12: THE FORK, the
+    sum of the branch's and the shortcut's gradient, 13: after the first relu's mask, which for a
+    0 / 1 mask is the same store as 12).  Points in `drop`
+    are skipped, which is how the test shows that each of them is pinned."""
+    def r(i, v):
+        return v if i in drop else _bf16_by_hand(v)
+
+    xa, xb = 0.8125, 1.40625                                  # bf16-representable data
+    w1, b1, w2, b2, w3, b3 = 0.7431, 0.10001, 0.611, 0.3, 0.9017, -0.05
+    W4, b4, label = (0.37, -0.83), (0.01, -0.02), 1
+    q1, q2, q3 = r(1, w1), r(2, w2), r(3, w3)
+    q4 = (r(4, W4[0]), r(4, W4[1]))
+    # forward, pixel by pixel
+    h1 = [r(5, max(x * q1 + b1, 0.0)) for x in (xa, xb)]
+    h2 = [r(6, max(h * q2 + b2, 0.0)) for h in h1]
+    h3 = [r(7, max(h2[j] * q3 + b3 + h1[j], 0.0)) for j in range(2)]
+    pooled = r(8, (h3[0] + h3[1]) / 2.0)
+    logits = [pooled * q4[c] + b4[c] for c in range(2)]
+    mx = max(logits)
+    ex = [math.exp(z - mx) for z in logits]
+    loss = mx + math.log(ex[0] + ex[1]) - logits[label]
+    # backward
+    dz = [r(9, ex[c] / (ex[0] + ex[1]) - (1.0 if c == label else 0.0)) for c in range(2)]
+    dW4 = [dz[c] * pooled for c in range(2)]
+    g_pool = r(10, dz[0] * q4[0] + dz[1] * q4[1])
+    g3 = [g_pool / 2.0 * (1.0 if h3[j] > 0 else 0.0) for j in range(2)]          # exact in bf16: halving
+    g2 = [r(11, g3[j] * q3 * (1.0 if h2[j] > 0 else 0.0)) for j in range(2)]
+    fork = [r(12, g2[j] * q2 + g3[j]) for j in range(2)]
+    g1 = [r(13, fork[j] * (1.0 if h1[j] > 0 else 0.0)) for j in range(2)]
+
+    def conv_dw(d, inp):
+        # [3][3] taps of a one-row image: row u = 1 only; tap v reads pixel j + v - 1
+        return {"centre": d[0] * inp[0] + d[1] * inp[1], "left": d[1] * inp[0], "right": d[0] * inp[1], "bias": d[0] + d[1]}
+
+    return {"loss": loss, "dW1": conv_dw(g1, (xa, xb)), "dW2": conv_dw(g2, h1), "dW3": conv_dw(g3, h2),
+            "dW4": dW4, "db4": dz}
+
+
+def test_rounded_mode_rounds_exactly_where_the_configuration_says_hand_worked_residual_fork():
+    """The oracle's mode "rounded" against a residual block worked by hand (the scalar chain above, with
+    its own bf16 rounding): every gradient must agree to float64 rounding.  Leaving out any single
+    rounding point in the hand computation (the fork included) moves at least one gradient far beyond
+    that, so a q() dropped from, or added to, the oracle at any of those places fails this test."""
+    for src, want in _golden_pairs("bf16_rne.txt"):          # the hand rounding itself, on the listed bit patterns
+        f = float(np.array([int(src, 16)], dtype=np.uint32).view(np.float32)[0])
+        if math.isfinite(f) and 1e-30 < abs(f) < 1e38:
+            got = np.array([_bf16_by_hand(f)], dtype=np.float32).view(np.uint32)[0]
+            assert got & 0xFFFF == 0 and (got >> 16) == int(want, 16), src
+    layers = [("conv3x3", 1, 1), ("relu",), ("res_begin",), ("conv3x3", 1, 1), ("relu",), ("conv3x3", 1, 1), ("res_end",),
+              ("gap",), ("linear", 2)]
+    centre = lambda w: [0, 0, 0, 0, w, 0, 0, 0, 0]
+    blob = np.array(centre(0.7431) + [0.10001] + centre(0.611) + [0.3] + centre(0.9017) + [-0.05]
+                    + [0.37, -0.83] + [0.01, -0.02])
+    x = np.array([0.8125, 1.40625]).reshape(1, 1, 2, 1)
+    net = po.Model(layers, (1, 2, 1), blob, "rounded")
+    loss, pred, grads = net.loss_and_grads(x, np.array([1]))
+
+    def flat(h):
+        out = []
+        for name in ("dW1", "dW2", "dW3"):
+            d = h[name]
+            out += [0, 0, 0, d["left"], d["centre"], d["right"], 0, 0, 0, d["bias"]]
+        return np.array(out + h["dW4"] + h["db4"])
+
+    got = po.Model.flatten_grads(grads)
+    want = _residual_fork_by_hand()
+    assert abs(loss - want["loss"]) <= 1e-14 * abs(want["loss"])
+    assert np.allclose(got, flat(want), rtol=1e-13, atol=0)
+    assert np.all(flat(want)[[3, 4, 5, 9, 13, 14, 15, 19, 23, 24, 25, 29, 30, 31, 32, 33]] != 0)   # every checked entry is live
+    # 12 and 13 are one store when the mask between them is 0 / 1 (rounding twice changes nothing), so
+    # they are dropped together; alone, either must leave the result as it is
+    for alone in (12, 13):
+        assert np.array_equal(flat(_residual_fork_by_hand(drop=(alone,))), flat(want))
+    for point in [(i,) for i in range(1, 12)] + [(12, 13)]:
+        other = _residual_fork_by_hand(drop=point)
+        moved = max(np.max(np.abs(flat(other) - flat(want)) / np.maximum(np.abs(flat(want)), 1e-300)),
+                    abs(other["loss"] - want["loss"]) / abs(want["loss"]))
+        assert moved > 1e-6, f"rounding point {point} is not pinned by this example (moves the result by {moved})"
+        assert not np.allclose(got, flat(other), rtol=1e-9, atol=0) or abs(loss - other["loss"]) > 1e-9 * abs(loss), point

@@ -149,6 +149,16 @@ def test_keep_best_breaks_ties_by_position():
     assert so.keep_best([3.0, 2.0, 1.0], 1) == [2]
 
 
+def test_keep_best_ranks_diverged_runs_last():
+    nan, inf = float("nan"), float("inf")
+    # a finite loss always survives ahead of inf, and inf ahead of NaN, wherever they sit
+    assert so.keep_best([nan, 5.0, inf, 1.0], 2) == [1, 3]
+    assert so.keep_best([nan, 5.0, inf, 1.0], 3) == [1, 2, 3]
+    assert so.keep_best([nan, nan, 2.0], 1) == [2]
+    assert so.keep_best([nan, nan, 2.0], 2) == [0, 2]
+    assert so.keep_best([inf, nan, inf], 2) == [0, 2]
+
+
 def test_hyperband_returns_the_best_sampled_configuration_and_grouping_does_not_change_it():
     confs = so.all_configurations()
     rng = np.random.default_rng(4)

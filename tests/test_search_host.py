@@ -63,6 +63,18 @@ def test_hyperband_plan_and_halving_agree_with_the_oracle():
         loss = np.round(rng.random(n), 1).astype(np.float32)          # many ties
         keep = int(rng.integers(0, n + 1))
         assert binding.halving_keep(loss, keep) == so.keep_best([float(v) for v in loss], keep)
+    # diverged configurations (NaN, inf) never displace a finite loss: same rule on both sides
+    for _ in range(200):
+        n = int(rng.integers(1, 30))
+        loss = np.round(rng.random(n), 1).astype(np.float32)
+        loss[rng.random(n) < 0.3] = np.nan
+        loss[rng.random(n) < 0.2] = np.inf
+        keep = int(rng.integers(0, n + 1))
+        got = binding.halving_keep(loss, keep)
+        assert got == so.keep_best([float(v) for v in loss], keep)
+        n_finite = int(np.isfinite(loss).sum())
+        assert sum(bool(np.isfinite(loss[i])) for i in got) == min(keep, n_finite)
+    assert binding.halving_keep(np.array([np.nan, 5.0, np.inf, 1.0], dtype=np.float32), 2) == [1, 3]
 
 
 def test_argument_errors():
