@@ -132,6 +132,19 @@ typedef struct {
 pack_status pack_create(const pack_input_spec* input, const pack_model_spec* models, int32_t K,
                         uint64_t seed, void* hip_stream, pack_t** out);
 
+/* Plan verification on the host; no GPU is involved and none is needed.  Plans the pack exactly as
+ * pack_create would (same planner, made-up device addresses) and replays, for every launch whose kernel
+ * has a host-side model of its address rules, what every thread would load, store to LDS and read back as
+ * matrix-instruction operands, against the definition of the product the launch computes (for the
+ * convolution weight gradient: the backward pass of the members' 3x3 convolutions, Section 2.2's
+ * "back-propagation ... as if trained alone").  A load that the hardware's range check would let through
+ * outside its tensor, an operand slot holding the wrong element, a tile dealt twice or not at all is an
+ * error.  input_mode: pack_input_mode.  Outputs (host, may be null): launches walked, matrix-product
+ * launches without a host model (skipped), loads and operand reads checked.
+ * Errors: PACK_EINVAL (bad arguments, or a violation: pack_last_error names launch and tile), PACK_ESHAPE, PACK_ENOMEM. */
+pack_status pack_plan_check(const pack_input_spec* input, const pack_model_spec* models, int32_t K, int32_t input_mode,
+                            int64_t* launches_walked, int64_t* launches_skipped, int64_t* loads_checked);
+
 /* free of ONE member of a live pack (Section 2.2 `free`; Section 3.3, Figure 3: the member that has
  * taken all its steps is freed while the others keep training).  The caller retrieves the
  * checkpoint first (pack_read_weights, pack_read_opt_state).  Slot k becomes vacant and the member's

@@ -27,7 +27,7 @@ EXPORTS = ["pack_create", "pack_write_weights", "pack_step", "pack_read_loss", "
            "pack_schedule_create", "pack_schedule_next", "pack_schedule_used", "pack_schedule_destroy",
            "pack_gather_batch", "pack_set_input_mode", "pack_config_distance", "pack_opt_knn", "pack_opt_random",
            "pack_opt_batchsize", "pack_hyperband_plan", "pack_halving_keep", "pack_estimate_bytes",
-           "pack_keep_grads", "pack_launch_bytes", "pack_measure_ceiling", "pack_launch_tile"]
+           "pack_keep_grads", "pack_launch_bytes", "pack_measure_ceiling", "pack_launch_tile", "pack_plan_check"]
 
 
 class pack_opt_spec(C.Structure):
@@ -128,6 +128,9 @@ def lib() -> C.CDLL:
         l.pack_launch_bytes.argtypes = [vp, i32, C.POINTER(C.c_double)]
         l.pack_launch_bytes.restype = C.c_int
         l.pack_launch_tile.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
+        i64p = C.POINTER(C.c_int64)
+        l.pack_plan_check.argtypes = [C.POINTER(pack_input_spec), C.POINTER(pack_model_spec), i32, i32, i64p, i64p, i64p]
+        l.pack_plan_check.restype = C.c_int
         for name in ("pack_free", "pack_load", "pack_set_batch", "pack_schedule_create", "pack_schedule_next",
                      "pack_schedule_used", "pack_gather_batch"):
             getattr(l, name).restype = C.c_int
@@ -157,6 +160,34 @@ def _layer_array(layers):
         arr[i].out = int(op[1]) if len(op) > 1 else 0
         arr[i].stride = int(op[2]) if len(op) > 2 else 1
     return arr
+
+
+def _model_specs(B: int, in_shape, dtype: str, models, batch):
+    """(input spec, array of member specs, objects to keep alive) for the entry points that take layer lists."""
+    K = len(models)
+    batch = list(batch) if batch is not None else [B] * K
+    keep = []
+    specs = (pack_model_spec * max(K, 1))()
+    for k, layers in enumerate(models):
+        arr = _layer_array(layers)
+        keep.append(arr)
+        specs[k].layers = arr
+        specs[k].n_layers = len(layers)
+        specs[k].batch = int(batch[k])
+    inp = pack_input_spec(B, in_shape[0], in_shape[1], in_shape[2], PACK_BF16 if dtype == "bf16" else PACK_F32)
+    return inp, specs, keep
+
+
+def plan_check(B: int, in_shape, dtype: str, models, batch=None, per_member_input: bool = False):
+    """pack_plan_check: plans the pack without a GPU and walks the kernels' address rules on the host.
+    Returns (launches walked, matrix-product launches without a host model, loads and operand reads checked);
+    raises PackError on a violation."""
+    inp, specs, keep = _model_specs(B, in_shape, dtype, models, batch)
+    walked, skipped, loads = C.c_int64(0), C.c_int64(0), C.c_int64(0)
+    _check(lib().pack_plan_check(C.byref(inp), specs, len(models), 1 if per_member_input else 0,
+                                 C.byref(walked), C.byref(skipped), C.byref(loads)))
+    del keep
+    return int(walked.value), int(skipped.value), int(loads.value)
 
 
 class Pack:

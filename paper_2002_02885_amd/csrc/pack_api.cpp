@@ -15,6 +15,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <string>
 #include <system_error>
 #include <thread>
@@ -107,6 +108,8 @@ struct Launch {
 }  // namespace
 
 namespace packk {
+std::string conv_dw_halo_walk(bool bf16, bool wide, const GemmProb& p, const TileRef& tr, long long a_bytes, long long b_bytes,
+                              bool every_chunk, long long* loads, long long* frag_reads);
 // for the library's other source files: records the text pack_last_error returns
 pack_status set_error(pack_status s, const std::string& msg) { return fail(s, msg); }
 }  // namespace packk
@@ -156,6 +159,12 @@ struct pack_ctx {
     long long profile_step = 0;  // steps since pack_profile_start
     struct Stamp { int launch; hipEvent_t t0, t1; };
     std::vector<Stamp> stamps;
+    // planning without a device (pack_plan_check): allocations hand out made-up addresses, nothing is
+    // uploaded, and the problem tables stay on the host
+    bool dry = false;
+    uintptr_t dry_next = (uintptr_t)1 << 44;
+    std::vector<std::pair<uintptr_t, size_t>> dry_regions;
+    std::vector<char> desc_host;
 };
 
 namespace {
@@ -581,6 +590,20 @@ void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<G
         }
     }
     if (!scalar.empty()) emit_gemm_launch(p, db, mode, GEMM_CFG_SCALAR, scalar);
+    if (mode == CONV_DW && !std::getenv("PACK_NO_HALO_DW")) {
+        // convolution weight gradients whose shape allows it take the halo form (all nine taps of a block of
+        // channel pairs in one workgroup; the input staged once per chunk of pixels): one launch per stride.
+        // PACK_NO_HALO_DW keeps them on the staged-tile form, for the test that compares the two bit for bit.
+        std::vector<GemmProb> halo[3], rest;
+        for (const GemmProb& g : probs) {
+            const int cfg = conv_dw_halo_cfg(p->bf16, g);
+            if (cfg >= 0) halo[cfg - GEMM_CFG_HALO_S1].push_back(g);
+            else rest.push_back(g);
+        }
+        for (int c = 0; c < 3; ++c)
+            if (!halo[c].empty()) emit_gemm_launch(p, db, mode, GEMM_CFG_HALO_S1 + c, halo[c]);
+        probs.swap(rest);
+    }
     if (probs.empty()) return;
     // The tile shape only partitions the output; the summation order of an element does not
     // depend on it, so a member's bits do not depend on who else is in the launch.  Each problem
@@ -667,7 +690,6 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
     size_t max_nodes = 0;
     for (const ModelInfo& m : p->models) max_nodes = std::max(max_nodes, m.nodes.size());
     ws_need = 0;
-    char* const ws = p->workspace;   // null during the sizing pass; offsets are added to it later
 
     const long long block_bytes = (long long)p->in.B * p->in.in_h * p->in.in_w * p->in.in_c * (long long)esz;
     auto x_off = [&](const ModelInfo& m) -> long long {
@@ -887,25 +909,40 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
                 }
                 // long reductions (many pixels) are split over workgroups; the split length
                 // depends on the layer shape only, partial results are summed in split order
-                const int out_tiles = ((nd.out + 127) / 128) * ((q_dim + 127) / 128);
-                const int chunk = (out_tiles == 1) ? 1024 : 8192;   // a one-tile output gets its parallelism from splits
-                int S = std::min(128, std::max(1, (rows + chunk - 1) / chunk));
+                int S;
+                if (dense) {
+                    const int out_tiles = ((nd.out + 127) / 128) * ((q_dim + 127) / 128);
+                    const int chunk = (out_tiles == 1) ? 1024 : 8192;   // a one-tile output gets its parallelism from splits
+                    S = std::min(128, std::max(1, (rows + chunk - 1) / chunk));
+                } else {
+                    // Convolutions: a split is sized for some tens of microseconds of matrix work per
+                    // workgroup (the float matrix rate is a sixteenth of the bfloat16 one), and a layer
+                    // with few channel blocks is split further until it offers at least 32 workgroups.
+                    // Only the layer's own shape enters, so a member's split does not depend on its pack.
+                    const int target = bf ? 8192 : 1024;
+                    S = std::min(128, std::max(1, (rows + target - 1) / target));
+                    const int blocks = ((nd.out + 63) / 64) * ((ti.c + 63) / 64);
+                    while (S < 128 && S * blocks < 32 && rows / (2 * S) >= 8 * BKc) S *= 2;
+                }
                 g.ksplit = (int)align_up((size_t)(rows + S - 1) / S, 64);
                 S = (rows + g.ksplit - 1) / g.ksplit;
                 const int member = (int)(&m - p->models.data());
                 void* const shadow_w = bf ? (void*)((char*)p->shadow + nd.w_off * 2) : nullptr;
                 if (S > 1) {
-                    g.C = ws + ws_off;
+                    // partial sums live in the step's workspace, addressed by offset: the kernels receive the
+                    // workspace as an argument (the pack's own, or the library's static scratch array)
+                    g.flags |= F_WS;
+                    g.C = (void*)(uintptr_t)ws_off;
                     g.split_stride = (long long)nd.w_arena;
                     ReduceProb r{};
-                    r.in = (const float*)g.C; r.out = dst; r.stride = (long long)nd.w_arena; r.n = (int)nd.w_arena; r.S = S;
+                    r.in = (const float*)(uintptr_t)ws_off; r.out = dst; r.stride = (long long)nd.w_arena; r.n = (int)nd.w_arena; r.S = S;
                     if (p->fused) { r.upd_w = p->master + nd.w_off; r.upd_shadow = shadow_w; r.member = member; r.keep_g = p->keep_grads; }
                     dw_red.push_back(r);
                     dw_red_blocks.push_back((int)((nd.w_arena + 1023) / 1024));
                     ws_off += align_up((size_t)S * nd.w_arena * 4, 256);
-                    g.dbias = (float*)(ws + ws_off);
+                    g.dbias = (float*)(uintptr_t)ws_off;
                     ReduceProb rb{};
-                    rb.in = g.dbias; rb.out = p->grad + nd.b_off; rb.stride = nd.out; rb.n = nd.out; rb.S = S;
+                    rb.in = (const float*)(uintptr_t)ws_off; rb.out = p->grad + nd.b_off; rb.stride = nd.out; rb.n = nd.out; rb.S = S;
                     if (p->fused) { rb.upd_w = p->master + nd.b_off; rb.member = member; rb.keep_g = p->keep_grads; }
                     dw_red.push_back(rb);
                     dw_red_blocks.push_back((nd.out + 1023) / 1024);
@@ -1037,6 +1074,13 @@ void build_plan(pack_ctx* p, DescBuilder& db, size_t& ws_need) {
 
 // frees every device buffer and event the pack holds; the host-side description stays
 void free_device(pack_ctx* p) {
+    if (p->dry) {
+        p->master = p->grad = nullptr; p->shadow = p->wt = nullptr; p->opt_m = p->opt_v = nullptr; p->opt_params = nullptr;
+        p->seg_end = nullptr; p->slab = p->workspace = p->desc = nullptr;
+        p->dry_regions.clear();
+        p->device_bytes = 0;
+        return;
+    }
     void** bufs[] = {(void**)&p->master, (void**)&p->grad, &p->shadow, &p->wt, (void**)&p->opt_m, (void**)&p->opt_v,
                      (void**)&p->opt_params, (void**)&p->seg_end, (void**)&p->slab, (void**)&p->workspace, (void**)&p->desc};
     for (void** b : bufs) {
@@ -1057,6 +1101,13 @@ void release(pack_ctx* p) {
 
 pack_status dev_alloc(void** ptr, size_t bytes, pack_ctx* p) {
     bytes = align_up(std::max<size_t>(bytes, 256), 256);
+    if (p->dry) {
+        *ptr = (void*)p->dry_next;
+        p->dry_regions.push_back({p->dry_next, bytes});
+        p->dry_next += align_up(bytes, (size_t)1 << 21) + ((size_t)1 << 21);   // a gap after every allocation
+        p->device_bytes += bytes;
+        return PACK_OK;
+    }
     hipError_t e = hipMalloc(ptr, bytes);
     if (e != hipSuccess) {
         (void)hipGetLastError();
@@ -1213,21 +1264,18 @@ pack_status build_device(pack_ctx* p) {
     p->zeros = p->slab + zeros_off;
     for (int k = 0; k < K; ++k) p->models[k].loss = p->loss_all + k;
 
-    // size the workspace with a dry run of the planner, then build the real plan
-    {
-        DescBuilder dry;
-        size_t need = 0;
-        build_plan(p, dry, need);
-        p->plan.clear();
-        p->workspace_bytes = need;
-        if (need) TRY_ALLOC(p->workspace, need);
-    }
     DescBuilder db;
     size_t need = 0;
     build_plan(p, db, need);
+    p->workspace_bytes = need;
+    if (need) TRY_ALLOC(p->workspace, need);
     TRY_ALLOC(p->desc, db.bytes.size());
     p->desc_bytes = db.bytes.size();
 #undef TRY_ALLOC
+    if (p->dry) {
+        p->desc_host.swap(db.bytes);
+        return PACK_OK;
+    }
 
     hipError_t e = hipMemcpy(p->desc, db.bytes.data(), db.bytes.size(), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(p->slab, 0, p->slab_bytes);
@@ -1427,6 +1475,88 @@ pack_status pack_create(const pack_input_spec* input, const pack_model_spec* mod
     return PACK_OK;
 }
 
+pack_status pack_plan_check(const pack_input_spec* input, const pack_model_spec* models, int32_t K, int32_t input_mode,
+                            int64_t* launches_walked, int64_t* launches_skipped, int64_t* loads_checked) {
+    if (!input || !models) return fail(PACK_EINVAL, "null argument");
+    if (K < 1 || K > PACK_MAX_MODELS) return fail(PACK_EINVAL, "K must be in [1, PACK_MAX_MODELS]");
+    if (input->B < 1 || input->in_h < 1 || input->in_w < 1 || input->in_c < 1) return fail(PACK_EINVAL, "bad input shape");
+    if (input->dtype != PACK_F32 && input->dtype != PACK_BF16) return fail(PACK_EINVAL, "unknown dtype");
+    if (input_mode != PACK_INPUT_SHARED && input_mode != PACK_INPUT_PER_MEMBER) return fail(PACK_EINVAL, "unknown input mode");
+    pack_ctx* p = new (std::nothrow) pack_ctx();
+    if (!p) return fail(PACK_ENOMEM, "host allocation failed");
+    p->dry = true;
+    p->bf16 = (input->dtype == PACK_BF16);
+    p->K = K;
+    p->in = *input;
+    p->own_input = input_mode == PACK_INPUT_PER_MEMBER;
+    p->models.resize(K);
+    p->opt.assign(K, pack_opt_spec{PACK_OPT_SGD, 0.f, 0.f, 0.f, 0.f, 0.f});
+    p->opt_t.assign(K, 0);
+    for (int k = 0; k < K; ++k) {
+        pack_status s = parse_model(*input, models[k], k, p->models[k]);
+        if (s != PACK_OK) { release(p); return s; }
+    }
+    pack_status s = build_device(p);
+    if (s != PACK_OK) { release(p); return s; }
+    // the step's input: one more made-up allocation
+    const size_t esz = p->bf16 ? 2 : 4;
+    const size_t x_bytes = (size_t)input->B * input->in_h * input->in_w * input->in_c * esz * (p->own_input ? (size_t)K : 1);
+    void* x_fake = nullptr;
+    (void)dev_alloc(&x_fake, x_bytes, p);
+    auto region_holds = [&](const void* ptr, long long bytes) {
+        const uintptr_t a = (uintptr_t)ptr;
+        for (const auto& r : p->dry_regions)
+            if (a >= r.first && a + (uintptr_t)bytes <= r.first + r.second) return true;
+        return false;
+    };
+    long long walked = 0, skipped = 0, loads = 0, frags = 0;
+    std::string err;
+    for (size_t li = 0; li < p->plan.size() && err.empty(); ++li) {
+        const Launch& L = p->plan[li];
+        if (L.kind != L_GEMM) continue;
+        const bool halo = L.mode == CONV_DW && is_halo_cfg(L.tile_cfg);
+        const int ci_t = halo ? GEMM_TILE_N[L.tile_cfg] / 9 : 0;      // input channels per tile
+        if (!halo) { ++skipped; continue; }
+        ++walked;
+        const GemmProb* probs = (const GemmProb*)(p->desc_host.data() + L.desc_off);
+        const TileRef* tiles = (const TileRef*)(p->desc_host.data() + L.map_off);
+        std::map<std::vector<int>, int> seen;          // (problem, tm, tn, ks) -> times dealt
+        int n_probs = 0;
+        for (int t = 0; t < L.n && err.empty(); ++t) {
+            const TileRef& tr = tiles[t];
+            if (tr.prob < 0) continue;
+            n_probs = std::max(n_probs, tr.prob + 1);
+            GemmProb g = probs[tr.prob];
+            if (g.flags & F_B_INPUT) g.B = (const char*)x_fake + g.x_off;
+            const long long a_bytes = (long long)g.Kd * g.Cout * (long long)esz;
+            const long long b_bytes = (long long)(g.Kd / (g.Ho * g.Wo)) * g.H * g.W * g.Cin * (long long)esz;
+            if (!region_holds(g.A, a_bytes) || !region_holds(g.B, b_bytes)) err = "an operand of a weight-gradient problem is not inside one allocation";
+            const long long out_bytes = (long long)g.Cout * g.ldc * 4;
+            const char* out_base = (g.flags & F_WS) ? p->workspace + (size_t)(uintptr_t)g.C : (const char*)g.C;
+            if (err.empty() && !region_holds(out_base + (long long)tr.ks * g.split_stride * 4, out_bytes)) err = "a weight-gradient output is not inside one allocation";
+            if (err.empty()) err = conv_dw_halo_walk(p->bf16, ci_t == 64, g, tr, a_bytes, b_bytes, false, &loads, &frags);
+            if (++seen[{tr.prob, tr.tm, tr.tn, tr.ks}] > 1 && err.empty()) err = "a tile is dealt twice";
+            if (!err.empty()) err = "launch " + std::to_string(li) + ", tile " + std::to_string(t) + " (problem " + std::to_string(tr.prob) + ", tm " +
+                                    std::to_string(tr.tm) + ", tn " + std::to_string(tr.tn) + ", split " + std::to_string(tr.ks) + "): " + err;
+        }
+        for (int i = 0; i < n_probs && err.empty(); ++i) {
+            const GemmProb& g = probs[i];
+            const int S = (g.Kd + g.ksplit - 1) / g.ksplit;
+            for (int ks = 0; ks < S; ++ks)
+                for (int tm = 0; tm < g.Cout / 64; ++tm)
+                    for (int tn = 0; tn < g.Cin / ci_t; ++tn)
+                        if (seen.find({i, tm, tn, ks}) == seen.end() && err.empty())
+                            err = "launch " + std::to_string(li) + ": problem " + std::to_string(i) + " lacks a tile";
+        }
+    }
+    release(p);
+    if (launches_walked) *launches_walked = walked;
+    if (launches_skipped) *launches_skipped = skipped;
+    if (loads_checked) *loads_checked = loads + frags;
+    if (!err.empty()) return fail(PACK_EINVAL, "plan check: " + err);
+    return PACK_OK;
+}
+
 pack_status pack_free(pack_t* p, int32_t k) {
     pack_status s = live_member(p, k);
     if (s != PACK_OK) return s;
@@ -1516,8 +1646,8 @@ pack_status pack_write_weights(pack_t* p, int32_t k, const float* host_src, size
     return upload_weights(p, k, host_src);
 }
 
-pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, const float* lr_host) {
-    if (!p || !x_dev || !labels_dev || !lr_host) return fail(PACK_EINVAL, "null argument");
+// one training step with the partial sums of split weight gradients in `ws`
+static pack_status step_with_workspace(pack_t* p, const void* x_dev, const int32_t* labels_dev, const float* lr_host, char* ws) {
     if (((uintptr_t)x_dev & 15) || ((uintptr_t)labels_dev & 3)) return fail(PACK_EINVAL, "x_dev must be 16-byte aligned");
     LrTable lr;
     for (int k = 0; k < PACK_LR_N; ++k) lr.lr[k] = (k < p->K) ? lr_host[k] : 0.f;
@@ -1537,9 +1667,9 @@ pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, c
         const char* mp = p->desc + L.map_off;
         switch (L.kind) {
             case L_GEMM:
-                e = launch_gemm(L.mode, bf, L.tile_cfg, (const GemmProb*)d, (const TileRef*)mp, L.n, x_dev, lr, p->stream);
+                e = launch_gemm(L.mode, bf, L.tile_cfg, (const GemmProb*)d, (const TileRef*)mp, L.n, x_dev, ws, lr, p->stream);
                 break;
-            case L_REDUCE: e = launch_reduce((const ReduceProb*)d, (const int2*)mp, L.n, lr, p->stream); break;
+            case L_REDUCE: e = launch_reduce((const ReduceProb*)d, (const int2*)mp, L.n, ws, lr, p->stream); break;
             case L_CE: e = launch_ce(bf, (const CeProb*)d, L.n, labels_dev, p->err_flag, p->stream); break;
             case L_HEAD: e = launch_head(bf, L.mode, (const HeadProb*)d, (const int2*)mp, L.n, labels_dev, p->err_flag, p->stream); break;
             case L_GAP_FWD: e = launch_gap(bf, false, (const GapProb*)d, (const int2*)mp, L.n, p->stream); break;
@@ -1575,6 +1705,11 @@ pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, c
         }
     }
     return PACK_OK;
+}
+
+pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, const float* lr_host) {
+    if (!p || !x_dev || !labels_dev || !lr_host) return fail(PACK_EINVAL, "null argument");
+    return step_with_workspace(p, x_dev, labels_dev, lr_host, p->workspace);
 }
 
 pack_status pack_profile_start(pack_t* p, int32_t which, int32_t every) {

@@ -43,7 +43,9 @@ enum GemmFlags : int {
     F_KEEP_G = 8192,   // with F_UPDATE: store the gradient as well
     F_SC_ID = 16384,   // dX of the first layer of a residual block: add the gradient that arrives through the
                        // identity shortcut, sc[row, col] (same shape as the output), before the mask
-    F_SC_DOWN = 32768  // likewise for the subsampling shortcut: pixel (2i, 2j) receives sc[b, i, j, col]
+    F_SC_DOWN = 32768, // likewise for the subsampling shortcut: pixel (2i, 2j) receives sc[b, i, j, col]
+    F_WS = 65536       // split weight gradient: C and dbias hold BYTE OFFSETS into the step's workspace (the
+                       // buffer of partial sums the launch receives as an argument), not addresses
 };
 
 // activation kinds (paper Table 3); the value is also what GemmProb::act / mask_act hold
@@ -85,7 +87,7 @@ struct TileRef {      // one workgroup's job; prob < 0 marks a filler slot
 };
 
 struct ReduceProb {   // out[e] = sum_{s < S} in[s * stride + e], fixed order
-    const float* in;
+    const float* in;      // a BYTE OFFSET into the step's workspace, not an address
     float* out;
     long long stride;
     int n, S;
@@ -154,9 +156,16 @@ struct TransposeProb {   // convolution weights [Cout][9][Cin] -> [Cin][9][Cout]
 // launch wrappers; all enqueue on `st` and return the launch status -----------------------------
 // tile_cfg indexes GEMM_TILE_M / GEMM_TILE_N
 // lr: the step's learning rates (used by weight-gradient launches whose problems carry F_UPDATE)
+// ws: the step's workspace (partial sums of split weight gradients; problems with F_WS address it by offset)
 hipError_t launch_gemm(int mode, bool bf16, int tile_cfg, const GemmProb* probs_dev, const TileRef* tiles_dev,
-                       int n_tiles, const void* x_dev, const LrTable& lr, hipStream_t st);
-hipError_t launch_reduce(const ReduceProb* probs_dev, const int2* map_dev, int n_blocks, const LrTable& lr, hipStream_t st);
+                       int n_tiles, const void* x_dev, char* ws, const LrTable& lr, hipStream_t st);
+// halo form of the convolution weight gradient (pack_conv_dw.hip): every problem of the launch has the
+// given stride and passes conv_dw_halo_ok
+hipError_t launch_conv_dw_halo(bool bf16, int tile_cfg, const GemmProb* probs_dev, const TileRef* tiles_dev, int n_tiles,
+                               const void* x_dev, char* ws, const LrTable& lr, hipStream_t st);
+// the halo configuration (GEMM_CFG_HALO*) problem p can take, or -1
+int conv_dw_halo_cfg(bool bf16, const GemmProb& p);
+hipError_t launch_reduce(const ReduceProb* probs_dev, const int2* map_dev, int n_blocks, const char* ws, const LrTable& lr, hipStream_t st);
 hipError_t launch_ce(bool bf16, const CeProb* probs_dev, int K, const int32_t* labels, int* err_flag, hipStream_t st);
 // max_c: the largest class count among the launch's members (<= HEAD_MAX_C)
 hipError_t launch_head(bool bf16, int max_c, const HeadProb* probs_dev, const int2* map_dev, int n_blocks, const int32_t* labels,
@@ -184,11 +193,18 @@ hipError_t launch_gather_rows(const void* data, const int32_t* labels_all, const
 // tile geometry the planner needs
 // configurations 0..2: aligned problems (16-byte operand loads); 3: the scalar gather for any shape
 // 4: the lean 128 x 128 form of the weight-gradient kernels (short reductions)
-constexpr int GEMM_TILE_M[6] = {128, 128, 64, 64, 128, 128};
-constexpr int GEMM_TILE_N[6] = {128, 64, 64, 64, 128, 64};
+// 6, 7: the halo form of the convolution weight gradient (stride 1, stride 2): a tile is 64 output channels
+// x 64 input channels x all nine taps, i.e. 64 x 576 of the [Cout][9 * Cin] gradient
+// 8: the same with 32 input channels per tile (layers whose input channels are a multiple of 32 only; stride 1)
+constexpr int GEMM_TILE_M[9] = {128, 128, 64, 64, 128, 128, 64, 64, 64};
+constexpr int GEMM_TILE_N[9] = {128, 64, 64, 64, 128, 64, 576, 576, 288};
 constexpr int GEMM_CFG_SCALAR = 3;
 constexpr int GEMM_CFG_LEAN = 4;     // weight gradients, 128 x 128, short reductions
 constexpr int GEMM_CFG_LEAN64 = 5;   // forward / input gradients, 128 x 64, short reductions
+constexpr int GEMM_CFG_HALO_S1 = 6;  // convolution weight gradients, halo form, stride 1
+constexpr int GEMM_CFG_HALO_S2 = 7;  // likewise, stride 2
+constexpr int GEMM_CFG_HALO32_S1 = 8;   // 64 x 32 channel pairs per tile, stride 1
+inline bool is_halo_cfg(int cfg) { return cfg >= GEMM_CFG_HALO_S1 && cfg <= GEMM_CFG_HALO32_S1; }
 constexpr int ELEMWISE_PER_BLOCK = 2048;   // elements one block of the elementwise kernels covers
 constexpr int SGD_PER_BLOCK = 2048;        // parameters one block of the update kernel covers (measured best of 1024..8192)
 

@@ -15,65 +15,12 @@
 // fixed order: results are bit-reproducible and a member's result does not depend on which
 // other members share the pack (the isolation guarantee of Section 2.2).
 #include "pack_internal.h"
+#include "pack_device.h"
 
 #include <type_traits>
 #include <utility>
 
 namespace packk {
-
-typedef unsigned short bf16_t;   // bfloat16 = upper half of an IEEE binary32
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(4))) float f32x4_t;
-typedef __attribute__((ext_vector_type(16))) float f32x16_t;
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
-
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
-typedef __attribute__((ext_vector_type(2))) float f32x2_t;
-
-// float -> bfloat16, round to nearest with ties to even, NaN stays NaN: the hardware conversion
-// (one instruction per pair of values)
-__device__ __forceinline__ unsigned pack2bf(float lo, float hi) {
-    const f32x2_t v = {lo, hi};
-    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
-}
-__device__ __forceinline__ bf16_t f2bf(float f) { return (bf16_t)(pack2bf(f, 0.f) & 0xffffu); }
-__device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((unsigned int)h) << 16); }
-
-// activations of the paper's search space (Table 3) and their derivatives written in terms of the
-// stored output (what the backward pass has at hand); leaky ReLU slope 0.2
-constexpr float LEAKY_SLOPE = 0.2f;
-__device__ __forceinline__ float act_apply(int kind, float z) {
-    switch (kind) {
-        case ACT_RELU: return fmaxf(z, 0.f);
-        case ACT_LEAKY: return z > 0.f ? z : LEAKY_SLOPE * z;
-        case ACT_SIGMOID: return 1.f / (1.f + expf(-z));
-        case ACT_TANH: return tanhf(z);
-        default: return z;
-    }
-}
-__device__ __forceinline__ float act_deriv(int kind, float out) {
-    switch (kind) {
-        case ACT_RELU: return out > 0.f ? 1.f : 0.f;
-        case ACT_LEAKY: return out > 0.f ? 1.f : LEAKY_SLOPE;
-        case ACT_SIGMOID: return out * (1.f - out);
-        case ACT_TANH: return 1.f - out * out;
-        default: return 1.f;
-    }
-}
-
-template <typename T> struct ET;
-template <> struct ET<float> {
-    static constexpr int V = 4;    // elements per 16-byte vector
-    static constexpr int BK = 32;  // reduction indices per LDS tile
-    static __device__ __forceinline__ float to_f(float v) { return v; }
-    static __device__ __forceinline__ float from_f(float v) { return v; }
-};
-template <> struct ET<bf16_t> {
-    static constexpr int V = 8;
-    static constexpr int BK = 64;
-    static __device__ __forceinline__ float to_f(bf16_t v) { return bf2f(v); }
-    static __device__ __forceinline__ bf16_t from_f(float v) { return f2bf(v); }
-};
 
 // F_ROWMAP problems (one parity class of a stride-2 input gradient): the tap that reduction
 // block `tc` of the class stands for, and the pixel an output row stands for
@@ -252,23 +199,6 @@ struct LoadsPerChunk {
     static constexpr bool KC = IS_A ? OperandLayout<MODE>::A_KC : OperandLayout<MODE>::B_KC;
     static constexpr int value = KC ? G::KC_SLOTS : 4 * G::RC_PER_THREAD;
 };
-
-// Blocks until at most NEWER asm loads issued after the given registers' loads are outstanding.
-// The registers are in-out operands so that nothing that reads them can move above the wait.
-template <int NEWER, int N>
-__device__ __forceinline__ void wait_stage(u32x4_t (&regs)[N]) {
-    static_assert(NEWER >= 0 && NEWER < 64, "vmcnt is a 6-bit counter");
-    if constexpr (N == 1) asm volatile("s_waitcnt vmcnt(%1)" : "+v"(regs[0]) : "n"(NEWER));
-    else if constexpr (N == 2) asm volatile("s_waitcnt vmcnt(%2)" : "+v"(regs[0]), "+v"(regs[1]) : "n"(NEWER));
-    else if constexpr (N == 4)
-        asm volatile("s_waitcnt vmcnt(%4)" : "+v"(regs[0]), "+v"(regs[1]), "+v"(regs[2]), "+v"(regs[3]) : "n"(NEWER));
-    else if constexpr (N == 8)
-        asm volatile("s_waitcnt vmcnt(%8)"
-                     : "+v"(regs[0]), "+v"(regs[1]), "+v"(regs[2]), "+v"(regs[3]), "+v"(regs[4]), "+v"(regs[5]),
-                       "+v"(regs[6]), "+v"(regs[7])
-                     : "n"(NEWER));
-    else static_assert(N == 1 || N == 2 || N == 4 || N == 8, "unsupported register count");
-}
 
 // gathers V scalars into one 16-byte register group (slow path for unaligned shapes)
 template <int MODE, typename T, bool IS_A, bool KC>
@@ -450,29 +380,6 @@ __device__ __forceinline__ u32x4_t asm_load16(const void* ptr) {
 // The loads are assembly statements for the same reason as before: their completion is awaited
 // by hand (wait_stage), not by the compiler.
 // ------------------------------------------------------------------------------------------------
-typedef __attribute__((ext_vector_type(4))) int i32x4_t;
-constexpr unsigned BUF_RECORDS = 0x80000000u;   // bytes a descriptor covers
-constexpr unsigned BUF_POISON = 0x80000000u;    // offset of an element that does not exist
-
-__device__ __forceinline__ i32x4_t make_rsrc(const void* base, long long margin_bytes) {
-    const unsigned long long a = (unsigned long long)base - (unsigned long long)margin_bytes;
-    i32x4_t r;
-    r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
-    r.y = __builtin_amdgcn_readfirstlane((int)(unsigned)(a >> 32));   // stride 0: raw buffer
-    r.z = (int)BUF_RECORDS;
-    r.w = 0x00020000;                                                 // 32-bit data format
-    return r;
-}
-
-__device__ __forceinline__ u32x4_t buf_load16(const i32x4_t rsrc, unsigned voff, unsigned soff) {
-    u32x4_t v;
-    // the scalar operands are wave-uniform by construction; say so, since values that went through
-    // vector arithmetic (an integer division) would otherwise be handed over in vector registers
-    const unsigned so = __builtin_amdgcn_readfirstlane(soff);
-    asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(v) : "v"(voff), "s"(rsrc), "s"(so) : "memory");
-    return v;
-}
-
 // Per-thread operand fetcher of one tile.  VEC kernels use the buffer form above: everything that
 // depends on the thread's rows (pixel coordinates, border validity of the nine taps) is decoded
 // ONCE per tile into the per-load offsets; it relies on the alignment the planner checks before
@@ -702,10 +609,6 @@ template <int BM, int BN, int BKM, bool VEC>
 struct StageCount {   // register stages of prefetch per tile shape (bounded by the register file): 2, 3, 4 from the largest tile down
     static constexpr int value = (BKM > 1 || !VEC) ? 2 : ((BM * BN >= 128 * 128) ? 2 : ((BM * BN >= 128 * 64) ? 3 : 4));
 };
-
-// the SGD update of one parameter; every path that applies it (update kernels, fused epilogues)
-// uses this one expression so that a member's bits do not depend on which path its pack takes
-__device__ __forceinline__ float sgd_apply(float w, float g, float lr) { return __builtin_fmaf(-lr, g, w); }
 
 __device__ __forceinline__ void update_one(const GemmProb& p, size_t off, float g, float lr) {
     const float w = sgd_apply(p.upd_w[off], g, lr);
@@ -1327,7 +1230,7 @@ using LrArg = typename std::conditional<MODE == LIN_DW || MODE == CONV_DW, LrTab
 template <int MODE, typename T, int BM, int BN, int BKM, bool VEC, bool LEAN = false>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ probs,
                                                    const TileRef* __restrict__ tiles,
-                                                   const void* __restrict__ x, LrArg<MODE> lr) {
+                                                   const void* __restrict__ x, char* __restrict__ ws, LrArg<MODE> lr) {
     constexpr int BK = ET<T>::BK * BKM;
     const TileRef tr = tiles[blockIdx.x];
     if (tr.prob < 0) return;
@@ -1338,6 +1241,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
     if (p.flags & F_A_INPUT) p.A = xin;
     if (p.flags & F_B_INPUT) p.B = xin;
     if (p.flags & F_AUX_INPUT) p.aux = xin;
+    if constexpr (MODE == LIN_DW || MODE == CONV_DW) {
+        if (p.flags & F_WS) {   // partial sums of a split reduction go to the workspace this launch was given
+            p.C = ws + (size_t)p.C;
+            p.dbias = (float*)(ws + (size_t)p.dbias);
+        }
+    }
     // one block: operand tiles A (two buffers) then B (two buffers); the epilogue reuses it
     constexpr int NBUF = LEAN ? 1 : 2;
     __shared__ __attribute__((aligned(16))) T lds[LdsBytes<T, BM, BN, BK, LEAN, (MODE == LIN_DW || MODE == CONV_DW)>::value / sizeof(T)];
@@ -1349,49 +1258,52 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
 }
 
 template <int MODE, typename T>
-static void launch_gemm_tile(int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, const LrTable& lr, hipStream_t st) {
+static void launch_gemm_tile(int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, char* ws, const LrTable& lr, hipStream_t st) {
     LrArg<MODE> la;
     if constexpr (MODE == LIN_DW || MODE == CONV_DW) la = lr;
     switch (tile_cfg) {
-        case 0: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 128, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, la); break;
-        case 1: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 64, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, la); break;
-        case 2: hipLaunchKernelGGL((gemm_kernel<MODE, T, 64, 64, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, la); break;
+        case 0: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 128, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, ws, la); break;
+        case 1: hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 64, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, ws, la); break;
+        case 2: hipLaunchKernelGGL((gemm_kernel<MODE, T, 64, 64, 1, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, ws, la); break;
         case GEMM_CFG_LEAN:
             if constexpr (MODE == LIN_DW || MODE == CONV_DW)
-                hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 128, 1, true, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, la);
+                hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 128, 1, true, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, ws, la);
             break;
         case GEMM_CFG_LEAN64:
             if constexpr (!(MODE == LIN_DW || MODE == CONV_DW))
-                hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 64, 1, true, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, la);
+                hipLaunchKernelGGL((gemm_kernel<MODE, T, 128, 64, 1, true, true>), dim3(n), dim3(256), 0, st, probs, tiles, x, ws, la);
             break;
-        default: hipLaunchKernelGGL((gemm_kernel<MODE, T, 64, 64, 1, false>), dim3(n), dim3(256), 0, st, probs, tiles, x, la); break;
+        default: hipLaunchKernelGGL((gemm_kernel<MODE, T, 64, 64, 1, false>), dim3(n), dim3(256), 0, st, probs, tiles, x, ws, la); break;
     }
 }
 
 template <int MODE>
-static hipError_t launch_gemm_mode(bool bf16, int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, const LrTable& lr, hipStream_t st) {
-    if (bf16) launch_gemm_tile<MODE, bf16_t>(tile_cfg, probs, tiles, n, x, lr, st);
-    else launch_gemm_tile<MODE, float>(tile_cfg, probs, tiles, n, x, lr, st);
+static hipError_t launch_gemm_mode(bool bf16, int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, char* ws, const LrTable& lr, hipStream_t st) {
+    if (bf16) launch_gemm_tile<MODE, bf16_t>(tile_cfg, probs, tiles, n, x, ws, lr, st);
+    else launch_gemm_tile<MODE, float>(tile_cfg, probs, tiles, n, x, ws, lr, st);
     return hipGetLastError();
 }
 
-hipError_t launch_gemm(int mode, bool bf16, int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, const LrTable& lr, hipStream_t st) {
+hipError_t launch_gemm(int mode, bool bf16, int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, char* ws, const LrTable& lr, hipStream_t st) {
     if (n <= 0) return hipSuccess;
+    if (mode == CONV_DW && is_halo_cfg(tile_cfg)) return launch_conv_dw_halo(bf16, tile_cfg, probs, tiles, n, x, ws, lr, st);
     switch (mode) {
-        case LIN_FWD: return launch_gemm_mode<LIN_FWD>(bf16, tile_cfg, probs, tiles, n, x, lr, st);
-        case LIN_DX: return launch_gemm_mode<LIN_DX>(bf16, tile_cfg, probs, tiles, n, x, lr, st);
-        case LIN_DW: return launch_gemm_mode<LIN_DW>(bf16, tile_cfg, probs, tiles, n, x, lr, st);
-        case CONV_FWD: return launch_gemm_mode<CONV_FWD>(bf16, tile_cfg, probs, tiles, n, x, lr, st);
-        case CONV_DX: return launch_gemm_mode<CONV_DX>(bf16, tile_cfg, probs, tiles, n, x, lr, st);
-        case CONV_DW: return launch_gemm_mode<CONV_DW>(bf16, tile_cfg, probs, tiles, n, x, lr, st);
+        case LIN_FWD: return launch_gemm_mode<LIN_FWD>(bf16, tile_cfg, probs, tiles, n, x, ws, lr, st);
+        case LIN_DX: return launch_gemm_mode<LIN_DX>(bf16, tile_cfg, probs, tiles, n, x, ws, lr, st);
+        case LIN_DW: return launch_gemm_mode<LIN_DW>(bf16, tile_cfg, probs, tiles, n, x, ws, lr, st);
+        case CONV_FWD: return launch_gemm_mode<CONV_FWD>(bf16, tile_cfg, probs, tiles, n, x, ws, lr, st);
+        case CONV_DX: return launch_gemm_mode<CONV_DX>(bf16, tile_cfg, probs, tiles, n, x, ws, lr, st);
+        case CONV_DW: return launch_gemm_mode<CONV_DW>(bf16, tile_cfg, probs, tiles, n, x, ws, lr, st);
         default: return hipErrorInvalidValue;
     }
 }
 
 // out[e] = sum over S partials, in order
-__global__ __launch_bounds__(256) void reduce_kernel(const ReduceProb* __restrict__ probs, const int2* __restrict__ map, LrTable lr) {
+__global__ __launch_bounds__(256) void reduce_kernel(const ReduceProb* __restrict__ probs, const int2* __restrict__ map,
+                                                     const char* __restrict__ ws, LrTable lr) {
     const int2 m = map[blockIdx.x];
-    const ReduceProb p = probs[m.x];
+    ReduceProb p = probs[m.x];
+    p.in = (const float*)(ws + (size_t)p.in);   // the partial sums lie in the workspace this launch was given
     const float lrk = p.upd_w ? lr.lr[p.member] : 0.f;
     // A thread owns four elements.  Partials are added in split order; the loads of eight splits of
     // all four elements (32 loads) are issued before their adds, so that the strided reads overlap
@@ -1424,9 +1336,9 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceProb* __restric
     }
 }
 
-hipError_t launch_reduce(const ReduceProb* probs, const int2* map, int n, const LrTable& lr, hipStream_t st) {
+hipError_t launch_reduce(const ReduceProb* probs, const int2* map, int n, const char* ws, const LrTable& lr, hipStream_t st) {
     if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(reduce_kernel, dim3(n), dim3(256), 0, st, probs, map, lr);
+    hipLaunchKernelGGL(reduce_kernel, dim3(n), dim3(256), 0, st, probs, map, ws, lr);
     return hipGetLastError();
 }
 

@@ -12,6 +12,28 @@ from paper_2002_02885_amd import binding
 TOL = {wl.F32: 1e-4, wl.BF16: 2e-2}    # max relative error the two paths may differ by
 
 
+def say(text: str):
+    """Progress line of a long test (an oracle step of the largest configuration takes minutes): to the
+    real stderr and, so that a runner watching the output folder sees the test is alive while pytest
+    holds the streams back, appended to gpurun_out/test_progress.log."""
+    import os
+    import sys
+    import time
+    line = f"[{time.strftime('%H:%M:%S')}] {text}\n"
+    try:
+        sys.__stderr__.write(line)
+        sys.__stderr__.flush()
+    except (OSError, ValueError):
+        pass
+    try:
+        folder = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+        os.makedirs(folder, exist_ok=True)
+        with open(os.path.join(folder, "test_progress.log"), "a") as f:
+            f.write(line)
+    except OSError:
+        pass
+
+
 def device_inputs(w: wl.PackWorkload):
     """The shared batch and labels as device tensors of the pack's element type."""
     x = torch.from_numpy(w.x)
@@ -62,6 +84,7 @@ def run_gpu(w: wl.PackWorkload, steps=None, lr=None, x_dev=None, y_dev=None, kee
 def run_oracle(w: wl.PackWorkload, steps=None, mode="exact", lr=None):
     steps = w.steps if steps is None else steps
     lr = w.lr if lr is None else lr
+    say(f"oracle: {w.name} K={w.K} steps={steps} mode={mode}")
     return po.train_pack(w.models, w.in_shape, [b.astype(np.float64) for b in w.weights], w.batch,
                          np.asarray(lr, dtype=np.float64), w.x.astype(np.float64), w.labels, steps,
                          mode=mode, keep_grads=True, optimizers=w.meta.get("optimizers"))
@@ -122,14 +145,19 @@ def measure(w: wl.PackWorkload, a: dict, ref: dict, what=("loss", "grads", "disp
 
 
 # Which measured items may take the oracle-sensitivity allowance (see gate): single entries of a
-# tensor (infinity norms) and displacements accumulated over several steps.  A 2-norm taken at step 1
-# and every loss are robust against a flipped ReLU unit or a value on a rounding boundary, and get none.
+# tensor (infinity norms) and what has accumulated over several steps (displacements, raw weights, the
+# losses of later steps: two trajectories that differ by rounding drift apart, fastest at large
+# learning rates).  A 2-norm taken at step 1 and the first step's loss are robust against a flipped
+# ReLU unit or a value on a rounding boundary, and get none.
 ALLOWANCE_KINDS_ALWAYS = ("grad_inf", "disp_inf")
-ALLOWANCE_KINDS_MULTI_STEP = ("disp_l2", "weights")
-MAX_ALLOWANCE_SHARE = 0.25     # of the eligible items of a comparison that may need the allowance
+ALLOWANCE_KINDS_MULTI_STEP = ("disp_l2", "weights", "loss")     # "loss": the losses of steps after the first
+MAX_ALLOWANCE_SHARE = 0.25     # of the eligible items of a comparison that may need the allowance (the full-size
+                               # configurations need it for 2 % (c3), 9 % (c2) and 15 % (c4) of theirs)
+MAX_ALLOWANCE_SHARE_SMALL = 0.6   # reduced cases: a handful of rows on maps of a few pixels under hundreds of channels
 
 
-def gate(name: str, errs: dict, tol: float, sens=None, steps: int = 1, max_share: float = MAX_ALLOWANCE_SHARE):
+def gate(name: str, errs: dict, tol: float, sens=None, steps: int = 1, max_share: float = MAX_ALLOWANCE_SHARE,
+         small_case: bool = False):
     """Asserts every measured error is within `tol` (+ what fp32 storage of the master weights alone
     contributes).  Items of the kinds listed above that exceed it are ill-conditioned candidates: a
     ReLU unit within accumulation noise of zero, or a value within that noise of a bf16 rounding
@@ -138,20 +166,28 @@ def gate(name: str, errs: dict, tol: float, sens=None, steps: int = 1, max_share
     a function returning one, evaluated only when needed) gives the oracle's own sensitivity: how far
     ITS result moves under fp32-sized accumulation noise.  An item whose sensitivity exceeds tol/4 is
     gated at tol + 4 x sensitivity and listed in the report; the share of eligible items that needed
-    this must stay below `max_share`.  Everything else fails outright.
+    this must stay below `max_share`.  Everything else fails outright.  `small_case`: a reduced test
+    case with a handful of rows and pixels, where one flipped unit is a visible share even of a tensor's
+    2-norm; there (and only there) the first step's 2-norm gradients and displacements are eligible too.
     Returns (worst error per kind among the items within tol, the items that took the allowance,
     number of eligible items)."""
-    eligible = set(ALLOWANCE_KINDS_ALWAYS) | (set(ALLOWANCE_KINDS_MULTI_STEP) if steps > 1 else set())
+    def eligible(key):
+        if key[0] in ALLOWANCE_KINDS_ALWAYS or (small_case and key[0] in ("grad_l2", "disp_l2", "weights")):
+            return True
+        if steps > 1 and key[0] in ALLOWANCE_KINDS_MULTI_STEP:
+            return key[0] != "loss" or key[2] > 0            # the first step's loss is never eligible
+        return False
+
     worst, over = {}, []
     for key, (e, allow) in errs.items():
         if e <= tol + allow:
             worst[key[0]] = max(worst.get(key[0], 0.0), float(e))
         else:
             over.append((key, float(e), float(allow)))
-    n_eligible = sum(1 for key in errs if key[0] in eligible)
+    n_eligible = sum(1 for key in errs if eligible(key))
     took = []
     if over:
-        hard = [(k, e) for k, e, _ in over if k[0] not in eligible]
+        hard = [(k, e) for k, e, _ in over if not eligible(k)]
         assert not hard, f"{name}: beyond {tol} with no allowance for this kind of item: {hard[:8]}"
         assert sens is not None, f"{name}: beyond {tol} and no sensitivity given: {[(k, e) for k, e, _ in over[:8]]}"
         sens = sens() if callable(sens) else sens
@@ -167,9 +203,11 @@ def gate(name: str, errs: dict, tol: float, sens=None, steps: int = 1, max_share
 
 
 def compare(w: wl.PackWorkload, gpu: dict, ref: dict, tol: float, what=("loss", "grads", "disp", "weights"),
-            label="", sens=None, max_share: float = MAX_ALLOWANCE_SHARE):
+            label="", sens=None, max_share: float = MAX_ALLOWANCE_SHARE, small_case: bool = False):
     steps = min(gpu["loss"].shape[0], ref["loss"].shape[0])
-    worst, took, n_eligible = gate(label + w.name, measure(w, gpu, ref, what), tol, sens, steps, max_share)
+    if small_case and max_share == MAX_ALLOWANCE_SHARE:
+        max_share = MAX_ALLOWANCE_SHARE_SMALL
+    worst, took, n_eligible = gate(label + w.name, measure(w, gpu, ref, what), tol, sens, steps, max_share, small_case)
     if took:
         worst["took_allowance"] = f"{len(took)} of {n_eligible} eligible items"
         worst["ill_conditioned"] = took
@@ -193,6 +231,7 @@ def oracle_sensitivity(w: wl.PackWorkload, steps, base: dict, mode="rounded", tr
     eps = accumulation_noise(w) if eps is None else eps
     out = {}
     for trial in range(trials):
+        say(f"oracle sensitivity: {w.name} K={w.K} steps={steps} mode={mode} trial {trial}")
         rng = np.random.default_rng(1000 + trial)
 
         def noisy(a):

@@ -39,6 +39,11 @@ def _check_production_form(w, steps, gpu):
     _same_bits(pu.run_gpu(w, steps, keep_first_grads=False), gpu)
 
 
+def _small(w):
+    """A reduced test case: fewer than 64 rows per member, where one flipped unit shows in a 2-norm."""
+    return max(w.batch) < 64
+
+
 def _check_f32(w, steps=None, trials=2, production_form=False):
     """fp32 packs against the float64 oracle at 1e-4: every loss, the step-1 gradients and the
     displacement of every tensor in the 2-norm and the infinity norm, the raw weights.  Single entries
@@ -48,7 +53,8 @@ def _check_f32(w, steps=None, trials=2, production_form=False):
     steps = w.steps if steps is None else steps
     gpu = pu.run_gpu(w, steps)
     ref = pu.run_oracle(w, steps)
-    worst = pu.compare(w, gpu, ref, F32_TOL, sens=lambda: pu.oracle_sensitivity(w, steps, ref, mode="exact", trials=trials))
+    worst = pu.compare(w, gpu, ref, F32_TOL, sens=lambda: pu.oracle_sensitivity(w, steps, ref, mode="exact", trials=trials),
+                       small_case=_small(w))
     n, skipped, lerr = pu.compare_pred(w, gpu["pred_first"], gpu["logits"], ref["pred"][0], ref["logits"][0])
     if production_form:
         _check_production_form(w, steps, gpu)
@@ -64,10 +70,8 @@ def _check_bf16(w, steps=None, trials=2, production_form=False):
     - every step against the oracle that rounds where the device rounds: loss, step-1
       gradients, displacement and weights within 2e-2, gated as for fp32 packs (parity_util.gate);
     - every step against the oracle that only rounds the per-step weight copy (the precision
-      the configuration itself fixes): loss, and the 2-norm of every tensor's displacement, within
-      2e-2 for every member on which the oracle's own two roundings agree to a quarter of that; the
-      others are reported as ill-conditioned (large learning rate on un-normalised inputs), not
-      passed silently."""
+      the configuration itself fixes): every loss, and the 2-norm of every tensor's displacement, no
+      farther from it than the rounding oracle itself lies plus 2e-2, no item excluded."""
     steps = w.steps if steps is None else steps
     gpu = pu.run_gpu(w, steps)
     exact = pu.run_oracle(w, 1, mode="exact")
@@ -76,35 +80,38 @@ def _check_bf16(w, steps=None, trials=2, production_form=False):
     first = {"loss": gpu["loss"][:1], "blobs": gpu["blobs"], "grads": None}
     w0 = pu.compare(w, first, exact, BF16_TOL, what=("loss",), label="exact step 1: ")
     w2 = pu.compare(w, gpu, rounded, BF16_TOL, what=("loss", "grads", "disp", "weights"), label="rounded: ",
-                    sens=lambda: pu.oracle_sensitivity(w, steps, rounded, trials=trials))
-    worst, worst_disp, ill = _check_against_weight_rounding(w, gpu, weights, rounded)
+                    sens=lambda: pu.oracle_sensitivity(w, steps, rounded, trials=trials), small_case=_small(w))
+    vs_weights = _check_against_weight_rounding(w, gpu, weights, rounded, w2)
     n, skipped, lerr = pu.compare_pred(w, gpu["pred_first"], gpu["logits"], rounded["pred"][0], rounded["logits"][0])
     if production_form:
         _check_production_form(w, steps, gpu)
     print(f"\n{w.name}: step-1 loss vs float64 {w0['loss']:.2e}; vs rounding oracle {w2}; "
-          f"vs weight-rounding oracle: loss {worst:.2e}, displacement (2-norm) {worst_disp:.2e}; "
-          f"ill-conditioned (member, what, oracle sensitivity, gpu err): {ill}; "
+          f"vs weight-rounding oracle (device error, and how far the rounding oracle itself lies from it) {vs_weights}; "
           f"argmax rows {n}, unresolvable {skipped} (largest logit difference {lerr:.1e}); launches {gpu['launches']}")
     return gpu, weights, rounded
 
 
-def _check_against_weight_rounding(w, gpu, weights, rounded, members=None):
+def _check_against_weight_rounding(w, gpu, weights, rounded, vs_rounded=None):
     """Loss at every step and the 2-norm displacement of every tensor against the oracle that rounds
-    only the per-step weight copy.  A member on which that oracle and the one with the device's
-    rounding points differ by more than tol/4 is not determined to the tolerance by the
-    configuration's own precision: it is reported with both numbers instead of being gated."""
-    ill, worst, worst_disp = [], 0.0, 0.0
-    n_members = 0
-    for k in (range(w.K) if members is None else members):
-        n_members += 1
-        sens = np.abs(weights["loss"][:, k] - rounded["loss"][:, k]) / np.abs(weights["loss"][:, k])
-        bad = np.maximum.accumulate(sens) > BF16_TOL / 4
+    only the per-step weight copy (the precision the configuration itself fixes).  Storing activations
+    and gradients in bf16 moves the oracle itself away from that reference (`own`: how far its mode
+    "rounded" lies from its mode "weights"); the device may lie no farther from it than that plus the
+    tolerance (plus, for an item that needed the ill-conditioning allowance in the comparison with the
+    rounding oracle, `vs_rounded`, that same allowance: the bound is the triangle inequality through the
+    rounding oracle).  No item is excluded.  Returns the worst device error, the worst `own`, for losses
+    and for displacements."""
+    worst = {"loss": 0.0, "loss_own": 0.0, "disp_l2": 0.0, "disp_l2_own": 0.0}
+    extra = {(key[1], key[2]): 4 * sens for key, sens, _ in (vs_rounded or {}).get("ill_conditioned", []) if key[0] == "disp_l2"}
+    extra_loss = {}
+    for key, sens, _ in (vs_rounded or {}).get("ill_conditioned", []):
+        if key[0] == "loss":
+            extra_loss[key[1]] = max(extra_loss.get(key[1], 0.0), 4 * sens)
+    for k in range(w.K):
+        # (once two trajectories have drifted apart they may cross again: the largest distance so far counts)
+        own = np.maximum.accumulate(np.abs(weights["loss"][:, k] - rounded["loss"][:, k]) / np.abs(weights["loss"][:, k]))
         err = np.abs(gpu["loss"][:, k] - weights["loss"][:, k]) / np.abs(weights["loss"][:, k])
-        if bad.any():
-            ill.append((k, "loss", float(sens.max()), float(err.max())))
-        if (~bad).any():
-            worst = max(worst, float(err[~bad].max()))
-            assert err[~bad].max() <= BF16_TOL, f"{w.name} member {k}: loss vs weight-rounding oracle {err}"
+        assert np.all(err <= own + BF16_TOL + extra_loss.get(k, 0.0)), f"{w.name} member {k}: loss vs weight-rounding oracle {err}, the oracles differ by {own}"
+        worst["loss"], worst["loss_own"] = max(worst["loss"], float(err.max())), max(worst["loss_own"], float(own.max()))
         if float(w.lr[k]) == 0.0:
             continue
         w0 = w.weights[k].astype(np.float64)
@@ -112,12 +119,9 @@ def _check_against_weight_rounding(w, gpu, weights, rounded, members=None):
             d_ref, d_rnd = weights["blobs"][k][s] - w0[s], rounded["blobs"][k][s] - w0[s]
             d_gpu = gpu["blobs"][k][s].astype(np.float64) - w0[s]
             own, e = pu.rel_l2(d_rnd, d_ref), pu.rel_l2(d_gpu, d_ref)
-            if own > BF16_TOL / 4:
-                ill.append((k, name, own, e))
-            else:
-                worst_disp = max(worst_disp, e)
-                assert e <= BF16_TOL, f"{w.name} member {k} {name}: displacement vs weight-rounding oracle {e} (oracles differ by {own})"
-    return worst, worst_disp, ill
+            assert e <= own + BF16_TOL + extra.get((k, name), 0.0), f"{w.name} member {k} {name}: displacement vs weight-rounding oracle {e}, the oracles differ by {own}"
+            worst["disp_l2"], worst["disp_l2_own"] = max(worst["disp_l2"], e), max(worst["disp_l2_own"], own)
+    return {key: float(f"{v:.3g}") for key, v in worst.items()}
 
 
 # ------------------------------------------------------------------ MLPs, fp32
@@ -212,6 +216,28 @@ def test_lean_form_of_forward_and_input_gradient_tiles_gives_the_same_bits(make,
         assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
 
 
+@pytest.mark.parametrize("make", [
+    lambda: wl.config5(K=2, B=8, size=16, steps=2),                                   # bf16: 16 and 8 pixel rows, both strides; 4 pixel rows stay on the staged tiles
+    lambda: wl.config5(K=2, B=2, size=64, widths=(64, 128), n_classes=10, steps=2),   # bf16: 64 and 32 pixel rows (one and two rows per chunk)
+    lambda: wl.config3(K=2, B=16, size=32, widths=(32, 64, 128), steps=2),            # fp32: 32 input channels per tile; stride 2, 16 pixel rows
+    lambda: wl.config5(K=1, B=4, size=32, widths=(64, 64), n_classes=10, steps=2, dtype=wl.F32),   # fp32, stride 1 and 2
+    lambda: wl.config3(K=2, B=4, size=32, widths=(32, 64, 64), steps=2, dtype=wl.BF16),            # bf16, 32 input channels per tile
+])
+def test_halo_form_of_the_convolution_weight_gradient_gives_the_same_bits_as_the_staged_tiles(make, monkeypatch):
+    # all nine taps of a block of channel pairs in one workgroup, the input staged once per chunk of pixels:
+    # same chunks, same order inside them, same splits, so the same bits as the form it replaces
+    w = make()
+    halo = pu.run_gpu(w, steps=2)
+    assert any(t[:2] in ((64, 576), (64, 288)) for t in halo["tiles"])
+    monkeypatch.setenv("PACK_NO_HALO_DW", "1")
+    staged = pu.run_gpu(w, steps=2)
+    assert not any(t[:2] in ((64, 576), (64, 288)) for t in staged["tiles"])
+    for key in ("grads", "blobs"):
+        for a, b in zip(halo[key], staged[key]):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), key
+    assert np.array_equal(halo["loss"], staged["loss"])
+
+
 def test_c5_resnet_style_bf16_full_width_reduced_images():
     _check_bf16(wl.config5(K=2, B=8, size=16, steps=2))
 
@@ -241,7 +267,7 @@ def test_c5_four_resnet_style_cnns_bf16_full_size():
     w2 = pu.compare(solo, one, rounded, BF16_TOL, label="rounded: ",
                     sens=lambda: pu.oracle_sensitivity(solo, 1, rounded, trials=1))
     weights = pu.run_oracle(solo, 1, mode="weights")
-    worst, worst_disp, ill = _check_against_weight_rounding(solo, one, weights, rounded)
+    vs_weights = _check_against_weight_rounding(solo, one, weights, rounded, w2)
     n, skipped, lerr = pu.compare_pred(solo, one["pred_first"], one["logits"], rounded["pred"][0], rounded["logits"][0])
     for j in range(w.K):
         alone = pu.run_gpu(_member(w, j), 1)
@@ -249,9 +275,8 @@ def test_c5_four_resnet_style_cnns_bf16_full_size():
         assert np.array_equal(alone["grads"][0].view(np.uint32), gpu["grads"][j].view(np.uint32)), j
         assert np.array_equal(alone["loss"][:, 0], gpu["loss"][:, j]), j
     _check_production_form(w, 1, gpu)
-    print(f"\nc5 full size: member {k} vs rounding oracle {w2}; vs weight-rounding oracle: loss {worst:.2e}, "
-          f"displacement (2-norm) {worst_disp:.2e}, ill-conditioned {ill}; argmax rows {n}, unresolvable {skipped} "
-          f"(largest logit difference {lerr:.1e}); launches {gpu['launches']}")
+    print(f"\nc5 full size: member {k} vs rounding oracle {w2}; vs weight-rounding oracle {vs_weights}; "
+          f"argmax rows {n}, unresolvable {skipped} (largest logit difference {lerr:.1e}); launches {gpu['launches']}")
 
 
 # ------------------------------------------------------------------ the paper's invariants on the device
