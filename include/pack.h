@@ -291,6 +291,25 @@ pack_status pack_write_weights(pack_t* p, int32_t k, const float* host_src, size
  * Errors: PACK_EINVAL (null argument), PACK_EDEVICE (launch failure). */
 pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, const float* lr_host);
 
+/* pack_step for callers that may not allocate device memory while they run: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  The same step with the same kernels and the same
+ * bits as pack_step; the only difference is where the partial sums of split weight gradients go: not into
+ * the workspace the pack allocated at creation but into a scratch array that is part of the library's code
+ * object (file-scope device memory, pack_static_scratch_bytes() = 128 MiB, 0.04 % of the card; every GPU
+ * the library runs on holds its own copy until the process ends).  The call allocates and frees nothing,
+ * on the device or through any library; the first call on a device looks the array's address up.
+ * A pack whose split weight gradients need more than the array holds (pack_workspace_bytes(p)) is rejected
+ * with PACK_ENOMEM and nothing is launched; the five reference configurations need at most 113 MB.  Launch
+ * timing must be off (PACK_EINVAL otherwise: events are allocations).  All packs of a process share the
+ * array of their GPU: a step overwrites what the previous one left there and needs nothing cleared, but
+ * two steps that overlap in time on one GPU (different streams or threads) race on it; keep such steps on
+ * one stream, or use pack_step.
+ * Errors: PACK_EINVAL, PACK_ENOMEM, PACK_EDEVICE. */
+pack_status pack_step_static(pack_t* p, const void* x_dev, const int32_t* labels_dev, const float* lr_host);
+size_t pack_static_scratch_bytes(void);
+/* Bytes of scratch one step of this pack needs for the partial sums of split weight gradients. */
+size_t pack_workspace_bytes(const pack_t* p);
+
 /* Choose member k's optimiser (default: PACK_OPT_SGD).  Resets the member's optimiser state to its
  * starting values and its step counter to 0; the weights are untouched.  Fields that the chosen
  * kind does not use are ignored.  Waits for the stream.  The learning rate stays the per-step

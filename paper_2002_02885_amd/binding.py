@@ -27,7 +27,8 @@ EXPORTS = ["pack_create", "pack_write_weights", "pack_step", "pack_read_loss", "
            "pack_schedule_create", "pack_schedule_next", "pack_schedule_used", "pack_schedule_destroy",
            "pack_gather_batch", "pack_set_input_mode", "pack_config_distance", "pack_opt_knn", "pack_opt_random",
            "pack_opt_batchsize", "pack_hyperband_plan", "pack_halving_keep", "pack_estimate_bytes",
-           "pack_keep_grads", "pack_launch_bytes", "pack_measure_ceiling", "pack_launch_tile", "pack_plan_check"]
+           "pack_keep_grads", "pack_launch_bytes", "pack_measure_ceiling", "pack_launch_tile", "pack_plan_check",
+           "pack_step_static", "pack_static_scratch_bytes", "pack_workspace_bytes"]
 
 
 class pack_opt_spec(C.Structure):
@@ -128,6 +129,12 @@ def lib() -> C.CDLL:
         l.pack_launch_bytes.argtypes = [vp, i32, C.POINTER(C.c_double)]
         l.pack_launch_bytes.restype = C.c_int
         l.pack_launch_tile.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
+        l.pack_step_static.argtypes = [vp, vp, vp, fp]
+        l.pack_step_static.restype = C.c_int
+        l.pack_static_scratch_bytes.argtypes = []
+        l.pack_static_scratch_bytes.restype = sz
+        l.pack_workspace_bytes.argtypes = [vp]
+        l.pack_workspace_bytes.restype = sz
         i64p = C.POINTER(C.c_int64)
         l.pack_plan_check.argtypes = [C.POINTER(pack_input_spec), C.POINTER(pack_model_spec), i32, i32, i64p, i64p, i64p]
         l.pack_plan_check.restype = C.c_int
@@ -178,6 +185,10 @@ def _model_specs(B: int, in_shape, dtype: str, models, batch):
     return inp, specs, keep
 
 
+def static_scratch_bytes() -> int:
+    return int(lib().pack_static_scratch_bytes())
+
+
 def plan_check(B: int, in_shape, dtype: str, models, batch=None, per_member_input: bool = False):
     """pack_plan_check: plans the pack without a GPU and walks the kernels' address rules on the host.
     Returns (launches walked, matrix-product launches without a host model, loads and operand reads checked);
@@ -224,6 +235,15 @@ class Pack:
         lr = np.ascontiguousarray(lr, dtype=np.float32)
         assert lr.size == self.K
         _check(lib().pack_step(self._h, C.c_void_p(x_ptr), C.c_void_p(labels_ptr), _fptr(lr)))
+
+    def step_static(self, x_ptr: int, labels_ptr: int, lr: np.ndarray):
+        """pack_step_static: the same step, allocating nothing; scratch in the library's static array."""
+        lr = np.ascontiguousarray(lr, dtype=np.float32)
+        assert lr.size == self.K
+        _check(lib().pack_step_static(self._h, C.c_void_p(x_ptr), C.c_void_p(labels_ptr), _fptr(lr)))
+
+    def workspace_bytes(self) -> int:
+        return int(lib().pack_workspace_bytes(self._h))
 
     def _refresh_slots(self):
         self.K = int(lib().pack_num_slots(self._h))

@@ -1712,6 +1712,33 @@ pack_status pack_step(pack_t* p, const void* x_dev, const int32_t* labels_dev, c
     return step_with_workspace(p, x_dev, labels_dev, lr_host, p->workspace);
 }
 
+size_t pack_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+size_t pack_workspace_bytes(const pack_t* p) { return p ? p->workspace_bytes : 0; }
+
+pack_status pack_step_static(pack_t* p, const void* x_dev, const int32_t* labels_dev, const float* lr_host) {
+    if (!p || !x_dev || !labels_dev || !lr_host) return fail(PACK_EINVAL, "null argument");
+    if (p->profiling) return fail(PACK_EINVAL, "pack_step_static does not time launches (events are allocations): call pack_profile_stop first");
+    if (p->workspace_bytes > STATIC_SCRATCH_BYTES)
+        return fail(PACK_ENOMEM, "the pack's split weight gradients need " + std::to_string(p->workspace_bytes) +
+                                 " bytes of scratch, the library's static array holds " + std::to_string(STATIC_SCRATCH_BYTES));
+    // the array's address on this device, looked up once per device (every GPU holds its own copy)
+    static std::mutex mu;
+    static char* scratch_of[64] = {nullptr};
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev), PACK_EDEVICE);
+    if (dev < 0 || dev >= 64) return fail(PACK_EDEVICE, "device index outside [0, 64)");
+    if (dev != p->device) return fail(PACK_EINVAL, "the pack was created on another device than the current one");
+    char* ws = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (!scratch_of[dev]) HIP_TRY(static_scratch(&scratch_of[dev]), PACK_EDEVICE);
+        ws = scratch_of[dev];
+    }
+    if (!ws) return fail(PACK_EDEVICE, "no address for the static scratch array");
+    return step_with_workspace(p, x_dev, labels_dev, lr_host, ws);
+}
+
 pack_status pack_profile_start(pack_t* p, int32_t which, int32_t every) {
     if (!p || every < 1) return fail(PACK_EINVAL, "null argument or every < 1");
     if (which >= (int32_t)p->plan.size()) return fail(PACK_EINVAL, "launch index out of range");

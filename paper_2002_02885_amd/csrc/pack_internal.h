@@ -166,6 +166,10 @@ hipError_t launch_conv_dw_halo(bool bf16, int tile_cfg, const GemmProb* probs_de
 // the halo configuration (GEMM_CFG_HALO*) problem p can take, or -1
 int conv_dw_halo_cfg(bool bf16, const GemmProb& p);
 hipError_t launch_reduce(const ReduceProb* probs_dev, const int2* map_dev, int n_blocks, const char* ws, const LrTable& lr, hipStream_t st);
+// The library's own scratch array (file-scope device memory, STATIC_SCRATCH_BYTES long, one copy per GPU):
+// its address on the current device.  For the entry point that may not allocate.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)128 << 20;
+hipError_t static_scratch(char** ptr);
 hipError_t launch_ce(bool bf16, const CeProb* probs_dev, int K, const int32_t* labels, int* err_flag, hipStream_t st);
 // max_c: the largest class count among the launch's members (<= HEAD_MAX_C)
 hipError_t launch_head(bool bf16, int max_c, const HeadProb* probs_dev, const int2* map_dev, int n_blocks, const int32_t* labels,

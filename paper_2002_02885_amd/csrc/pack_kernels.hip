@@ -2155,6 +2155,20 @@ hipError_t launch_fill_zero(void* dst, long long bytes, hipStream_t st) {
     return hipGetLastError();
 }
 
+// ---- scratch memory the library owns without allocating it ---------------------------------------
+// For callers that may not allocate device memory (pack_step_static): the partial sums of split weight
+// gradients go here instead of into the pack's own workspace.  Every GPU the library runs on holds its
+// own copy of the array, at its own address, until the process ends; host code never uses the array's
+// name as an address, only what hipGetSymbolAddress returns for the current device.
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+hipError_t static_scratch(char** ptr) {
+    void* dev = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&dev, HIP_SYMBOL(scratch));
+    *ptr = (e == hipSuccess) ? (char*)dev : nullptr;
+    return e;
+}
+
 // ---- measured ceilings --------------------------------------------------------------------------
 // Two measuring aids, so that a kernel's rate can be set beside what this chip delivers on the
 // simplest possible code as well as beside the published peak: a streaming copy (every byte read
