@@ -31,17 +31,19 @@ namespace packk {
 constexpr unsigned HALO_POISON = 0x80000000u;   // byte offset of a vector that does not exist (beyond any image)
 
 // Compile-time shape of one kernel instantiation.  ESZ: bytes per element (2 = bfloat16, 4 = float);
-// WM x WN: grid of wavefronts, each owning a 32 x 32 block of (output channel, input channel) for all taps.
-template <int ESZ, int WM, int WN, int STRIDE>
+// WM x WN: grid of wavefronts, each owning a 32 x 32 block of (output channel, input channel); TG: the nine
+// taps of a block are dealt over TG waves (1: one wave holds all nine; 2: taps 0-4 and taps 5-8; 3: one tap row each), i.e.
+// TG waves per SIMD, which hide each other's waits.
+template <int ESZ, int WM, int WN, int STRIDE, int TG_ = 1>
 struct HaloCfg {
-    static constexpr int S = STRIDE;
-    static constexpr int NT = 64 * WM * WN;              // threads per workgroup
+    static constexpr int S = STRIDE, TG = TG_;
+    static constexpr int NT = 64 * WM * WN * TG;         // threads per workgroup
     static constexpr int CH = (ESZ == 2) ? 64 : 32;      // output pixels per chunk (the reduction runs in ascending chunks of this many)
     static constexpr int CO_T = 32 * WM, CI_T = 32 * WN;
     static constexpr int VE = 16 / ESZ;                  // elements per 16-byte vector
     static constexpr int VPP_A = CO_T / VE, VPP_B = CI_T / VE;   // vectors per pixel of the dZ / input block
-    static constexpr int NLA = CH * VPP_A / NT;          // dZ vectors a thread loads per chunk
-    static constexpr int NLD = (STRIDE == 1) ? 7 : 11;   // halo vectors a thread loads per chunk (upper bound; the planner checks it)
+    static constexpr int NLA = (CH * VPP_A + NT - 1) / NT;   // dZ vectors a thread loads per chunk (threads beyond the block load none)
+    static constexpr int NLD = (((STRIDE == 1) ? 7 : 11) + TG - 1) / TG;   // halo vectors a thread loads per chunk (upper bound; the planner checks it)
     static constexpr int MAX_SLOTS = NLD * NT / VPP_B;   // halo pixels that fit those loads
     // bytes from one pixel to the next in LDS: the channels plus padding chosen so that the 32 lanes that a
     // transposing read serves together (four consecutive output pixels, i.e. halo pixels S apart, 64 bytes of
@@ -50,7 +52,6 @@ struct HaloCfg {
     static constexpr int PIXB_B = CI_T * ESZ + ((ESZ == 2) ? ((STRIDE == 1) ? (WN == 2 ? 64 : 0) : 32) : 0);
     static constexpr int HALO_BYTES = MAX_SLOTS * PIXB_B, DZ_BYTES = CH * PIXB_A;
     static constexpr int LDS_BYTES = 2 * (HALO_BYTES + DZ_BYTES);   // two buffers of each
-    static_assert(CH * VPP_A % NT == 0, "dZ vectors divide evenly over the threads");
 };
 
 // Run-time shape of one problem.
@@ -116,6 +117,7 @@ PACK_HD inline int halo_lds_offset(int v) { return (v / Cfg::VPP_B) * Cfg::PIXB_
 // dZ vector v of a chunk (v = pixel * VPP_A + part): byte offset from the chunk's first pixel, channel o0
 template <class Cfg, int ESZ>
 PACK_HD inline unsigned dz_vec_offset(const HaloGeom& g, int o0, int v) {
+    if (v >= Cfg::CH * Cfg::VPP_A) return HALO_POISON;
     return (unsigned)(((v / Cfg::VPP_A) * g.Cout + o0) * ESZ + (v % Cfg::VPP_A) * 16);
 }
 template <class Cfg>
@@ -144,5 +146,9 @@ PACK_HD inline int frag_holds_channel(int lane) { return lane & 31; }
 // lanes 32-63 pixel B of the step.  Eight pixels are consumed by four instructions that pair pixel j with
 // pixel j + 4 (j = 0..3), the pairing and order of the staged-tile form of the same product.
 PACK_HD inline int frag_pixel_f32(int lane, int k8, int j) { return k8 * 8 + j + (lane >> 5) * 4; }
+
+// taps of tap group tg: first tap and number of taps
+template <int TG> PACK_HD constexpr int tap_first(int tg) { return TG == 1 ? 0 : TG == 2 ? (tg == 0 ? 0 : 5) : 3 * tg; }
+template <int TG> PACK_HD constexpr int tap_count(int tg) { return TG == 1 ? 9 : TG == 2 ? (tg == 0 ? 5 : 4) : 3; }
 
 }  // namespace packk

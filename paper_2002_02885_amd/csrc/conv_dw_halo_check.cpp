@@ -32,9 +32,9 @@ struct Walk {
 constexpr long long ZERO = -1;      // symbolic value: the load returned zeros
 constexpr long long UNSET = -2;     // LDS position never written
 
-template <int ESZ, int WM, int WN, int STRIDE>
+template <int ESZ, int WM, int WN, int STRIDE, int TG = 1>
 bool walk_tile(const GemmProb& p, const TileRef& tr, long long a_bytes, long long b_bytes, bool every_chunk, Walk& w) {
-    typedef HaloCfg<ESZ, WM, WN, STRIDE> Cfg;
+    typedef HaloCfg<ESZ, WM, WN, STRIDE, TG> Cfg;
     constexpr int NT = Cfg::NT, CH = Cfg::CH, VE = Cfg::VE;
     if (!halo_supported<Cfg, ESZ>(p)) return w.fail("problem does not satisfy halo_supported");
     const HaloGeom g = halo_geom<ESZ, CH>(p);
@@ -50,7 +50,7 @@ bool walk_tile(const GemmProb& p, const TileRef& tr, long long a_bytes, long lon
 
     // symbolic LDS: one entry per element position of the halo block and of the dZ block
     std::vector<long long> halo((size_t)Cfg::HALO_BYTES / ESZ), dz((size_t)Cfg::DZ_BYTES / ESZ);
-    for (int t = 0; t < nk + 2; ++t) {        // the kernel prefetches two chunks beyond the reduction
+    for (int t = 0; t < nk + 3; ++t) {        // the kernel prefetches up to three chunks beyond the reduction
         const bool live = t < nk;
         const int k0 = kbeg + t * CH;
         const int img = live ? k0 / g.img_px : 0;
@@ -101,6 +101,10 @@ bool walk_tile(const GemmProb& p, const TileRef& tr, long long a_bytes, long lon
                 const unsigned soff = live ? (unsigned)k0 * (unsigned)(g.Cout * ESZ) : 0u;
                 ++w.loads;
                 if (!live) continue;                                   // empty descriptor: nothing is read
+                if (v >= CH * Cfg::VPP_A) {                            // a thread beyond the block: its load must be cut off
+                    if (off < 0x80000000u) return w.fail("a dZ load slot beyond the block touches memory");
+                    continue;
+                }
                 if (off >= 0x80000000u) return w.fail("dZ offset beyond the descriptor");
                 const long long byte = (long long)soff + off;
                 if (byte + 16 > a_bytes) return w.fail("dZ load leaves the output-gradient tensor");
@@ -122,8 +126,12 @@ bool walk_tile(const GemmProb& p, const TileRef& tr, long long a_bytes, long lon
             if (y < 0 || y >= g.H || xx < 0 || xx >= g.W) return ZERO;
             return (((long long)img * g.H + y) * g.W + xx) * g.Cin + c;
         };
-        for (int wave = 0; wave < WM * WN; ++wave) {
+        std::vector<int> tap_owners(9, 0);            // every tap of every channel block belongs to exactly one wave
+        for (int wave_id = 0; wave_id < WM * WN * TG; ++wave_id) {
+            const int tg = wave_id / (WM * WN), wave = wave_id % (WM * WN);
             const int wm = wave / WN, wn = wave % WN;
+            const int tap0 = tap_first<TG>(tg), ntap = tap_count<TG>(tg);
+            for (int t = tap0; t < tap0 + ntap; ++t) ++tap_owners[t];
             for (int lane = 0; lane < 64; ++lane) {
                 if (ESZ == 2) {
                     for (int kk = 0; kk < 4; ++kk)
@@ -140,8 +148,9 @@ bool walk_tile(const GemmProb& p, const TileRef& tr, long long a_bytes, long lon
                                     if (dz[(size_t)byte / 2] != want) return w.fail("dZ fragment holds the wrong element");
                                     ++w.frag_reads;
                                 }
-                                for (int u = 0; u < 3; ++u)
-                                    for (int v = 0; v < 3; ++v) {
+                                for (int tap = tap0; tap < tap0 + ntap; ++tap) {
+                                    const int u = tap / 3, v = tap % 3;
+                                    {
                                         const int slot = halo_slot(g, frag_pixel_bf16(src, kk, 0)) + r * 4 * STRIDE + halo_tap_slots(g, u, v);
                                         const int byte = slot * Cfg::PIXB_B + (wn * 32 + frag_channel_bf16(src)) * 2 + 2 * (l % 4);
                                         if (byte < 0 || byte + 2 > Cfg::HALO_BYTES) return w.fail("input fragment read leaves its LDS block");
@@ -149,6 +158,7 @@ bool walk_tile(const GemmProb& p, const TileRef& tr, long long a_bytes, long lon
                                         if (halo[(size_t)byte / 2] != want) return w.fail("input fragment holds the wrong element");
                                         ++w.frag_reads;
                                     }
+                                }
                             }
                 } else {
                     for (int k8 = 0; k8 < CH / 8; ++k8)
@@ -158,17 +168,21 @@ bool walk_tile(const GemmProb& p, const TileRef& tr, long long a_bytes, long lon
                             if (abyte < 0 || abyte + 4 > Cfg::DZ_BYTES) return w.fail("dZ fragment read leaves its LDS block");
                             if (dz[(size_t)abyte / 4] != (long long)(k0 + q) * g.Cout + o0 + wm * 32 + ch) return w.fail("dZ fragment holds the wrong element");
                             ++w.frag_reads;
-                            for (int u = 0; u < 3; ++u)
-                                for (int v = 0; v < 3; ++v) {
+                            for (int tap = tap0; tap < tap0 + ntap; ++tap) {
+                                const int u = tap / 3, v = tap % 3;
+                                {
                                     const int byte = (halo_slot(g, q) + halo_tap_slots(g, u, v)) * Cfg::PIXB_B + (wn * 32 + ch) * 4;
                                     if (byte < 0 || byte + 4 > Cfg::HALO_BYTES) return w.fail("input fragment read leaves its LDS block");
                                     if (halo[(size_t)byte / 4] != in_def(q, u, v, c0 + wn * 32 + ch)) return w.fail("input fragment holds the wrong element");
                                     ++w.frag_reads;
                                 }
+                            }
                         }
                 }
             }
         }
+        for (int t = 0; t < 9; ++t)
+            if (tap_owners[t] != WM * WN) return w.fail("a tap is not owned by exactly one wave per channel block");
     }
     return true;
 }
@@ -184,7 +198,7 @@ std::string conv_dw_halo_walk(bool bf16, bool wide, const GemmProb& p, const Til
     Walk w;
     const bool s1 = p.stride == 1;
     if (wide) {
-        if (bf16) s1 ? walk_tile<2, 2, 2, 1>(p, tr, a_bytes, b_bytes, every_chunk, w) : walk_tile<2, 2, 2, 2>(p, tr, a_bytes, b_bytes, every_chunk, w);
+        if (bf16) s1 ? walk_tile<2, 2, 2, 1, 2>(p, tr, a_bytes, b_bytes, every_chunk, w) : walk_tile<2, 2, 2, 2, 2>(p, tr, a_bytes, b_bytes, every_chunk, w);
         else s1 ? walk_tile<4, 2, 2, 1>(p, tr, a_bytes, b_bytes, every_chunk, w) : walk_tile<4, 2, 2, 2>(p, tr, a_bytes, b_bytes, every_chunk, w);
     } else if (!s1) {
         w.fail("there is no 32-channel form at stride 2");

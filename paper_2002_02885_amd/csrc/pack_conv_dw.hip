@@ -42,33 +42,22 @@ __device__ __forceinline__ void static_for(std::integer_sequence<int, Is...>, F&
     (f(std::integral_constant<int, Is>{}), ...);
 }
 
-template <typename T, int WM, int WN, int STRIDE>
-__global__ __launch_bounds__(64 * WM * WN) void conv_dw_halo_kernel(const GemmProb* __restrict__ probs,
-                                                                    const TileRef* __restrict__ tiles,
-                                                                    const void* __restrict__ x, char* __restrict__ ws, LrTable lr) {
+// The work of one wave; TGI: its tap group (compile-time, so that every accumulator index is static).
+template <typename T, int WM, int WN, int STRIDE, int TG, int TGI>
+__device__ __forceinline__ void conv_dw_halo_body(const GemmProb& p, const TileRef& tr, char* __restrict__ lds, const float lrk) {
     constexpr int ESZ = (int)sizeof(T);
-    typedef HaloCfg<ESZ, WM, WN, STRIDE> Cfg;
+    typedef HaloCfg<ESZ, WM, WN, STRIDE, TG> Cfg;
     constexpr int NT = Cfg::NT, CH = Cfg::CH, NLD = Cfg::NLD, NLA = Cfg::NLA, LOADS = NLD + NLA;
     constexpr int PIXB_A = Cfg::PIXB_A, PIXB_B = Cfg::PIXB_B;
-    __shared__ __attribute__((aligned(16))) char lds[Cfg::LDS_BYTES];
-
-    const TileRef tr = tiles[blockIdx.x];
-    if (tr.prob < 0) return;
-    GemmProb p = probs[tr.prob];
-    if (p.flags & F_B_INPUT) p.B = (const char*)x + p.x_off;
-    if (p.flags & F_WS) {   // partial sums of a split reduction go to the workspace this launch was given
-        p.C = ws + (size_t)p.C;
-        p.dbias = (float*)(ws + (size_t)p.dbias);
-    }
+    constexpr int TAP0 = tap_first<TG>(TGI), NTAP = tap_count<TG>(TGI);
     const HaloGeom g = halo_geom<ESZ, CH>(p);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) % (WM * WN);
     const int wm = wave / WN, wn = wave % WN;
     const int o0 = tr.tm * Cfg::CO_T, c0 = tr.tn * Cfg::CI_T;
     const int kbeg = tr.ks * p.ksplit;
     const int kend = min(p.Kd, kbeg + p.ksplit);
     const int nk = (kend - kbeg) / CH;
     const bool do_bias_grad = tr.tn == 0 && p.dbias != nullptr;
-    const float lrk = lr.lr[p.member];
 
     // what a thread loads per chunk, relative to the chunk's origin (fixed for the whole tile)
     unsigned hv[NLD], av[NLA];
@@ -80,7 +69,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_dw_halo_kernel(const GemmPr
     // Chunk t: the output gradient through a descriptor over the whole tensor, the chunk's position in
     // the scalar offset; the input through a descriptor over the ONE image the chunk lies in, so that a
     // halo row above or below the image is out of the descriptor's range and reads as zeros.  A chunk
-    // beyond the reduction (the pipeline always prefetches two ahead) gets empty descriptors.
+    // beyond the reduction (the pipeline always prefetches ahead) gets empty descriptors.
     auto issue = [&](int t, u32x4_t(&rh)[NLD], u32x4_t(&ra)[NLA]) {
         const int k0 = kbeg + t * CH;
         const bool live = t < nk;
@@ -114,19 +103,21 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_dw_halo_kernel(const GemmPr
             *reinterpret_cast<u32x4_t*>(hb + halo_lds_offset<Cfg>(tid + NT * i)) = rh[i];
         }
 #pragma unroll
-        for (int j = 0; j < NLA; ++j) *reinterpret_cast<u32x4_t*>(db + dz_lds_offset<Cfg>(tid + NT * j)) = ra[j];
+        for (int j = 0; j < NLA; ++j)
+            if (Cfg::CH * Cfg::VPP_A % NT == 0 || tid + NT * j < Cfg::CH * Cfg::VPP_A)
+                *reinterpret_cast<u32x4_t*>(db + dz_lds_offset<Cfg>(tid + NT * j)) = ra[j];
     };
 
-    f32x16_t acc[9];
+    f32x16_t acc[NTAP];
 #pragma unroll
-    for (int t = 0; t < 9; ++t)
+    for (int t = 0; t < NTAP; ++t)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
     // Bias gradient = sum of dZ over the pixels, in pixel order.  The waves of the first column of the wave
     // grid hold it: lane l < 32 of wave (wm, 0) owns output channel o0 + 32 * wm + l, and the values to add
     // are the ones the wave holds anyway as its dZ operand (see bias_step).
     float bias_grad = 0.f;
-    const bool bias_wave = do_bias_grad && wn == 0;
+    const bool bias_wave = do_bias_grad && wn == 0 && TGI == 0;
 
     // lane constants of the fragment reads
     int a_lane, b_lane;          // byte offset of the lane's channels inside a pixel of the dZ / halo block
@@ -144,28 +135,31 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_dw_halo_kernel(const GemmPr
 
     // One step of the reduction = sixteen pixels (bfloat16: one matrix instruction per tap) or eight (float:
     // four instructions per tap, instruction j pairing pixel j with pixel j + 4).  A chunk is a fixed
-    // sequence of NI matrix instructions, instruction idx = (step, j, tap).  With one wave per SIMD nothing
+    // sequence of NI matrix instructions, instruction idx = (step, j, tap of this wave's tap group).  With one wave per SIMD nothing
     // but the wave's own matrix instructions can hide the latency of its LDS reads, so the operands of
     // instruction idx + AHEAD are requested before instruction idx is issued (a ring of AHEAD + 1 operand
     // registers), and scheduling barriers keep the compiler from undoing that order.
-    constexpr int SUB = (ESZ == 2) ? 1 : 4, PER_STEP = SUB * 9, NI = 4 * PER_STEP;
-    constexpr int AHEAD = 6, RING = AHEAD + 1;
+    constexpr int SUB = (ESZ == 2) ? 1 : 4, PER_STEP = SUB * NTAP, NI = 4 * PER_STEP;
+    constexpr int AHEAD = (TG >= 3) ? 4 : 6, RING = AHEAD + 1;
     static_assert(CH == ((ESZ == 2) ? 64 : 32), "four steps per chunk");
     typedef short v8s_t __attribute__((ext_vector_type(8)));
-    v8s_t a16[2], b16[RING];       // bfloat16 operands: eight pixels per lane
-    float a32[2][4], b32[RING];    // float operands: one pixel per lane and instruction
+    // (the dZ operand of a step is shared by the step's taps and is requested with the first of them, up to
+    // AHEAD instructions early, i.e. possibly two steps ahead of the one being multiplied: a ring of three)
+    static_assert(AHEAD < 2 * PER_STEP, "the dZ operand ring holds three steps");
+    v8s_t a16[3], b16[RING];       // bfloat16 operands: eight pixels per lane
+    float a32[3][4], b32[RING];    // float operands: one pixel per lane and instruction
     const char* bp = nullptr;      // LDS address of the lane's tap (0, 0) operand of the (step, j) being read
     auto read_operands = [&](int buf, auto IDX) {
         constexpr int idx = decltype(IDX)::value;
-        constexpr int kk = idx / PER_STEP, j = (idx / 9) % SUB, tap = idx % 9, u = tap / 3, v = tap % 3;
+        constexpr int kk = idx / PER_STEP, j = (idx / NTAP) % SUB, t = idx % NTAP, tap = TAP0 + t, u = tap / 3, v = tap % 3;
         const char* const hb = lds + buf * (Cfg::HALO_BYTES + Cfg::DZ_BYTES);
         const char* const db = hb + Cfg::HALO_BYTES;
         if constexpr (ESZ == 2) {
-            if constexpr (tap == 0) {
+            if constexpr (t == 0) {
                 const char* ap = db + frag_pixel_bf16(lane, kk, 0) * PIXB_A + a_lane;
                 const v4s_t a_lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)ap);
                 const v4s_t a_hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(ap + 4 * PIXB_A));
-                a16[kk & 1] = __builtin_shufflevector(a_lo, a_hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                a16[kk % 3] = __builtin_shufflevector(a_lo, a_hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 bp = hb + b_slot[kk] * PIXB_B + b_lane;
             }
             const char* tp = bp + u * row_step + v * PIXB_B;
@@ -173,9 +167,9 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_dw_halo_kernel(const GemmPr
             const v4s_t b_hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(tp + 4 * STRIDE * PIXB_B));
             b16[idx % RING] = __builtin_shufflevector(b_lo, b_hi, 0, 1, 2, 3, 4, 5, 6, 7);
         } else {
-            if constexpr (tap == 0) {
+            if constexpr (t == 0) {
                 const int q = frag_pixel_f32(lane, kk, j);
-                a32[kk & 1][j] = *reinterpret_cast<const float*>(db + q * PIXB_A + a_lane);
+                a32[kk % 3][j] = *reinterpret_cast<const float*>(db + q * PIXB_A + a_lane);
                 bp = hb + halo_slot(g, q) * PIXB_B + b_lane;
             }
             b32[idx % RING] = *reinterpret_cast<const float*>(bp + u * row_step + v * PIXB_B);
@@ -183,12 +177,12 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_dw_halo_kernel(const GemmPr
     };
     auto multiply = [&](auto IDX) {
         constexpr int idx = decltype(IDX)::value;
-        constexpr int kk = idx / PER_STEP, j = (idx / 9) % SUB, tap = idx % 9;
+        constexpr int kk = idx / PER_STEP, j = (idx / NTAP) % SUB, t = idx % NTAP;
         if constexpr (ESZ == 2)
-            acc[tap] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a16[kk & 1]), __builtin_bit_cast(bf16x8_t, b16[idx % RING]),
-                                                               acc[tap], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a16[kk % 3]), __builtin_bit_cast(bf16x8_t, b16[idx % RING]),
+                                                             acc[t], 0, 0, 0);
         else
-            acc[tap] = __builtin_amdgcn_mfma_f32_32x32x2f32(a32[kk & 1][j], b32[idx % RING], acc[tap], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a32[kk % 3][j], b32[idx % RING], acc[t], 0, 0, 0);
     };
     // The pixels of a step in ascending order: lanes 0-31 hold the first half of them (eight, or four) for
     // their channel, lanes 32-63 the second half.  The running sum sits in the lower lanes, is carried to
@@ -209,42 +203,45 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_dw_halo_kernel(const GemmPr
         float s0 = bias_grad;
         if constexpr (ESZ == 2) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) s0 += bf2f((bf16_t)a16[kk & 1][e]);
+            for (int e = 0; e < 8; ++e) s0 += bf2f((bf16_t)a16[kk % 3][e]);
             float s1 = lower_to_upper(s0);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) s1 += bf2f((bf16_t)a16[kk & 1][e]);
+            for (int e = 0; e < 8; ++e) s1 += bf2f((bf16_t)a16[kk % 3][e]);
             bias_grad = upper_to_lower(s1);
         } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) s0 += a32[kk & 1][j];
+            for (int j = 0; j < 4; ++j) s0 += a32[kk % 3][j];
             float s1 = lower_to_upper(s0);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) s1 += a32[kk & 1][j];
+            for (int j = 0; j < 4; ++j) s1 += a32[kk % 3][j];
             bias_grad = upper_to_lower(s1);
         }
     };
 
-    // Two register stages and two LDS buffers, one barrier per chunk.  After the barrier of chunk `it`
+    // ST register stages and two LDS buffers, one barrier per chunk.  After the barrier of chunk `it`
     // (complete in its buffer; nobody reads the other buffer any more): the stage emptied by the previous
-    // chunk is refilled with the loads of chunk it + 2, the first step of chunk `it` is multiplied,
-    // chunk it + 1 (whose loads were requested a whole chunk ago) is stored to the other buffer under those
-    // matrix instructions, then the remaining steps.
-    u32x4_t rh[2][NLD], ra[2][NLA];
-    issue(0, rh[0], ra[0]);
-    __builtin_amdgcn_sched_barrier(0);
-    issue(1, rh[1], ra[1]);
-    __builtin_amdgcn_sched_barrier(0);
-    wait_loads<LOADS>();
+    // chunk is refilled with the loads of chunk it + ST, the first step of chunk `it` is multiplied, chunk
+    // it + 1 (whose loads were requested ST - 1 chunks ago: a chunk's worth of matrix instructions is shorter
+    // than the slowest of a chunk's loads takes to come back, which is what two stages ran into) is stored
+    // to the other buffer under those matrix instructions, then the remaining steps.
+    constexpr int ST = (TG >= 2 && STRIDE == 1) ? 3 : 2;   // (three stages of the larger stride-2 halo do not fit the register file)
+    u32x4_t rh[ST][NLD], ra[ST][NLA];
+#pragma unroll
+    for (int s = 0; s < ST; ++s) {
+        issue(s, rh[s], ra[s]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    wait_loads<(ST - 1) * LOADS>();
     pin_regs(rh[0]);
     pin_regs(ra[0]);
     stash(0, rh[0], ra[0]);
     using std::integral_constant;
-    auto chunk = [&](auto PAR, const int it) {
-        constexpr int par = decltype(PAR)::value;
+    auto chunk = [&](auto STG, auto PAR, const int it) {
+        constexpr int stg = decltype(STG)::value, par = decltype(PAR)::value, nxt = (stg + 1) % ST;
         __syncthreads();
         static_for(std::make_integer_sequence<int, AHEAD>{}, [&](auto I) { read_operands(par, I); });
         __builtin_amdgcn_sched_barrier(0);
-        issue(it + 2, rh[par], ra[par]);
+        issue(it + ST, rh[stg], ra[stg]);
         __builtin_amdgcn_sched_barrier(0);
         static_for(std::make_integer_sequence<int, NI>{}, [&](auto I) {
             constexpr int idx = decltype(I)::value;
@@ -253,27 +250,35 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_dw_halo_kernel(const GemmPr
             multiply(I);
             if constexpr (idx % PER_STEP == PER_STEP - 1) bias_step(integral_constant<int, idx / PER_STEP>{});
             if constexpr (idx == PER_STEP - 1) {
-                wait_loads<LOADS>();
-                pin_regs(rh[par ^ 1]);
-                pin_regs(ra[par ^ 1]);
-                stash(par ^ 1, rh[par ^ 1], ra[par ^ 1]);
+                wait_loads<(ST - 1) * LOADS>();
+                pin_regs(rh[nxt]);
+                pin_regs(ra[nxt]);
+                stash(par ^ 1, rh[nxt], ra[nxt]);
             }
             __builtin_amdgcn_sched_barrier(0);
         });
     };
+    // chunks run in groups of G (a multiple of the stage count and of the two buffers), so that stage and
+    // buffer of every chunk in the unrolled body are compile-time constants
+    constexpr int G = (ST % 2 == 0) ? ST : 2 * ST;
     int it = 0;
-    for (; it + 2 <= nk; it += 2) {
-        chunk(integral_constant<int, 0>{}, it);
-        chunk(integral_constant<int, 1>{}, it + 1);
-    }
-    if (it < nk) chunk(integral_constant<int, 0>{}, it);
+    for (; it + G <= nk; it += G)
+        static_for(std::make_integer_sequence<int, G>{}, [&](auto J) {
+            constexpr int j = decltype(J)::value;
+            chunk(integral_constant<int, j % ST>{}, integral_constant<int, j & 1>{}, it + j);
+        });
+    static_for(std::make_integer_sequence<int, G - 1>{}, [&](auto J) {
+        constexpr int j = decltype(J)::value;
+        if (it + j < nk) chunk(integral_constant<int, j % ST>{}, integral_constant<int, j & 1>{}, it + j);
+    });
     // the last chunks requested loads beyond the reduction (empty descriptors): they still target the
     // stage registers, which must not count as free before they have landed
     wait_loads<0>();
-    pin_regs(rh[0]);
-    pin_regs(ra[0]);
-    pin_regs(rh[1]);
-    pin_regs(ra[1]);
+#pragma unroll
+    for (int s = 0; s < ST; ++s) {
+        pin_regs(rh[s]);
+        pin_regs(ra[s]);
+    }
 
     // ---- epilogue ----
     // Accumulator register e of a wave's 32 x 32 block: output channel 8*(e/4) + 4*(lane/32) + e%4, input
@@ -288,13 +293,13 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_dw_halo_kernel(const GemmPr
     float* const gf = (float*)p.C + (size_t)tr.ks * p.split_stride;
     const int c = c0 + wn * 32 + (lane & 31);
 #pragma unroll
-    for (int t = 0; t < 9; ++t) {
+    for (int t = 0; t < NTAP; ++t) {
         float wv[16];
         size_t off[16];
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const int o = o0 + wm * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-            off[e] = (size_t)o * p.ldc + (size_t)t * g.Cin + c;
+            off[e] = (size_t)o * p.ldc + (size_t)(TAP0 + t) * g.Cin + c;
             if (upd) wv[e] = p.upd_w[off[e]];
         }
 #pragma unroll
@@ -310,9 +315,31 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_dw_halo_kernel(const GemmPr
     }
 }
 
-template <typename T, int WM, int WN, int STRIDE>
+template <typename T, int WM, int WN, int STRIDE, int TG>
+__global__ __launch_bounds__(64 * WM * WN * TG) void conv_dw_halo_kernel(const GemmProb* __restrict__ probs,
+                                                                         const TileRef* __restrict__ tiles,
+                                                                         const void* __restrict__ x, char* __restrict__ ws, LrTable lr) {
+    typedef HaloCfg<(int)sizeof(T), WM, WN, STRIDE, TG> Cfg;
+    __shared__ __attribute__((aligned(16))) char lds[Cfg::LDS_BYTES];
+    const TileRef tr = tiles[blockIdx.x];
+    if (tr.prob < 0) return;
+    GemmProb p = probs[tr.prob];
+    if (p.flags & F_B_INPUT) p.B = (const char*)x + p.x_off;
+    if (p.flags & F_WS) {   // partial sums of a split reduction go to the workspace this launch was given
+        p.C = ws + (size_t)p.C;
+        p.dbias = (float*)(ws + (size_t)p.dbias);
+    }
+    const float lrk = lr.lr[p.member];
+    // the waves of a tap group run the same instruction sequence (same number of barriers in both groups)
+    const int tg = (int)(threadIdx.x >> 6) / (WM * WN);
+    if (TG == 1 || tg == 0) conv_dw_halo_body<T, WM, WN, STRIDE, TG, 0>(p, tr, lds, lrk);
+    else if (TG == 2 || tg == 1) conv_dw_halo_body<T, WM, WN, STRIDE, TG, (TG > 1 ? 1 : 0)>(p, tr, lds, lrk);
+    else conv_dw_halo_body<T, WM, WN, STRIDE, TG, (TG > 2 ? 2 : 0)>(p, tr, lds, lrk);
+}
+
+template <typename T, int WM, int WN, int STRIDE, int TG>
 static hipError_t launch_halo(const GemmProb* probs, const TileRef* tiles, int n, const void* x, char* ws, const LrTable& lr, hipStream_t st) {
-    hipLaunchKernelGGL((conv_dw_halo_kernel<T, WM, WN, STRIDE>), dim3(n), dim3(64 * WM * WN), 0, st, probs, tiles, x, ws, lr);
+    hipLaunchKernelGGL((conv_dw_halo_kernel<T, WM, WN, STRIDE, TG>), dim3(n), dim3(64 * WM * WN * TG), 0, st, probs, tiles, x, ws, lr);
     return hipGetLastError();
 }
 
@@ -321,11 +348,11 @@ hipError_t launch_conv_dw_halo(bool bf16, int tile_cfg, const GemmProb* probs, c
     if (n <= 0) return hipSuccess;
     switch (tile_cfg) {
         case GEMM_CFG_HALO_S1:
-            return bf16 ? launch_halo<bf16_t, 2, 2, 1>(probs, tiles, n, x, ws, lr, st) : launch_halo<float, 2, 2, 1>(probs, tiles, n, x, ws, lr, st);
+            return bf16 ? launch_halo<bf16_t, 2, 2, 1, 2>(probs, tiles, n, x, ws, lr, st) : launch_halo<float, 2, 2, 1, 1>(probs, tiles, n, x, ws, lr, st);
         case GEMM_CFG_HALO_S2:
-            return bf16 ? launch_halo<bf16_t, 2, 2, 2>(probs, tiles, n, x, ws, lr, st) : launch_halo<float, 2, 2, 2>(probs, tiles, n, x, ws, lr, st);
+            return bf16 ? launch_halo<bf16_t, 2, 2, 2, 2>(probs, tiles, n, x, ws, lr, st) : launch_halo<float, 2, 2, 2, 1>(probs, tiles, n, x, ws, lr, st);
         case GEMM_CFG_HALO32_S1:
-            return bf16 ? launch_halo<bf16_t, 2, 1, 1>(probs, tiles, n, x, ws, lr, st) : launch_halo<float, 2, 1, 1>(probs, tiles, n, x, ws, lr, st);
+            return bf16 ? launch_halo<bf16_t, 2, 1, 1, 1>(probs, tiles, n, x, ws, lr, st) : launch_halo<float, 2, 1, 1, 1>(probs, tiles, n, x, ws, lr, st);
         default: return hipErrorInvalidValue;   // (no 32-channel form at stride 2: its load stages do not fit the register file)
     }
 }
@@ -335,7 +362,7 @@ int conv_dw_halo_cfg(bool bf16, const GemmProb& p) {
     const bool s1 = p.stride == 1;
     bool wide, narrow;
     if (bf16) {
-        wide = s1 ? halo_supported<HaloCfg<2, 2, 2, 1>, 2>(p) : halo_supported<HaloCfg<2, 2, 2, 2>, 2>(p);
+        wide = s1 ? halo_supported<HaloCfg<2, 2, 2, 1, 2>, 2>(p) : halo_supported<HaloCfg<2, 2, 2, 2, 2>, 2>(p);
         narrow = s1 && halo_supported<HaloCfg<2, 2, 1, 1>, 2>(p);
     } else {
         wide = s1 ? halo_supported<HaloCfg<4, 2, 2, 1>, 4>(p) : halo_supported<HaloCfg<4, 2, 2, 2>, 4>(p);
