@@ -604,6 +604,21 @@ void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<G
             if (!halo[c].empty()) emit_gemm_launch(p, db, mode, GEMM_CFG_HALO_S1 + c, halo[c]);
         probs.swap(rest);
     }
+    if ((mode == CONV_FWD || mode == CONV_DX) && !std::getenv("PACK_NO_HALO_ROWS")) {
+        // stride-1 convolutions whose shape allows it take the halo form of the forward pass and input gradient
+        // (the pixels a tile's taps reach staged once per block of channels).  Whether a problem does depends on
+        // its own shape only, so a member's bits do not depend on who else is in the pack.
+        // PACK_NO_HALO_ROWS keeps them on the staged-tile form, for the test that compares the two.
+        std::vector<GemmProb> rows[2], rest;
+        for (const GemmProb& g : probs) {
+            const int cfg = conv_rows_halo_cfg(p->bf16, mode, g);
+            if (cfg >= 0) rows[cfg - GEMM_CFG_ROWS64].push_back(g);
+            else rest.push_back(g);
+        }
+        for (int c = 0; c < 2; ++c)
+            if (!rows[c].empty()) emit_gemm_launch(p, db, mode, GEMM_CFG_ROWS64 + c, rows[c]);
+        probs.swap(rest);
+    }
     if (probs.empty()) return;
     // The tile shape only partitions the output; the summation order of an element does not
     // depend on it, so a member's bits do not depend on who else is in the launch.  Each problem

@@ -23,20 +23,6 @@ namespace packk {
 typedef short v4s_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) v4s_t* lds_v4s_ptr;
 
-template <int N>
-__device__ __forceinline__ void pin_regs(u32x4_t (&r)[N]) {
-    // makes every register of a load stage an operand of a statement that sits after the wait, so that
-    // nothing that reads them can be moved above it (the loads themselves are assembly statements whose
-    // completion the compiler does not track)
-#pragma unroll
-    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(r[i]));
-}
-template <int NEWER>
-__device__ __forceinline__ void wait_loads() {
-    static_assert(NEWER >= 0 && NEWER < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NEWER) : "memory");
-}
-
 template <int... Is, typename F>
 __device__ __forceinline__ void static_for(std::integer_sequence<int, Is...>, F&& f) {
     (f(std::integral_constant<int, Is>{}), ...);
@@ -267,10 +253,18 @@ __device__ __forceinline__ void conv_dw_halo_body(const GemmProb& p, const TileR
             constexpr int j = decltype(J)::value;
             chunk(integral_constant<int, j % ST>{}, integral_constant<int, j & 1>{}, it + j);
         });
-    static_for(std::make_integer_sequence<int, G - 1>{}, [&](auto J) {
+    // (the remaining chunks as nested conditions: chunk j + 1 only after chunk j, so that no path through
+    // the code skips a chunk and runs a later one with the stages out of step)
+    auto rest = [&](auto self, auto J) -> void {
         constexpr int j = decltype(J)::value;
-        if (it + j < nk) chunk(integral_constant<int, j % ST>{}, integral_constant<int, j & 1>{}, it + j);
-    });
+        if constexpr (j < G - 1) {
+            if (it + j < nk) {
+                chunk(integral_constant<int, j % ST>{}, integral_constant<int, j & 1>{}, it + j);
+                self(self, integral_constant<int, j + 1>{});
+            }
+        }
+    };
+    rest(rest, integral_constant<int, 0>{});
     // the last chunks requested loads beyond the reduction (empty descriptors): they still target the
     // stage registers, which must not count as free before they have landed
     wait_loads<0>();

@@ -102,6 +102,20 @@ __device__ __forceinline__ void wait_stage(u32x4_t (&regs)[N]) {
     else static_assert(N == 1 || N == 2 || N == 4 || N == 8, "unsupported register count");
 }
 
+template <int N>
+__device__ __forceinline__ void pin_regs(u32x4_t (&r)[N]) {
+    // makes every register of a load stage an operand of a statement that sits after the wait, so that
+    // nothing that reads them can be moved above it (the loads themselves are assembly statements whose
+    // completion the compiler does not track)
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(r[i]));
+}
+template <int NEWER>
+__device__ __forceinline__ void wait_loads() {
+    static_assert(NEWER >= 0 && NEWER < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NEWER) : "memory");
+}
+
 // the SGD update of one parameter; every path that applies it (update kernels, fused epilogues)
 // uses this one expression so that a member's bits do not depend on which path its pack takes
 __device__ __forceinline__ float sgd_apply(float w, float g, float lr) { return __builtin_fmaf(-lr, g, w); }

@@ -165,6 +165,9 @@ hipError_t launch_conv_dw_halo(bool bf16, int tile_cfg, const GemmProb* probs_de
                                const void* x_dev, char* ws, const LrTable& lr, hipStream_t st);
 // the halo configuration (GEMM_CFG_HALO*) problem p can take, or -1
 int conv_dw_halo_cfg(bool bf16, const GemmProb& p);
+// the halo configuration (GEMM_CFG_ROWS*) a stride-1 convolution forward (mode CONV_FWD) or input-gradient (CONV_DX)
+// problem can take, or -1
+int conv_rows_halo_cfg(bool bf16, int mode, const GemmProb& p);
 hipError_t launch_reduce(const ReduceProb* probs_dev, const int2* map_dev, int n_blocks, const char* ws, const LrTable& lr, hipStream_t st);
 // The library's own scratch array (file-scope device memory, STATIC_SCRATCH_BYTES long, one copy per GPU):
 // its address on the current device.  For the entry point that may not allocate.
@@ -200,8 +203,8 @@ hipError_t launch_gather_rows(const void* data, const int32_t* labels_all, const
 // 6, 7: the halo form of the convolution weight gradient (stride 1, stride 2): a tile is 64 output channels
 // x 64 input channels x all nine taps, i.e. 64 x 576 of the [Cout][9 * Cin] gradient
 // 8: the same with 32 input channels per tile (layers whose input channels are a multiple of 32 only; stride 1)
-constexpr int GEMM_TILE_M[9] = {128, 128, 64, 64, 128, 128, 64, 64, 64};
-constexpr int GEMM_TILE_N[9] = {128, 64, 64, 64, 128, 64, 576, 576, 288};
+constexpr int GEMM_TILE_M[11] = {128, 128, 64, 64, 128, 128, 64, 64, 64, 256, 256};
+constexpr int GEMM_TILE_N[11] = {128, 64, 64, 64, 128, 64, 576, 576, 288, 64, 32};
 constexpr int GEMM_CFG_SCALAR = 3;
 constexpr int GEMM_CFG_LEAN = 4;     // weight gradients, 128 x 128, short reductions
 constexpr int GEMM_CFG_LEAN64 = 5;   // forward / input gradients, 128 x 64, short reductions
@@ -209,6 +212,9 @@ constexpr int GEMM_CFG_HALO_S1 = 6;  // convolution weight gradients, halo form,
 constexpr int GEMM_CFG_HALO_S2 = 7;  // likewise, stride 2
 constexpr int GEMM_CFG_HALO32_S1 = 8;   // 64 x 32 channel pairs per tile, stride 1
 inline bool is_halo_cfg(int cfg) { return cfg >= GEMM_CFG_HALO_S1 && cfg <= GEMM_CFG_HALO32_S1; }
+constexpr int GEMM_CFG_ROWS64 = 9;   // stride-1 convolution forward / input gradient, halo form, 256 pixels x 64 columns
+constexpr int GEMM_CFG_ROWS32 = 10;  // likewise, 256 pixels x 32 columns
+inline bool is_rows_cfg(int cfg) { return cfg == GEMM_CFG_ROWS64 || cfg == GEMM_CFG_ROWS32; }
 constexpr int ELEMWISE_PER_BLOCK = 2048;   // elements one block of the elementwise kernels covers
 constexpr int SGD_PER_BLOCK = 2048;        // parameters one block of the update kernel covers (measured best of 1024..8192)
 

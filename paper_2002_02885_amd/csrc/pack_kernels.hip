@@ -16,6 +16,7 @@
 // other members share the pack (the isolation guarantee of Section 2.2).
 #include "pack_internal.h"
 #include "pack_device.h"
+#include "conv_rows_halo.h"
 
 #include <type_traits>
 #include <utility>
@@ -651,6 +652,195 @@ struct LdsBytes {
     static constexpr size_t value = (LEAN && !IS_DW && staging > operands) ? staging : operands;
 };
 
+// The tail of a forward or input-gradient tile, shared by the staged-tile and the halo kernels.  The
+// accumulators lie in LDS as fp32 (`stage`, BM rows of SLD floats), so that global memory is touched with
+// 16-byte vectors along rows: bias, residual / mask source and previous value are read and the result is
+// written as full vectors.  256 threads; bias_v: the forward bias of the thread's eight columns (vector form).
+template <int MODE, typename T, int BM, int BN>
+__device__ __forceinline__ void finish_tile(const GemmProb& p, const int row0, const int col0, float (*stage)[BN + 8],
+                                            const float (&bias_v)[8], const bool vec_out) {
+    constexpr bool IS_DW = false;   // (weight-gradient tiles have a tail of their own)
+    constexpr bool IS_FWD = (MODE == LIN_FWD || MODE == CONV_FWD);
+    const bool out_f32 = IS_FWD && (p.flags & F_OUT_F32);
+    // element-wise tail of one output element; `v` comes from the staging tile
+    auto finish = [&](float v, int row, int col, size_t off) -> float {
+        if constexpr (IS_FWD) {
+            v += p.bias[col];
+            if (p.flags & F_RES_ID) v += ET<T>::to_f(((const T*)p.aux)[off]);
+            if (p.flags & F_RES_DOWN) {
+                if (col < p.resC) {
+                    int bb, i, j;
+                    decode_row(p, row, bb, i, j);
+                    v += ET<T>::to_f(((const T*)p.aux)[((size_t)(bb * p.resH + 2 * i) * p.resW + 2 * j) * p.resC + col]);
+                }
+            }
+            if (p.flags & F_RELU) v = fmaxf(v, 0.f);
+            else if (p.act > ACT_RELU) v = act_apply(p.act, v);
+        } else if constexpr (!IS_DW) {
+            if (p.flags & (F_SC_ID | F_SC_DOWN)) {
+                const long long so = shortcut_row(p, row);
+                if (so >= 0) v += ET<T>::to_f(((const T*)p.sc)[so + col]);
+            }
+            if (p.flags & F_MASK) {
+                const float a = ET<T>::to_f(((const T*)p.aux)[off]);
+                if (p.mask_act == ACT_RELU) { if (!(a > 0.f)) v = 0.f; }
+                else v *= act_deriv(p.mask_act, a);
+            }
+            if (p.flags & F_ACCUM) v += ET<T>::to_f(((const T*)p.C)[off]);
+        }
+        return v;
+    };
+    float* const cf = (float*)p.C;
+
+    // vector form: 8 consecutive columns per thread (two 16-byte LDS reads); needs aligned rows.
+    // A thread keeps its column group for all its rows.  What the tail reads from global memory
+    // (shortcut source, mask source, previous value) is requested for a batch of rows before any
+    // of it is used, so a batch costs one round trip instead of one per row.
+    if (vec_out) {
+        constexpr int GROUPS = BN / 8, NIT = BM * GROUPS / 256, RSTEP = 256 / GROUPS;
+        constexpr int BATCH = (NIT < 4) ? NIT : 4;
+        static_assert(256 % GROUPS == 0 && NIT % BATCH == 0, "tile shape");
+        const int lc = (threadIdx.x % GROUPS) * 8, lr0 = threadIdx.x / GROUPS;
+        const int col = col0 + lc;
+        const bool full = col + 8 <= p.Q;
+        typedef typename std::conditional<sizeof(T) == 2, u32x4_t, f32x4_t>::type ev_t;   // 8 bf16 or 4 floats
+        constexpr int EV = (sizeof(T) == 2) ? 1 : 2;   // vectors per 8 elements
+        if (col < p.Q) {
+#pragma unroll 1
+            for (int n0 = 0; n0 < NIT; n0 += BATCH) {
+                size_t off[BATCH];
+                bool live[BATCH];
+                ev_t auxv[BATCH][EV], oldv[BATCH][EV];
+#pragma unroll
+                for (int n = 0; n < BATCH; ++n) {
+                    const int row = row0 + lr0 + (n0 + n) * RSTEP;
+                    live[n] = row < p.R;
+                    off[n] = out_row_base(p, live[n] ? row : row0) + col;
+                    const T* ap = nullptr;
+                    const T* op = nullptr;
+                    if (live[n] && full) {
+                        if constexpr (IS_FWD) {
+                            if (p.flags & F_RES_ID) {
+                                ap = (const T*)p.aux + off[n];
+                            } else if ((p.flags & F_RES_DOWN) && col < p.resC) {
+                                int bb, i, j;
+                                decode_row(p, row, bb, i, j);
+                                ap = (const T*)p.aux + ((size_t)(bb * p.resH + 2 * i) * p.resW + 2 * j) * p.resC + col;
+                            }
+                        } else if constexpr (!IS_DW) {
+                            if (p.flags & F_MASK) ap = (const T*)p.aux + off[n];
+                            if (p.flags & F_ACCUM) op = (const T*)p.C + off[n];
+                            if (p.flags & (F_SC_ID | F_SC_DOWN)) {   // never together with F_ACCUM
+                                const long long so = shortcut_row(p, row);
+                                if (so >= 0) op = (const T*)p.sc + so + col;
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int h = 0; h < EV; ++h) {
+                        // absent source: zeros for the shortcut and the previous value, ones for the mask
+                        const float fill = (!IS_FWD && !IS_DW) ? 1.f : 0.f;
+                        ev_t fz;
+                        if constexpr (sizeof(T) == 2) fz = u32x4_t{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+                        else fz = f32x4_t{fill, fill, fill, fill};
+                        if constexpr (sizeof(T) == 2) { if (IS_FWD) fz = u32x4_t{0u, 0u, 0u, 0u}; }
+                        auxv[n][h] = ap ? *reinterpret_cast<const ev_t*>(ap + h * 4) : fz;
+                        ev_t oz;
+                        if constexpr (sizeof(T) == 2) oz = u32x4_t{0u, 0u, 0u, 0u};
+                        else oz = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                        oldv[n][h] = op ? *reinterpret_cast<const ev_t*>(op + h * 4) : oz;
+                    }
+                }
+#pragma unroll
+                for (int n = 0; n < BATCH; ++n) {
+                    if (!live[n]) continue;
+                    const int lr = lr0 + (n0 + n) * RSTEP;
+                    const int row = row0 + lr;
+                    float v[8];
+                    {
+                        const f32x4_t s0 = *reinterpret_cast<const f32x4_t*>(&stage[lr][lc]);
+                        const f32x4_t s1 = *reinterpret_cast<const f32x4_t*>(&stage[lr][lc + 4]);
+                        v[0] = s0.x; v[1] = s0.y; v[2] = s0.z; v[3] = s0.w;
+                        v[4] = s1.x; v[5] = s1.y; v[6] = s1.z; v[7] = s1.w;
+                    }
+                    if (!full) {   // ragged right edge: element by element
+                        for (int e = 0; e < 8 && col + e < p.Q; ++e) {
+                            const float r = finish(v[e], row, col + e, off[n] + e);
+                            if (out_f32) cf[off[n] + e] = r;
+                            else ((T*)p.C)[off[n] + e] = ET<T>::from_f(r);
+                        }
+                        continue;
+                    }
+                    float ax[8], old[8];
+                    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            ax[2 * d] = __uint_as_float(auxv[n][0][d] << 16); ax[2 * d + 1] = __uint_as_float(auxv[n][0][d] & 0xffff0000u);
+                            old[2 * d] = __uint_as_float(oldv[n][0][d] << 16); old[2 * d + 1] = __uint_as_float(oldv[n][0][d] & 0xffff0000u);
+                        }
+                    } else {
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            ax[d] = auxv[n][0][d]; ax[4 + d] = auxv[n][EV - 1][d];
+                            old[d] = oldv[n][0][d]; old[4 + d] = oldv[n][EV - 1][d];
+                        }
+                    }
+                    if constexpr (IS_FWD) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = (v[e] + bias_v[e]) + ax[e];
+                        if (p.flags & F_RELU) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+                        } else if (p.act > ACT_RELU) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[e] = act_apply(p.act, v[e]);
+                        }
+                    } else if constexpr (!IS_DW) {
+                        const bool accum = (p.flags & F_ACCUM) != 0;
+                        if (p.flags & (F_SC_ID | F_SC_DOWN)) {   // the shortcut's share joins before the mask
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[e] += old[e];
+                        }
+                        if (!(p.flags & F_MASK) || p.mask_act == ACT_RELU) {   // absent mask source reads as ones
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (!(ax[e] > 0.f)) v[e] = 0.f;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[e] *= act_deriv(p.mask_act, ax[e]);
+                        }
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (accum) v[e] += old[e];
+                    }
+                    if (out_f32) {
+                        *reinterpret_cast<f32x4_t*>(cf + off[n]) = f32x4_t{v[0], v[1], v[2], v[3]};
+                        *reinterpret_cast<f32x4_t*>(cf + off[n] + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
+                    } else if constexpr (sizeof(T) == 2) {
+                        u32x4_t o;
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) o[d] = pack2bf(v[2 * d], v[2 * d + 1]);
+                        *reinterpret_cast<u32x4_t*>((T*)p.C + off[n]) = o;
+                    } else {
+                        *reinterpret_cast<f32x4_t*>((float*)p.C + off[n]) = f32x4_t{v[0], v[1], v[2], v[3]};
+                        *reinterpret_cast<f32x4_t*>((float*)p.C + off[n] + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
+                    }
+                }
+            }
+        }
+    } else {
+        for (int idx = threadIdx.x; idx < BM * BN; idx += 256) {
+            const int lr = idx / BN, lc = idx % BN;
+            const int row = row0 + lr, col = col0 + lc;
+            if (row >= p.R || col >= p.Q) continue;
+            const size_t off = out_row_base(p, row) + col;
+            const float r = finish(stage[lr][lc], row, col, off);
+            if (out_f32) cf[off] = r;
+            else ((T*)p.C)[off] = ET<T>::from_f(r);
+        }
+    }
+}
+
 template <int MODE, typename T, int BM, int BN, int BKM, bool VEC, bool LEAN = false>
 __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, T* __restrict__ As_, T* __restrict__ Bs_, float lrk) {
     constexpr int V = ET<T>::V, BK = ET<T>::BK * BKM;
@@ -876,10 +1066,18 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
             constexpr int j = decltype(J)::value;
             chunk(integral_constant<int, j % ST>{}, integral_constant<int, j & 1>{}, it0 + j);
         });
-    for_each_stage(std::make_integer_sequence<int, G - 1>{}, [&](auto J) {
+    // (the remaining chunks as nested conditions: chunk j + 1 only after chunk j, so that no path through
+    // the code skips a chunk and runs a later one with the stages out of step)
+    auto rest = [&](auto self, auto J) -> void {
         constexpr int j = decltype(J)::value;
-        if (it0 + j < nk) chunk(integral_constant<int, j % ST>{}, integral_constant<int, j & 1>{}, it0 + j);
-    });
+        if constexpr (j < G - 1) {
+            if (it0 + j < nk) {
+                chunk(integral_constant<int, j % ST>{}, integral_constant<int, j & 1>{}, it0 + j);
+                self(self, integral_constant<int, j + 1>{});
+            }
+        }
+    };
+    rest(rest, integral_constant<int, 0>{});
     if constexpr (VEC) {
         // The last chunks prefetched beyond the reduction (reads of the zeros block).
         // Those loads are invisible to the compiler and still target the stage registers, which
@@ -1037,185 +1235,184 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
         return;
     }
 
-    constexpr bool IS_FWD = (MODE == LIN_FWD || MODE == CONV_FWD);
-    const bool out_f32 = IS_FWD && (p.flags & F_OUT_F32);
-    // element-wise tail of one output element; `v` comes from the staging tile
-    auto finish = [&](float v, int row, int col, size_t off) -> float {
-        if constexpr (IS_FWD) {
-            v += p.bias[col];
-            if (p.flags & F_RES_ID) v += ET<T>::to_f(((const T*)p.aux)[off]);
-            if (p.flags & F_RES_DOWN) {
-                if (col < p.resC) {
-                    int bb, i, j;
-                    decode_row(p, row, bb, i, j);
-                    v += ET<T>::to_f(((const T*)p.aux)[((size_t)(bb * p.resH + 2 * i) * p.resW + 2 * j) * p.resC + col]);
-                }
-            }
-            if (p.flags & F_RELU) v = fmaxf(v, 0.f);
-            else if (p.act > ACT_RELU) v = act_apply(p.act, v);
-        } else if constexpr (!IS_DW) {
-            if (p.flags & (F_SC_ID | F_SC_DOWN)) {
-                const long long so = shortcut_row(p, row);
-                if (so >= 0) v += ET<T>::to_f(((const T*)p.sc)[so + col]);
-            }
-            if (p.flags & F_MASK) {
-                const float a = ET<T>::to_f(((const T*)p.aux)[off]);
-                if (p.mask_act == ACT_RELU) { if (!(a > 0.f)) v = 0.f; }
-                else v *= act_deriv(p.mask_act, a);
-            }
-            if (p.flags & F_ACCUM) v += ET<T>::to_f(((const T*)p.C)[off]);
-        }
-        return v;
-    };
-    float* const cf = (float*)p.C;
+    if constexpr (!IS_DW) finish_tile<MODE, T, BM, BN>(p, row0, col0, stage, bias_v, vec_out);
+}
 
-    // vector form: 8 consecutive columns per thread (two 16-byte LDS reads); needs aligned rows.
-    // A thread keeps its column group for all its rows.  What the tail reads from global memory
-    // (shortcut source, mask source, previous value) is requested for a batch of rows before any
-    // of it is used, so a batch costs one round trip instead of one per row.
-    if (vec_out) {
-        constexpr int GROUPS = BN / 8, NIT = BM * GROUPS / 256, RSTEP = 256 / GROUPS;
-        constexpr int BATCH = (NIT < 4) ? NIT : 4;
-        static_assert(256 % GROUPS == 0 && NIT % BATCH == 0, "tile shape");
-        const int lc = (threadIdx.x % GROUPS) * 8, lr0 = threadIdx.x / GROUPS;
-        const int col = col0 + lc;
-        const bool full = col + 8 <= p.Q;
-        typedef typename std::conditional<sizeof(T) == 2, u32x4_t, f32x4_t>::type ev_t;   // 8 bf16 or 4 floats
-        constexpr int EV = (sizeof(T) == 2) ? 1 : 2;   // vectors per 8 elements
-        if (col < p.Q) {
-#pragma unroll 1
-            for (int n0 = 0; n0 < NIT; n0 += BATCH) {
-                size_t off[BATCH];
-                bool live[BATCH];
-                ev_t auxv[BATCH][EV], oldv[BATCH][EV];
+// ------------------------------------------------------------------------------------------------
+// Halo form of the stride-1 convolution forward pass and input gradient (address rules: conv_rows_halo.h).
+//
+// The staged-tile form gathers the pixel operand again for every tap: nine times the tile's pixels cross
+// the L2 -> LDS path per block of channels, and those launches run at the rate the L2 delivers, not the
+// matrix cores'.  Here the pixels a tile's nine taps can reach lie in LDS once per block of channels, as
+// they lie in memory, and a tap is a shift of the fragment reads' pixel slot.  The weight operand is
+// staged per (channel block, tap) exactly as in the staged-tile form (same fetcher, two LDS buffers, two
+// register stages, one barrier per tap).  The reduction runs channel block by channel block and tap by tap
+// inside a block; with a single channel block that is the staged-tile form's order, and the bits are the same.
+// ------------------------------------------------------------------------------------------------
+template <int MODE, typename T, int WM, int WN, int TN>
+__global__ __launch_bounds__(256, 2) void conv_rows_halo_kernel(const GemmProb* __restrict__ probs, const TileRef* __restrict__ tiles,
+                                                               const void* __restrict__ x) {
+    static_assert(MODE == CONV_FWD || MODE == CONV_DX, "rows are pixels");
+    constexpr int ESZ = (int)sizeof(T);
+    typedef RowsCfg<ESZ, WM, WN, TN> Cfg;
+    constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::CB, V = ET<T>::V, TM = 2, NLD = Cfg::NLD, PIXB = Cfg::PIXB;
+    static_assert(BK == ET<T>::BK, "a channel block is one chunk of the weight operand");
+    typedef TileGeom<T, BN, BK> GB;
+    constexpr size_t B_BYTES = (size_t)BN * GB::LDS_LD * ESZ, OPERANDS = Cfg::HALO_BYTES + 2 * B_BYTES, STAGING = (size_t)BM * (BN + 8) * 4;
+    constexpr size_t LDS_BYTES = OPERANDS > STAGING ? OPERANDS : STAGING;
+    static_assert(2 * LDS_BYTES <= 160 * 1024, "two workgroups per compute unit");
+    static_assert(GB::LDS_LD * ESZ == PIXB, "both operands: 128 bytes of reduction indices per row plus 16");
+    __shared__ __attribute__((aligned(16))) char lds[LDS_BYTES];
+
+    const TileRef tr = tiles[blockIdx.x];
+    if (tr.prob < 0) return;
+    GemmProb p = probs[tr.prob];
+    const void* const xin = (const char*)x + p.x_off;
+    if (p.flags & F_A_INPUT) p.A = xin;
+    if (p.flags & F_AUX_INPUT) p.aux = xin;
+
+    const RowsGeom g = rows_geom<BM>(p, MODE == CONV_DX);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int row0 = tr.tm * BM, col0 = tr.tn * BN;
+    const int ncb = g.SC / BK, nq = 9 * ncb;
+
+    char* const halo = lds;
+    T(*Bs)[BN][GB::LDS_LD] = reinterpret_cast<T(*)[BN][GB::LDS_LD]>(lds + Cfg::HALO_BYTES);
+
+    // the pixel operand: a descriptor over the images of this tile, so that nothing outside them can be read
+    int b0, y0;
+    rows_tile_origin<BM>(p, g, tr.tm, b0, y0);
+    const long long img_bytes = (long long)g.SH * g.SW * g.SC * ESZ;
+    i32x4_t rs;
+    {
+        const unsigned long long base = (unsigned long long)p.A + (unsigned long long)b0 * (unsigned long long)img_bytes;
+        rs.x = __builtin_amdgcn_readfirstlane((int)(unsigned)base);
+        rs.y = __builtin_amdgcn_readfirstlane((int)(unsigned)(base >> 32));
+        rs.z = __builtin_amdgcn_readfirstlane((int)(g.nimg * img_bytes));
+        rs.w = 0x00020000;
+    }
+    unsigned hv[NLD];
 #pragma unroll
-                for (int n = 0; n < BATCH; ++n) {
-                    const int row = row0 + lr0 + (n0 + n) * RSTEP;
-                    live[n] = row < p.R;
-                    off[n] = out_row_base(p, live[n] ? row : row0) + col;
-                    const T* ap = nullptr;
-                    const T* op = nullptr;
-                    if (live[n] && full) {
-                        if constexpr (IS_FWD) {
-                            if (p.flags & F_RES_ID) {
-                                ap = (const T*)p.aux + off[n];
-                            } else if ((p.flags & F_RES_DOWN) && col < p.resC) {
-                                int bb, i, j;
-                                decode_row(p, row, bb, i, j);
-                                ap = (const T*)p.aux + ((size_t)(bb * p.resH + 2 * i) * p.resW + 2 * j) * p.resC + col;
-                            }
-                        } else if constexpr (!IS_DW) {
-                            if (p.flags & F_MASK) ap = (const T*)p.aux + off[n];
-                            if (p.flags & F_ACCUM) op = (const T*)p.C + off[n];
-                            if (p.flags & (F_SC_ID | F_SC_DOWN)) {   // never together with F_ACCUM
-                                const long long so = shortcut_row(p, row);
-                                if (so >= 0) op = (const T*)p.sc + so + col;
-                            }
-                        }
-                    }
+    for (int i = 0; i < NLD; ++i) hv[i] = rows_vec_offset<Cfg, ESZ>(g, y0, tid + 256 * i);
+    // channel block cb of the halo: global -> registers -> LDS (all of it before anything else goes on)
+    auto load_halo = [&](int cb) {
+        u32x4_t r[NLD];
 #pragma unroll
-                    for (int h = 0; h < EV; ++h) {
-                        // absent source: zeros for the shortcut and the previous value, ones for the mask
-                        const float fill = (!IS_FWD && !IS_DW) ? 1.f : 0.f;
-                        ev_t fz;
-                        if constexpr (sizeof(T) == 2) fz = u32x4_t{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
-                        else fz = f32x4_t{fill, fill, fill, fill};
-                        if constexpr (sizeof(T) == 2) { if (IS_FWD) fz = u32x4_t{0u, 0u, 0u, 0u}; }
-                        auxv[n][h] = ap ? *reinterpret_cast<const ev_t*>(ap + h * 4) : fz;
-                        ev_t oz;
-                        if constexpr (sizeof(T) == 2) oz = u32x4_t{0u, 0u, 0u, 0u};
-                        else oz = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                        oldv[n][h] = op ? *reinterpret_cast<const ev_t*>(op + h * 4) : oz;
-                    }
-                }
+        for (int i = 0; i < NLD; ++i) r[i] = buf_load16(rs, hv[i], (unsigned)(cb * 128));
+        wait_loads<0>();
+        pin_regs(r);
 #pragma unroll
-                for (int n = 0; n < BATCH; ++n) {
-                    if (!live[n]) continue;
-                    const int lr = lr0 + (n0 + n) * RSTEP;
-                    const int row = row0 + lr;
-                    float v[8];
-                    {
-                        const f32x4_t s0 = *reinterpret_cast<const f32x4_t*>(&stage[lr][lc]);
-                        const f32x4_t s1 = *reinterpret_cast<const f32x4_t*>(&stage[lr][lc + 4]);
-                        v[0] = s0.x; v[1] = s0.y; v[2] = s0.z; v[3] = s0.w;
-                        v[4] = s1.x; v[5] = s1.y; v[6] = s1.z; v[7] = s1.w;
-                    }
-                    if (!full) {   // ragged right edge: element by element
-                        for (int e = 0; e < 8 && col + e < p.Q; ++e) {
-                            const float r = finish(v[e], row, col + e, off[n] + e);
-                            if (out_f32) cf[off[n] + e] = r;
-                            else ((T*)p.C)[off[n] + e] = ET<T>::from_f(r);
-                        }
-                        continue;
-                    }
-                    float ax[8], old[8];
-                    if constexpr (sizeof(T) == 2) {
-#pragma unroll
-                        for (int d = 0; d < 4; ++d) {
-                            ax[2 * d] = __uint_as_float(auxv[n][0][d] << 16); ax[2 * d + 1] = __uint_as_float(auxv[n][0][d] & 0xffff0000u);
-                            old[2 * d] = __uint_as_float(oldv[n][0][d] << 16); old[2 * d + 1] = __uint_as_float(oldv[n][0][d] & 0xffff0000u);
-                        }
-                    } else {
-#pragma unroll
-                        for (int d = 0; d < 4; ++d) {
-                            ax[d] = auxv[n][0][d]; ax[4 + d] = auxv[n][EV - 1][d];
-                            old[d] = oldv[n][0][d]; old[4 + d] = oldv[n][EV - 1][d];
-                        }
-                    }
-                    if constexpr (IS_FWD) {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) v[e] = (v[e] + bias_v[e]) + ax[e];
-                        if (p.flags & F_RELU) {
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
-                        } else if (p.act > ACT_RELU) {
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) v[e] = act_apply(p.act, v[e]);
-                        }
-                    } else if constexpr (!IS_DW) {
-                        const bool accum = (p.flags & F_ACCUM) != 0;
-                        if (p.flags & (F_SC_ID | F_SC_DOWN)) {   // the shortcut's share joins before the mask
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) v[e] += old[e];
-                        }
-                        if (!(p.flags & F_MASK) || p.mask_act == ACT_RELU) {   // absent mask source reads as ones
-#pragma unroll
-                            for (int e = 0; e < 8; ++e)
-                                if (!(ax[e] > 0.f)) v[e] = 0.f;
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) v[e] *= act_deriv(p.mask_act, ax[e]);
-                        }
-#pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            if (accum) v[e] += old[e];
-                    }
-                    if (out_f32) {
-                        *reinterpret_cast<f32x4_t*>(cf + off[n]) = f32x4_t{v[0], v[1], v[2], v[3]};
-                        *reinterpret_cast<f32x4_t*>(cf + off[n] + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
-                    } else if constexpr (sizeof(T) == 2) {
-                        u32x4_t o;
-#pragma unroll
-                        for (int d = 0; d < 4; ++d) o[d] = pack2bf(v[2 * d], v[2 * d + 1]);
-                        *reinterpret_cast<u32x4_t*>((T*)p.C + off[n]) = o;
-                    } else {
-                        *reinterpret_cast<f32x4_t*>((float*)p.C + off[n]) = f32x4_t{v[0], v[1], v[2], v[3]};
-                        *reinterpret_cast<f32x4_t*>((float*)p.C + off[n] + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
-                    }
-                }
-            }
-        }
-    } else {
-        for (int idx = threadIdx.x; idx < BM * BN; idx += 256) {
-            const int lr = idx / BN, lc = idx % BN;
-            const int row = row0 + lr, col = col0 + lc;
-            if (row >= p.R || col >= p.Q) continue;
-            const size_t off = out_row_base(p, row) + col;
-            const float r = finish(stage[lr][lc], row, col, off);
-            if (out_f32) cf[off] = r;
-            else ((T*)p.C)[off] = ET<T>::from_f(r);
+        for (int i = 0; i < NLD; ++i)
+            if (Cfg::MAXP * 8 % 256 == 0 || tid + 256 * i < Cfg::MAXP * 8)
+                *reinterpret_cast<u32x4_t*>(halo + rows_lds_offset<Cfg>(tid + 256 * i)) = r[i];
+    };
+
+    // the weight operand, as in the staged-tile form
+    Fetcher<MODE, T, false, BN, BK, true> fb;
+    fb.init(p, col0);
+    constexpr int LOADS_B = LoadsPerChunk<MODE, T, false, BN, BK>::value;
+    u32x4_t rb[2][GB::NREG];
+    auto k_of = [&](int q) { const int cb = q / 9, tap = q - 9 * cb; return tap * g.span + cb * BK; };
+
+    const bool vec_out = (p.ldc % 8 == 0) && (!(p.flags & F_RES_DOWN) || (p.resC % 8 == 0));
+    float bias_v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if constexpr (MODE == CONV_FWD) {
+        const int bcol = col0 + (tid % (BN / 8)) * 8;
+        if (vec_out && bcol + 8 <= p.Q) {
+            const f32x4_t b0v = *reinterpret_cast<const f32x4_t*>(p.bias + bcol);
+            const f32x4_t b1v = *reinterpret_cast<const f32x4_t*>(p.bias + bcol + 4);
+            bias_v[0] = b0v.x; bias_v[1] = b0v.y; bias_v[2] = b0v.z; bias_v[3] = b0v.w;
+            bias_v[4] = b1v.x; bias_v[5] = b1v.y; bias_v[6] = b1v.z; bias_v[7] = b1v.w;
         }
     }
+
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+
+    // byte offset of the lane's fragment of block a inside the halo, at tap displacement (-1, -1)
+    int a_off[TM];
+#pragma unroll
+    for (int a = 0; a < TM; ++a) a_off[a] = rows_slot(g, wm * 64 + a * 32 + (lane & 31)) * PIXB + (lane >> 5) * 16;
+
+    fb.fetch(p, k_of(0), p.Kd, rb[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    fb.fetch(p, k_of(1), p.Kd, rb[1]);
+    __builtin_amdgcn_sched_barrier(0);
+    load_halo(0);                                     // (its wait covers the two weight tiles as well)
+    wait_stage<0>(rb[0]);
+    stash_tile<MODE, T, false, BN, BK, true>(&Bs[0][0][0], rb[0]);
+
+    // step q = (channel block, tap); weight tile q in buffer q & 1, register stage q & 1
+    auto step = [&](auto PAR, const int q) {
+        constexpr int par = decltype(PAR)::value;
+        const int cb = q / 9, tap = q - 9 * cb;
+        __syncthreads();                              // tile q (and the halo) complete; nobody reads buffer par ^ 1 any more
+        fb.fetch(p, (q + 2 < nq) ? k_of(q + 2) : p.Kd, p.Kd, rb[par]);   // beyond the reduction: zeros, no memory access
+        __builtin_amdgcn_sched_barrier(0);
+        const int u = tap / 3, v = tap - 3 * u;
+        const char* const hp = halo + rows_tap_slots(g, u, v) * PIXB;
+        T(*Bb)[GB::LDS_LD] = Bs[par];
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2 * V) {
+            u32x4_t fa[TM], fbv[TN];
+#pragma unroll
+            for (int a = 0; a < TM; ++a) fa[a] = *reinterpret_cast<const u32x4_t*>(hp + a_off[a] + kk * ESZ);
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+                fbv[b] = *reinterpret_cast<const u32x4_t*>(&Bb[wn * (TN * 32) + b * 32 + (lane & 31)][kk + (lane >> 5) * V]);
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b) {
+                    if constexpr (ESZ == 2) {
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8_t, fa[a]), __builtin_bit_cast(bf16x8_t, fbv[b]), acc[a][b], 0, 0, 0);
+                    } else {
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[a].x), __uint_as_float(fbv[b].x), acc[a][b], 0, 0, 0);
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[a].y), __uint_as_float(fbv[b].y), acc[a][b], 0, 0, 0);
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[a].z), __uint_as_float(fbv[b].z), acc[a][b], 0, 0, 0);
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[a].w), __uint_as_float(fbv[b].w), acc[a][b], 0, 0, 0);
+                    }
+                }
+            if (kk == 0) {
+                wait_stage<LOADS_B>(rb[par ^ 1]);
+                stash_tile<MODE, T, false, BN, BK, true>(&Bs[par ^ 1][0][0], rb[par ^ 1]);
+            }
+        }
+        if (tap == 8 && cb + 1 < ncb) {               // the next channel block replaces the halo once everybody has left it
+            __syncthreads();
+            load_halo(cb + 1);
+        }
+    };
+    using std::integral_constant;
+    int q = 0;
+    for (; q + 2 <= nq; q += 2) {
+        step(integral_constant<int, 0>{}, q);
+        step(integral_constant<int, 1>{}, q + 1);
+    }
+    if (q < nq) step(integral_constant<int, 0>{}, q);
+    // the requests beyond the last tap still target the stage registers
+    wait_stage<0>(rb[0]);
+    wait_stage<0>(rb[1]);
+
+    // accumulators -> LDS as fp32, then the tail shared with the staged-tile form
+    float(*stage)[BN + 8] = reinterpret_cast<float(*)[BN + 8]>(lds);
+    __syncthreads();   // every wave is done with the operand blocks
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                stage[wm * 64 + a * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)][wn * (TN * 32) + b * 32 + (lane & 31)] = acc[a][b][e];
+    __syncthreads();
+    finish_tile<MODE, T, BM, BN>(p, row0, col0, stage, bias_v, vec_out);
 }
 
 // weight-gradient kernels also take the step's learning rates (by value), the others nothing
@@ -1284,8 +1481,31 @@ static hipError_t launch_gemm_mode(bool bf16, int tile_cfg, const GemmProb* prob
     return hipGetLastError();
 }
 
+template <int MODE, typename T>
+static void launch_rows_halo(int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, hipStream_t st) {
+    if (tile_cfg == GEMM_CFG_ROWS64) hipLaunchKernelGGL((conv_rows_halo_kernel<MODE, T, 4, 1, 2>), dim3(n), dim3(256), 0, st, probs, tiles, x);
+    else hipLaunchKernelGGL((conv_rows_halo_kernel<MODE, T, 4, 1, 1>), dim3(n), dim3(256), 0, st, probs, tiles, x);
+}
+
+int conv_rows_halo_cfg(bool bf16, int mode, const GemmProb& p) {
+    if (mode != CONV_FWD && mode != CONV_DX) return -1;
+    const bool dx = mode == CONV_DX;
+    if (p.flags & (F_A_INPUT | F_B_INPUT)) return -1;
+    const bool narrow = p.Q <= 32;
+    const bool ok = bf16 ? (narrow ? rows_halo_supported<RowsCfg<2, 4, 1, 1>>(p, dx) : rows_halo_supported<RowsCfg<2, 4, 1, 2>>(p, dx))
+                         : (narrow ? rows_halo_supported<RowsCfg<4, 4, 1, 1>>(p, dx) : rows_halo_supported<RowsCfg<4, 4, 1, 2>>(p, dx));
+    if (!ok) return -1;
+    return narrow ? GEMM_CFG_ROWS32 : GEMM_CFG_ROWS64;
+}
+
 hipError_t launch_gemm(int mode, bool bf16, int tile_cfg, const GemmProb* probs, const TileRef* tiles, int n, const void* x, char* ws, const LrTable& lr, hipStream_t st) {
     if (n <= 0) return hipSuccess;
+    if (is_rows_cfg(tile_cfg)) {
+        if (mode == CONV_FWD) { if (bf16) launch_rows_halo<CONV_FWD, bf16_t>(tile_cfg, probs, tiles, n, x, st); else launch_rows_halo<CONV_FWD, float>(tile_cfg, probs, tiles, n, x, st); }
+        else if (mode == CONV_DX) { if (bf16) launch_rows_halo<CONV_DX, bf16_t>(tile_cfg, probs, tiles, n, x, st); else launch_rows_halo<CONV_DX, float>(tile_cfg, probs, tiles, n, x, st); }
+        else return hipErrorInvalidValue;
+        return hipGetLastError();
+    }
     if (mode == CONV_DW && is_halo_cfg(tile_cfg)) return launch_conv_dw_halo(bf16, tile_cfg, probs, tiles, n, x, ws, lr, st);
     switch (mode) {
         case LIN_FWD: return launch_gemm_mode<LIN_FWD>(bf16, tile_cfg, probs, tiles, n, x, ws, lr, st);

@@ -238,6 +238,34 @@ def test_halo_form_of_the_convolution_weight_gradient_gives_the_same_bits_as_the
     assert np.array_equal(halo["loss"], staged["loss"])
 
 
+@pytest.mark.parametrize("make,one_block", [
+    (lambda: wl.config5(K=2, B=4, size=64, widths=(64, 64), n_classes=10, steps=2), True),     # bf16, 64 channels: one block; 64 and 32 pixel rows
+    (lambda: wl.config3(K=2, B=16, size=32, widths=(32, 32, 64), steps=2), True),              # fp32, 32 channels: one block; 32-column input gradient
+    (lambda: wl.config5(K=2, B=16, size=32, steps=2), False),                                  # bf16, up to 512 channels; 32 to 4 pixel rows (whole images per tile)
+    (lambda: wl.config5(K=1, B=8, size=32, widths=(64, 128), n_classes=10, steps=2, dtype=wl.F32), False),   # fp32, several blocks
+])
+def test_halo_form_of_stride_1_forward_and_input_gradient_against_the_staged_tiles(make, one_block, monkeypatch):
+    # the pixels a tile's nine taps reach staged once per block of channels.  With one channel block the
+    # reduction order is that of the staged-tile form (the same bits); with several it runs block by block
+    # instead of tap by tap: the same sums in another order
+    w = make()
+    halo = pu.run_gpu(w, steps=2)
+    assert any(t[:2] in ((256, 64), (256, 32)) for t in halo["tiles"]), halo["tiles"]
+    monkeypatch.setenv("PACK_NO_HALO_ROWS", "1")
+    staged = pu.run_gpu(w, steps=2)
+    assert not any(t[:2] in ((256, 64), (256, 32)) for t in staged["tiles"])
+    for key in ("grads", "blobs", "logits"):
+        for a, b in zip(halo[key], staged[key]):
+            if one_block:
+                assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), key
+            else:
+                scale = float(np.max(np.abs(b))) + 1e-30
+                tol = (BF16_TOL if w.dtype == wl.BF16 else F32_TOL)
+                assert float(np.max(np.abs(a.astype(np.float64) - b.astype(np.float64)))) <= tol * scale, key
+    if one_block:
+        assert np.array_equal(halo["loss"], staged["loss"])
+
+
 def test_c5_resnet_style_bf16_full_width_reduced_images():
     _check_bf16(wl.config5(K=2, B=8, size=16, steps=2))
 
