@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpack.so")
-SOURCES = ["pack_kernels.hip", "pack_conv_dw.hip", "conv_dw_halo_check.cpp", "pack_api.cpp", "pack_schedule.cpp", "pack_search.cpp"]
+SOURCES = ["pack_kernels.hip", "pack_conv_dw.hip", "conv_dw_halo_check.cpp", "conv_rows_halo_check.cpp", "pack_api.cpp", "pack_schedule.cpp", "pack_search.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread",
          # do not generate packed-fp32 instructions (v_pk_*_f32)
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -41,8 +41,9 @@ def check_no_spills(report: str) -> int:
             want = 16 * (int(t.group(1)) // 64) * (int(t.group(2)) // 64) if t else 16 * 9
             if not t and agprs == 0:
                 want = 0   # these keep their accumulator blocks in ordinary registers (no more than five, or four, per wave)
-            if "conv_rows_halo_kernel" in name:
-                want = 0
+            r = re.search(r"conv_rows_halo_kernelILi\d+E[tf]Li\d+ELi\d+ELi(\d+)E", name)
+            if r:   # two blocks of pixels x TN blocks of columns per wave, in AGPRs or all in ordinary registers
+                want = 0 if agprs == 0 else 32 * int(r.group(1))
             if int(m.group(1)) != 0 or agprs != want:
                 raise RuntimeError(f"{name}: scratch {m.group(1)} bytes, {agprs} AGPRs (accumulators need {want}): "
                                    "the kernel spills; the assembly-load pipeline would be unsound")

@@ -21,6 +21,12 @@
 #define PACK_HD __host__ __device__
 #endif
 
+// PACK_HALO_PLANT (0 in every build of the library): a CPU test compiles the host-side walk with one rule
+// deliberately wrong, to show that the walk notices.
+#ifndef PACK_HALO_PLANT
+#define PACK_HALO_PLANT 0
+#endif
+
 namespace packk {
 
 constexpr unsigned ROWS_POISON = 0x80000000u;   // byte offset of a vector that does not exist (beyond any descriptor)
@@ -86,6 +92,7 @@ PACK_HD inline bool rows_halo_supported(const GemmProb& p, bool dx) {
     const int sc = dx ? p.Cout : p.Cin;
     if (sc % Cfg::CB) return false;
     if (p.Kd != 9 * sc || p.ksplit < p.Kd) return false;
+    if (p.Kd < 512 && Cfg::BN > 32) return false;                      // (measured: a reduction that short is no faster here than on the staged tiles)
     if (p.W < 4 || (p.W & (p.W - 1)) || (p.H & (p.H - 1))) return false;                    // rows and pixels are found by shifts
     const int img = p.H * p.W;
     if (img >= Cfg::BM ? (Cfg::BM % p.W || img % Cfg::BM) : (Cfg::BM % img)) return false;
@@ -114,7 +121,7 @@ PACK_HD inline unsigned rows_vec_offset(const RowsGeom& g, int y0, int v) {
     if (slot >= g.NP) return ROWS_POISON;
     const int ii = rows_div(slot, g.mblk), rem = slot - ii * g.blk;
     const int hr = rows_div(rem, g.mHWD), hc = rem - hr * g.HWD;
-    const int y = y0 + hr - 1, x = hc - 1;
+    const int y = y0 + hr - 1, x = hc - 1 + (PACK_HALO_PLANT == 6);
     if (y < 0 || y >= g.SH || x < 0 || x >= g.SW) return ROWS_POISON;
     return (unsigned)((((ii * g.SH + y) * g.SW + x) * g.SC) * ESZ + part * 16);
 }
@@ -129,7 +136,7 @@ PACK_HD inline int rows_slot(const RowsGeom& g, int m) {
 }
 // slots from there to the pixel tap (u, v) reads
 PACK_HD inline int rows_tap_slots(const RowsGeom& g, int u, int v) {
-    return g.dx ? (2 - u) * g.HWD + (2 - v) : u * g.HWD + v;
+    return (g.dx && PACK_HALO_PLANT != 5) ? (2 - u) * g.HWD + (2 - v) : u * g.HWD + v;
 }
 
 }  // namespace packk

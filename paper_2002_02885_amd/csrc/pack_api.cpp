@@ -110,6 +110,8 @@ struct Launch {
 namespace packk {
 std::string conv_dw_halo_walk(bool bf16, bool wide, const GemmProb& p, const TileRef& tr, long long a_bytes, long long b_bytes,
                               bool every_chunk, long long* loads, long long* frag_reads);
+std::string conv_rows_halo_walk(bool bf16, bool narrow, bool dx, const GemmProb& p, const TileRef& tr, long long a_bytes,
+                                long long* loads, long long* frag_reads);
 // for the library's other source files: records the text pack_last_error returns
 pack_status set_error(pack_status s, const std::string& msg) { return fail(s, msg); }
 }  // namespace packk
@@ -1530,11 +1532,39 @@ pack_status pack_plan_check(const pack_input_spec* input, const pack_model_spec*
         const Launch& L = p->plan[li];
         if (L.kind != L_GEMM) continue;
         const bool halo = L.mode == CONV_DW && is_halo_cfg(L.tile_cfg);
+        const bool rows = (L.mode == CONV_FWD || L.mode == CONV_DX) && is_rows_cfg(L.tile_cfg);
         const int ci_t = halo ? GEMM_TILE_N[L.tile_cfg] / 9 : 0;      // input channels per tile
-        if (!halo) { ++skipped; continue; }
+        if (!halo && !rows) { ++skipped; continue; }
         ++walked;
         const GemmProb* probs = (const GemmProb*)(p->desc_host.data() + L.desc_off);
         const TileRef* tiles = (const TileRef*)(p->desc_host.data() + L.map_off);
+        if (rows) {
+            // stride-1 forward / input gradient, halo form: the gathered operand of every tile, and every tile once
+            const int BMc = GEMM_TILE_M[L.tile_cfg], BNc = GEMM_TILE_N[L.tile_cfg];
+            const bool dx = L.mode == CONV_DX;
+            std::map<std::vector<int>, int> dealt;
+            int n_probs = 0;
+            for (int t = 0; t < L.n && err.empty(); ++t) {
+                const TileRef& tr = tiles[t];
+                if (tr.prob < 0) continue;
+                n_probs = std::max(n_probs, tr.prob + 1);
+                const GemmProb& g = probs[tr.prob];
+                const long long a_bytes = (long long)g.R * (dx ? g.Cout : g.Cin) * (long long)esz;
+                if (!region_holds(g.A, a_bytes)) err = "the gathered operand is not inside one allocation";
+                if (err.empty() && (tr.ks != 0 || tr.tm < 0 || tr.tm >= g.R / BMc || tr.tn < 0 || tr.tn >= (g.Q + BNc - 1) / BNc)) err = "a tile lies outside its problem";
+                // (the gathered operand does not depend on the column tile: walked once per row tile)
+                if (err.empty() && tr.tn == 0) err = conv_rows_halo_walk(p->bf16, L.tile_cfg == GEMM_CFG_ROWS32, dx, g, tr, a_bytes, &loads, &frags);
+                if (++dealt[{tr.prob, tr.tm, tr.tn}] > 1 && err.empty()) err = "a tile is dealt twice";
+                if (!err.empty()) err = "launch " + std::to_string(li) + ", tile " + std::to_string(t) + " (problem " + std::to_string(tr.prob) + ", tm " +
+                                        std::to_string(tr.tm) + ", tn " + std::to_string(tr.tn) + "): " + err;
+            }
+            for (int i = 0; i < n_probs && err.empty(); ++i)
+                for (int tm = 0; tm < probs[i].R / BMc; ++tm)
+                    for (int tn = 0; tn < (probs[i].Q + BNc - 1) / BNc; ++tn)
+                        if (dealt.find({i, tm, tn}) == dealt.end() && err.empty())
+                            err = "launch " + std::to_string(li) + ": problem " + std::to_string(i) + " lacks a tile";
+            continue;
+        }
         std::map<std::vector<int>, int> seen;          // (problem, tm, tn, ks) -> times dealt
         int n_probs = 0;
         for (int t = 0; t < L.n && err.empty(); ++t) {

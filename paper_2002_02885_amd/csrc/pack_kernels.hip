@@ -656,9 +656,13 @@ struct LdsBytes {
 // accumulators lie in LDS as fp32 (`stage`, BM rows of SLD floats), so that global memory is touched with
 // 16-byte vectors along rows: bias, residual / mask source and previous value are read and the result is
 // written as full vectors.  256 threads; bias_v: the forward bias of the thread's eight columns (vector form).
-template <int MODE, typename T, int BM, int BN>
+// MAXB: rows whose global reads are requested together (one round trip per batch).  `staged()` is called
+// once, before the first read of `stage`: a caller that fills `stage` there (barrier, writes, barrier) has the
+// first batch's round trip run under that instead of after it.
+struct NoHook { __device__ __forceinline__ void operator()() const {} };
+template <int MODE, typename T, int BM, int BN, int MAXB = 4, class Hook = NoHook>
 __device__ __forceinline__ void finish_tile(const GemmProb& p, const int row0, const int col0, float (*stage)[BN + 8],
-                                            const float (&bias_v)[8], const bool vec_out) {
+                                            const float (&bias_v)[8], const bool vec_out, Hook staged = Hook()) {
     constexpr bool IS_DW = false;   // (weight-gradient tiles have a tail of their own)
     constexpr bool IS_FWD = (MODE == LIN_FWD || MODE == CONV_FWD);
     const bool out_f32 = IS_FWD && (p.flags & F_OUT_F32);
@@ -698,14 +702,15 @@ __device__ __forceinline__ void finish_tile(const GemmProb& p, const int row0, c
     // of it is used, so a batch costs one round trip instead of one per row.
     if (vec_out) {
         constexpr int GROUPS = BN / 8, NIT = BM * GROUPS / 256, RSTEP = 256 / GROUPS;
-        constexpr int BATCH = (NIT < 4) ? NIT : 4;
+        constexpr int BATCH = (NIT < MAXB) ? NIT : MAXB;
         static_assert(256 % GROUPS == 0 && NIT % BATCH == 0, "tile shape");
         const int lc = (threadIdx.x % GROUPS) * 8, lr0 = threadIdx.x / GROUPS;
         const int col = col0 + lc;
         const bool full = col + 8 <= p.Q;
         typedef typename std::conditional<sizeof(T) == 2, u32x4_t, f32x4_t>::type ev_t;   // 8 bf16 or 4 floats
         constexpr int EV = (sizeof(T) == 2) ? 1 : 2;   // vectors per 8 elements
-        if (col < p.Q) {
+        const bool col_ok = col < p.Q;   // (a thread beyond the last column still walks the loop: `staged` may hold barriers)
+        {
 #pragma unroll 1
             for (int n0 = 0; n0 < NIT; n0 += BATCH) {
                 size_t off[BATCH];
@@ -714,7 +719,7 @@ __device__ __forceinline__ void finish_tile(const GemmProb& p, const int row0, c
 #pragma unroll
                 for (int n = 0; n < BATCH; ++n) {
                     const int row = row0 + lr0 + (n0 + n) * RSTEP;
-                    live[n] = row < p.R;
+                    live[n] = col_ok && row < p.R;
                     off[n] = out_row_base(p, live[n] ? row : row0) + col;
                     const T* ap = nullptr;
                     const T* op = nullptr;
@@ -751,6 +756,7 @@ __device__ __forceinline__ void finish_tile(const GemmProb& p, const int row0, c
                         oldv[n][h] = op ? *reinterpret_cast<const ev_t*>(op + h * 4) : oz;
                     }
                 }
+                if (n0 == 0) staged();
 #pragma unroll
                 for (int n = 0; n < BATCH; ++n) {
                     if (!live[n]) continue;
@@ -829,6 +835,7 @@ __device__ __forceinline__ void finish_tile(const GemmProb& p, const int row0, c
             }
         }
     } else {
+        staged();
         for (int idx = threadIdx.x; idx < BM * BN; idx += 256) {
             const int lr = idx / BN, lc = idx % BN;
             const int row = row0 + lr, col = col0 + lc;
@@ -1295,18 +1302,22 @@ __global__ __launch_bounds__(256, 2) void conv_rows_halo_kernel(const GemmProb* 
     unsigned hv[NLD];
 #pragma unroll
     for (int i = 0; i < NLD; ++i) hv[i] = rows_vec_offset<Cfg, ESZ>(g, y0, tid + 256 * i);
-    // channel block cb of the halo: global -> registers -> LDS (all of it before anything else goes on)
-    auto load_halo = [&](int cb) {
-        u32x4_t r[NLD];
+    // channel block cb of the halo: global -> registers, and (once at most NEWER younger loads are outstanding) -> LDS
+    u32x4_t rh[NLD];
+    auto request_halo = [&](int cb) {
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) r[i] = buf_load16(rs, hv[i], (unsigned)(cb * 128));
-        wait_loads<0>();
-        pin_regs(r);
+        for (int i = 0; i < NLD; ++i) rh[i] = buf_load16(rs, hv[i], (unsigned)(cb * 128));
+    };
+    auto stash_halo = [&](auto NEWER) {
+        wait_loads<decltype(NEWER)::value>();
+        pin_regs(rh);
 #pragma unroll
         for (int i = 0; i < NLD; ++i)
             if (Cfg::MAXP * 8 % 256 == 0 || tid + 256 * i < Cfg::MAXP * 8)
-                *reinterpret_cast<u32x4_t*>(halo + rows_lds_offset<Cfg>(tid + 256 * i)) = r[i];
+                *reinterpret_cast<u32x4_t*>(halo + rows_lds_offset<Cfg>(tid + 256 * i)) = rh[i];
     };
+    request_halo(0);   // first of all: its round trip runs under the rest of the set-up
+    __builtin_amdgcn_sched_barrier(0);
 
     // the weight operand, as in the staged-tile form
     Fetcher<MODE, T, false, BN, BK, true> fb;
@@ -1344,8 +1355,8 @@ __global__ __launch_bounds__(256, 2) void conv_rows_halo_kernel(const GemmProb* 
     __builtin_amdgcn_sched_barrier(0);
     fb.fetch(p, k_of(1), p.Kd, rb[1]);
     __builtin_amdgcn_sched_barrier(0);
-    load_halo(0);                                     // (its wait covers the two weight tiles as well)
-    wait_stage<0>(rb[0]);
+    stash_halo(std::integral_constant<int, 2 * LOADS_B>{});
+    wait_stage<LOADS_B>(rb[0]);
     stash_tile<MODE, T, false, BN, BK, true>(&Bs[0][0][0], rb[0]);
 
     // step q = (channel block, tap); weight tile q in buffer q & 1, register stage q & 1
@@ -1387,7 +1398,8 @@ __global__ __launch_bounds__(256, 2) void conv_rows_halo_kernel(const GemmProb* 
         }
         if (tap == 8 && cb + 1 < ncb) {               // the next channel block replaces the halo once everybody has left it
             __syncthreads();
-            load_halo(cb + 1);
+            request_halo(cb + 1);
+            stash_halo(std::integral_constant<int, 0>{});
         }
     };
     using std::integral_constant;
@@ -1401,18 +1413,21 @@ __global__ __launch_bounds__(256, 2) void conv_rows_halo_kernel(const GemmProb* 
     wait_stage<0>(rb[0]);
     wait_stage<0>(rb[1]);
 
-    // accumulators -> LDS as fp32, then the tail shared with the staged-tile form
+    // The tail shared with the staged-tile form.  What it reads from global memory is requested for all of a
+    // thread's rows at once, and the accumulators go to LDS (as fp32) while that round trip runs.
     float(*stage)[BN + 8] = reinterpret_cast<float(*)[BN + 8]>(lds);
-    __syncthreads();   // every wave is done with the operand blocks
+    auto fill_stage = [&]() {
+        __syncthreads();   // every wave is done with the operand blocks
 #pragma unroll
-    for (int a = 0; a < TM; ++a)
+        for (int a = 0; a < TM; ++a)
 #pragma unroll
-        for (int b = 0; b < TN; ++b)
+            for (int b = 0; b < TN; ++b)
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                stage[wm * 64 + a * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)][wn * (TN * 32) + b * 32 + (lane & 31)] = acc[a][b][e];
-    __syncthreads();
-    finish_tile<MODE, T, BM, BN>(p, row0, col0, stage, bias_v, vec_out);
+                for (int e = 0; e < 16; ++e)
+                    stage[wm * 64 + a * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)][wn * (TN * 32) + b * 32 + (lane & 31)] = acc[a][b][e];
+        __syncthreads();
+    };
+    finish_tile<MODE, T, BM, BN, 8>(p, row0, col0, stage, bias_v, vec_out, fill_stage);
 }
 
 // weight-gradient kernels also take the step's learning rates (by value), the others nothing

@@ -1,8 +1,9 @@
 """Plan verification on the host (pack_plan_check): the planner's real launch plans of the convolution
-configurations, at full size, walked through the halo weight-gradient kernel's address rules without a
-GPU: every load of every thread of every chunk of every tile (prefetches beyond the reduction included)
-must stay inside its tensor or be cut off by the range check, and every matrix-instruction operand slot
-must hold the element the definition of the product puts there."""
+configurations, at full size, walked through the address rules of the halo kernels (weight gradient;
+stride-1 forward pass and input gradient) without a GPU: every load of every thread of every chunk of
+every tile (prefetches beyond the reduction included) must stay inside its tensor or be cut off by the
+range check, and every matrix-instruction operand slot must hold the element the definition of the
+product puts there."""
 import pytest
 
 import workloads as wl
@@ -19,7 +20,10 @@ def test_full_size_plans_of_the_convolution_configurations():
     w3, w5 = wl.config3(), wl.config5()
     walked3, _, loads3 = _check(w3)
     walked5, _, loads5 = _check(w5)
-    assert walked3 == 2 and walked5 == 2          # fp32: 32 channels stride 1, 64 channels stride 2; bf16: stride 1 and stride 2
+    # weight gradients: fp32 32 channels stride 1, 64 channels stride 2; bf16 stride 1 and stride 2.
+    # c3 adds the 32-column input gradient of its second convolution; c5 the forward pass and the input
+    # gradient of its five stride-1 convolutions
+    assert walked3 == 2 + 1 and walked5 == 2 + 5 + 5
     assert loads5 > 10 * loads3 > 10 ** 8
 
 
@@ -77,6 +81,39 @@ def test_the_walk_notices_planted_mistakes(tmp_path):
         r = subprocess.run([clean, *c], capture_output=True, text=True)
         assert r.returncode == 0 and r.stdout.startswith("OK"), (c, r.stdout)
     for plant in (1, 2, 3, 4):
+        exe = build(plant)
+        results = [subprocess.run([exe, *c], capture_output=True, text=True) for c in cases]
+        assert any(r.returncode == 1 and "FAIL" in r.stdout for r in results), plant
+
+
+def test_the_walk_of_the_stride_1_forward_and_input_gradient_form_notices_planted_mistakes(tmp_path):
+    """Same for the halo form of the stride-1 forward pass and input gradient: input-gradient taps displaced
+    the forward way, halo columns fetched one pixel to the right."""
+    import os
+    import shutil
+    import subprocess
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not (os.path.exists(hipcc) or shutil.which(hipcc)):
+        pytest.skip("no hipcc to compile the driver with")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    csrc = os.path.join(root, "paper_2002_02885_amd", "csrc")
+    # bf16, dx, B, H, W, Cin, Cout: rows of 64, 32, 16 and 8 pixels (whole images per tile from 16 down); both
+    # directions; one and several channel blocks; the 32-column form
+    cases = [("1", "0", "1", "64", "64", "64", "64"), ("1", "1", "2", "32", "32", "128", "128"), ("1", "0", "4", "16", "16", "256", "64"),
+             ("1", "1", "8", "8", "8", "64", "512"), ("0", "0", "1", "32", "32", "64", "64"), ("0", "1", "2", "32", "32", "32", "64")]
+
+    def build(plant):
+        exe = str(tmp_path / f"rows{plant}")
+        subprocess.run([hipcc, "-x", "hip", "--cuda-host-only", "-std=c++17", "-O1", f"-DPACK_HALO_PLANT={plant}", "-I", csrc,
+                        os.path.join(csrc, "conv_rows_halo_check.cpp"), os.path.join(root, "tests", "rows_walk_driver.cpp"), "-o", exe],
+                       check=True, capture_output=True)
+        return exe
+
+    clean = build(0)
+    for c in cases:
+        r = subprocess.run([clean, *c], capture_output=True, text=True)
+        assert r.returncode == 0 and r.stdout.startswith("OK"), (c, r.stdout)
+    for plant in (5, 6):
         exe = build(plant)
         results = [subprocess.run([exe, *c], capture_output=True, text=True) for c in cases]
         assert any(r.returncode == 1 and "FAIL" in r.stdout for r in results), plant
