@@ -133,14 +133,17 @@ pack_status pack_create(const pack_input_spec* input, const pack_model_spec* mod
                         uint64_t seed, void* hip_stream, pack_t** out);
 
 /* Plan verification on the host; no GPU is involved and none is needed.  Plans the pack exactly as
- * pack_create would (same planner, made-up device addresses) and replays, for every launch whose kernel
- * has a host-side model of its address rules, what every thread would load, store to LDS and read back as
- * matrix-instruction operands, against the definition of the product the launch computes (for the
- * convolution weight gradient: the backward pass of the members' 3x3 convolutions, Section 2.2's
- * "back-propagation ... as if trained alone").  A load that the hardware's range check would let through
- * outside its tensor, an operand slot holding the wrong element, a tile dealt twice or not at all is an
- * error.  input_mode: pack_input_mode.  Outputs (host, may be null): launches walked, matrix-product
- * launches without a host model (skipped), loads and operand reads checked.
+ * pack_create would (same planner, made-up device addresses) and walks every matrix-product launch of the
+ * plan: for the staged-tile kernels the kernels' own fetchers are run on the CPU, thread by thread and chunk
+ * by chunk (prefetches beyond the reduction included), and every load is held against the definition of the
+ * operands of the product the launch computes (the forward and backward passes of the members' layers,
+ * Section 2.2: "as if trained alone"); for the halo kernels of the 3x3 convolutions the walk also follows
+ * what is stored to LDS and read back as matrix-instruction operands.  A load of existing elements outside
+ * its descriptor's window or its allocation, a load of missing elements that is not cut off by construction,
+ * an operand slot holding the wrong element, a tile dealt twice or not at all is an error.
+ * input_mode: pack_input_mode.  Outputs (host, may be null): launches walked, matrix-product launches on the
+ * element-by-element kernels for unaligned shapes (skipped: they load by the definition itself), loads and
+ * operand reads checked.
  * Errors: PACK_EINVAL (bad arguments, or a violation: pack_last_error names launch and tile), PACK_ESHAPE, PACK_ENOMEM. */
 pack_status pack_plan_check(const pack_input_spec* input, const pack_model_spec* models, int32_t K, int32_t input_mode,
                             int64_t* launches_walked, int64_t* launches_skipped, int64_t* loads_checked);

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpack.so")
-SOURCES = ["pack_kernels.hip", "pack_conv_dw.hip", "conv_dw_halo_check.cpp", "conv_rows_halo_check.cpp", "pack_api.cpp", "pack_schedule.cpp", "pack_search.cpp"]
+SOURCES = ["pack_kernels.hip", "pack_conv_dw.hip", "conv_dw_halo_check.cpp", "conv_rows_halo_check.cpp", "gemm_fetch_check.cpp", "pack_api.cpp", "pack_schedule.cpp", "pack_search.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread",
          # do not generate packed-fp32 instructions (v_pk_*_f32)
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

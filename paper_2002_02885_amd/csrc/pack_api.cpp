@@ -112,6 +112,8 @@ std::string conv_dw_halo_walk(bool bf16, bool wide, const GemmProb& p, const Til
                               bool every_chunk, long long* loads, long long* frag_reads);
 std::string conv_rows_halo_walk(bool bf16, bool narrow, bool dx, const GemmProb& p, const TileRef& tr, long long a_bytes,
                                 long long* loads, long long* frag_reads);
+std::string gemm_fetch_walk(bool bf16, int mode, int bm, int bn, const GemmProb& p, const TileRef& tr, unsigned long long* a_lo,
+                            unsigned long long* a_hi, unsigned long long* b_lo, unsigned long long* b_hi, long long* loads);
 // for the library's other source files: records the text pack_last_error returns
 pack_status set_error(pack_status s, const std::string& msg) { return fail(s, msg); }
 }  // namespace packk
@@ -1534,10 +1536,42 @@ pack_status pack_plan_check(const pack_input_spec* input, const pack_model_spec*
         const bool halo = L.mode == CONV_DW && is_halo_cfg(L.tile_cfg);
         const bool rows = (L.mode == CONV_FWD || L.mode == CONV_DX) && is_rows_cfg(L.tile_cfg);
         const int ci_t = halo ? GEMM_TILE_N[L.tile_cfg] / 9 : 0;      // input channels per tile
-        if (!halo && !rows) { ++skipped; continue; }
+        const bool staged = !halo && !rows && L.tile_cfg != GEMM_CFG_SCALAR;
+        if (!halo && !rows && !staged) { ++skipped; continue; }      // the element-by-element kernels load by the definition itself
         ++walked;
         const GemmProb* probs = (const GemmProb*)(p->desc_host.data() + L.desc_off);
         const TileRef* tiles = (const TileRef*)(p->desc_host.data() + L.map_off);
+        if (staged) {
+            // aligned staged-tile kernels: the fetchers themselves, run on the CPU, against the definition of the operands
+            const int BMc = GEMM_TILE_M[L.tile_cfg], BNc = GEMM_TILE_N[L.tile_cfg];
+            std::map<std::vector<int>, int> dealt;
+            int n_probs = 0;
+            for (int t = 0; t < L.n && err.empty(); ++t) {
+                const TileRef& tr = tiles[t];
+                if (tr.prob < 0) continue;
+                n_probs = std::max(n_probs, tr.prob + 1);
+                GemmProb g = probs[tr.prob];
+                if (g.flags & F_A_INPUT) g.A = (const char*)x_fake + g.x_off;
+                if (g.flags & F_B_INPUT) g.B = (const char*)x_fake + g.x_off;
+                unsigned long long alo, ahi, blo, bhi;
+                err = gemm_fetch_walk(p->bf16, L.mode, BMc, BNc, g, tr, &alo, &ahi, &blo, &bhi, &loads);
+                if (err.empty() && alo < ahi && !region_holds((const void*)(uintptr_t)alo, (long long)(ahi - alo))) err = "the loads of operand A are not inside one allocation";
+                if (err.empty() && blo < bhi && !region_holds((const void*)(uintptr_t)blo, (long long)(bhi - blo))) err = "the loads of operand B are not inside one allocation";
+                if (++dealt[{tr.prob, tr.tm, tr.tn, tr.ks}] > 1 && err.empty()) err = "a tile is dealt twice";
+                if (!err.empty()) err = "launch " + std::to_string(li) + " (mode " + std::to_string(L.mode) + "), tile " + std::to_string(t) + " (problem " + std::to_string(tr.prob) +
+                                        ", tm " + std::to_string(tr.tm) + ", tn " + std::to_string(tr.tn) + ", split " + std::to_string(tr.ks) + "): " + err;
+            }
+            for (int i = 0; i < n_probs && err.empty(); ++i) {
+                const GemmProb& g = probs[i];
+                const int S = std::max(1, (g.Kd + g.ksplit - 1) / g.ksplit);
+                for (int ks = 0; ks < S; ++ks)
+                    for (int tm = 0; tm < (g.R + BMc - 1) / BMc; ++tm)
+                        for (int tn = 0; tn < (g.Q + BNc - 1) / BNc; ++tn)
+                            if (dealt.find({i, tm, tn, ks}) == dealt.end() && err.empty())
+                                err = "launch " + std::to_string(li) + ": problem " + std::to_string(i) + " lacks a tile";
+            }
+            continue;
+        }
         if (rows) {
             // stride-1 forward / input gradient, halo form: the gathered operand of every tile, and every tile once
             const int BMc = GEMM_TILE_M[L.tile_cfg], BNc = GEMM_TILE_N[L.tile_cfg];

@@ -8,11 +8,9 @@
 
 namespace packk {
 
-typedef unsigned short bf16_t;   // bfloat16 = upper half of an IEEE binary32
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(2))) float f32x2_t;
@@ -61,20 +59,6 @@ template <> struct ET<bf16_t> {
     static __device__ __forceinline__ float to_f(bf16_t v) { return bf2f(v); }
     static __device__ __forceinline__ bf16_t from_f(float v) { return f2bf(v); }
 };
-
-typedef __attribute__((ext_vector_type(4))) int i32x4_t;
-constexpr unsigned BUF_RECORDS = 0x80000000u;   // bytes a descriptor covers
-constexpr unsigned BUF_POISON = 0x80000000u;    // offset of an element that does not exist
-
-__device__ __forceinline__ i32x4_t make_rsrc(const void* base, long long margin_bytes) {
-    const unsigned long long a = (unsigned long long)base - (unsigned long long)margin_bytes;
-    i32x4_t r;
-    r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
-    r.y = __builtin_amdgcn_readfirstlane((int)(unsigned)(a >> 32));   // stride 0: raw buffer
-    r.z = (int)BUF_RECORDS;
-    r.w = 0x00020000;                                                 // 32-bit data format
-    return r;
-}
 
 __device__ __forceinline__ u32x4_t buf_load16(const i32x4_t rsrc, unsigned voff, unsigned soff) {
     u32x4_t v;

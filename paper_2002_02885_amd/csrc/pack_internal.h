@@ -51,6 +51,15 @@ enum GemmFlags : int {
 // activation kinds (paper Table 3); the value is also what GemmProb::act / mask_act hold
 enum ActKind { ACT_NONE = 0, ACT_RELU = 1, ACT_LEAKY = 2, ACT_SIGMOID = 3, ACT_TANH = 4 };
 
+// element and vector types shared by the kernels and the host-side walks of their address rules
+typedef unsigned short bf16_t;   // bfloat16 = upper half of an IEEE binary32
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+typedef __attribute__((ext_vector_type(4))) int i32x4_t;
+// raw buffer descriptors of the aligned kernels: the window a descriptor covers, and the byte offset that
+// stands for "this element does not exist" (at or beyond the window: the load returns zeros, no memory access)
+constexpr unsigned BUF_RECORDS = 0x80000000u;
+constexpr unsigned BUF_POISON = 0x80000000u;
+
 struct GemmProb {
     const void* A;
     const void* B;
