@@ -72,12 +72,9 @@ PACK_HD inline RowsGeom rows_geom(const GemmProb& p, bool dx) {
     g.blk = (g.rows + 2) * g.HWD;
     g.NP = g.nimg * g.blk;
     g.span = g.SC;
-    g.lgW = 0;
-    while ((1 << g.lgW) < g.SW) ++g.lgW;
-    g.lgPer = 0;
-    while ((1 << g.lgPer) < g.rows * g.SW) ++g.lgPer;
-    g.lgImg = 0;
-    while ((1 << g.lgImg) < g.SH * g.SW) ++g.lgImg;
+    g.lgW = 31 - __builtin_clz((unsigned)g.SW);
+    g.lgPer = 31 - __builtin_clz((unsigned)(g.rows * g.SW));
+    g.lgImg = 31 - __builtin_clz((unsigned)(g.SH * g.SW));
     g.mHWD = ((1u << 20) + (unsigned)g.HWD - 1) / (unsigned)g.HWD;
     g.mblk = ((1u << 20) + (unsigned)g.blk - 1) / (unsigned)g.blk;
     return g;

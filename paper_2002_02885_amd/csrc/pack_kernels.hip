@@ -318,6 +318,121 @@ __device__ __forceinline__ void finish_tile(const GemmProb& p, const int row0, c
         typedef typename std::conditional<sizeof(T) == 2, u32x4_t, f32x4_t>::type ev_t;   // 8 bf16 or 4 floats
         constexpr int EV = (sizeof(T) == 2) ? 1 : 2;   // vectors per 8 elements
         const bool col_ok = col < p.Q;   // (a thread beyond the last column still walks the loop: `staged` may hold barriers)
+        // Whole tiles of the plain cases (rows numbered as they lie in memory, shortcut and residual at the same
+        // pixel, ReLU or no activation, output in the pack's type): every address is the first row's plus a
+        // multiple of one stride and the flags are looked at once per tile instead of once per row.  The
+        // arithmetic per element is that of the general form below, operation for operation.
+        bool plain = !(p.flags & (F_ROWMAP | F_RES_DOWN | F_SC_DOWN)) && !out_f32 && row0 + BM <= p.R && col0 + BN <= p.Q;
+        if constexpr (IS_FWD) plain = plain && ((p.flags & F_RELU) || !(p.act > ACT_RELU));
+        else plain = plain && (!(p.flags & F_MASK) || p.mask_act == ACT_RELU);
+        if (plain) {
+            const size_t base = (size_t)(row0 + lr0) * p.ldc + col, step = (size_t)RSTEP * p.ldc;
+            const T* ap = nullptr;
+            const T* op = nullptr;
+            bool relu = false, add_sc = false, mask = false, accum = false;
+            if constexpr (IS_FWD) {
+                if (p.flags & F_RES_ID) ap = (const T*)p.aux + base;
+                relu = (p.flags & F_RELU) != 0;
+            } else {
+                mask = (p.flags & F_MASK) != 0;
+                accum = (p.flags & F_ACCUM) != 0;
+                add_sc = (p.flags & F_SC_ID) != 0;
+                if (mask) ap = (const T*)p.aux + base;
+                if (accum) op = (const T*)p.C + base;
+                if (add_sc) op = (const T*)p.sc + base;   // never together with F_ACCUM
+            }
+            T* const out = (T*)p.C + base;
+#pragma unroll 1
+            for (int n0 = 0; n0 < NIT; n0 += BATCH) {
+                ev_t auxv[BATCH][EV], oldv[BATCH][EV];
+                if (ap) {
+#pragma unroll
+                    for (int n = 0; n < BATCH; ++n)
+#pragma unroll
+                        for (int h = 0; h < EV; ++h) auxv[n][h] = *reinterpret_cast<const ev_t*>(ap + (size_t)(n0 + n) * step + h * 4);
+                } else {
+#pragma unroll
+                    for (int n = 0; n < BATCH; ++n)
+#pragma unroll
+                        for (int h = 0; h < EV; ++h) {
+                            if constexpr (sizeof(T) == 2) auxv[n][h] = u32x4_t{0u, 0u, 0u, 0u};
+                            else auxv[n][h] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                        }
+                }
+                if (op) {
+#pragma unroll
+                    for (int n = 0; n < BATCH; ++n)
+#pragma unroll
+                        for (int h = 0; h < EV; ++h) oldv[n][h] = *reinterpret_cast<const ev_t*>(op + (size_t)(n0 + n) * step + h * 4);
+                } else {
+#pragma unroll
+                    for (int n = 0; n < BATCH; ++n)
+#pragma unroll
+                        for (int h = 0; h < EV; ++h) {
+                            if constexpr (sizeof(T) == 2) oldv[n][h] = u32x4_t{0u, 0u, 0u, 0u};
+                            else oldv[n][h] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                        }
+                }
+                if (n0 == 0) staged();
+#pragma unroll
+                for (int n = 0; n < BATCH; ++n) {
+                    const int lr = lr0 + (n0 + n) * RSTEP;
+                    float v[8], ax[8], old[8];
+                    {
+                        const f32x4_t s0 = *reinterpret_cast<const f32x4_t*>(&stage[lr][lc]);
+                        const f32x4_t s1 = *reinterpret_cast<const f32x4_t*>(&stage[lr][lc + 4]);
+                        v[0] = s0.x; v[1] = s0.y; v[2] = s0.z; v[3] = s0.w;
+                        v[4] = s1.x; v[5] = s1.y; v[6] = s1.z; v[7] = s1.w;
+                    }
+                    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            ax[2 * d] = __uint_as_float(auxv[n][0][d] << 16); ax[2 * d + 1] = __uint_as_float(auxv[n][0][d] & 0xffff0000u);
+                            old[2 * d] = __uint_as_float(oldv[n][0][d] << 16); old[2 * d + 1] = __uint_as_float(oldv[n][0][d] & 0xffff0000u);
+                        }
+                    } else {
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            ax[d] = auxv[n][0][d]; ax[4 + d] = auxv[n][EV - 1][d];
+                            old[d] = oldv[n][0][d]; old[4 + d] = oldv[n][EV - 1][d];
+                        }
+                    }
+                    if constexpr (IS_FWD) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = (v[e] + bias_v[e]) + ax[e];
+                        if (relu) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+                        }
+                    } else {
+                        if (add_sc) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[e] += old[e];
+                        }
+                        if (mask) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (!(ax[e] > 0.f)) v[e] = 0.f;
+                        }
+                        if (accum) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[e] += old[e];
+                        }
+                    }
+                    T* const o = out + (size_t)(n0 + n) * step;
+                    if constexpr (sizeof(T) == 2) {
+                        u32x4_t w;
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) w[d] = pack2bf(v[2 * d], v[2 * d + 1]);
+                        *reinterpret_cast<u32x4_t*>(o) = w;
+                    } else {
+                        *reinterpret_cast<f32x4_t*>(o) = f32x4_t{v[0], v[1], v[2], v[3]};
+                        *reinterpret_cast<f32x4_t*>(o + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
+                    }
+                }
+            }
+            return;
+        }
         {
 #pragma unroll 1
             for (int n0 = 0; n0 < NIT; n0 += BATCH) {
