@@ -23,6 +23,11 @@
 #include <utility>
 
 namespace packk {
+// Workgroup barrier for LDS hand-over only: waits for this wave's outstanding LDS operations, not for its
+// global loads (__syncthreads waits for those too, which would put every round trip requested before the
+// barrier in front of it).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 typedef const __attribute__((address_space(1))) u32x4_t* gvec_ptr;
 typedef const __attribute__((address_space(1))) unsigned short* gu16_ptr;
 typedef const __attribute__((address_space(1))) float* gf32_ptr;
@@ -643,14 +648,14 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
         for (int it = 0; it < nk; ++it) {
             wait_stage<0>(ra[0]);
             wait_stage<0>(rb[0]);
-            __syncthreads();
+            lds_barrier();
             stash_tile<MODE, T, true, BM, BK, VEC>(&As[0][0][0], ra[0]);
             stash_tile<MODE, T, false, BN, BK, VEC>(&Bs[0][0][0], rb[0]);
             __builtin_amdgcn_sched_barrier(0);
             fa.fetch(p, kbeg + (it + 1) * BK, kend, ra[0]);   // beyond the reduction: zeros, no memory access
             fb.fetch(p, kbeg + (it + 1) * BK, kend, rb[0]);
             __builtin_amdgcn_sched_barrier(0);
-            __syncthreads();
+            lds_barrier();
             T(*Ab)[GA::LDS_LD] = As[0];
             T(*Bb)[GB::LDS_LD] = Bs[0];
             if (do_bias_grad && threadIdx.x < BM) {
@@ -726,7 +731,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
         constexpr int s = decltype(S)::value;
         constexpr int par = decltype(PAR)::value;
         constexpr int sn = (s + 1) % ST;
-        __syncthreads();
+        lds_barrier();
         fa.fetch(p, kbeg + (it + ST) * BK, kend, ra[s]);
         fb.fetch(p, kbeg + (it + ST) * BK, kend, rb[s]);
         __builtin_amdgcn_sched_barrier(0);
@@ -859,7 +864,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
         const int col = col0 + dw_lc;
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-            __syncthreads();   // operand tiles (half 0) or the previous half's staging no longer read
+            lds_barrier();   // operand tiles (half 0) or the previous half's staging no longer read
             if (wm == half) {
 #pragma unroll
                 for (int a = 0; a < TM; ++a)
@@ -869,7 +874,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
                         for (int e = 0; e < 16; ++e)
                             stage[a * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)][wn * (BN / 2) + b * 32 + (lane & 31)] = acc[a][b][e];
             }
-            __syncthreads();
+            lds_barrier();
             if (vec_out) {
                 if (col < p.Q) {
 #pragma unroll
@@ -911,15 +916,18 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
         }
         return;
     }
-    __syncthreads();   // every wave is done with the operand tiles
+    auto fill_stage = [&]() {
+        lds_barrier();   // every wave is done with the operand tiles
 #pragma unroll
-    for (int a = 0; a < TM; ++a)
+        for (int a = 0; a < TM; ++a)
 #pragma unroll
-        for (int b = 0; b < TN; ++b)
+            for (int b = 0; b < TN; ++b)
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                stage[wm * (BM / 2) + a * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)][wn * (BN / 2) + b * 32 + (lane & 31)] = acc[a][b][e];
-    __syncthreads();
+                for (int e = 0; e < 16; ++e)
+                    stage[wm * (BM / 2) + a * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)][wn * (BN / 2) + b * 32 + (lane & 31)] = acc[a][b][e];
+        lds_barrier();
+    };
+    if constexpr (IS_DW) fill_stage();
 
     if constexpr (IS_DW) {
         float* const gf = (float*)p.C + (size_t)tr.ks * p.split_stride;
@@ -965,7 +973,9 @@ __device__ __forceinline__ void gemm_body(const GemmProb& p, const TileRef& tr, 
         return;
     }
 
-    if constexpr (!IS_DW) finish_tile<MODE, T, BM, BN>(p, row0, col0, stage, bias_v, vec_out);
+    // forward / input gradient: what the tail reads from global memory is requested first, the accumulators are
+    // staged while that round trip runs
+    if constexpr (!IS_DW) finish_tile<MODE, T, BM, BN>(p, row0, col0, stage, bias_v, vec_out, fill_stage);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1086,7 +1096,7 @@ __global__ __launch_bounds__(256, 2) void conv_rows_halo_kernel(const GemmProb* 
     auto step = [&](auto PAR, const int q) {
         constexpr int par = decltype(PAR)::value;
         const int cb = q / 9, tap = q - 9 * cb;
-        __syncthreads();                              // tile q (and the halo) complete; nobody reads buffer par ^ 1 any more
+        lds_barrier();                              // tile q (and the halo) complete; nobody reads buffer par ^ 1 any more
         fb.fetch(p, (q + 2 < nq) ? k_of(q + 2) : p.Kd, p.Kd, rb[par]);   // beyond the reduction: zeros, no memory access
         __builtin_amdgcn_sched_barrier(0);
         const int u = tap / 3, v = tap - 3 * u;
@@ -1120,7 +1130,7 @@ __global__ __launch_bounds__(256, 2) void conv_rows_halo_kernel(const GemmProb* 
             }
         }
         if (tap == 8 && cb + 1 < ncb) {               // the next channel block replaces the halo once everybody has left it
-            __syncthreads();
+            lds_barrier();
             request_halo(cb + 1);
             stash_halo(std::integral_constant<int, 0>{});
         }
@@ -1140,7 +1150,7 @@ __global__ __launch_bounds__(256, 2) void conv_rows_halo_kernel(const GemmProb* 
     // thread's rows at once, and the accumulators go to LDS (as fp32) while that round trip runs.
     float(*stage)[BN + 8] = reinterpret_cast<float(*)[BN + 8]>(lds);
     auto fill_stage = [&]() {
-        __syncthreads();   // every wave is done with the operand blocks
+        lds_barrier();   // every wave is done with the operand blocks
 #pragma unroll
         for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -1148,7 +1158,7 @@ __global__ __launch_bounds__(256, 2) void conv_rows_halo_kernel(const GemmProb* 
 #pragma unroll
                 for (int e = 0; e < 16; ++e)
                     stage[wm * 64 + a * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)][wn * (TN * 32) + b * 32 + (lane & 31)] = acc[a][b][e];
-        __syncthreads();
+        lds_barrier();
     };
     finish_tile<MODE, T, BM, BN, 8>(p, row0, col0, stage, bias_v, vec_out, fill_stage);
 }
