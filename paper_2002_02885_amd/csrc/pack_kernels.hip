@@ -323,38 +323,44 @@ __device__ __forceinline__ void finish_tile(const GemmProb& p, const int row0, c
         typedef typename std::conditional<sizeof(T) == 2, u32x4_t, f32x4_t>::type ev_t;   // 8 bf16 or 4 floats
         constexpr int EV = (sizeof(T) == 2) ? 1 : 2;   // vectors per 8 elements
         const bool col_ok = col < p.Q;   // (a thread beyond the last column still walks the loop: `staged` may hold barriers)
-        // Whole tiles of the plain cases (rows numbered as they lie in memory, shortcut and residual at the same
-        // pixel, ReLU or no activation, output in the pack's type): every address is the first row's plus a
-        // multiple of one stride and the flags are looked at once per tile instead of once per row.  The
-        // arithmetic per element is that of the general form below, operation for operation.
-        bool plain = !(p.flags & (F_ROWMAP | F_RES_DOWN | F_SC_DOWN)) && !out_f32 && row0 + BM <= p.R && col0 + BN <= p.Q;
+        // Whole tiles of the plain cases (shortcut and residual at the same pixel, ReLU or no activation, output in
+        // the pack's type): one offset per row serves every tensor the tail touches (the first row's plus a multiple
+        // of one stride, or the row's pixel for the parity classes of a stride-2 input gradient) and the flags are
+        // looked at once per tile instead of once per row.  The arithmetic per element is that of the general form
+        // below, operation for operation.
+        bool plain = !(p.flags & (F_RES_DOWN | F_SC_DOWN)) && !out_f32 && row0 + BM <= p.R && col0 + BN <= p.Q;
         if constexpr (IS_FWD) plain = plain && ((p.flags & F_RELU) || !(p.act > ACT_RELU));
         else plain = plain && (!(p.flags & F_MASK) || p.mask_act == ACT_RELU);
         if (plain) {
+            const bool by_pixel = (p.flags & F_ROWMAP) != 0;
             const size_t base = (size_t)(row0 + lr0) * p.ldc + col, step = (size_t)RSTEP * p.ldc;
             const T* ap = nullptr;
             const T* op = nullptr;
             bool relu = false, add_sc = false, mask = false, accum = false;
             if constexpr (IS_FWD) {
-                if (p.flags & F_RES_ID) ap = (const T*)p.aux + base;
+                if (p.flags & F_RES_ID) ap = (const T*)p.aux;
                 relu = (p.flags & F_RELU) != 0;
             } else {
                 mask = (p.flags & F_MASK) != 0;
                 accum = (p.flags & F_ACCUM) != 0;
                 add_sc = (p.flags & F_SC_ID) != 0;
-                if (mask) ap = (const T*)p.aux + base;
-                if (accum) op = (const T*)p.C + base;
-                if (add_sc) op = (const T*)p.sc + base;   // never together with F_ACCUM
+                if (mask) ap = (const T*)p.aux;
+                if (accum) op = (const T*)p.C;
+                if (add_sc) op = (const T*)p.sc;   // never together with F_ACCUM
             }
-            T* const out = (T*)p.C + base;
+            T* const out = (T*)p.C;
 #pragma unroll 1
             for (int n0 = 0; n0 < NIT; n0 += BATCH) {
                 ev_t auxv[BATCH][EV], oldv[BATCH][EV];
+                size_t offn[BATCH];
+#pragma unroll
+                for (int n = 0; n < BATCH; ++n)
+                    offn[n] = by_pixel ? out_row_base(p, row0 + lr0 + (n0 + n) * RSTEP) + col : base + (size_t)(n0 + n) * step;
                 if (ap) {
 #pragma unroll
                     for (int n = 0; n < BATCH; ++n)
 #pragma unroll
-                        for (int h = 0; h < EV; ++h) auxv[n][h] = *reinterpret_cast<const ev_t*>(ap + (size_t)(n0 + n) * step + h * 4);
+                        for (int h = 0; h < EV; ++h) auxv[n][h] = *reinterpret_cast<const ev_t*>(ap + offn[n] + h * 4);
                 } else {
 #pragma unroll
                     for (int n = 0; n < BATCH; ++n)
@@ -368,7 +374,7 @@ __device__ __forceinline__ void finish_tile(const GemmProb& p, const int row0, c
 #pragma unroll
                     for (int n = 0; n < BATCH; ++n)
 #pragma unroll
-                        for (int h = 0; h < EV; ++h) oldv[n][h] = *reinterpret_cast<const ev_t*>(op + (size_t)(n0 + n) * step + h * 4);
+                        for (int h = 0; h < EV; ++h) oldv[n][h] = *reinterpret_cast<const ev_t*>(op + offn[n] + h * 4);
                 } else {
 #pragma unroll
                     for (int n = 0; n < BATCH; ++n)
@@ -424,7 +430,7 @@ __device__ __forceinline__ void finish_tile(const GemmProb& p, const int row0, c
                             for (int e = 0; e < 8; ++e) v[e] += old[e];
                         }
                     }
-                    T* const o = out + (size_t)(n0 + n) * step;
+                    T* const o = out + offn[n];
                     if constexpr (sizeof(T) == 2) {
                         u32x4_t w;
 #pragma unroll
