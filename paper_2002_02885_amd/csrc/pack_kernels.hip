@@ -1108,33 +1108,44 @@ __global__ __launch_bounds__(256, 2) void conv_rows_halo_kernel(const GemmProb* 
         const int u = tap / 3, v = tap - 3 * u;
         const char* const hp = halo + rows_tap_slots(g, u, v) * PIXB;
         T(*Bb)[GB::LDS_LD] = Bs[par];
+        // The fragments of reduction step s + 1 are requested before the matrix instructions of step s are issued
+        // (two sets of fragment registers; scheduling barriers keep that order), so that a wave's LDS latency
+        // runs under its own matrix instructions.
+        constexpr int STEPS = BK / (2 * V);
+        u32x4_t fa[2][TM], fbv[2][TN];
+        auto read_step = [&](auto S) {
+            constexpr int st = decltype(S)::value, kk = st * 2 * V;
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 2 * V) {
-            u32x4_t fa[TM], fbv[TN];
-#pragma unroll
-            for (int a = 0; a < TM; ++a) fa[a] = *reinterpret_cast<const u32x4_t*>(hp + a_off[a] + kk * ESZ);
+            for (int a = 0; a < TM; ++a) fa[st & 1][a] = *reinterpret_cast<const u32x4_t*>(hp + a_off[a] + kk * ESZ);
 #pragma unroll
             for (int b = 0; b < TN; ++b)
-                fbv[b] = *reinterpret_cast<const u32x4_t*>(&Bb[wn * (TN * 32) + b * 32 + (lane & 31)][kk + (lane >> 5) * V]);
+                fbv[st & 1][b] = *reinterpret_cast<const u32x4_t*>(&Bb[wn * (TN * 32) + b * 32 + (lane & 31)][kk + (lane >> 5) * V]);
+        };
+        read_step(std::integral_constant<int, 0>{});
+        for_each_stage(std::make_integer_sequence<int, STEPS>{}, [&](auto S) {
+            constexpr int st = decltype(S)::value;
+            if constexpr (st + 1 < STEPS) read_step(std::integral_constant<int, st + 1>{});
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int a = 0; a < TM; ++a)
 #pragma unroll
                 for (int b = 0; b < TN; ++b) {
+                    const u32x4_t va = fa[st & 1][a], vb = fbv[st & 1][b];
                     if constexpr (ESZ == 2) {
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8_t, fa[a]), __builtin_bit_cast(bf16x8_t, fbv[b]), acc[a][b], 0, 0, 0);
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, va), __builtin_bit_cast(bf16x8_t, vb), acc[a][b], 0, 0, 0);
                     } else {
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[a].x), __uint_as_float(fbv[b].x), acc[a][b], 0, 0, 0);
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[a].y), __uint_as_float(fbv[b].y), acc[a][b], 0, 0, 0);
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[a].z), __uint_as_float(fbv[b].z), acc[a][b], 0, 0, 0);
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[a].w), __uint_as_float(fbv[b].w), acc[a][b], 0, 0, 0);
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(va.x), __uint_as_float(vb.x), acc[a][b], 0, 0, 0);
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(va.y), __uint_as_float(vb.y), acc[a][b], 0, 0, 0);
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(va.z), __uint_as_float(vb.z), acc[a][b], 0, 0, 0);
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(va.w), __uint_as_float(vb.w), acc[a][b], 0, 0, 0);
                     }
                 }
-            if (kk == 0) {
+            if constexpr (st == 0) {
                 wait_stage<LOADS_B>(rb[par ^ 1]);
                 stash_tile<MODE, T, false, BN, BK, true>(&Bs[par ^ 1][0][0], rb[par ^ 1]);
             }
-        }
+            __builtin_amdgcn_sched_barrier(0);
+        });
         if (tap == 8 && cb + 1 < ncb) {               // the next channel block replaces the halo once everybody has left it
             lds_barrier();
             request_halo(cb + 1);
