@@ -554,7 +554,12 @@ void emit_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, int cfg, const std
     p->plan.push_back(L);
 }
 
-void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<GemmProb>& all_probs) {
+void add_gemm_launch(pack_ctx* p, DescBuilder& db, int mode, const std::vector<GemmProb>& all_probs_in) {
+    // PACK_GENERAL_TAIL: every forward / input-gradient tile takes the general form of the tail, for the test that
+    // compares it bit for bit with the form whole tiles of the plain cases take
+    std::vector<GemmProb> all_probs = all_probs_in;
+    if (std::getenv("PACK_GENERAL_TAIL"))
+        for (GemmProb& g : all_probs) g.flags |= F_GENERAL_TAIL;
     // problems whose operands are not aligned for 16-byte loads go to the scalar-gather kernel
     std::vector<GemmProb> probs, scalar;
     for (const GemmProb& g : all_probs) {

@@ -44,8 +44,10 @@ enum GemmFlags : int {
     F_SC_ID = 16384,   // dX of the first layer of a residual block: add the gradient that arrives through the
                        // identity shortcut, sc[row, col] (same shape as the output), before the mask
     F_SC_DOWN = 32768, // likewise for the subsampling shortcut: pixel (2i, 2j) receives sc[b, i, j, col]
-    F_WS = 65536       // split weight gradient: C and dbias hold BYTE OFFSETS into the step's workspace (the
+    F_WS = 65536,      // split weight gradient: C and dbias hold BYTE OFFSETS into the step's workspace (the
                        // buffer of partial sums the launch receives as an argument), not addresses
+    F_GENERAL_TAIL = 131072   // forward / input gradient: every tile takes the general form of the tail (set by a test
+                              // that compares it with the form whole tiles of the plain cases take)
 };
 
 // activation kinds (paper Table 3); the value is also what GemmProb::act / mask_act hold

@@ -328,7 +328,7 @@ __device__ __forceinline__ void finish_tile(const GemmProb& p, const int row0, c
         // of one stride, or the row's pixel for the parity classes of a stride-2 input gradient) and the flags are
         // looked at once per tile instead of once per row.  The arithmetic per element is that of the general form
         // below, operation for operation.
-        bool plain = !(p.flags & (F_RES_DOWN | F_SC_DOWN)) && !out_f32 && row0 + BM <= p.R && col0 + BN <= p.Q;
+        bool plain = !(p.flags & (F_RES_DOWN | F_SC_DOWN | F_GENERAL_TAIL)) && !out_f32 && row0 + BM <= p.R && col0 + BN <= p.Q;
         if constexpr (IS_FWD) plain = plain && ((p.flags & F_RELU) || !(p.act > ACT_RELU));
         else plain = plain && (!(p.flags & F_MASK) || p.mask_act == ACT_RELU);
         if (plain) {
