@@ -95,6 +95,25 @@ PACK_HD inline bool halo_supported(const GemmProb& p) {
     return true;
 }
 
+// Where a chunk lies: its image and its first output pixel inside that image.  The kernel finds it once per
+// tile and then steps from chunk to chunk (a chunk never straddles two images), without a division per chunk.
+struct HaloCursor {
+    int img, pix;
+};
+PACK_HD inline HaloCursor halo_cursor(const HaloGeom& g, int k0) {
+    HaloCursor c;
+    c.img = k0 / g.img_px;
+    c.pix = k0 - c.img * g.img_px;
+    return c;
+}
+PACK_HD inline void halo_cursor_advance(const HaloGeom& g, int chunk, HaloCursor& c) {
+    c.pix += chunk;
+    if (c.pix >= g.img_px) {
+        c.pix -= g.img_px;
+        ++c.img;
+    }
+}
+
 // ---- global -> LDS ---------------------------------------------------------------------------------
 // Halo vector number v of a chunk (v = pixel slot * VPP_B + part; slot = halo row * HWD + halo column):
 // its byte offset from the first element of halo row 0, image column 0, channel c0 of the image the chunk

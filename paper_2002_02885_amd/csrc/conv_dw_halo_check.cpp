@@ -50,11 +50,14 @@ bool walk_tile(const GemmProb& p, const TileRef& tr, long long a_bytes, long lon
 
     // symbolic LDS: one entry per element position of the halo block and of the dZ block
     std::vector<long long> halo((size_t)Cfg::HALO_BYTES / ESZ), dz((size_t)Cfg::DZ_BYTES / ESZ);
+    HaloCursor cur = halo_cursor(g, kbeg);     // the kernel's way from chunk to chunk
     for (int t = 0; t < nk + 3; ++t) {        // the kernel prefetches up to three chunks beyond the reduction
         const bool live = t < nk;
         const int k0 = kbeg + t * CH;
         const int img = live ? k0 / g.img_px : 0;
         const int i0 = live ? ((k0 - img * g.img_px) >> g.lgWo) : 0;
+        if (live && (cur.img != img || (cur.pix >> g.lgWo) != i0 || (cur.pix & (g.Wo - 1)))) return w.fail("the chunk cursor is not where the chunk lies");
+        halo_cursor_advance(g, CH, cur);
         if (live && (k0 % g.img_px) + CH > g.img_px) return w.fail("chunk straddles two images");
         const unsigned records = live ? (unsigned)g.img_bytes : 0u;
         const unsigned roff = (unsigned)halo_row_offset(g, i0);

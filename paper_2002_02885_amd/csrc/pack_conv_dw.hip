@@ -56,11 +56,14 @@ __device__ __forceinline__ void conv_dw_halo_body(const GemmProb& p, const TileR
     // the scalar offset; the input through a descriptor over the ONE image the chunk lies in, so that a
     // halo row above or below the image is out of the descriptor's range and reads as zeros.  A chunk
     // beyond the reduction (the pipeline always prefetches ahead) gets empty descriptors.
+    // (called for t = 0, 1, 2, ... in turn: the cursor steps from chunk to chunk)
+    HaloCursor cur = halo_cursor(g, kbeg);
     auto issue = [&](int t, u32x4_t(&rh)[NLD], u32x4_t(&ra)[NLA]) {
         const int k0 = kbeg + t * CH;
         const bool live = t < nk;
-        const int img = live ? k0 / g.img_px : 0;
-        const int i0 = live ? ((k0 - img * g.img_px) >> g.lgWo) : 0;
+        const int img = live ? cur.img : 0;
+        const int i0 = live ? (cur.pix >> g.lgWo) : 0;
+        halo_cursor_advance(g, CH, cur);
         const unsigned long long ib = (unsigned long long)p.B + (unsigned long long)img * (unsigned long long)g.img_bytes;
         i32x4_t rs;
         rs.x = __builtin_amdgcn_readfirstlane((int)(unsigned)ib);
@@ -205,8 +208,9 @@ __device__ __forceinline__ void conv_dw_halo_body(const GemmProb& p, const TileR
     };
 
     // ST register stages and two LDS buffers, one barrier per chunk.  After the barrier of chunk `it`
-    // (complete in its buffer; nobody reads the other buffer any more): the stage emptied by the previous
-    // chunk is refilled with the loads of chunk it + ST, the first step of chunk `it` is multiplied, chunk
+    // (complete in its buffer; nobody reads the other buffer any more): the first matrix instructions of chunk
+    // `it` are issued, behind them the stage emptied by the previous chunk is refilled with the loads of chunk
+    // it + ST, the rest of the first step is multiplied, chunk
     // it + 1 (whose loads were requested ST - 1 chunks ago: a chunk's worth of matrix instructions is shorter
     // than the slowest of a chunk's loads takes to come back, which is what two stages ran into) is stored
     // to the other buffer under those matrix instructions, then the remaining steps.
@@ -227,13 +231,14 @@ __device__ __forceinline__ void conv_dw_halo_body(const GemmProb& p, const TileR
         __syncthreads();
         static_for(std::make_integer_sequence<int, AHEAD>{}, [&](auto I) { read_operands(par, I); });
         __builtin_amdgcn_sched_barrier(0);
-        issue(it + ST, rh[stg], ra[stg]);
-        __builtin_amdgcn_sched_barrier(0);
         static_for(std::make_integer_sequence<int, NI>{}, [&](auto I) {
             constexpr int idx = decltype(I)::value;
             if constexpr (idx + AHEAD < NI) read_operands(par, integral_constant<int, idx + AHEAD>{});
             __builtin_amdgcn_sched_barrier(0);
             multiply(I);
+            // (the requests of chunk it + ST go out behind the chunk's first matrix instructions, under which
+            // their address arithmetic runs, instead of between the barrier and the first of them)
+            if constexpr (idx == 1) issue(it + ST, rh[stg], ra[stg]);
             if constexpr (idx % PER_STEP == PER_STEP - 1) bias_step(integral_constant<int, idx / PER_STEP>{});
             if constexpr (idx == PER_STEP - 1) {
                 wait_loads<(ST - 1) * LOADS>();
