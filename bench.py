@@ -38,9 +38,9 @@ HEADLINE = "c5"                # the largest configuration that fits one GPU
 # scaled by a copy kernel of known size; the summary under profiles/ named here), valid only for the
 # kernel source it was measured on (hash of the kernel's text): {workload: {...}}.
 COUNTER_TRAFFIC = {
-    "c2": {"kernel": "gemm_lin_dw+sgd", "bytes": 373.4e6, "kernel_sha": "2d18a77cff671b63", "sources": "staged",
+    "c2": {"kernel": "gemm_lin_dw+sgd", "bytes": 373.4e6, "kernel_sha": "4df60122164a5d1a", "sources": "staged",
            "profile": "profiles/c2_weight_gradient_update_hbm_counters.txt"},
-    "c5": {"kernel": "gemm_conv_dw+sgd", "bytes": 1093.6e6, "kernel_sha": "af90d38c6514f51b", "sources": "conv_dw_halo",
+    "c5": {"kernel": "gemm_conv_dw+sgd", "bytes": 1108.6e6, "kernel_sha": "e8dbb0d29c1761f9", "sources": "conv_dw_halo",
            "profile": "profiles/c5_convolution_weight_gradient_hbm_counters.txt"},
 }
 
