@@ -15,7 +15,7 @@ TOL = {wl.F32: 1e-4, wl.BF16: 2e-2}    # max relative error the two paths may di
 def say(text: str):
     """Progress line of a long test (an oracle step of the largest configuration takes minutes): to the
     real stderr and, so that a runner watching the output folder sees the test is alive while pytest
-    holds the streams back, appended to gpurun_out/test_progress.log."""
+    holds the streams back, appended to a progress log in that folder."""
     import os
     import sys
     import time
